@@ -1,0 +1,253 @@
+/*
+ * CPU oracle for the learned-cache lookup.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, single-threaded, fp64 statement of what one lookup computes, written
+ * from the paper's description of a learned cache (Section 3, "Learned Cache
+ * Design"): a prediction operation followed by a selection operation, with hits
+ * leaving the batch and misses continuing to the next layer (Section 1, "cache
+ * misses continue inference on the base model").  It shares no code, header,
+ * table or constant with the HIP library and must never be linked into or called
+ * from the product path; only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg use it.
+ *
+ * Every function is the definition written out as loops with double
+ * accumulators: no blocking, no vectorisation, no reordering.
+ *
+ * Pins (tests/test_oracle_*.py): hand-computed cases in exact rational
+ * arithmetic, closed forms (K=2 softmax = logistic; zero weights), invariants
+ * (sum/count, softmax sums to 1, shift invariance, hits and misses partition the
+ * batch, order preserved), brute force over all hit masks, an independent
+ * library affine map as a third opinion, and the paper's printed effective
+ * hit-rate example (Section 4 toy example; Appendix A.1 "effective cache-hit
+ * rate" equation).  The paper prints no worked numeric lookup, so full-lookup
+ * values are pinned by those hand cases, not by paper numbers.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_NCS = 0, ORACLE_NSC = 1 };
+
+typedef struct {
+    int32_t C, S, H, K;
+    int32_t act_dtype;       /* ORACLE_F32 / ORACLE_BF16: element type of the activation  */
+    int32_t layout;          /* ORACLE_NCS: x[(r*C+c)*S+s];  ORACLE_NSC: x[(r*S+s)*C+c]   */
+    int32_t round_operands;  /* 1: bf16 cache arithmetic: W1, W2, and the FC operands p, h
+                                are rounded to bf16 (nearest even) before each product;
+                                0: nothing is rounded ("ideal" arithmetic)                 */
+    float   threshold;       /* tau: hit iff confidence > tau (strict)                    */
+} oracle_desc_t;
+
+typedef struct {
+    const float *W1;  /* [H,C] */
+    const float *b1;  /* [H]   */
+    const float *W2;  /* [K,H] */
+    const float *b2;  /* [K]   */
+    const float *ws;  /* [C+K], pooled features first, class probabilities after */
+    float bs;
+} oracle_weights_t;
+
+/* ---- number formats ------------------------------------------------------------ */
+
+/* bf16 bit pattern -> real value (exact): bf16 is the top 16 bits of an IEEE fp32. */
+static double bf16_bits_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* Nearest bf16 value (8 significant bits, ties to even) of a double, as a double.
+ * Works on the value itself, not on fp32 bit patterns. */
+double oracle_round_bf16(double x)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(x, &e);                /* x = m * 2^e with 0.5 <= |m| < 1 */
+    int q = e - 8;                     /* quantum exponent for 8 significant bits */
+    if (q < -133) q = -133;            /* bf16 subnormal spacing */
+    double r = ldexp(nearbyint(ldexp(x, -q)), q);   /* nearbyint: ties to even */
+    if (fabs(r) > 3.3895313892515355e38) r = (x > 0) ? INFINITY : -INFINITY;
+    return r;
+}
+
+static double act_at(const oracle_desc_t *d, const void *act, int64_t r, int c, int s)
+{
+    int64_t idx = (d->layout == ORACLE_NCS)
+        ? ((r * d->C + c) * (int64_t)d->S + s)
+        : ((r * d->S + s) * (int64_t)d->C + c);
+    if (d->act_dtype == ORACLE_BF16) return bf16_bits_to_double(((const uint16_t *)act)[idx]);
+    return (double)((const float *)act)[idx];
+}
+
+/* ---- the steps ------------------------------------------------------------------- */
+
+/* Global average pool: p[c] = (sum over s of x[c,s]) / S, rounded once to fp32.
+ * (Pooling predictor, Table "model architectures": Input -Pool-> Hidden; here the
+ * pool extent is the whole spatial / token axis.) */
+void oracle_pool_row(const oracle_desc_t *d, const void *act, int64_t r, float *p)
+{
+    for (int c = 0; c < d->C; ++c) {
+        double sum = 0.0;
+        for (int s = 0; s < d->S; ++s) sum += act_at(d, act, r, c, s);
+        p[c] = (float)(sum / (double)d->S);
+    }
+}
+
+/* Operand preparation for the bf16 cache arithmetic: a vector rounded element by
+ * element to the nearest bf16 value (or copied unchanged when nothing is rounded).
+ * Rounding a weight once here or once per product gives the same number. */
+static void operand_f32(const oracle_desc_t *d, const float *src, int64_t n, double *dst)
+{
+    for (int64_t i = 0; i < n; ++i)
+        dst[i] = d->round_operands ? oracle_round_bf16((double)src[i]) : (double)src[i];
+}
+static void operand_f64(const oracle_desc_t *d, const double *src, int64_t n, double *dst)
+{
+    for (int64_t i = 0; i < n; ++i)
+        dst[i] = d->round_operands ? oracle_round_bf16(src[i]) : src[i];
+}
+
+/* Hidden layer of the predictor: h[j] = max(0, b1[j] + sum_c W1[j,c] p[c]).
+ * (Table "model architectures": -FC-> Hidden Layer, ReLU activation.)
+ * W1op / pop are the operands after preparation. */
+static void fc1_relu(const oracle_desc_t *d, const double *W1op, const float *b1,
+                     const double *pop, double *h)
+{
+    for (int j = 0; j < d->H; ++j) {
+        double acc = 0.0;
+        for (int c = 0; c < d->C; ++c) acc += W1op[(int64_t)j * d->C + c] * pop[c];
+        acc += (double)b1[j];
+        h[j] = acc > 0.0 ? acc : 0.0;
+    }
+}
+
+/* Output layer of the predictor: z[k] = b2[k] + sum_j W2[k,j] h[j].
+ * (Table "model architectures": Hidden Layer -FC-> Output.) */
+static void fc2(const oracle_desc_t *d, const double *W2op, const float *b2,
+                const double *hop, double *z)
+{
+    for (int k = 0; k < d->K; ++k) {
+        double acc = 0.0;
+        for (int j = 0; j < d->H; ++j) acc += W2op[(int64_t)k * d->H + j] * hop[j];
+        z[k] = acc + (double)b2[k];
+    }
+}
+
+/* Step-level entry points for the pin tests: one row through one FC layer. */
+int oracle_fc1_relu(const oracle_desc_t *d, const oracle_weights_t *w, const float *p, double *h)
+{
+    int64_t nw = (int64_t)d->H * d->C;
+    double *W1op = (double *)malloc(sizeof(double) * (size_t)nw);
+    double *pop  = (double *)malloc(sizeof(double) * (size_t)d->C);
+    if (!W1op || !pop) { free(W1op); free(pop); return -1; }
+    operand_f32(d, w->W1, nw, W1op);
+    operand_f32(d, p, d->C, pop);
+    fc1_relu(d, W1op, w->b1, pop, h);
+    free(W1op); free(pop);
+    return 0;
+}
+int oracle_fc2(const oracle_desc_t *d, const oracle_weights_t *w, const double *h, double *z)
+{
+    int64_t nw = (int64_t)d->K * d->H;
+    double *W2op = (double *)malloc(sizeof(double) * (size_t)nw);
+    double *hop  = (double *)malloc(sizeof(double) * (size_t)d->H);
+    if (!W2op || !hop) { free(W2op); free(hop); return -1; }
+    operand_f32(d, w->W2, nw, W2op);
+    operand_f64(d, h, d->H, hop);
+    fc2(d, W2op, w->b2, hop, z);
+    free(W2op); free(hop);
+    return 0;
+}
+
+/* Class distribution and predicted class (Section 3, "Training Learned Caches":
+ * the prediction is a distribution of class probabilities whose argmax is the
+ * predicted class).  The class is decided on the fp32-rounded logits, the
+ * precision the library reports them in; ties go to the lowest index. */
+int32_t oracle_softmax_argmax(int K, const double *z, double *q)
+{
+    double m = z[0];
+    for (int k = 1; k < K; ++k) if (z[k] > m) m = z[k];
+    double denom = 0.0;
+    for (int k = 0; k < K; ++k) denom += exp(z[k] - m);
+    for (int k = 0; k < K; ++k) q[k] = exp(z[k] - m) / denom;
+    int32_t best = 0;
+    float bestv = (float)z[0];
+    for (int k = 1; k < K; ++k) {
+        float v = (float)z[k];
+        if (v > bestv) { bestv = v; best = k; }
+    }
+    return best;
+}
+
+/* Selector: u = bs + sum_c ws[c] p[c] + sum_k ws[C+k] q[k]; confidence = logistic(u).
+ * (Section 3, "Selector Network Design" and T = sigma_i(PR); the input here is the
+ * pooled features followed by the class distribution.) */
+double oracle_selector_score(const oracle_desc_t *d, const oracle_weights_t *w,
+                             const float *p, const double *q)
+{
+    double u = (double)w->bs;
+    for (int c = 0; c < d->C; ++c) u += (double)w->ws[c] * (double)p[c];
+    for (int k = 0; k < d->K; ++k) u += (double)w->ws[d->C + k] * q[k];
+    return u;
+}
+
+static double logistic(double u) { return 1.0 / (1.0 + exp(-u)); }
+
+/* One lookup per active row i (source row r = row_index ? row_index[i] : i).
+ * Any output pointer may be NULL.  Returns 0, or -1 on allocation failure. */
+int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void *act,
+                  const int32_t *row_index, int32_t n,
+                  float *pooled /*[n,C]*/, float *logits /*[n,K]*/, double *probs /*[n,K]*/,
+                  int32_t *pred_class /*[n]*/, double *score /*[n]*/, float *confidence /*[n]*/,
+                  uint8_t *hit /*[n]*/)
+{
+    int64_t n1 = (int64_t)d->H * d->C, n2 = (int64_t)d->K * d->H;
+    float  *p    = (float *)malloc(sizeof(float) * (size_t)d->C);
+    double *pop  = (double *)malloc(sizeof(double) * (size_t)d->C);
+    double *h    = (double *)malloc(sizeof(double) * (size_t)d->H);
+    double *hop  = (double *)malloc(sizeof(double) * (size_t)d->H);
+    double *z    = (double *)malloc(sizeof(double) * (size_t)d->K);
+    double *q    = (double *)malloc(sizeof(double) * (size_t)d->K);
+    double *W1op = (double *)malloc(sizeof(double) * (size_t)n1);
+    double *W2op = (double *)malloc(sizeof(double) * (size_t)n2);
+    int rc = -1;
+    if (!p || !pop || !h || !hop || !z || !q || !W1op || !W2op) goto done;
+    operand_f32(d, w->W1, n1, W1op);
+    operand_f32(d, w->W2, n2, W2op);
+    for (int32_t i = 0; i < n; ++i) {
+        int64_t r = row_index ? (int64_t)row_index[i] : (int64_t)i;
+        oracle_pool_row(d, act, r, p);
+        operand_f32(d, p, d->C, pop);
+        fc1_relu(d, W1op, w->b1, pop, h);
+        operand_f64(d, h, d->H, hop);
+        fc2(d, W2op, w->b2, hop, z);
+        int32_t cls = oracle_softmax_argmax(d->K, z, q);
+        double u = oracle_selector_score(d, w, p, q);
+        float conf = (float)logistic(u);
+        if (pooled) memcpy(pooled + (int64_t)i * d->C, p, sizeof(float) * (size_t)d->C);
+        if (logits) for (int k = 0; k < d->K; ++k) logits[(int64_t)i * d->K + k] = (float)z[k];
+        if (probs)  memcpy(probs + (int64_t)i * d->K, q, sizeof(double) * (size_t)d->K);
+        if (pred_class) pred_class[i] = cls;
+        if (score) score[i] = u;
+        if (confidence) confidence[i] = conf;
+        if (hit) hit[i] = (conf > d->threshold) ? 1 : 0;   /* decided in fp32, strictly above */
+    }
+    rc = 0;
+done:
+    free(p); free(pop); free(h); free(hop); free(z); free(q); free(W1op); free(W2op);
+    return rc;
+}
+
+/* Misses continue: the ids whose hit flag is 0, in their incoming order.
+ * ids_in == NULL means the identity list 0..n-1.  Returns the miss count. */
+int32_t oracle_compact_misses(const uint8_t *hit, const int32_t *ids_in, int32_t n, int32_t *ids_out)
+{
+    int32_t m = 0;
+    for (int32_t i = 0; i < n; ++i)
+        if (!hit[i]) ids_out[m++] = ids_in ? ids_in[i] : i;
+    return m;
+}

@@ -1,0 +1,140 @@
+"""Shapes of the five synthetic workloads.
+
+Each workload is a stack of learned caches, one per hooked block of a base
+network (the paper places a lookup after every layer, Section 2 "caching
+proposal" figure and Section 3).  Only shapes, dtypes and the knobs of the
+input distribution live here.
+"""
+from __future__ import annotations
+
+import json
+import os
+from dataclasses import dataclass, field, replace
+from typing import List, Optional
+
+
+@dataclass(frozen=True)
+class LayerSpec:
+    C: int            # channels / hidden width of the activation
+    S: int            # reduced length: H*W of the feature map, or tokens
+    H: int            # predictor hidden width
+    K: int            # classes
+    layout: str       # "ncs" ([n,C,S], S contiguous) or "nsc" ([n,S,C], C contiguous)
+    dtype: str        # "f32" or "bf16"
+    threshold: float  # selector threshold tau
+    gamma: float      # class-mean scale: element mean = gamma * d[label][c]
+    relu: bool        # ReLU-Gaussian (CNN block outputs) or plain Gaussian (tokens)
+    bs: float = 0.0   # selector bias (calibrated per layer for the hit-rate ramps)
+    target_hit: Optional[float] = None  # per-layer hit-rate target the bias was fitted to
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+    @property
+    def row_bytes(self) -> int:
+        return self.C * self.S * self.elem_bytes
+
+
+@dataclass(frozen=True)
+class WorkloadSpec:
+    name: str
+    batch: int
+    zipf_s: float
+    seed: int
+    layers: List[LayerSpec] = field(default_factory=list)
+    # "gather": every layer holds the full batch, lookups index it by request id.
+    # "dense":  layer l holds only the rows still active, in miss-list order.
+    storage: str = "gather"
+
+    def scaled(self, batch: int, name: Optional[str] = None) -> "WorkloadSpec":
+        """Same stack at another batch size (parity-test sized variants)."""
+        return replace(self, batch=batch, name=name or f"{self.name}@{batch}")
+
+
+def _resnet_stack(blocks, H, K, dtype, tau, gammas):
+    layers = []
+    idx = 0
+    total = sum(b for _, _, b in blocks)
+    for (C, hw, reps) in blocks:
+        for _ in range(reps):
+            g = gammas[0] + (gammas[1] - gammas[0]) * (idx / max(1, total - 1))
+            layers.append(LayerSpec(C=C, S=hw * hw, H=H, K=K, layout="ncs", dtype=dtype,
+                                    threshold=tau, gamma=g, relu=True))
+            idx += 1
+    return layers
+
+
+def _linear_ramp(first, last, n):
+    return [first + (last - first) * i / max(1, n - 1) for i in range(n)]
+
+
+def _build():
+    w = {}
+    # cfg 0: one tiny fp32 cache, [64,64,8,8], 64 -> 128 -> 10, selector 74 -> 1, tau 0.5
+    w["tiny"] = WorkloadSpec(
+        name="tiny", batch=64, zipf_s=1.1, seed=0,
+        layers=[LayerSpec(C=64, S=64, H=128, K=10, layout="ncs", dtype="f32",
+                          threshold=0.5, gamma=6.0, relu=True)])
+    # cfg 1: ResNet-18-shaped, 8 basic-block outputs, fp32, batch 256, tau 0.6
+    w["resnet18"] = WorkloadSpec(
+        name="resnet18", batch=256, zipf_s=1.1, seed=0,
+        layers=_resnet_stack([(64, 56, 2), (128, 28, 2), (256, 14, 2), (512, 7, 2)],
+                             H=256, K=1000, dtype="f32", tau=0.6, gammas=(8.0, 24.0)))
+    # cfg 2: ResNet-50-shaped, 16 bottleneck outputs (3+4+6+3), bf16, batch 512
+    w["resnet50"] = WorkloadSpec(
+        name="resnet50", batch=512, zipf_s=1.1, seed=0,
+        layers=_resnet_stack([(256, 56, 3), (512, 28, 4), (1024, 14, 6), (2048, 7, 3)],
+                             H=512, K=1000, dtype="bf16", tau=0.6, gammas=(8.0, 32.0)))
+    # cfg 3: BERT-base-shaped, 12 encoder outputs [1024,128,768], token-mean pool
+    w["bert_base"] = WorkloadSpec(
+        name="bert_base", batch=1024, zipf_s=1.2, seed=0,
+        layers=[LayerSpec(C=768, S=128, H=256, K=20, layout="nsc", dtype="bf16",
+                          threshold=0.5, gamma=4.0 + 1.0 * i, relu=False)
+                for i in range(12)])
+    # cfg 4: ResNet-152-shaped, 50 block outputs (3+8+36+3), bf16, streaming batch 4096,
+    # each layer stored only for the rows still active
+    w["resnet152"] = WorkloadSpec(
+        name="resnet152", batch=4096, zipf_s=1.1, seed=0, storage="dense",
+        layers=_resnet_stack([(256, 56, 3), (512, 28, 8), (1024, 14, 36), (2048, 7, 3)],
+                             H=512, K=1000, dtype="bf16", tau=0.6, gammas=(8.0, 32.0)))
+    return w
+
+
+# Per-layer hit-rate targets (fraction of the rows looked up at that layer).
+# resnet50: linear ramp whose product of miss rates leaves ~40 % after layer 16.
+# resnet152: 2 % -> 70 % linear ramp over the 50 layers.
+HIT_TARGETS = {
+    "resnet50": [0.0065 * (i + 1) for i in range(16)],
+    "resnet152": _linear_ramp(0.02, 0.70, 50),
+}
+
+_CAL_PATH = os.path.join(os.path.dirname(__file__), "calibration.json")
+
+
+def _apply_calibration(w):
+    """Fold the fitted selector biases (a stored text fixture) into the specs."""
+    if not os.path.exists(_CAL_PATH):
+        return w
+    with open(_CAL_PATH) as f:
+        cal = json.load(f)
+    for name, entry in cal.items():
+        if name not in w:
+            continue
+        bs = entry["bs"]
+        tgt = entry.get("target_hit", [None] * len(bs))
+        spec = w[name]
+        if len(bs) != len(spec.layers):
+            continue
+        layers = [replace(l, bs=float(b), target_hit=t) for l, b, t in zip(spec.layers, bs, tgt)]
+        w[name] = replace(spec, layers=layers)
+    return w
+
+
+WORKLOADS = _apply_calibration(_build())
+
+
+def get_workload(name: str) -> WorkloadSpec:
+    if name not in WORKLOADS:
+        raise KeyError(f"unknown workload {name!r}; have {sorted(WORKLOADS)}")
+    return WORKLOADS[name]
