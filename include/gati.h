@@ -1,0 +1,152 @@
+/*
+ * gati.h - C ABI of the learned-cache lookup library for AMD MI355X (gfx950).
+ *
+ * A learned cache sits after one hidden layer of a base DNN.  Its interface is that of
+ * any cache: given the hidden layer's output it returns a prediction when it hits
+ * (paper, Section 2.3 "Towards Learned Caches").  It is made of two small networks run in
+ * sequence (Section 3, "Learned Cache Design"): a predictor that maps the hidden
+ * layer output to a class distribution, and a selector that decides whether that
+ * prediction may be served as a hit.  Hits leave the batch; misses continue on the
+ * base model and meet the next layer's cache (Section 1; Appendix A.1, effective
+ * cache-hit rate).
+ *
+ * This library is that lookup for a whole batch of in-flight requests at one layer,
+ * plus the stable compaction of the misses that feeds the next layer:
+ *
+ *   pooled[c]  = mean over the spatial / token axis of the activation   (pooling predictor,
+ *                                                                         Section 3 table of
+ *                                                                         predictor architectures)
+ *   hidden     = relu(W1 pooled + b1)                                    (hidden layer, ReLU)
+ *   logits     = W2 hidden + b2,  prob = softmax(logits),  class = argmax
+ *   score      = ws . [pooled ; prob] + bs,  confidence = 1/(1+exp(-score))   (selector)
+ *   hit        = confidence > threshold
+ *   misses     = ids whose hit flag is 0, in their incoming order
+ *
+ * All pointers named "device" are HIP device pointers valid on the device that was
+ * current when the cache was created; "host" pointers are ordinary host memory.  The
+ * library never frees or keeps caller buffers.  Every call that takes a stream only
+ * enqueues work on it and returns; nothing synchronises the device and nothing is
+ * allocated after gati_cache_create.  No function throws or aborts: errors come back
+ * as a gati_status_t and leave the outputs untouched (argument errors are detected on
+ * the host before anything is launched).
+ */
+#ifndef GATI_H
+#define GATI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gati_cache gati_cache_t; /* opaque, owned by the library */
+
+typedef enum {
+    GATI_OK = 0,
+    GATI_ERR_INVALID_ARG = 1, /* null required pointer, bad enum, non-positive size, n_max out of range */
+    GATI_ERR_UNSUPPORTED = 2, /* a valid request this build has no kernel for */
+    GATI_ERR_OOM = 3,         /* device or host allocation failed in gati_cache_create */
+    GATI_ERR_DEVICE = 4       /* a HIP call failed (launch, copy, wrong device) */
+} gati_status_t;
+
+typedef enum { GATI_F32 = 0, GATI_BF16 = 1 } gati_dtype_t;
+
+typedef enum {
+    GATI_LAYOUT_NCS = 0, /* [n, C, S]: channel-major, S = H*W contiguous (NCHW feature maps) */
+    GATI_LAYOUT_NSC = 1  /* [n, S, C]: token-major / channels-last, C contiguous              */
+} gati_layout_t;
+
+/* Shape of one learned cache (Section 3: predictor Input -> Hidden(h) -> Output, selector).
+ *   C, S       activation channels and reduced length (pool extent = all of S)
+ *   H, K       predictor hidden width and number of classes
+ *   act_dtype  element type of the activation tensor.  It also fixes the arithmetic of the
+ *              two FC layers: GATI_F32 -> fp32 operands; GATI_BF16 -> W1, W2 and the FC
+ *              operands (pooled, hidden) rounded to bf16 (nearest even), fp32 accumulation.
+ *              Pooling, biases, softmax, selector and sigmoid are fp32 in both.
+ *   threshold  tau; a row is a hit iff confidence > tau (strictly)
+ *   max_rows   largest n_max any later call may pass (sizes the library's workspace)   */
+typedef struct {
+    int32_t C, S, H, K;
+    gati_dtype_t act_dtype;
+    gati_layout_t layout;
+    float threshold;
+    int32_t max_rows;
+} gati_cache_desc_t;
+
+/* Weights, HOST pointers, fp32, row-major [out, in].  Copied (and converted) by
+ * gati_cache_create; the caller may free them as soon as it returns. */
+typedef struct {
+    const float *W1; /* [H, C]                                                    */
+    const float *b1; /* [H]                                                       */
+    const float *W2; /* [K, H]                                                    */
+    const float *b2; /* [K]                                                       */
+    const float *ws; /* [C + K]: weights of the pooled features first, then of the class probabilities */
+    float bs;        /* selector bias                                             */
+} gati_cache_weights_t;
+
+/* Build a cache on the current HIP device: uploads the weights in the library's private
+ * layout and allocates a workspace for max_rows rows.  *out is set only on GATI_OK. */
+gati_status_t gati_cache_create(const gati_cache_desc_t *desc, const gati_cache_weights_t *weights,
+                                gati_cache_t **out);
+
+/* Free everything the cache owns.  The caller must have finished (synchronised) all work
+ * that uses it.  NULL is GATI_OK. */
+gati_status_t gati_cache_destroy(gati_cache_t *cache);
+
+/* Replace the selector bias and threshold of an existing cache (host scalars; takes effect
+ * for calls issued afterwards). */
+gati_status_t gati_cache_set_selector(gati_cache_t *cache, float bs, float threshold);
+
+/* One lookup per active row (Section 3: prediction operation, then selection operation).
+ *
+ *   act         device; the layer's activation tensor.  Row r starts at act + r*C*S*elem.
+ *   row_index   device [n] int32 or NULL.  Active row i reads activation row row_index[i]
+ *               (NULL: row i).  Entries must address rows that exist in act.
+ *   n_max       host upper bound on the number of active rows, 0 <= n_max <= max_rows.
+ *   n_dev       device int32 scalar holding the true count, or NULL for n = n_max.  The
+ *               kernels use min(max(*n_dev,0), n_max), so a previous layer's miss count can
+ *               feed this call without a host round trip.
+ *   pred_class  device [n_max] int32   argmax of the logits, lowest index on ties
+ *   confidence  device [n_max] float   selector confidence
+ *   hit         device [n_max] uint8   1 = hit, 0 = miss
+ *   logits      device [n_max, K] float or NULL to skip writing them
+ *   stream      hipStream_t (NULL = the default stream)
+ *
+ * Outputs at indices >= n are left untouched.  n = 0 is GATI_OK and writes nothing.
+ * Calls on the same cache must not overlap in time (they share its workspace). */
+gati_status_t gati_cache_lookup(gati_cache_t *cache, const void *act, const int32_t *row_index,
+                                int32_t n_max, const int32_t *n_dev,
+                                int32_t *pred_class, float *confidence, uint8_t *hit,
+                                float *logits, void *stream);
+
+/* The pooling step alone (pooling predictor, Section 3): pooled[i, c] = mean over s of the
+ * activation of active row i, fp32.  pooled is device [n_max, C].  Same row_index / n_max /
+ * n_dev meaning as gati_cache_lookup. */
+gati_status_t gati_cache_pool(gati_cache_t *cache, const void *act, const int32_t *row_index,
+                              int32_t n_max, const int32_t *n_dev, float *pooled, void *stream);
+
+/* Misses continue to the next layer (Section 1: a request that misses keeps running on
+ * the base model): ids_out = [ids_in[i] for i < n if hit[i] == 0], order preserved;
+ * *n_miss_dev = number written.
+ *
+ *   hit         device [n_max] uint8 (any non-zero byte is a hit)
+ *   ids_in      device [n_max] int32 or NULL for the identity list 0..n-1
+ *   n_max,n_dev as above (cache->max_rows bounds n_max when cache is not NULL; cache may be
+ *               NULL, the call needs no cache state)
+ *   ids_out     device [n_max] int32; must not alias ids_in
+ *   n_miss_dev  device int32 scalar; may alias n_dev (it is read before it is written) */
+gati_status_t gati_compact_misses(gati_cache_t *cache, const uint8_t *hit, const int32_t *ids_in,
+                                  int32_t n_max, const int32_t *n_dev,
+                                  int32_t *ids_out, int32_t *n_miss_dev, void *stream);
+
+/* Static, never-NULL description of a status code. */
+const char *gati_status_string(gati_status_t status);
+
+/* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_seg",
+ * "nsc_vec", "generic"); static string, for reports and profiles. */
+const char *gati_cache_pool_variant(const gati_cache_t *cache);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GATI_H */

@@ -4,8 +4,8 @@
  * A plain, single-threaded, fp64 statement of what one lookup computes, written
  * from the paper's description of a learned cache (Section 3, "Learned Cache
  * Design"): a prediction operation followed by a selection operation, with hits
- * leaving the batch and misses continuing to the next layer (Section 1, "cache
- * misses continue inference on the base model").  It shares no code, header,
+ * leaving the batch and misses continuing to the next layer (Section 1: a request
+ * that misses keeps running on the base model).  It shares no code, header,
  * table or constant with the HIP library and must never be linked into or called
  * from the product path; only the tests, the smoke check and the benchmark's
  * cpu_baseline leg use it.

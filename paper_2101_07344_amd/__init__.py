@@ -1,0 +1,14 @@
+"""Learned-cache lookup for AMD MI355X: thin Python binding over the C-ABI HIP library.
+
+Everything the lookup computes runs in the hand-written kernels of ``libgati.so``;
+this package only marshals arguments (PyTorch supplies device memory and streams).
+There is no CPU or PyTorch fallback: if the library is missing, loading fails.
+"""
+from .binding import (  # noqa: F401
+    GATI_OK, GATI_ERR_INVALID_ARG, GATI_ERR_UNSUPPORTED, GATI_ERR_OOM, GATI_ERR_DEVICE,
+    GATI_F32, GATI_BF16, GATI_LAYOUT_NCS, GATI_LAYOUT_NSC,
+    GatiError, CacheDesc, CacheWeights, Cache, CacheStack,
+    load_library, library_path, exported_symbols,
+    gati_cache_create, gati_cache_destroy, gati_cache_lookup, gati_cache_pool,
+    gati_compact_misses, gati_cache_set_selector, gati_status_string, gati_cache_pool_variant,
+)

@@ -1,0 +1,234 @@
+"""ctypes binding with the same names as include/gati.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgati.so")
+
+GATI_OK, GATI_ERR_INVALID_ARG, GATI_ERR_UNSUPPORTED, GATI_ERR_OOM, GATI_ERR_DEVICE = range(5)
+GATI_F32, GATI_BF16 = 0, 1
+GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
+
+# every extern "C" symbol include/gati.h declares
+exported_symbols = (
+    "gati_cache_create", "gati_cache_destroy", "gati_cache_set_selector", "gati_cache_lookup",
+    "gati_cache_pool", "gati_compact_misses", "gati_status_string", "gati_cache_pool_variant",
+)
+
+
+class CacheDesc(C.Structure):
+    _fields_ = [("C", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("K", C.c_int32),
+                ("act_dtype", C.c_int), ("layout", C.c_int), ("threshold", C.c_float),
+                ("max_rows", C.c_int32)]
+
+
+class CacheWeights(C.Structure):
+    _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+                ("ws", C.c_void_p), ("bs", C.c_float)]
+
+
+class GatiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {gati_status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libgati.so (built in-tree by ``python -m paper_2101_07344_amd.build``).
+    Raises if it is not there: there is no other implementation to fall back to."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2101_07344_amd.build`")
+    try:
+        import torch  # noqa: F401  (brings in the HIP runtime the library shares with the caller)
+    except Exception:
+        pass
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32 = C.c_void_p, C.c_int32
+    lib.gati_cache_create.restype = C.c_int
+    lib.gati_cache_create.argtypes = [C.POINTER(CacheDesc), C.POINTER(CacheWeights), C.POINTER(vp)]
+    lib.gati_cache_destroy.restype = C.c_int
+    lib.gati_cache_destroy.argtypes = [vp]
+    lib.gati_cache_set_selector.restype = C.c_int
+    lib.gati_cache_set_selector.argtypes = [vp, C.c_float, C.c_float]
+    lib.gati_cache_lookup.restype = C.c_int
+    lib.gati_cache_lookup.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.gati_cache_pool.restype = C.c_int
+    lib.gati_cache_pool.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+    lib.gati_compact_misses.restype = C.c_int
+    lib.gati_compact_misses.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.gati_status_string.restype = C.c_char_p
+    lib.gati_status_string.argtypes = [C.c_int]
+    lib.gati_cache_pool_variant.restype = C.c_char_p
+    lib.gati_cache_pool_variant.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def _dptr(t) -> Optional[int]:
+    """Device (or host) address of a tensor / raw int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        if not torch.cuda.is_available():
+            return None
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+# ---- the C entry points, one to one ---------------------------------------------------
+
+def gati_status_string(status: int) -> str:
+    return load_library().gati_status_string(int(status)).decode()
+
+
+def gati_cache_create(desc: CacheDesc, weights: CacheWeights):
+    """Returns (status, handle)."""
+    h = C.c_void_p()
+    st = load_library().gati_cache_create(C.byref(desc) if desc is not None else None,
+                                          C.byref(weights) if weights is not None else None,
+                                          C.byref(h))
+    return st, h.value
+
+
+def gati_cache_destroy(handle) -> int:
+    return load_library().gati_cache_destroy(handle)
+
+
+def gati_cache_set_selector(handle, bs: float, threshold: float) -> int:
+    return load_library().gati_cache_set_selector(handle, bs, threshold)
+
+
+def gati_cache_lookup(handle, act, row_index, n_max: int, n_dev, pred_class, confidence, hit,
+                      logits=None, stream=None) -> int:
+    return load_library().gati_cache_lookup(handle, _dptr(act), _dptr(row_index), int(n_max), _dptr(n_dev),
+                                            _dptr(pred_class), _dptr(confidence), _dptr(hit),
+                                            _dptr(logits), _stream(stream))
+
+
+def gati_cache_pool(handle, act, row_index, n_max: int, n_dev, pooled, stream=None) -> int:
+    return load_library().gati_cache_pool(handle, _dptr(act), _dptr(row_index), int(n_max), _dptr(n_dev),
+                                          _dptr(pooled), _stream(stream))
+
+
+def gati_compact_misses(handle, hit, ids_in, n_max: int, n_dev, ids_out, n_miss_dev, stream=None) -> int:
+    return load_library().gati_compact_misses(handle, _dptr(hit), _dptr(ids_in), int(n_max), _dptr(n_dev),
+                                              _dptr(ids_out), _dptr(n_miss_dev), _stream(stream))
+
+
+def gati_cache_pool_variant(handle) -> str:
+    return load_library().gati_cache_pool_variant(handle).decode()
+
+
+# ---- small conveniences over the handles (still marshalling only) -----------------------
+
+def _check(st: int, where: str):
+    if st != GATI_OK:
+        raise GatiError(st, where)
+
+
+class Cache:
+    """Owns one gati_cache_t."""
+
+    def __init__(self, C_: int, S: int, H: int, K: int, dtype: str, layout: str, threshold: float,
+                 max_rows: int, weights: dict):
+        self.C, self.S, self.H, self.K = C_, S, H, K
+        self.dtype, self.layout, self.max_rows = dtype, layout, max_rows
+        desc = CacheDesc(C_, S, H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
+                         GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows)
+        keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in ("W1", "b1", "W2", "b2", "ws")}
+        assert keep["W1"].shape == (H, C_) and keep["W2"].shape == (K, H) and keep["ws"].shape == (C_ + K,)
+        w = CacheWeights(*(keep[k].ctypes.data for k in ("W1", "b1", "W2", "b2", "ws")), float(weights["bs"]))
+        st, self.handle = gati_cache_create(desc, w)
+        _check(st, "gati_cache_create")
+
+    def lookup(self, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits=None, stream=None):
+        _check(gati_cache_lookup(self.handle, act, row_index, n_max, n_dev, pred_class, confidence, hit,
+                                 logits, stream), "gati_cache_lookup")
+
+    def pool(self, act, row_index, n_max, n_dev, pooled, stream=None):
+        _check(gati_cache_pool(self.handle, act, row_index, n_max, n_dev, pooled, stream), "gati_cache_pool")
+
+    def compact(self, hit, ids_in, n_max, n_dev, ids_out, n_miss_dev, stream=None):
+        _check(gati_compact_misses(self.handle, hit, ids_in, n_max, n_dev, ids_out, n_miss_dev, stream),
+               "gati_compact_misses")
+
+    def set_selector(self, bs: float, threshold: float):
+        _check(gati_cache_set_selector(self.handle, bs, threshold), "gati_cache_set_selector")
+
+    @property
+    def pool_variant(self) -> str:
+        return gati_cache_pool_variant(self.handle)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            gati_cache_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class CacheStack:
+    """A stack of caches with the device buffers one pass needs, chained on the device:
+    layer l+1 looks up only layer l's misses, and the miss count never visits the host."""
+
+    def __init__(self, caches: Sequence[Cache], batch: int, storage: str = "gather", keep_logits: bool = False):
+        import torch
+        self.caches, self.batch, self.storage = list(caches), batch, storage
+        dev = "cuda"
+        L = len(self.caches)
+        self.ids = [torch.empty(batch, dtype=torch.int32, device=dev) for _ in range(L + 1)]
+        self.ids[0].copy_(torch.arange(batch, dtype=torch.int32))
+        self.counts = torch.zeros(L + 1, dtype=torch.int32, device=dev)
+        self.counts[0] = batch
+        self.pred_class = [torch.zeros(batch, dtype=torch.int32, device=dev) for _ in range(L)]
+        self.confidence = [torch.zeros(batch, dtype=torch.float32, device=dev) for _ in range(L)]
+        self.hit = [torch.zeros(batch, dtype=torch.uint8, device=dev) for _ in range(L)]
+        self.logits = ([torch.zeros(batch, c.K, dtype=torch.float32, device=dev) for c in self.caches]
+                       if keep_logits else [None] * L)
+
+    def run(self, acts: Sequence, stream=None):
+        """Enqueue one pass over all layers.  acts[l] is the layer's activation tensor:
+        the full batch indexed by request id ("gather"), or the rows still active in
+        miss-list order ("dense")."""
+        es = self.counts.element_size()
+        cbase = self.counts.data_ptr()
+        for l, cache in enumerate(self.caches):
+            n_dev = cbase + l * es
+            row_index = self.ids[l] if self.storage == "gather" else None
+            cache.lookup(acts[l], row_index, self.batch, n_dev, self.pred_class[l], self.confidence[l],
+                         self.hit[l], self.logits[l], stream)
+            cache.compact(self.hit[l], self.ids[l], self.batch, n_dev, self.ids[l + 1],
+                          cbase + (l + 1) * es, stream)
+
+    def close(self):
+        for c in self.caches:
+            c.close()

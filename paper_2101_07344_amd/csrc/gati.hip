@@ -1,0 +1,398 @@
+// C ABI of the learned-cache lookup library (see include/gati.h): argument checking, the
+// cache object (device weights in the kernels' private layout + a per-cache workspace), and
+// the choice of kernel variant per shape.  gfx950 only.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/gati.h"
+#include "common.h"
+#include "compact_kernels.h"
+#include "head_kernels.h"
+#include "pool_kernels.h"
+
+using namespace gati;
+
+namespace {
+
+enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3 };
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+inline uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int env_int(const char* name, int dflt) {
+    const char* v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    const int x = std::atoi(v);
+    return x > 0 ? x : dflt;
+}
+
+}  // namespace
+
+struct gati_cache {
+    gati_cache_desc_t desc;
+    int device = 0;
+    int num_cu = 256;
+    bool bf16 = false;
+    int elem = 4;
+    // padded sizes: Cp % 64 == 0 (FC1 reduction), Hp % 32 == 0, Kp % 32 == 0, rows_pad % 32 == 0
+    int Cp = 0, Hp = 0, Kp = 0, rows_pad = 0;
+    // device weights
+    void* W1 = nullptr;       // [Hp, Cp] bf16 | f32
+    void* W2 = nullptr;       // [Kp, Hp] bf16 | f32
+    float* b1 = nullptr;      // [Hp]
+    float* b2 = nullptr;      // [Kp]
+    float* ws_pool = nullptr; // [Cp]
+    float* ws_prob = nullptr; // [Kp]
+    float bs = 0.f, tau = 0.5f;
+    // workspace
+    float* p = nullptr;       // [rows_pad, Cp]
+    void* h = nullptr;        // [rows_pad, Hp]
+    float* u_pool = nullptr;  // [rows_pad]
+    // pooling plan
+    PoolVariant variant = POOL_GENERIC;
+    int vpc = 0;              // ncs_wave: 16-byte vectors per channel
+    int wave_cfg = 0;         // ncs_wave: index into the (LPC, CPI) table
+    int gt = 0, tiles_per_row = 0, tpc_log2 = 0;  // ncs_seg
+    unsigned magic_S = 0;
+    int gw = 64, cvb_per_row = 0;                 // nsc_vec
+    int pool_blocks_per_cu = 8;
+    // head plan
+    int fc2_tpw = 1, fc2_waves = 1;
+};
+
+namespace {
+
+void free_all(gati_cache* c) {
+    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->h, c->u_pool};
+    for (void* q : ptrs)
+        if (q) (void)hipFree(q);
+}
+
+gati_status_t upload(void** dst, const void* src, size_t bytes) {
+    hipError_t e = hipMalloc(dst, bytes);
+    if (e != hipSuccess) { *dst = nullptr; (void)hipGetLastError(); return GATI_ERR_OOM; }
+    e = src ? hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) : hipMemset(*dst, 0, bytes);
+    if (e != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+    return GATI_OK;
+}
+
+// Pick the pooling kernel for a shape.  Everything the vector kernels assume is checked here.
+void plan_pool(gati_cache* c) {
+    const int C = c->desc.C, S = c->desc.S;
+    const int V = 16 / c->elem;
+    c->variant = POOL_GENERIC;
+    if (c->desc.layout == GATI_LAYOUT_NSC) {
+        if (C % V == 0) {
+            const int CV = C / V;
+            // widest lane group that wastes the fewest lanes on the last channel block
+            int best = 64, best_waste = round_up(CV, 64) - CV;
+            for (int gw : {32, 16}) {
+                const int waste = round_up(CV, gw) - CV;
+                if (waste < best_waste) { best = gw; best_waste = waste; }
+            }
+            c->gw = best;
+            c->cvb_per_row = (CV + best - 1) / best;
+            c->variant = POOL_NSC_VEC;
+        }
+        return;
+    }
+    // [n,C,S]
+    if ((long)S * c->elem % 16 == 0 && S / V >= 32) {
+        c->vpc = S / V;
+        const int lpc = (c->vpc + 63) / 64;
+        // (LPC, CPI) table index: 0:(1,8) 1:(2,4) 2:(4,2) 3:(8,2) 4:(16,1)
+        c->wave_cfg = lpc <= 1 ? 0 : lpc <= 2 ? 1 : lpc <= 4 ? 2 : lpc <= 8 ? 3 : 4;
+        c->variant = POOL_NCS_WAVE;
+        return;
+    }
+    if (S >= V && ((long)C * S) % V == 0 && (long)S < 65536) {
+        // smallest channel count whose byte size is a multiple of 16
+        int g0 = 1;
+        while (((long)g0 * S) % V != 0) ++g0;
+        const int max_mult = (int)((1024L * V) / ((long)g0 * S));   // tile <= 1024 vectors
+        if (max_mult >= 1) {
+            int mult = max_mult;
+            for (int m = max_mult; m >= (max_mult + 1) / 2; --m)
+                if (C % (m * g0) == 0) { mult = m; break; }
+            int gt = mult * g0;
+            if (gt > 256) gt = 256 / g0 * g0;
+            if (gt >= g0 && gt > 0) {
+                if (gt > C) gt = round_up(C, g0);   // C*S % V == 0 makes C a multiple of g0
+                c->gt = gt;
+                c->tiles_per_row = (C + gt - 1) / gt;
+                int tpc_log2 = 0;
+                const int partials = (S + V - 1) / V + 1;
+                while ((gt << (tpc_log2 + 1)) <= 256 && (2 << tpc_log2) <= partials / 2 && tpc_log2 < 6)
+                    ++tpc_log2;
+                c->tpc_log2 = tpc_log2;
+                c->magic_S = (unsigned)(((1ull << 32) / (unsigned long long)S) + 1ull);
+                c->variant = POOL_NCS_SEG;
+            }
+        }
+    }
+}
+
+void plan_head(gati_cache* c) {
+    const int tiles = c->Kp / 32;
+    if (tiles <= 1) { c->fc2_waves = 1; c->fc2_tpw = 1; }
+    else if (tiles <= 2) { c->fc2_waves = 2; c->fc2_tpw = 1; }
+    else if (tiles <= 4) { c->fc2_waves = 4; c->fc2_tpw = 1; }
+    else if (tiles <= 8) { c->fc2_waves = 4; c->fc2_tpw = 2; }
+    else if (tiles <= 16) { c->fc2_waves = 4; c->fc2_tpw = 4; }
+    else { c->fc2_waves = 4; c->fc2_tpw = 8; }
+}
+
+template <typename Tag>
+hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, hipStream_t st) {
+    const int max_blocks = c->num_cu * c->pool_blocks_per_cu;
+    switch (variant) {
+    case POOL_NCS_WAVE: {
+        static const int cpi_of[] = {8, 4, 2, 2, 1};
+        const long groups = (long)a.n_max * ((a.C + cpi_of[c->wave_cfg] - 1) / cpi_of[c->wave_cfg]);
+        const int blocks = (int)std::min<long>((groups + 3) / 4, max_blocks);
+        switch (c->wave_cfg) {
+        case 0: pool_ncs_wave_kernel<Tag, 1, 8><<<blocks, 256, 0, st>>>(a, c->vpc); break;
+        case 1: pool_ncs_wave_kernel<Tag, 2, 4><<<blocks, 256, 0, st>>>(a, c->vpc); break;
+        case 2: pool_ncs_wave_kernel<Tag, 4, 2><<<blocks, 256, 0, st>>>(a, c->vpc); break;
+        case 3: pool_ncs_wave_kernel<Tag, 8, 2><<<blocks, 256, 0, st>>>(a, c->vpc); break;
+        default: pool_ncs_wave_kernel<Tag, 16, 1><<<blocks, 256, 0, st>>>(a, c->vpc); break;
+        }
+        break;
+    }
+    case POOL_NCS_SEG: {
+        const long tiles = (long)a.n_max * c->tiles_per_row;
+        const int blocks = (int)std::min<long>(tiles, max_blocks);
+        pool_ncs_seg_kernel<Tag><<<blocks, 256, 0, st>>>(a, c->gt, c->tiles_per_row, c->tpc_log2, c->magic_S);
+        break;
+    }
+    case POOL_NSC_VEC: {
+        const long items = (long)a.n_max * c->cvb_per_row;
+        const int blocks = (int)std::min<long>(items, max_blocks);
+        if (c->gw == 64) pool_nsc_kernel<Tag, 64><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
+        else if (c->gw == 32) pool_nsc_kernel<Tag, 32><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
+        else pool_nsc_kernel<Tag, 16><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
+        break;
+    }
+    default: {
+        const long items = (long)a.n_max * a.C;
+        const int blocks = (int)std::min<long>((items + 255) / 256, max_blocks);
+        pool_generic_kernel<Tag><<<blocks, 256, 0, st>>>(a, c->desc.layout == GATI_LAYOUT_NSC ? 1 : 0);
+        break;
+    }
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_pool(const gati_cache* c, const void* act, const int32_t* row_index, int n_max,
+                       const int32_t* n_dev, float* out, int out_stride, hipStream_t st) {
+    PoolArgs a;
+    a.act = act; a.row_index = row_index; a.n_dev = n_dev; a.n_max = n_max;
+    a.C = c->desc.C; a.S = c->desc.S; a.inv_S = 1.0f / (float)c->desc.S;
+    a.out = out; a.out_stride = out_stride;
+    // the vector kernels need 16-byte aligned rows; rows are multiples of 16 bytes by plan
+    PoolVariant v = c->variant;
+    if (v != POOL_GENERIC && (reinterpret_cast<uintptr_t>(act) & 15u) != 0) v = POOL_GENERIC;
+    return c->bf16 ? launch_pool_t<BF16Tag>(c, a, v, st) : launch_pool_t<F32Tag>(c, a, v, st);
+}
+
+template <bool BF16>
+hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, int32_t* pred_class,
+                         float* confidence, uint8_t* hit, float* logits, hipStream_t st) {
+    const int row_tiles = (n_max + 31) / 32;
+    Fc1Args f1;
+    f1.p = c->p; f1.W1 = c->W1; f1.b1 = c->b1; f1.h = c->h; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool;
+    f1.Cp = c->Cp; f1.Hp = c->Hp; f1.n_max = n_max; f1.n_dev = n_dev;
+    fc1_kernel<BF16><<<dim3(c->Hp / 32 + 1, row_tiles), 64, 0, st>>>(f1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    Fc2Args f2;
+    f2.h = c->h; f2.W2 = c->W2; f2.b2 = c->b2; f2.ws_prob = c->ws_prob; f2.u_pool = c->u_pool;
+    f2.bs = c->bs; f2.tau = c->tau; f2.Hp = c->Hp; f2.K = c->desc.K; f2.Kp = c->Kp;
+    f2.n_max = n_max; f2.n_dev = n_dev;
+    f2.pred_class = pred_class; f2.confidence = confidence; f2.hit = hit; f2.logits = logits;
+    const int threads = c->fc2_waves * 64;
+    switch (c->fc2_tpw) {
+    case 1: fc2_head_kernel<BF16, 1><<<row_tiles, threads, 0, st>>>(f2); break;
+    case 2: fc2_head_kernel<BF16, 2><<<row_tiles, threads, 0, st>>>(f2); break;
+    case 4: fc2_head_kernel<BF16, 4><<<row_tiles, threads, 0, st>>>(f2); break;
+    default: fc2_head_kernel<BF16, 8><<<row_tiles, threads, 0, st>>>(f2); break;
+    }
+    return hipGetLastError();
+}
+
+bool on_cache_device(const gati_cache* c) {
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == c->device;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gati_status_string(gati_status_t s) {
+    switch (s) {
+    case GATI_OK: return "ok";
+    case GATI_ERR_INVALID_ARG: return "invalid argument";
+    case GATI_ERR_UNSUPPORTED: return "unsupported configuration";
+    case GATI_ERR_OOM: return "out of memory";
+    case GATI_ERR_DEVICE: return "HIP device error";
+    }
+    return "unknown status";
+}
+
+gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_weights_t* w,
+                                gati_cache_t** out) {
+    if (!desc || !w || !out) return GATI_ERR_INVALID_ARG;
+    if (desc->C <= 0 || desc->S <= 0 || desc->H <= 0 || desc->K <= 0 || desc->max_rows <= 0)
+        return GATI_ERR_INVALID_ARG;
+    if (desc->act_dtype != GATI_F32 && desc->act_dtype != GATI_BF16) return GATI_ERR_INVALID_ARG;
+    if (desc->layout != GATI_LAYOUT_NCS && desc->layout != GATI_LAYOUT_NSC) return GATI_ERR_INVALID_ARG;
+    if (!w->W1 || !w->b1 || !w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
+    if (!(desc->threshold == desc->threshold)) return GATI_ERR_INVALID_ARG;   // NaN
+    // sizes whose padded products still fit the kernels' 32-bit tile arithmetic
+    if (desc->C > (1 << 20) || desc->H > (1 << 20) || desc->K > (1 << 20) || desc->max_rows > (1 << 22))
+        return GATI_ERR_UNSUPPORTED;
+    if ((long)desc->max_rows * desc->C >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
+
+    gati_cache* c = new (std::nothrow) gati_cache();
+    if (!c) return GATI_ERR_OOM;
+    c->desc = *desc;
+    c->bf16 = desc->act_dtype == GATI_BF16;
+    c->elem = c->bf16 ? 2 : 4;
+    c->bs = w->bs;
+    c->tau = desc->threshold;
+    c->Cp = round_up(desc->C, 64);
+    c->Hp = round_up(desc->H, 32);
+    c->Kp = round_up(desc->K, 32);
+    c->rows_pad = round_up(desc->max_rows, 32);
+
+    if (hipGetDevice(&c->device) != hipSuccess) { (void)hipGetLastError(); delete c; return GATI_ERR_DEVICE; }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
+        c->num_cu = cus;
+    else
+        (void)hipGetLastError();
+    c->pool_blocks_per_cu = env_int("GATI_POOL_BLOCKS_PER_CU", 8);
+
+    plan_pool(c);
+    plan_head(c);
+
+    const int C = desc->C, H = desc->H, K = desc->K;
+    gati_status_t st = GATI_OK;
+    try {
+        // weights in the kernels' layout: zero padded, reduction axis contiguous
+        const size_t n1 = (size_t)c->Hp * c->Cp, n2 = (size_t)c->Kp * c->Hp;
+        if (c->bf16) {
+            std::vector<uint16_t> t1(n1, 0), t2(n2, 0);
+            for (int j = 0; j < H; ++j)
+                for (int k = 0; k < C; ++k) t1[(size_t)j * c->Cp + k] = f32_to_bf16_rne(w->W1[(size_t)j * C + k]);
+            for (int j = 0; j < K; ++j)
+                for (int k = 0; k < H; ++k) t2[(size_t)j * c->Hp + k] = f32_to_bf16_rne(w->W2[(size_t)j * H + k]);
+            st = upload(&c->W1, t1.data(), n1 * 2);
+            if (st == GATI_OK) st = upload(&c->W2, t2.data(), n2 * 2);
+        } else {
+            std::vector<float> t1(n1, 0.f), t2(n2, 0.f);
+            for (int j = 0; j < H; ++j) std::memcpy(&t1[(size_t)j * c->Cp], &w->W1[(size_t)j * C], (size_t)C * 4);
+            for (int j = 0; j < K; ++j) std::memcpy(&t2[(size_t)j * c->Hp], &w->W2[(size_t)j * H], (size_t)H * 4);
+            st = upload(&c->W1, t1.data(), n1 * 4);
+            if (st == GATI_OK) st = upload(&c->W2, t2.data(), n2 * 4);
+        }
+        std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
+        std::memcpy(b1.data(), w->b1, (size_t)H * 4);
+        std::memcpy(b2.data(), w->b2, (size_t)K * 4);
+        std::memcpy(wp.data(), w->ws, (size_t)C * 4);
+        std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
+        if (st == GATI_OK) st = upload((void**)&c->b1, b1.data(), b1.size() * 4);
+        if (st == GATI_OK) st = upload((void**)&c->b2, b2.data(), b2.size() * 4);
+        if (st == GATI_OK) st = upload((void**)&c->ws_pool, wp.data(), wp.size() * 4);
+        if (st == GATI_OK) st = upload((void**)&c->ws_prob, wq.data(), wq.size() * 4);
+    } catch (const std::bad_alloc&) {
+        st = GATI_ERR_OOM;
+    }
+    // workspace, zeroed once: the padding columns of p are never written and must read as 0
+    if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
+    if (st == GATI_OK) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
+    if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
+    if (st == GATI_OK && hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); st = GATI_ERR_DEVICE; }
+    if (st != GATI_OK) { free_all(c); delete c; return st; }
+    *out = c;
+    return GATI_OK;
+}
+
+gati_status_t gati_cache_destroy(gati_cache_t* c) {
+    if (!c) return GATI_OK;
+    free_all(c);
+    delete c;
+    return GATI_OK;
+}
+
+gati_status_t gati_cache_set_selector(gati_cache_t* c, float bs, float threshold) {
+    if (!c || !(bs == bs) || !(threshold == threshold)) return GATI_ERR_INVALID_ARG;
+    c->bs = bs;
+    c->tau = threshold;
+    c->desc.threshold = threshold;
+    return GATI_OK;
+}
+
+gati_status_t gati_cache_pool(gati_cache_t* c, const void* act, const int32_t* row_index, int32_t n_max,
+                              const int32_t* n_dev, float* pooled, void* stream) {
+    if (!c || n_max < 0 || n_max > c->desc.max_rows) return GATI_ERR_INVALID_ARG;
+    if (n_max == 0) return GATI_OK;
+    if (!act || !pooled) return GATI_ERR_INVALID_ARG;
+    if (!on_cache_device(c)) return GATI_ERR_DEVICE;
+    const hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, pooled, c->desc.C, (hipStream_t)stream);
+    return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+
+gati_status_t gati_cache_lookup(gati_cache_t* c, const void* act, const int32_t* row_index, int32_t n_max,
+                                const int32_t* n_dev, int32_t* pred_class, float* confidence, uint8_t* hit,
+                                float* logits, void* stream) {
+    if (!c || n_max < 0 || n_max > c->desc.max_rows) return GATI_ERR_INVALID_ARG;
+    if (n_max == 0) return GATI_OK;
+    if (!act || !pred_class || !confidence || !hit) return GATI_ERR_INVALID_ARG;
+    if (!on_cache_device(c)) return GATI_ERR_DEVICE;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, c->p, c->Cp, st);
+    if (e != hipSuccess) return GATI_ERR_DEVICE;
+    e = c->bf16 ? launch_head_t<true>(c, n_max, n_dev, pred_class, confidence, hit, logits, st)
+                : launch_head_t<false>(c, n_max, n_dev, pred_class, confidence, hit, logits, st);
+    return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+
+gati_status_t gati_compact_misses(gati_cache_t* c, const uint8_t* hit, const int32_t* ids_in, int32_t n_max,
+                                  const int32_t* n_dev, int32_t* ids_out, int32_t* n_miss_dev, void* stream) {
+    if (n_max < 0 || !n_miss_dev) return GATI_ERR_INVALID_ARG;
+    if (c && n_max > c->desc.max_rows) return GATI_ERR_INVALID_ARG;
+    if (n_max > 0 && (!hit || !ids_out)) return GATI_ERR_INVALID_ARG;
+    if (ids_in && ids_in == ids_out) return GATI_ERR_INVALID_ARG;
+    if (c && !on_cache_device(c)) return GATI_ERR_DEVICE;
+    CompactArgs a;
+    a.hit = hit; a.ids_in = ids_in; a.n_dev = n_dev; a.n_max = n_max; a.ids_out = ids_out; a.n_miss = n_miss_dev;
+    compact_misses_kernel<<<1, 1024, 0, (hipStream_t)stream>>>(a);
+    return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+
+const char* gati_cache_pool_variant(const gati_cache_t* c) {
+    if (!c) return "none";
+    switch (c->variant) {
+    case POOL_NCS_WAVE: return "ncs_wave";
+    case POOL_NCS_SEG: return "ncs_seg";
+    case POOL_NSC_VEC: return "nsc_vec";
+    default: return "generic";
+    }
+}
+
+}  // extern "C"

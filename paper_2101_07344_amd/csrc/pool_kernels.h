@@ -1,0 +1,256 @@
+// Global average pooling of the activation tensor: pooled[i,c] = mean_s x[row(i),c,s].
+// (Pooling predictor of the paper's Section 3 table of predictor architectures, with the
+// pool extent taken over the whole spatial / token axis.)
+//
+// This is the stage that moves nearly all the bytes of a lookup, so every variant is a
+// pure streaming read: 16-byte loads, many independent loads in flight per lane, fp32
+// accumulation in a fixed order (no float atomics: results are bit-reproducible).
+// All kernels are persistent: a fixed grid strides over the work, and the true row count
+// is read on the device.
+#pragma once
+
+#include "common.h"
+
+namespace gati {
+
+struct PoolArgs {
+    const void* act;           // activation tensor, device
+    const int32_t* row_index;  // [n] source rows, or null for the identity
+    const int32_t* n_dev;      // device row count, or null
+    int n_max;
+    int C, S;
+    float inv_S;
+    float* out;                // [n, out_stride] fp32
+    int out_stride;
+};
+
+// ---------------------------------------------------------------------------------------
+// [n,C,S], S*elem a multiple of 16 bytes: one wave sums one channel at a time, CPI channels
+// per iteration so that LPC*CPI 16-byte loads per lane are in flight before the first add.
+// vpc = 16-byte vectors per channel; a channel needs ceil(vpc/64) loads per lane, taken in
+// chunks of LPC.
+// ---------------------------------------------------------------------------------------
+template <typename Tag, int LPC, int CPI>
+__global__ __launch_bounds__(256) void pool_ncs_wave_kernel(PoolArgs a, int vpc) {
+    const int n = active_rows(a.n_dev, a.n_max);
+    const int lane = threadIdx.x & 63;
+    const int waves_per_block = blockDim.x >> 6;
+    const unsigned wave = blockIdx.x * waves_per_block + (threadIdx.x >> 6);
+    const unsigned nwaves = gridDim.x * waves_per_block;
+    const unsigned gpr = (unsigned)(a.C + CPI - 1) / CPI;  // channel groups per row
+    const unsigned total = (unsigned)n * gpr;
+
+    for (unsigned g = wave; g < total; g += nwaves) {
+        const unsigned i = g / gpr;
+        const int c0 = (int)(g - i * gpr) * CPI;
+        const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+        const u32x4_t* base =
+            reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) +
+                                             ((r * a.C + c0) * (long)a.S) * Tag::kBytes);
+        float s[CPI];
+#pragma unroll
+        for (int q = 0; q < CPI; ++q) s[q] = 0.f;
+
+        for (int b = 0; b < vpc; b += 64 * LPC) {
+            // Every load is unconditional and in bounds: slots past the end of the channel
+            // (or past the last channel) re-read the last valid vector and are zeroed after.
+            u32x4_t v[CPI][LPC];
+#pragma unroll
+            for (int q = 0; q < CPI; ++q) {
+                const int qc = min(q, a.C - 1 - c0);
+#pragma unroll
+                for (int u = 0; u < LPC; ++u) {
+                    const int idx = b + u * 64 + lane;
+                    v[q][u] = base[(long)qc * vpc + min(idx, vpc - 1)];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < CPI; ++q) {
+#pragma unroll
+                for (int u = 0; u < LPC; ++u)
+                    v[q][u] = keep_or_zero(v[q][u], (b + u * 64 + lane < vpc) && (c0 + q < a.C));
+            }
+#pragma unroll
+            for (int q = 0; q < CPI; ++q) {
+#pragma unroll
+                for (int u = 0; u < LPC; ++u) s[q] += vec_sum<Tag>(v[q][u]);
+            }
+        }
+        float mine = 0.f;
+#pragma unroll
+        for (int q = 0; q < CPI; ++q) {
+            const float t = wave_sum(s[q]);
+            mine = (lane == q) ? t : mine;
+        }
+        if (lane < CPI && c0 + lane < a.C)
+            a.out[(long)i * a.out_stride + c0 + lane] = mine * a.inv_S;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// [n,C,S] with short or 16-byte-unaligned channels (S = 49, 196, 64, ...).  A sample's
+// channels are one flat, contiguous stream, so a workgroup takes a tile of `gt` whole
+// channels whose byte size is a multiple of 16 and reads it with fully coalesced 16-byte
+// loads.  A vector may straddle one channel boundary (S >= elements per vector): each lane
+// splits its vector into the part that belongs to the channel of its first element (a) and
+// the part that belongs to the next channel (b), parks both in LDS, and after a barrier
+// `tpc` lanes per channel add up that channel's partial sums in a fixed order.
+// Requirements (checked on the host): gt*S % kVec == 0, C*S % kVec == 0, gt*S/kVec <= 1024,
+// S >= kVec, gt << tpc_log2 <= 256.
+// ---------------------------------------------------------------------------------------
+template <typename Tag>
+__global__ __launch_bounds__(256) void pool_ncs_seg_kernel(PoolArgs a, int gt, int tiles_per_row,
+                                                           int tpc_log2, unsigned magic_S) {
+    constexpr int V = Tag::kVec;
+    constexpr int kMaxVec = 1024;
+    __shared__ float sA[2][kMaxVec];
+    __shared__ float sB[2][kMaxVec];
+
+    const int n = active_rows(a.n_dev, a.n_max);
+    const unsigned total = (unsigned)n * (unsigned)tiles_per_row;
+    const int tid = threadIdx.x;
+    const int tpc = 1 << tpc_log2;
+    const int lc = tid >> tpc_log2;   // tile-local channel this lane helps to finish
+    const int sub = tid & (tpc - 1);
+    int buf = 0;
+
+    for (unsigned w = blockIdx.x; w < total; w += gridDim.x, buf ^= 1) {
+        const unsigned i = w / (unsigned)tiles_per_row;
+        const int t = (int)(w - i * (unsigned)tiles_per_row);
+        const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+        const int c_first = t * gt;
+        const int nch = min(gt, a.C - c_first);
+        const int tile_vecs = (nch * a.S) / V;
+        const u32x4_t* base =
+            reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) +
+                                             ((r * a.C + c_first) * (long)a.S) * Tag::kBytes);
+        u32x4_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)   // unconditional, clamped into the tile; extras are ignored below
+            v[j] = base[min(tid + 256 * j, tile_vecs - 1)];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = tid + 256 * j;
+            if (idx < tile_vecs) {
+                const unsigned o = (unsigned)idx * V;            // first element, tile-local
+                const unsigned ch = __umulhi(o, magic_S);        // o / S
+                const int cnt = a.S - (int)(o - ch * (unsigned)a.S);  // elements left in that channel
+                float e[V];
+                vec_unpack<Tag>(v[j], e);
+                float pa = 0.f, pb = 0.f;
+#pragma unroll
+                for (int k = 0; k < V; ++k) {
+                    pa += (k < cnt) ? e[k] : 0.f;
+                    pb += (k < cnt) ? 0.f : e[k];
+                }
+                sA[buf][idx] = pa;
+                sB[buf][idx] = pb;
+            }
+        }
+        __syncthreads();
+        float acc = 0.f;
+        const bool live = lc < nch;
+        if (live) {
+            const int start = lc * a.S;
+            const int lo = (start + V - 1) / V;
+            const int hi = (start + a.S + V - 1) / V;
+            for (int k = lo + sub; k < hi; k += tpc) acc += sA[buf][k];
+            if (sub == 0 && (start % V) != 0) acc += sB[buf][lo - 1];
+        }
+        for (int m = tpc >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+        if (live && sub == 0) a.out[(long)i * a.out_stride + c_first + lc] = acc * a.inv_S;
+        // The other LDS buffer is written next; the barrier of the next iteration orders
+        // this iteration's reads against the writes two iterations ahead.
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// [n,S,C] (tokens / channels-last): a lane owns one 16-byte vector of channels and walks
+// down the token axis.  A workgroup covers GW channel-vectors and splits the tokens over
+// its 256/GW lane groups; the groups' partial sums meet in LDS and are added in group order.
+// Requires C % kVec == 0.
+// ---------------------------------------------------------------------------------------
+template <typename Tag, int GW>
+__global__ __launch_bounds__(256) void pool_nsc_kernel(PoolArgs a, int cvb_per_row) {
+    constexpr int V = Tag::kVec;
+    constexpr int NG = 256 / GW;   // token slices
+    constexpr int UN = 8;          // loads in flight per lane
+    __shared__ float red[NG][V * GW];
+
+    const int n = active_rows(a.n_dev, a.n_max);
+    const unsigned total = (unsigned)n * (unsigned)cvb_per_row;
+    const int gl = threadIdx.x % GW;
+    const int grp = threadIdx.x / GW;
+    const int CV = a.C / V;
+
+    for (unsigned w = blockIdx.x; w < total; w += gridDim.x) {
+        const unsigned i = w / (unsigned)cvb_per_row;
+        const int cb = (int)(w - i * (unsigned)cvb_per_row);
+        const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+        const int cv = cb * GW + gl;
+        const bool ok = cv < CV;
+        const u32x4_t* base =
+            reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) +
+                                             (r * a.S * (long)a.C) * Tag::kBytes) + min(cv, CV - 1);
+        float acc[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) acc[k] = 0.f;
+        for (int s0 = grp; s0 < a.S; s0 += NG * UN) {
+            u32x4_t v[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u)   // unconditional, clamped to the last token
+                v[u] = base[(long)min(s0 + u * NG, a.S - 1) * CV];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                v[u] = keep_or_zero(v[u], ok && (s0 + u * NG < a.S));
+                float e[V];
+                vec_unpack<Tag>(v[u], e);
+#pragma unroll
+                for (int k = 0; k < V; ++k) acc[k] += e[k];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < V; ++k) red[grp][k * GW + gl] = acc[k];
+        __syncthreads();
+        for (int e = threadIdx.x; e < V * GW; e += 256) {
+            const int k = e / GW, l = e - k * GW;
+            const int c = (cb * GW + l) * V + k;
+            if (c < a.C) {
+                float s = 0.f;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) s += red[g][e];
+                a.out[(long)i * a.out_stride + c] = s * a.inv_S;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Any shape, layout and alignment: one lane per (row, channel), scalar loads.  Slow; only
+// for shapes the vector kernels cannot take.
+// ---------------------------------------------------------------------------------------
+template <typename Tag>
+__global__ __launch_bounds__(256) void pool_generic_kernel(PoolArgs a, int nsc_layout) {
+    const int n = active_rows(a.n_dev, a.n_max);
+    const long total = (long)n * a.C;
+    const long stride = (long)gridDim.x * blockDim.x;
+    for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const long i = idx / a.C;
+        const int c = (int)(idx - i * a.C);
+        const long r = a.row_index ? (long)a.row_index[i] : i;
+        const long first = nsc_layout ? (r * a.S * (long)a.C + c) : ((r * a.C + c) * (long)a.S);
+        const long step = nsc_layout ? a.C : 1;
+        float s = 0.f;
+        if (Tag::kBytes == 4) {
+            const float* x = static_cast<const float*>(a.act);
+            for (int k = 0; k < a.S; ++k) s += x[first + k * step];
+        } else {
+            const uint16_t* x = static_cast<const uint16_t*>(a.act);
+            for (int k = 0; k < a.S; ++k) s += __uint_as_float((uint32_t)x[first + k * step] << 16);
+        }
+        a.out[i * a.out_stride + c] = s * a.inv_S;
+    }
+}
+
+}  // namespace gati

@@ -1,0 +1,60 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+declared symbol, and rejects bad arguments before touching the device."""
+import re
+import os
+
+import numpy as np
+import pytest
+
+import paper_2101_07344_amd as g
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_is_built_and_exports_the_declared_symbols():
+    lib = g.load_library()
+    with open(os.path.join(ROOT, "include", "gati.h")) as f:
+        header = f.read()
+    declared = set(re.findall(r"\b(gati_[a-z_]+)\s*\(", header))
+    assert declared == set(g.exported_symbols)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    seen = {g.gati_status_string(s) for s in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert g.gati_status_string(99)
+
+
+def _weights(C, H, K):
+    arrs = [np.zeros((H, C), np.float32), np.zeros(H, np.float32), np.zeros((K, H), np.float32),
+            np.zeros(K, np.float32), np.zeros(C + K, np.float32)]
+    return arrs, g.CacheWeights(*(a.ctypes.data for a in arrs), 0.0)
+
+
+def test_create_rejects_bad_arguments_on_the_host():
+    keep, w = _weights(4, 4, 4)
+    good = dict(C=4, S=4, H=4, K=4, act_dtype=g.GATI_F32, layout=g.GATI_LAYOUT_NCS, threshold=0.5, max_rows=8)
+    assert g.gati_cache_create(None, w)[0] == g.GATI_ERR_INVALID_ARG
+    assert g.gati_cache_create(g.CacheDesc(**good), None)[0] == g.GATI_ERR_INVALID_ARG
+    for key, bad in (("C", 0), ("S", -1), ("H", 0), ("K", 0), ("max_rows", 0), ("act_dtype", 7), ("layout", 3),
+                     ("threshold", float("nan"))):
+        st, h = g.gati_cache_create(g.CacheDesc(**{**good, key: bad}), w)
+        assert st == g.GATI_ERR_INVALID_ARG and h is None, key
+    w_null = g.CacheWeights(keep[0].ctypes.data, None, keep[2].ctypes.data, keep[3].ctypes.data,
+                            keep[4].ctypes.data, 0.0)
+    assert g.gati_cache_create(g.CacheDesc(**good), w_null)[0] == g.GATI_ERR_INVALID_ARG
+    assert g.gati_cache_create(g.CacheDesc(**{**good, "C": 1 << 21}), w)[0] == g.GATI_ERR_UNSUPPORTED
+
+
+def test_calls_reject_null_handles_and_bad_counts_on_the_host():
+    assert g.gati_cache_lookup(None, 16, None, 4, None, 16, 16, 16, None, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_cache_pool(None, 16, None, 4, None, 16, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_cache_set_selector(None, 0.0, 0.5) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_cache_destroy(None) == g.GATI_OK
+    assert g.gati_compact_misses(None, 16, None, -1, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_compact_misses(None, 16, None, 4, None, 16, None, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_compact_misses(None, None, None, 4, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_compact_misses(None, 16, 32, 4, None, 32, 16, stream=0) == g.GATI_ERR_INVALID_ARG   # in/out alias
+    assert g.gati_cache_pool_variant(None) == "none"

@@ -1,0 +1,111 @@
+"""GPU parity of the pooling kernels against the oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2101_07344_amd as g
+from oracle import CacheDef
+
+pytestmark = pytest.mark.gpu
+
+# fp32 accumulation of S values of size O(1) in a fixed tree: a few ulp of the mean
+POOL_ATOL = 2e-6
+
+
+def _weights(C, H, K):
+    return {"W1": np.zeros((H, C), np.float32), "b1": np.zeros(H, np.float32),
+            "W2": np.zeros((K, H), np.float32), "b2": np.zeros(K, np.float32),
+            "ws": np.zeros(C + K, np.float32), "bs": 0.0}
+
+
+def _act(n, C, S, dtype, layout, seed):
+    gen = torch.Generator().manual_seed(seed)
+    shape = (n, C, S) if layout == "ncs" else (n, S, C)
+    x = torch.randn(shape, generator=gen).clamp_(min=-0.5) + 0.25
+    x = x.bfloat16() if dtype == "bf16" else x
+    host = x.view(torch.int16).numpy().view(np.uint16) if dtype == "bf16" else x.numpy()
+    return x, host
+
+
+SHAPES = [
+    # (C, S, dtype, layout, expected variant)  -- every shape of the five workloads
+    (64, 64, "f32", "ncs", "ncs_seg"),
+    (64, 3136, "f32", "ncs", "ncs_wave"), (128, 784, "f32", "ncs", "ncs_wave"),
+    (256, 196, "f32", "ncs", "ncs_wave"), (512, 49, "f32", "ncs", "ncs_seg"),
+    (256, 3136, "bf16", "ncs", "ncs_wave"), (512, 784, "bf16", "ncs", "ncs_wave"),
+    (1024, 196, "bf16", "ncs", "ncs_seg"), (2048, 49, "bf16", "ncs", "ncs_seg"),
+    (768, 128, "bf16", "nsc", "nsc_vec"), (768, 128, "f32", "nsc", "nsc_vec"),
+    # ragged / odd shapes
+    (24, 50, "bf16", "ncs", "ncs_seg"), (40, 49, "bf16", "ncs", "ncs_seg"), (12, 9, "f32", "ncs", "ncs_seg"),
+    (7, 33, "f32", "ncs", "generic"), (5, 3, "bf16", "ncs", "generic"), (3, 5000, "bf16", "ncs", "ncs_wave"),
+    (10, 1024 + 8, "bf16", "ncs", "ncs_wave"), (100, 37, "bf16", "nsc", "generic"),
+    (104, 37, "bf16", "nsc", "nsc_vec"), (2056, 5, "f32", "nsc", "nsc_vec"), (8, 1, "bf16", "nsc", "nsc_vec"),
+    (130, 64, "f32", "ncs", "ncs_seg"),
+]
+
+
+@pytest.mark.parametrize("C,S,dtype,layout,variant", SHAPES)
+def test_pool_matches_oracle(C, S, dtype, layout, variant):
+    n = 11
+    x, host = _act(n, C, S, dtype, layout, seed=C * 7 + S)
+    cache = g.Cache(C, S, 4, 4, dtype, layout, 0.5, 64, _weights(C, 4, 4))
+    assert cache.pool_variant == variant
+    xd = x.cuda()
+    want = oracle.pool(CacheDef(C=C, S=S, H=4, K=4, dtype=dtype, layout=layout), host)
+    # all rows, identity
+    out = torch.full((n, C), -7.0, device="cuda")
+    cache.pool(xd, None, n, None, out)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(out.cpu().numpy() - want)) <= POOL_ATOL
+    # gather list + device-side count smaller than n_max: rows past the count stay untouched
+    idx = torch.tensor([7, 0, 10, 3, 3, 9, 1, 2], dtype=torch.int32, device="cuda")
+    n_dev = torch.tensor([5], dtype=torch.int32, device="cuda")
+    out = torch.full((8, C), -7.0, device="cuda")
+    cache.pool(xd, idx, 8, n_dev, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.max(np.abs(got[:5] - want[[7, 0, 10, 3, 3]])) <= POOL_ATOL
+    assert np.all(got[5:] == -7.0)
+    # run twice: bit-identical (fixed reduction order)
+    out2 = torch.full((8, C), -7.0, device="cuda")
+    cache.pool(xd, idx, 8, n_dev, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    cache.close()
+
+
+def test_pool_unaligned_base_takes_the_generic_path():
+    C, S, n = 16, 64, 4
+    x, host = _act(n + 1, C, S, "bf16", "ncs", seed=5)
+    flat = torch.zeros((n + 1) * C * S + 1, dtype=torch.bfloat16, device="cuda")
+    flat[1:] = x.reshape(-1).cuda()            # element offset 1 -> base is 2-byte aligned only
+    view = flat[1:1 + n * C * S]
+    assert view.data_ptr() % 16 != 0
+    cache = g.Cache(C, S, 4, 4, "bf16", "ncs", 0.5, 8, _weights(C, 4, 4))
+    out = torch.zeros((n, C), device="cuda")
+    cache.pool(view, None, n, None, out)
+    torch.cuda.synchronize()
+    want = oracle.pool(CacheDef(C=C, S=S, H=4, K=4, dtype="bf16"), host[:n])
+    assert np.max(np.abs(out.cpu().numpy() - want)) <= 1e-5
+    cache.close()
+
+
+def test_pool_zero_rows_and_bounds():
+    cache = g.Cache(8, 16, 4, 4, "f32", "ncs", 0.5, 4, _weights(8, 4, 4))
+    x = torch.ones(4, 8, 16, device="cuda")
+    out = torch.full((4, 8), 3.0, device="cuda")
+    assert g.gati_cache_pool(cache.handle, x, None, 0, None, out) == g.GATI_OK
+    n_dev = torch.tensor([0], dtype=torch.int32, device="cuda")
+    assert g.gati_cache_pool(cache.handle, x, None, 4, n_dev, out) == g.GATI_OK
+    n_dev2 = torch.tensor([-3], dtype=torch.int32, device="cuda")
+    assert g.gati_cache_pool(cache.handle, x, None, 4, n_dev2, out) == g.GATI_OK
+    torch.cuda.synchronize()
+    assert torch.all(out == 3.0)
+    assert g.gati_cache_pool(cache.handle, x, None, 5, None, out) == g.GATI_ERR_INVALID_ARG   # > max_rows
+    assert g.gati_cache_pool(cache.handle, None, None, 4, None, out) == g.GATI_ERR_INVALID_ARG
+    n_big = torch.tensor([1000], dtype=torch.int32, device="cuda")      # clamped to n_max
+    assert g.gati_cache_pool(cache.handle, x, None, 2, n_big, out) == g.GATI_OK
+    torch.cuda.synchronize()
+    assert torch.all(out[:2] == 1.0) and torch.all(out[2:] == 3.0)
+    cache.close()
