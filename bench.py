@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the learned-cache lookup hot path on one MI355X.
+
+A step is one pass of a whole cache stack over one batch of synthetic activations
+already resident in HBM: for every layer, pool -> predictor FCs -> softmax/argmax ->
+selector -> hit flags -> miss compaction, the next layer looking up only the misses,
+with the miss counts chained on the device (no host round trip inside a step).
+
+Prints ONE JSON line: lookups/s for the whole job, the pooling kernel's achieved HBM
+bandwidth against the MI355X peak (measured with HIP events around every pooling
+launch), and the CPU oracle timed on the host cores on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
+
+# HBM traffic of the dominant pooling kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (summaries under profiles/); keyed by workload.  None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_workload(name, torch, g, W):
+    """Caches, device buffers and activations of one workload.  For "gather" storage every
+    layer holds the full batch; for "dense" storage a first untimed pass generates each layer
+    only for the rows still active and stores them in miss-list order."""
+    spec = W.get_workload(name)
+    K = spec.layers[0].K
+    labels = W.zipf_labels(spec.batch, K, spec.zipf_s, spec.seed)
+    weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
+    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w)
+              for L, w in zip(spec.layers, weights)]
+    stack = g.CacheStack(caches, spec.batch, storage=spec.storage)
+    acts = []
+    if spec.storage == "gather":
+        req = np.arange(spec.batch)
+        for l in range(len(spec.layers)):
+            acts.append(W.activation_bulk(spec, l, labels, req, device="cuda"))
+    else:
+        # pass 1 (untimed): layer by layer, reading the miss list back to generate the next layer
+        es = stack.counts.element_size()
+        base = stack.counts.data_ptr()
+        active = np.arange(spec.batch)
+        for l, cache in enumerate(caches):
+            a = W.activation_bulk(spec, l, labels, active if len(active) else np.arange(1), device="cuda")
+            acts.append(a)
+            cache.lookup(a, None, spec.batch, base + l * es, stack.pred_class[l], stack.confidence[l], stack.hit[l])
+            cache.compact(stack.hit[l], stack.ids[l], spec.batch, base + l * es, stack.ids[l + 1], base + (l + 1) * es)
+            torch.cuda.synchronize()
+            n_next = int(stack.counts[l + 1].item())
+            active = stack.ids[l + 1][:n_next].cpu().numpy().astype(np.int64)
+    torch.cuda.synchronize()
+    return spec, labels, weights, caches, stack, acts
+
+
+def time_stack(stack, acts, steps, warmup, torch):
+    for _ in range(warmup):
+        stack.run(acts)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        stack.run(acts)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def time_pool_launches(spec, caches, stack, acts, counts, reps, torch):
+    """HIP events around every pooling launch, all layers in stack order so that no layer
+    is re-read from cache; same kernel, launch shape, row lists and device counts as in a
+    stack pass.  Returns per-layer mean duration in ms."""
+    L = len(caches)
+    pooled = [torch.empty(spec.batch, c.C, dtype=torch.float32, device="cuda") for c in caches]
+    es, base = stack.counts.element_size(), stack.counts.data_ptr()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+          for _ in range(reps)]
+    for r in range(-1, reps):           # r = -1: warm-up
+        for l, c in enumerate(caches):
+            row_index = stack.ids[l] if spec.storage == "gather" else None
+            if r >= 0:
+                ev[r][l][0].record()
+            c.pool(acts[l], row_index, spec.batch, base + l * es, pooled[l])
+            if r >= 0:
+                ev[r][l][1].record()
+    torch.cuda.synchronize()
+    ms = np.array([[a.elapsed_time(b) for a, b in row] for row in ev])
+    return ms.mean(axis=0)
+
+
+def cpu_baseline(spec, weights, acts, stack, counts, budget_requests, torch, W):
+    """The CPU oracle, one thread, on the first `budget_requests` requests of the same batch
+    through the whole stack (its own hits and compaction).  TEST INFRASTRUCTURE timed as a
+    reported baseline only."""
+    import oracle
+    from oracle import admit
+    defs = admit.cache_defs(spec, mirror=True)
+    m = min(budget_requests, spec.batch)
+    host = []
+    if spec.storage == "gather":
+        for a in acts:
+            host.append(W.to_host_array(a[:m]))
+    else:
+        # dense storage: row i of layer l belongs to request ids[l][i]; take the rows of requests < m
+        for l, a in enumerate(acts):
+            ids = stack.ids[l][:counts[l]].cpu().numpy()
+            sel = np.nonzero(ids < m)[0]
+            rows = a[torch.from_numpy(sel).cuda()] if len(sel) else a[:0]
+            full = torch.zeros((m,) + tuple(a.shape[1:]), dtype=a.dtype)
+            if len(sel):
+                full[torch.from_numpy(ids[sel].astype(np.int64))] = rows.cpu()
+            host.append(W.to_host_array(full))
+    t0 = time.perf_counter()
+    res = oracle.stack(defs, weights, host, m, storage="gather")
+    dt = time.perf_counter() - t0
+    lookups = int(sum(len(r.ids_in) for r in res))
+    return {"value": lookups / dt, "unit": "lookups/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {m} of {spec.batch} requests through all {len(defs)} layers "
+                      f"({lookups} lookups, {dt:.1f} s, single thread, gcc -O2, fp64 accumulation)"}
+
+
+def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W):
+    t_build = time.perf_counter()
+    spec, labels, weights, caches, stack, acts = build_workload(name, torch, g, W)
+    log(f"[{name}] inputs ready in {time.perf_counter() - t_build:.1f}s "
+        f"({sum(a.numel() * a.element_size() for a in acts) / 1e9:.2f} GB of activations)")
+    ms_step, wall_ms = time_stack(stack, acts, steps, warmup, torch)
+    counts = stack.counts.cpu().numpy().astype(np.int64)
+    n_layers = len(caches)
+    lookups = int(counts[:n_layers].sum())
+    hits = [(int(counts[l] - counts[l + 1]) / int(counts[l])) if counts[l] else None for l in range(n_layers)]
+
+    pool_ms = time_pool_launches(spec, caches, stack, acts, counts, max(3, min(steps, 20)), torch)
+    elem = spec.layers[0].elem_bytes
+    per_layer, by_kernel = [], {}
+    for l, (L, c) in enumerate(zip(spec.layers, caches)):
+        n = int(counts[l])
+        algo = n * L.C * L.S * elem + n * L.C * 4          # activation read + pooled write
+        gbs = algo / (pool_ms[l] * 1e-3) / 1e9 if n else 0.0
+        key = f"{c.pool_variant}[C={L.C},S={L.S},{L.dtype}]"
+        per_layer.append({"layer": l, "n": n, "kernel": key, "pool_us": round(float(pool_ms[l]) * 1e3, 2),
+                          "pool_GBps": round(gbs, 1), "hit_rate": None if hits[l] is None else round(hits[l], 4)})
+        k = by_kernel.setdefault(key, {"bytes": 0, "ms": 0.0, "launches": 0})
+        if n:
+            k["bytes"] += algo
+            k["ms"] += float(pool_ms[l])
+            k["launches"] += 1
+    # dominant kernel = the pooling instance that takes the most time in a pass
+    dom_key = max(by_kernel, key=lambda kk: by_kernel[kk]["ms"])
+    dom = by_kernel[dom_key]
+    achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 if dom["ms"] > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": dom_key, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "bytes_per_launch": int(dom["bytes"] / max(1, dom["launches"])),
+                "avg_launch_us": round(dom["ms"] / max(1, dom["launches"]) * 1e3, 2),
+                "launches_per_step": dom["launches"]}
+    pool_total_bytes = sum(k["bytes"] for k in by_kernel.values())
+    pool_total_ms = sum(k["ms"] for k in by_kernel.values())
+    out = {
+        "workload": name, "ms_per_step": round(ms_step, 4), "wall_ms_per_step": round(wall_ms, 4),
+        "lookups_per_step": lookups, "lookups_per_s": lookups / (ms_step * 1e-3),
+        "request_layers_per_s": spec.batch * n_layers / (ms_step * 1e-3),
+        "cumulative_hit_rate": round(1.0 - counts[n_layers] / spec.batch, 4),
+        "pool_all_layers": {"GBps": round(pool_total_bytes / (pool_total_ms * 1e-3) / 1e9, 1),
+                            "frac_of_peak": round(pool_total_bytes / (pool_total_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                            "us_per_step": round(pool_total_ms * 1e3, 1),
+                            "share_of_step": round(pool_total_ms / ms_step, 3)},
+        "roofline": roofline,
+        "pool_kernels": {k: {"GBps": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] else 0.0,
+                             "launches": v["launches"]} for k, v in by_kernel.items()},
+        "layers": per_layer,
+    }
+    if with_cpu:
+        out["cpu_baseline"] = cpu_baseline(spec, weights, acts, stack, counts, cpu_requests, torch, W)
+    stack.close()
+    del acts
+    torch.cuda.empty_cache()
+    return spec, out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50",
+                    help="tiny | resnet18 | resnet50 | bert_base | resnet152")
+    ap.add_argument("--also", default="bert_base",
+                    help="comma-separated further workloads reported under 'others' ('' for none)")
+    ap.add_argument("--cpu-requests", type=int, default=192,
+                    help="requests of the batch the CPU oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", action="store_true", help="include the per-layer table in the JSON line")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU (one process, one MI355X); run it with --gpus 1. "
+              "Requests are independent, so more GPUs would each run this same path on a share of the batch.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists for the product path)", file=sys.stderr)
+        sys.exit(3)
+    import paper_2101_07344_amd as g
+    import workloads as W
+    g.load_library()
+    torch.cuda.set_device(0)
+
+    stream = torch.cuda.Stream()          # default priority; every launch and event goes here
+    with torch.cuda.stream(stream):
+        spec, main_res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
+                                      args.cpu_requests, torch, g, W)
+        others = {}
+        for name in [n for n in args.also.split(",") if n and n != args.workload]:
+            _, r = run_workload(name, args.steps, args.warmup, False, 0, torch, g, W)
+            r.pop("layers", None)
+            others[name] = r
+
+    L0 = spec.layers[0]
+    line = {
+        "metric": "learned-cache lookups/sec (samples x layers)",
+        "value": main_res["lookups_per_s"],
+        "unit": "lookups/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": L0.dtype, "data": "synthetic",
+        "config": {"workload": f"{spec.name}: batch {spec.batch}, {len(spec.layers)} caches, "
+                               f"{L0.dtype} activations, storage {spec.storage}",
+                   "lookups_per_step": main_res["lookups_per_step"],
+                   "cumulative_hit_rate": main_res["cumulative_hit_rate"]},
+        "roofline": main_res["roofline"],
+        "cpu_baseline": main_res.get("cpu_baseline"),
+        "request_layers_per_s": main_res["request_layers_per_s"],
+        "pool_all_layers": main_res["pool_all_layers"],
+        "pool_kernels": main_res["pool_kernels"],
+        "others": others,
+    }
+    if args.layers:
+        line["layers"] = main_res["layers"]
+    else:
+        log(json.dumps(main_res["layers"]))
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

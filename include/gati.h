@@ -139,6 +139,16 @@ gati_status_t gati_compact_misses(gati_cache_t *cache, const uint8_t *hit, const
                                   int32_t n_max, const int32_t *n_dev,
                                   int32_t *ids_out, int32_t *n_miss_dev, void *stream);
 
+/* gati_cache_lookup followed by gati_compact_misses on its hit flags, as one call: the last
+ * kernel of the lookup also compacts (Section 1 / Appendix A.1: only the misses of one
+ * layer's cache reach the next layer's).  Arguments as in the two calls above; ids_out and
+ * n_miss_dev are required; outputs are identical to calling the two entry points in turn. */
+gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, const int32_t *row_index,
+                                        int32_t n_max, const int32_t *n_dev,
+                                        int32_t *pred_class, float *confidence, uint8_t *hit,
+                                        float *logits, const int32_t *ids_in,
+                                        int32_t *ids_out, int32_t *n_miss_dev, void *stream);
+
 /* Static, never-NULL description of a status code. */
 const char *gati_status_string(gati_status_t status);
 

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE (uses the oracle).  Writes ``workloads/calibration.json``:
 
-    python -m oracle.calibrate [workload ...]
+    python -m oracle.calibrate [--sample N] [workload ...]
 
 The configs ask for a hit rate that rises with depth (the paper's per-block
 tables show exactly that shape).  With random weights the selector score is
@@ -77,13 +77,18 @@ def calibrate(name: str, sample: int = 512, verbose: bool = True) -> dict:
 
 
 def main(argv):
+    sample = 512
+    if "--sample" in argv:
+        i = argv.index("--sample")
+        sample = int(argv[i + 1])
+        argv = argv[:i] + argv[i + 2:]
     names = argv or sorted(HIT_TARGETS)
     cal = {}
     if os.path.exists(_OUT):
         with open(_OUT) as f:
             cal = json.load(f)
     for n in names:
-        cal[n] = calibrate(n)
+        cal[n] = calibrate(n, sample=sample)
         with open(_OUT, "w") as f:
             json.dump(cal, f, indent=1)
             f.write("\n")

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     GATI_F32, GATI_BF16, GATI_LAYOUT_NCS, GATI_LAYOUT_NSC,
     GatiError, CacheDesc, CacheWeights, Cache, CacheStack,
     load_library, library_path, exported_symbols,
-    gati_cache_create, gati_cache_destroy, gati_cache_lookup, gati_cache_pool,
+    gati_cache_create, gati_cache_destroy, gati_cache_lookup, gati_cache_lookup_compact, gati_cache_pool,
     gati_compact_misses, gati_cache_set_selector, gati_status_string, gati_cache_pool_variant,
 )

@@ -17,7 +17,7 @@ GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
 # every extern "C" symbol include/gati.h declares
 exported_symbols = (
     "gati_cache_create", "gati_cache_destroy", "gati_cache_set_selector", "gati_cache_lookup",
-    "gati_cache_pool", "gati_compact_misses", "gati_status_string", "gati_cache_pool_variant",
+    "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_status_string", "gati_cache_pool_variant",
 )
 
 
@@ -68,6 +68,8 @@ def load_library():
     lib.gati_cache_set_selector.argtypes = [vp, C.c_float, C.c_float]
     lib.gati_cache_lookup.restype = C.c_int
     lib.gati_cache_lookup.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.gati_cache_lookup_compact.restype = C.c_int
+    lib.gati_cache_lookup_compact.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.gati_cache_pool.restype = C.c_int
     lib.gati_cache_pool.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.gati_compact_misses.restype = C.c_int
@@ -130,6 +132,13 @@ def gati_cache_lookup(handle, act, row_index, n_max: int, n_dev, pred_class, con
                                             _dptr(logits), _stream(stream))
 
 
+def gati_cache_lookup_compact(handle, act, row_index, n_max: int, n_dev, pred_class, confidence, hit,
+                              logits, ids_in, ids_out, n_miss_dev, stream=None) -> int:
+    return load_library().gati_cache_lookup_compact(
+        handle, _dptr(act), _dptr(row_index), int(n_max), _dptr(n_dev), _dptr(pred_class), _dptr(confidence),
+        _dptr(hit), _dptr(logits), _dptr(ids_in), _dptr(ids_out), _dptr(n_miss_dev), _stream(stream))
+
+
 def gati_cache_pool(handle, act, row_index, n_max: int, n_dev, pooled, stream=None) -> int:
     return load_library().gati_cache_pool(handle, _dptr(act), _dptr(row_index), int(n_max), _dptr(n_dev),
                                           _dptr(pooled), _stream(stream))
@@ -169,6 +178,12 @@ class Cache:
     def lookup(self, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits=None, stream=None):
         _check(gati_cache_lookup(self.handle, act, row_index, n_max, n_dev, pred_class, confidence, hit,
                                  logits, stream), "gati_cache_lookup")
+
+    def lookup_compact(self, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits,
+                       ids_in, ids_out, n_miss_dev, stream=None):
+        _check(gati_cache_lookup_compact(self.handle, act, row_index, n_max, n_dev, pred_class, confidence,
+                                         hit, logits, ids_in, ids_out, n_miss_dev, stream),
+               "gati_cache_lookup_compact")
 
     def pool(self, act, row_index, n_max, n_dev, pooled, stream=None):
         _check(gati_cache_pool(self.handle, act, row_index, n_max, n_dev, pooled, stream), "gati_cache_pool")
@@ -215,19 +230,25 @@ class CacheStack:
         self.logits = ([torch.zeros(batch, c.K, dtype=torch.float32, device=dev) for c in self.caches]
                        if keep_logits else [None] * L)
 
-    def run(self, acts: Sequence, stream=None):
+    def run(self, acts: Sequence, stream=None, fused: bool = True):
         """Enqueue one pass over all layers.  acts[l] is the layer's activation tensor:
         the full batch indexed by request id ("gather"), or the rows still active in
-        miss-list order ("dense")."""
+        miss-list order ("dense").  fused: one gati_cache_lookup_compact per layer instead of
+        gati_cache_lookup + gati_compact_misses (same results)."""
         es = self.counts.element_size()
         cbase = self.counts.data_ptr()
         for l, cache in enumerate(self.caches):
             n_dev = cbase + l * es
             row_index = self.ids[l] if self.storage == "gather" else None
-            cache.lookup(acts[l], row_index, self.batch, n_dev, self.pred_class[l], self.confidence[l],
-                         self.hit[l], self.logits[l], stream)
-            cache.compact(self.hit[l], self.ids[l], self.batch, n_dev, self.ids[l + 1],
-                          cbase + (l + 1) * es, stream)
+            if fused:
+                cache.lookup_compact(acts[l], row_index, self.batch, n_dev, self.pred_class[l],
+                                     self.confidence[l], self.hit[l], self.logits[l], self.ids[l],
+                                     self.ids[l + 1], cbase + (l + 1) * es, stream)
+            else:
+                cache.lookup(acts[l], row_index, self.batch, n_dev, self.pred_class[l], self.confidence[l],
+                             self.hit[l], self.logits[l], stream)
+                cache.compact(self.hit[l], self.ids[l], self.batch, n_dev, self.ids[l + 1],
+                              cbase + (l + 1) * es, stream)
 
     def close(self):
         for c in self.caches:

@@ -8,6 +8,7 @@ namespace gati {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 // 16 bytes of activation data.  A native vector type, so that a load is one
 // global_load_dwordx4 and a masked select stays a whole-vector operation.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));

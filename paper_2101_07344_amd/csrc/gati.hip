@@ -46,20 +46,23 @@ struct gati_cache {
     int num_cu = 256;
     bool bf16 = false;
     int elem = 4;
-    // padded sizes: Cp % 64 == 0 (FC1 reduction), Hp % 32 == 0, Kp % 32 == 0, rows_pad % 32 == 0
+    // padded sizes: Cp % 64 == 0 and Hp % 64 == 0 (reduction axes: 4 waves x whole k-steps),
+    // Kp % (32*fc2_nt) == 0, rows_pad % 32 == 0
     int Cp = 0, Hp = 0, Kp = 0, rows_pad = 0;
-    // device weights
-    void* W1 = nullptr;       // [Hp, Cp] bf16 | f32
-    void* W2 = nullptr;       // [Kp, Hp] bf16 | f32
+    // device weights, packed in MFMA fragment order (head_kernels.h)
+    void* W1 = nullptr;       // [Hp/32][Cp/kStep][64][kLane] bf16 | f32
+    void* W2 = nullptr;       // [Kp/32][Hp/kStep][64][kLane] bf16 | f32
     float* b1 = nullptr;      // [Hp]
     float* b2 = nullptr;      // [Kp]
     float* ws_pool = nullptr; // [Cp]
     float* ws_prob = nullptr; // [Kp]
     float bs = 0.f, tau = 0.5f;
     // workspace
-    float* p = nullptr;       // [rows_pad, Cp]
+    float* p = nullptr;       // [rows_pad, Cp] pooled features, fp32
+    void* p16 = nullptr;      // [rows_pad, Cp] the same rounded to bf16 (bf16 caches only)
     void* h = nullptr;        // [rows_pad, Hp]
     float* u_pool = nullptr;  // [rows_pad]
+    TileStat* stats = nullptr; // [rows_pad, Kp/(32*fc2_nt)]
     // pooling plan
     PoolVariant variant = POOL_GENERIC;
     int vpc = 0;              // ncs_wave: 16-byte vectors per channel
@@ -68,14 +71,14 @@ struct gati_cache {
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
     int pool_blocks_per_cu = 8;
-    // head plan
-    int fc2_tpw = 1, fc2_waves = 1;
+    // head plan: column tiles per workgroup of the output layer
+    int fc2_nt = 1;
 };
 
 namespace {
 
 void free_all(gati_cache* c) {
-    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->h, c->u_pool};
+    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
 }
@@ -144,14 +147,21 @@ void plan_pool(gati_cache* c) {
     }
 }
 
-void plan_head(gati_cache* c) {
-    const int tiles = c->Kp / 32;
-    if (tiles <= 1) { c->fc2_waves = 1; c->fc2_tpw = 1; }
-    else if (tiles <= 2) { c->fc2_waves = 2; c->fc2_tpw = 1; }
-    else if (tiles <= 4) { c->fc2_waves = 4; c->fc2_tpw = 1; }
-    else if (tiles <= 8) { c->fc2_waves = 4; c->fc2_tpw = 2; }
-    else if (tiles <= 16) { c->fc2_waves = 4; c->fc2_tpw = 4; }
-    else { c->fc2_waves = 4; c->fc2_tpw = 8; }
+// Weights [rows, cols] (row-major, fp32, host) -> MFMA fragment order, zero padded to
+// [rows_p, cols_p]; element type bf16 (nearest even) or fp32.
+template <typename T, typename Conv>
+void pack_weights(const float* W, int rows, int cols, int rows_p, int cols_p, int k_step, std::vector<T>& out,
+                  Conv conv) {
+    const int k_lane = k_step / 2, KS = cols_p / k_step;
+    out.assign((size_t)rows_p * cols_p, conv(0.f));
+    for (int nt = 0; nt < rows_p / 32; ++nt)
+        for (int ks = 0; ks < KS; ++ks)
+            for (int l = 0; l < 64; ++l)
+                for (int e = 0; e < k_lane; ++e) {
+                    const int row = nt * 32 + (l & 31), col = ks * k_step + (l >> 5) * k_lane + e;
+                    if (row < rows && col < cols)
+                        out[(((size_t)nt * KS + ks) * 64 + l) * k_lane + e] = conv(W[(size_t)row * cols + col]);
+                }
 }
 
 template <typename Tag>
@@ -196,8 +206,9 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
 }
 
 hipError_t launch_pool(const gati_cache* c, const void* act, const int32_t* row_index, int n_max,
-                       const int32_t* n_dev, float* out, int out_stride, hipStream_t st) {
+                       const int32_t* n_dev, float* out, void* out16, int out_stride, hipStream_t st) {
     PoolArgs a;
+    a.out16 = static_cast<__bf16*>(out16);
     a.act = act; a.row_index = row_index; a.n_dev = n_dev; a.n_max = n_max;
     a.C = c->desc.C; a.S = c->desc.S; a.inv_S = 1.0f / (float)c->desc.S;
     a.out = out; a.out_stride = out_stride;
@@ -207,29 +218,36 @@ hipError_t launch_pool(const gati_cache* c, const void* act, const int32_t* row_
     return c->bf16 ? launch_pool_t<BF16Tag>(c, a, v, st) : launch_pool_t<F32Tag>(c, a, v, st);
 }
 
+// FC1 (+ pooled half of the selector), FC2 (+ per-tile softmax summaries), then the per-row
+// finish; with ids_out the finish also compacts the misses.
 template <bool BF16>
 hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, int32_t* pred_class,
-                         float* confidence, uint8_t* hit, float* logits, hipStream_t st) {
+                         float* confidence, uint8_t* hit, float* logits, const int32_t* ids_in,
+                         int32_t* ids_out, int32_t* n_miss, hipStream_t st) {
     const int row_tiles = (n_max + 31) / 32;
-    Fc1Args f1;
-    f1.p = c->p; f1.W1 = c->W1; f1.b1 = c->b1; f1.h = c->h; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool;
-    f1.Cp = c->Cp; f1.Hp = c->Hp; f1.n_max = n_max; f1.n_dev = n_dev;
-    fc1_kernel<BF16><<<dim3(c->Hp / 32 + 1, row_tiles), 64, 0, st>>>(f1);
+    FcArgs f1 = {};
+    f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
+    f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
+    f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp;
+    fc_kernel<BF16, 1, true><<<dim3(c->Hp / 32 + 1, row_tiles), 256, 0, st>>>(f1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    Fc2Args f2;
-    f2.h = c->h; f2.W2 = c->W2; f2.b2 = c->b2; f2.ws_prob = c->ws_prob; f2.u_pool = c->u_pool;
-    f2.bs = c->bs; f2.tau = c->tau; f2.Hp = c->Hp; f2.K = c->desc.K; f2.Kp = c->Kp;
+    FcArgs f2 = {};
+    f2.A = c->h; f2.Wp = c->W2; f2.bias = c->b2; f2.Kdim = c->Hp; f2.N = c->Kp;
     f2.n_max = n_max; f2.n_dev = n_dev;
-    f2.pred_class = pred_class; f2.confidence = confidence; f2.hit = hit; f2.logits = logits;
-    const int threads = c->fc2_waves * 64;
-    switch (c->fc2_tpw) {
-    case 1: fc2_head_kernel<BF16, 1><<<row_tiles, threads, 0, st>>>(f2); break;
-    case 2: fc2_head_kernel<BF16, 2><<<row_tiles, threads, 0, st>>>(f2); break;
-    case 4: fc2_head_kernel<BF16, 4><<<row_tiles, threads, 0, st>>>(f2); break;
-    default: fc2_head_kernel<BF16, 8><<<row_tiles, threads, 0, st>>>(f2); break;
-    }
+    f2.K = c->desc.K; f2.ws_prob = c->ws_prob; f2.logits = logits; f2.stats = c->stats;
+    const int n_tiles = c->Kp / (32 * c->fc2_nt);
+    if (c->fc2_nt == 2) fc_kernel<BF16, 2, false><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
+    else fc_kernel<BF16, 1, false><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    FinalizeArgs fa = {};
+    fa.stats = c->stats; fa.n_tiles = n_tiles; fa.u_pool = c->u_pool; fa.bs = c->bs; fa.tau = c->tau;
+    fa.n_max = n_max; fa.n_dev = n_dev; fa.pred_class = pred_class; fa.confidence = confidence; fa.hit = hit;
+    fa.ids_in = ids_in; fa.ids_out = ids_out; fa.n_miss = n_miss;
+    finalize_kernel<<<1, 1024, 0, st>>>(fa);
     return hipGetLastError();
 }
 
@@ -275,8 +293,9 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     c->bs = w->bs;
     c->tau = desc->threshold;
     c->Cp = round_up(desc->C, 64);
-    c->Hp = round_up(desc->H, 32);
-    c->Kp = round_up(desc->K, 32);
+    c->Hp = round_up(desc->H, 64);
+    c->fc2_nt = desc->K > 96 ? 2 : 1;
+    c->Kp = round_up(desc->K, 32 * c->fc2_nt);
     c->rows_pad = round_up(desc->max_rows, 32);
 
     if (hipGetDevice(&c->device) != hipSuccess) { (void)hipGetLastError(); delete c; return GATI_ERR_DEVICE; }
@@ -288,27 +307,24 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     c->pool_blocks_per_cu = env_int("GATI_POOL_BLOCKS_PER_CU", 8);
 
     plan_pool(c);
-    plan_head(c);
 
     const int C = desc->C, H = desc->H, K = desc->K;
     gati_status_t st = GATI_OK;
     try {
-        // weights in the kernels' layout: zero padded, reduction axis contiguous
-        const size_t n1 = (size_t)c->Hp * c->Cp, n2 = (size_t)c->Kp * c->Hp;
+        // weights in MFMA fragment order, zero padded
         if (c->bf16) {
-            std::vector<uint16_t> t1(n1, 0), t2(n2, 0);
-            for (int j = 0; j < H; ++j)
-                for (int k = 0; k < C; ++k) t1[(size_t)j * c->Cp + k] = f32_to_bf16_rne(w->W1[(size_t)j * C + k]);
-            for (int j = 0; j < K; ++j)
-                for (int k = 0; k < H; ++k) t2[(size_t)j * c->Hp + k] = f32_to_bf16_rne(w->W2[(size_t)j * H + k]);
-            st = upload(&c->W1, t1.data(), n1 * 2);
-            if (st == GATI_OK) st = upload(&c->W2, t2.data(), n2 * 2);
+            std::vector<uint16_t> t1, t2;
+            pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
+            pack_weights(w->W2, K, H, c->Kp, c->Hp, 16, t2, f32_to_bf16_rne);
+            st = upload(&c->W1, t1.data(), t1.size() * 2);
+            if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 2);
         } else {
-            std::vector<float> t1(n1, 0.f), t2(n2, 0.f);
-            for (int j = 0; j < H; ++j) std::memcpy(&t1[(size_t)j * c->Cp], &w->W1[(size_t)j * C], (size_t)C * 4);
-            for (int j = 0; j < K; ++j) std::memcpy(&t2[(size_t)j * c->Hp], &w->W2[(size_t)j * H], (size_t)H * 4);
-            st = upload(&c->W1, t1.data(), n1 * 4);
-            if (st == GATI_OK) st = upload(&c->W2, t2.data(), n2 * 4);
+            std::vector<float> t1, t2;
+            auto same = [](float x) { return x; };
+            pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);
+            pack_weights(w->W2, K, H, c->Kp, c->Hp, 8, t2, same);
+            st = upload(&c->W1, t1.data(), t1.size() * 4);
+            if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 4);
         }
         std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
         std::memcpy(b1.data(), w->b1, (size_t)H * 4);
@@ -324,8 +340,11 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     }
     // workspace, zeroed once: the padding columns of p are never written and must read as 0
     if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
+    if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);
     if (st == GATI_OK) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
     if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
+    if (st == GATI_OK)
+        st = upload((void**)&c->stats, nullptr, (size_t)c->rows_pad * (c->Kp / (32 * c->fc2_nt)) * sizeof(TileStat));
     if (st == GATI_OK && hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); st = GATI_ERR_DEVICE; }
     if (st != GATI_OK) { free_all(c); delete c; return st; }
     *out = c;
@@ -353,9 +372,22 @@ gati_status_t gati_cache_pool(gati_cache_t* c, const void* act, const int32_t* r
     if (n_max == 0) return GATI_OK;
     if (!act || !pooled) return GATI_ERR_INVALID_ARG;
     if (!on_cache_device(c)) return GATI_ERR_DEVICE;
-    const hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, pooled, c->desc.C, (hipStream_t)stream);
+    const hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, pooled, nullptr, c->desc.C, (hipStream_t)stream);
     return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
 }
+
+namespace {
+gati_status_t lookup_impl(gati_cache_t* c, const void* act, const int32_t* row_index, int32_t n_max,
+                          const int32_t* n_dev, int32_t* pred_class, float* confidence, uint8_t* hit,
+                          float* logits, const int32_t* ids_in, int32_t* ids_out, int32_t* n_miss,
+                          hipStream_t st) {
+    hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, c->p, c->p16, c->Cp, st);
+    if (e != hipSuccess) return GATI_ERR_DEVICE;
+    e = c->bf16 ? launch_head_t<true>(c, n_max, n_dev, pred_class, confidence, hit, logits, ids_in, ids_out, n_miss, st)
+                : launch_head_t<false>(c, n_max, n_dev, pred_class, confidence, hit, logits, ids_in, ids_out, n_miss, st);
+    return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+}  // namespace
 
 gati_status_t gati_cache_lookup(gati_cache_t* c, const void* act, const int32_t* row_index, int32_t n_max,
                                 const int32_t* n_dev, int32_t* pred_class, float* confidence, uint8_t* hit,
@@ -364,12 +396,26 @@ gati_status_t gati_cache_lookup(gati_cache_t* c, const void* act, const int32_t*
     if (n_max == 0) return GATI_OK;
     if (!act || !pred_class || !confidence || !hit) return GATI_ERR_INVALID_ARG;
     if (!on_cache_device(c)) return GATI_ERR_DEVICE;
-    hipStream_t st = (hipStream_t)stream;
-    hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, c->p, c->Cp, st);
-    if (e != hipSuccess) return GATI_ERR_DEVICE;
-    e = c->bf16 ? launch_head_t<true>(c, n_max, n_dev, pred_class, confidence, hit, logits, st)
-                : launch_head_t<false>(c, n_max, n_dev, pred_class, confidence, hit, logits, st);
-    return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+    return lookup_impl(c, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits, nullptr, nullptr,
+                       nullptr, (hipStream_t)stream);
+}
+
+gati_status_t gati_cache_lookup_compact(gati_cache_t* c, const void* act, const int32_t* row_index,
+                                        int32_t n_max, const int32_t* n_dev, int32_t* pred_class,
+                                        float* confidence, uint8_t* hit, float* logits, const int32_t* ids_in,
+                                        int32_t* ids_out, int32_t* n_miss_dev, void* stream) {
+    if (!c || n_max < 0 || n_max > c->desc.max_rows || !n_miss_dev) return GATI_ERR_INVALID_ARG;
+    if (n_max > 0 && (!act || !pred_class || !confidence || !hit || !ids_out)) return GATI_ERR_INVALID_ARG;
+    if (ids_in && ids_in == ids_out) return GATI_ERR_INVALID_ARG;
+    if (!on_cache_device(c)) return GATI_ERR_DEVICE;
+    if (n_max == 0) {   // nothing to look up: the miss list is empty
+        CompactArgs a;
+        a.hit = nullptr; a.ids_in = nullptr; a.n_dev = n_dev; a.n_max = 0; a.ids_out = ids_out; a.n_miss = n_miss_dev;
+        compact_misses_kernel<<<1, 1024, 0, (hipStream_t)stream>>>(a);
+        return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+    }
+    return lookup_impl(c, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits, ids_in, ids_out,
+                       n_miss_dev, (hipStream_t)stream);
 }
 
 gati_status_t gati_compact_misses(gati_cache_t* c, const uint8_t* hit, const int32_t* ids_in, int32_t n_max,

@@ -4,15 +4,21 @@
 //
 // Both FC layers are real dense contractions (rows x C x H and rows x H x K), so they run
 // on the matrix cores: v_mfma_f32_32x32x16_bf16 for bf16 caches, v_mfma_f32_32x32x2_f32 for
-// fp32 caches, fp32 accumulation in both.  A and B operands are both contiguous along the
-// reduction axis ([rows, C] x [H, C]^T), which is exactly the per-lane fragment the 32x32
-// MFMA wants (8 consecutive k for one row / column), so fragments are loaded straight from
-// global memory / L2 with 16-byte loads; the matrices are a few MB and stay cache resident.
+// fp32 caches, fp32 accumulation in both.  The GEMMs are small (at most a few GFLOP) and
+// latency-bound, so the design goal is many short workgroups rather than big tiles:
+//   * one workgroup = one 32-row x (32*NT)-column output tile; its 4 waves split the
+//     reduction axis (split-K) and meet in LDS, added in a fixed order;
+//   * the weights are repacked once, at cache creation, into MFMA fragment order, so a
+//     wave's B operand for consecutive k-steps is one contiguous, fully coalesced stream;
+//   * the A operand (pooled features / hidden activations) is row-major with the reduction
+//     axis contiguous, which is the per-lane fragment the 32x32 MFMA wants.
 //
-// Fragment layout used here (wave of 64 lanes, r = lane % 32, kb = lane / 32):
-//   A: lane holds A[m = r][k = 8*kb .. 8*kb+7]      (bf16; f32: one k per MFMA)
-//   B: lane holds B[k = 8*kb .. 8*kb+7][n = r]
+// Fragment layout (wave of 64 lanes, r = lane % 32, kb = lane / 32), per k-step of
+// kStep = 16 (bf16) or 8 (fp32) reduction elements, kLane = kStep/2 per lane:
+//   A: lane holds A[m = r][k = kLane*kb .. kLane*kb + kLane-1]
+//   B: lane holds B[k = kLane*kb .. ][n = r]
 //   D: acc[j] is D[m = 8*(j/4) + 4*kb + j%4][n = r]
+// Packed weights: Wp[((nt*KS + ks)*64 + lane)*kLane + e] = W[nt*32 + r][ks*kStep + kb*kLane + e].
 #pragma once
 
 #include "common.h"
@@ -21,78 +27,88 @@ namespace gati {
 
 __device__ __forceinline__ int mfma_row(int j, int kb) { return 8 * (j >> 2) + 4 * kb + (j & 3); }
 
-// One 32x32 tile step over 16 (bf16) or 8 (f32) values of the reduction axis.
-template <bool BF16> struct MmaStep;
+template <bool BF16> struct Mma;
 
-template <> struct MmaStep<true> {
-    static constexpr int kStep = 16;     // reduction elements consumed per call
-    static constexpr int kLane = 8;      // consecutive k held by one lane
-    // A from fp32 memory (rounded to bf16, nearest even), B from bf16 memory.
-    static __device__ __forceinline__ bf16x8_t load_a_f32(const float* p) {
-        const float4 x = *reinterpret_cast<const float4*>(p);
-        const float4 y = *reinterpret_cast<const float4*>(p + 4);
-        bf16x8_t a;
-        a[0] = (__bf16)x.x; a[1] = (__bf16)x.y; a[2] = (__bf16)x.z; a[3] = (__bf16)x.w;
-        a[4] = (__bf16)y.x; a[5] = (__bf16)y.y; a[6] = (__bf16)y.z; a[7] = (__bf16)y.w;
-        return a;
-    }
-    static __device__ __forceinline__ bf16x8_t load_bf16(const void* p) {
-        return *reinterpret_cast<const bf16x8_t*>(p);
-    }
-    static __device__ __forceinline__ f32x16_t mma(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+template <> struct Mma<true> {
+    typedef bf16x8_t frag_t;            // 16 bytes: 8 bf16
+    static constexpr int kStep = 16, kLane = 8;
+    static __device__ __forceinline__ f32x16_t mma(frag_t a, frag_t b, f32x16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
 };
 
-template <> struct MmaStep<false> {
-    static constexpr int kStep = 8;
-    static constexpr int kLane = 4;
-    // Lane (r, kb) holds k = 4*kb .. 4*kb+3; MFMA number j multiplies element j of every
-    // lane, i.e. k = j and k = 4 + j.  A and B use the same order, so the sum over the 8 k
-    // values is complete after 4 MFMAs.
-    static __device__ __forceinline__ f32x16_t mma(const float4& a, const float4& b, f32x16_t c) {
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, c, 0, 0, 0);
+template <> struct Mma<false> {
+    typedef f32x4_t frag_t;             // 16 bytes: 4 fp32
+    static constexpr int kStep = 8, kLane = 4;
+    // MFMA number e multiplies element e of every lane, i.e. k = e (lanes 0-31) and k = 4 + e
+    // (lanes 32-63).  A and B use the same order, so 4 MFMAs cover the 8 k values.
+    static __device__ __forceinline__ f32x16_t mma(frag_t a, frag_t b, f32x16_t c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], c, 0, 0, 0);
         return c;
     }
 };
 
-struct Fc1Args {
-    const float* p;        // [rows_pad, Cp] pooled features, fp32, zero in the padding columns
-    const void* W1;        // [Hp, Cp] bf16 or f32, zero padded
-    const float* b1;       // [Hp]
-    void* h;               // [rows_pad, Hp] bf16 or f32
-    const float* ws_pool;  // [Cp] selector weights of the pooled features, zero padded
-    float* u_pool;         // [rows_pad] out: ws_pool . p[row]
-    int Cp, Hp;
-    int n_max;
-    const int32_t* n_dev;
+// Per-(row, column tile) summary of the logits, combined across tiles by finalize_kernel.
+struct __attribute__((aligned(16))) TileStat {
+    float max;    // largest logit of the tile (-inf if the tile holds only padding classes)
+    float sum;    // sum over the tile of exp(z - max)
+    float wsum;   // sum over the tile of ws_prob[k] * exp(z - max)
+    int arg;      // lowest class index attaining max
 };
 
-// grid = (Hp/32 + 1, rows_pad/32), block = one wave.  Column tile Hp/32 is not a tile of the
-// hidden layer: that wave computes the pooled-feature half of the selector's dot product in
-// fp32 for the 32 rows, so it overlaps with the MFMA tiles instead of serialising later.
-template <bool BF16>
-__global__ __launch_bounds__(64) void fc1_kernel(Fc1Args a) {
-    using Step = MmaStep<BF16>;
+struct FcArgs {
+    const void* A;         // [rows_pad, K] row-major operand (bf16 or f32), zero in padding columns
+    const void* Wp;        // packed weights, see above
+    const float* bias;     // [N]
+    int Kdim;              // padded reduction length (multiple of 4*kStep)
+    int N;                 // padded output width (multiple of 32*NT)
+    int n_max;
+    const int32_t* n_dev;
+    // epilogue of the hidden layer
+    void* h;               // [rows_pad, N] bf16 or f32: relu(A W^T + bias)
+    const float* p32;      // [rows_pad, ldp] fp32 pooled features (selector half)
+    const float* ws_pool;  // [ldp]
+    float* u_pool;         // [rows_pad] out: ws_pool . p32[row]
+    int ldp;
+    // epilogue of the output layer
+    int K;                 // real number of classes (<= N)
+    const float* ws_prob;  // [N] selector weights of the class probabilities, zero padded
+    float* logits;         // [n, K] or null
+    TileStat* stats;       // [rows_pad, N/(32*NT)]
+};
+
+// grid = (N/(32*NT) [+1 when HIDDEN], ceil(n_max/32)), block = 256.
+// HIDDEN: epilogue bias + ReLU -> h; the extra column block computes the pooled-feature half
+// of the selector's dot product in fp32, overlapping with the MFMA tiles.
+// !HIDDEN: epilogue bias -> logits (optional store) and the tile's softmax/argmax summary.
+template <bool BF16, int NT, bool HIDDEN>
+__global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
+    using M = Mma<BF16>;
+    using frag_t = typename M::frag_t;
+    constexpr int kStep = M::kStep, kLane = M::kLane;
+    __shared__ float red[4][NT * 16][64];      // split-K partial tiles, [wave][tile*16 + j][lane]
+
     const int n = active_rows(a.n_dev, a.n_max);
     const int row0 = blockIdx.y * 32;
     if (row0 >= n) return;
-    const int lane = threadIdx.x;
-    const int ct = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int r = lane & 31, kb = lane >> 5;
+    const int n_tiles_x = a.N / (32 * NT);
 
-    if (ct == a.Hp / 32) {
-        const float4* wv = reinterpret_cast<const float4*>(a.ws_pool);
-        const int nvec = a.Cp / 4;
-        for (int rr = 0; rr < 32 && row0 + rr < n; ++rr) {
-            const float4* pr = reinterpret_cast<const float4*>(a.p + (long)(row0 + rr) * a.Cp);
+    if (HIDDEN && (int)blockIdx.x == n_tiles_x) {
+        const f32x4_t* wv = reinterpret_cast<const f32x4_t*>(a.ws_pool);
+        const int nvec = a.ldp / 4;
+        for (int rr = wave * 8; rr < wave * 8 + 8 && row0 + rr < n; ++rr) {
+            const f32x4_t* pr = reinterpret_cast<const f32x4_t*>(a.p32 + (long)(row0 + rr) * a.ldp);
             float acc = 0.f;
             for (int k = lane; k < nvec; k += 64) {
-                const float4 x = pr[k], w = wv[k];
-                acc = fmaf(x.x, w.x, acc); acc = fmaf(x.y, w.y, acc);
-                acc = fmaf(x.z, w.z, acc); acc = fmaf(x.w, w.w, acc);
+                const f32x4_t x = pr[k], w = wv[k];
+                acc = fmaf(x[0], w[0], acc); acc = fmaf(x[1], w[1], acc);
+                acc = fmaf(x[2], w[2], acc); acc = fmaf(x[3], w[3], acc);
             }
             acc = wave_sum(acc);
             if (lane == 0) a.u_pool[row0 + rr] = acc;
@@ -100,239 +116,201 @@ __global__ __launch_bounds__(64) void fc1_kernel(Fc1Args a) {
         return;
     }
 
-    const int r = lane & 31, kb = lane >> 5;
-    f32x16_t acc;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-    const float* arow = a.p + (long)(row0 + r) * a.Cp + kb * Step::kLane;
+    // ---- split-K MFMA over this wave's quarter of the reduction axis ----
+    const int KS = a.Kdim / kStep;
+    const int ksw = KS >> 2;                    // k-steps per wave
+    const int ks0 = wave * ksw;
+    const int nt0 = blockIdx.x * NT;
+    const frag_t* ap = reinterpret_cast<const frag_t*>(
+        static_cast<const char*>(a.A) + ((long)(row0 + r) * a.Kdim + (long)ks0 * kStep + kb * kLane) * (BF16 ? 2 : 4));
+    // A advances kStep elements = 2 fragments of 16 bytes per k-step
+    const frag_t* bp = reinterpret_cast<const frag_t*>(a.Wp) + ((long)nt0 * KS + ks0) * 64 + lane;
+    const long b_tile = (long)KS * 64;          // fragments between consecutive column tiles
 
-    if constexpr (BF16) {
-        const __bf16* brow = static_cast<const __bf16*>(a.W1) + (long)(ct * 32 + r) * a.Cp + kb * 8;
-        for (int k0 = 0; k0 < a.Cp; k0 += 64) {   // Cp is a multiple of 64
-            bf16x8_t af[4], bf[4];
+    f32x16_t acc[NT];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                af[u] = Step::load_a_f32(arow + k0 + 16 * u);
-                bf[u] = Step::load_bf16(brow + k0 + 16 * u);
-            }
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc = Step::mma(af[u], bf[u], acc);
+        for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
+
+    int ks = 0;
+    for (; ks + 4 <= ksw; ks += 4) {
+        frag_t af[4], bf[NT][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            af[u] = ap[(ks + u) * 2];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) bf[t][u] = bp[t * b_tile + (long)(ks + u) * 64];
         }
-    } else {
-        const float* brow = static_cast<const float*>(a.W1) + (long)(ct * 32 + r) * a.Cp + kb * 4;
-        for (int k0 = 0; k0 < a.Cp; k0 += 32) {
-            float4 af[4], bf[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                af[u] = *reinterpret_cast<const float4*>(arow + k0 + 8 * u);
-                bf[u] = *reinterpret_cast<const float4*>(brow + k0 + 8 * u);
-            }
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc = Step::mma(af[u], bf[u], acc);
-        }
+            for (int t = 0; t < NT; ++t) acc[t] = M::mma(af[u], bf[t][u], acc[t]);
+    }
+    for (; ks < ksw; ++ks) {
+        const frag_t af = ap[ks * 2];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = M::mma(af, bp[t * b_tile + (long)ks * 64], acc[t]);
     }
 
-    const int col = ct * 32 + r;
-    const float bias = a.b1[col];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int row = row0 + mfma_row(j, kb);
-        const float v = fmaxf(acc[j] + bias, 0.f);
-        if constexpr (BF16)
-            static_cast<__bf16*>(a.h)[(long)row * a.Hp + col] = (__bf16)v;
-        else
-            static_cast<float*>(a.h)[(long)row * a.Hp + col] = v;
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) red[wave][t * 16 + j][lane] = acc[t][j];
+    __syncthreads();
+
+    // ---- fixed-order sum of the four partial tiles; thread (wave, lane) takes slots q*4 + wave ----
+    float z[4 * NT];
+#pragma unroll
+    for (int q = 0; q < 4 * NT; ++q) {
+        const int tj = q * 4 + wave;
+        z[q] = (red[0][tj][lane] + red[1][tj][lane]) + (red[2][tj][lane] + red[3][tj][lane]);
+    }
+
+    if constexpr (HIDDEN) {
+#pragma unroll
+        for (int q = 0; q < 4 * NT; ++q) {
+            const int tj = q * 4 + wave;
+            const int col = (nt0 + (tj >> 4)) * 32 + r;
+            const int row = row0 + mfma_row(tj & 15, kb);
+            const float v = fmaxf(z[q] + a.bias[col], 0.f);
+            if constexpr (BF16)
+                static_cast<__bf16*>(a.h)[(long)row * a.N + col] = (__bf16)v;
+            else
+                static_cast<float*>(a.h)[(long)row * a.N + col] = v;
+        }
+    } else {
+        constexpr int TW = 32 * NT;                 // tile width in classes
+        __shared__ float zt[32][TW + 1];
+        const int col_base = nt0 * 32;
+#pragma unroll
+        for (int q = 0; q < 4 * NT; ++q) {
+            const int tj = q * 4 + wave;
+            const int lc = (tj >> 4) * 32 + r;
+            const int col = col_base + lc;
+            const int lr = mfma_row(tj & 15, kb);
+            const bool valid = col < a.K;
+            const float v = z[q] + (valid ? a.bias[col] : 0.f);
+            if (a.logits && valid && row0 + lr < n) a.logits[(long)(row0 + lr) * a.K + col] = v;
+            zt[lr][lc] = valid ? v : -INFINITY;
+        }
+        __syncthreads();
+        // 8 lanes per row; lane `sub` takes classes sub, sub+8, ...
+        const int lr = tid >> 3, sub = tid & 7;
+        float bm = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int c = sub; c < TW; c += 8) {
+            const float v = zt[lr][c];
+            if (v > bm) { bm = v; bi = col_base + c; }     // ascending c: lowest index on equality
+        }
+#pragma unroll
+        for (int m = 4; m >= 1; m >>= 1) {
+            const float ov = __shfl_xor(bm, m, 64);
+            const int oi = __shfl_xor(bi, m, 64);
+            if (ov > bm || (ov == bm && oi < bi)) { bm = ov; bi = oi; }
+        }
+        float ps = 0.f, pt = 0.f;
+#pragma unroll
+        for (int c = sub; c < TW; c += 8) {
+            const float v = zt[lr][c];
+            if (v > -INFINITY) {
+                const float e = expf(v - bm);
+                ps += e;
+                pt = fmaf(e, a.ws_prob[col_base + c], pt);
+            }
+        }
+#pragma unroll
+        for (int m = 4; m >= 1; m >>= 1) {
+            ps += __shfl_xor(ps, m, 64);
+            pt += __shfl_xor(pt, m, 64);
+        }
+        if (sub == 0) {
+            TileStat s;
+            s.max = bm; s.sum = ps; s.wsum = pt; s.arg = bi;
+            a.stats[(long)(row0 + lr) * n_tiles_x + blockIdx.x] = s;
+        }
     }
 }
 
-struct Fc2Args {
-    const void* h;        // [rows_pad, Hp] bf16 or f32
-    const void* W2;       // [Kp, Hp] bf16 or f32, zero padded
-    const float* b2;      // [Kp]
-    const float* ws_prob; // [Kp] selector weights of the class probabilities, zero padded
-    const float* u_pool;  // [rows_pad]
+struct FinalizeArgs {
+    const TileStat* stats;   // [rows_pad, n_tiles]
+    int n_tiles;
+    const float* u_pool;     // [rows_pad]
     float bs, tau;
-    int Hp, K, Kp;
     int n_max;
     const int32_t* n_dev;
-    int32_t* pred_class;
-    float* confidence;
-    uint8_t* hit;
-    float* logits;        // [n, K] or null
+    int32_t* pred_class;     // [n]
+    float* confidence;       // [n]
+    uint8_t* hit;            // [n]
+    // optional fused miss compaction (ids_out null = lookup only)
+    const int32_t* ids_in;   // [n] or null (identity)
+    int32_t* ids_out;        // [n]
+    int32_t* n_miss;         // device scalar, may alias n_dev
 };
 
-// One workgroup of NW waves owns 32 rows.  Per pass it forms NW*TPW*32 logits per row in
-// registers (TPW 32x32 tiles per wave), then reduces them to the row's running maximum,
-// argmax, sum of exponentials and probability-weighted selector sum; wider class counts
-// take several passes with the usual rescaling by exp(old max - new max).  Finally
-// confidence = logistic(bs + u_pool + sum_k ws[k] prob[k]) and hit = confidence > tau.
-template <bool BF16, int TPW>
-__global__ __launch_bounds__(256) void fc2_head_kernel(Fc2Args a) {
-    using Step = MmaStep<BF16>;
-    constexpr int kPartials = 4 * 32;               // partial columns per row at most (4 waves)
-    __shared__ float s_f[32][kPartials + 1];
-    __shared__ float s_g[32][kPartials + 1];        // second float plane (reinterpreted as int for argmax)
-    __shared__ float row_max[32], row_sum[32], row_wsum[32];
-    __shared__ int row_arg[32];
-
-    const int n = active_rows(a.n_dev, a.n_max);
-    const int row0 = blockIdx.x * 32;
-    if (row0 >= n) return;
+// Combine the per-tile summaries of each row into class, confidence and hit flag
+// (confidence = logistic(bs + u_pool + sum_k ws[k] softmax(z)[k])), and, when asked, compact the
+// misses in the same pass: one workgroup of 1024 lanes, 1024 rows per step, wave ballots and a
+// scan of the 16 wave totals, order preserved.
+__global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
+    __shared__ int wave_total[16];
+    __shared__ int wave_offset[16];
+    __shared__ int carry, carry_next;
+    const int n = active_rows(a.n_dev, a.n_max);   // read before n_miss is written (they may alias)
     const int tid = threadIdx.x;
-    const int nw = blockDim.x >> 6;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int r = lane & 31, kb = lane >> 5;
-    const int tpr = blockDim.x >> 5;                // lanes that share one row in the reductions
-    const int red_row = tid / tpr, red_sub = tid - red_row * tpr;
-    const int npart = nw * 32;
+    const int lane = tid & 63, wave = tid >> 6;
+    const bool compact = a.ids_out != nullptr;
+    if (tid == 0) carry = 0;
 
-    if (tid < 32) { row_max[tid] = -INFINITY; row_sum[tid] = 0.f; row_wsum[tid] = 0.f; row_arg[tid] = 0; }
-    __syncthreads();
-
-    const int chunk_cols = nw * TPW * 32;
-    for (int chunk0 = 0; chunk0 < a.Kp; chunk0 += chunk_cols) {
-        const int colbase = chunk0 + wave * TPW * 32;
-        f32x16_t acc[TPW];
-#pragma unroll
-        for (int t = 0; t < TPW; ++t)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
-
-        if constexpr (BF16) {
-            const __bf16* arow = static_cast<const __bf16*>(a.h) + (long)(row0 + r) * a.Hp + kb * 8;
-            const __bf16* bbase = static_cast<const __bf16*>(a.W2) + (long)(colbase + r) * a.Hp + kb * 8;
-            for (int k0 = 0; k0 < a.Hp; k0 += 32) {   // Hp is a multiple of 32
-                const bf16x8_t a0 = Step::load_bf16(arow + k0);
-                const bf16x8_t a1 = Step::load_bf16(arow + k0 + 16);
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    if (colbase + t * 32 < a.Kp) {     // wave-uniform
-                        const __bf16* bp = bbase + (long)t * 32 * a.Hp + k0;
-                        const bf16x8_t b0 = Step::load_bf16(bp);
-                        const bf16x8_t b1 = Step::load_bf16(bp + 16);
-                        acc[t] = Step::mma(a0, b0, acc[t]);
-                        acc[t] = Step::mma(a1, b1, acc[t]);
-                    }
-                }
+    for (int base = 0; base < n; base += 1024) {
+        const int i = base + tid;
+        bool miss = false;
+        if (i < n) {
+            const TileStat* st = a.stats + (long)i * a.n_tiles;
+            float m = -INFINITY;
+            int arg = 0;
+            for (int t = 0; t < a.n_tiles; ++t) {
+                const TileStat s = st[t];
+                if (s.max > m) { m = s.max; arg = s.arg; }   // earlier tile keeps the class on equality
             }
-        } else {
-            const float* arow = static_cast<const float*>(a.h) + (long)(row0 + r) * a.Hp + kb * 4;
-            const float* bbase = static_cast<const float*>(a.W2) + (long)(colbase + r) * a.Hp + kb * 4;
-            for (int k0 = 0; k0 < a.Hp; k0 += 16) {
-                const float4 a0 = *reinterpret_cast<const float4*>(arow + k0);
-                const float4 a1 = *reinterpret_cast<const float4*>(arow + k0 + 8);
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    if (colbase + t * 32 < a.Kp) {
-                        const float* bp = bbase + (long)t * 32 * a.Hp + k0;
-                        const float4 b0 = *reinterpret_cast<const float4*>(bp);
-                        const float4 b1 = *reinterpret_cast<const float4*>(bp + 8);
-                        acc[t] = Step::mma(a0, b0, acc[t]);
-                        acc[t] = Step::mma(a1, b1, acc[t]);
-                    }
-                }
+            float sum = 0.f, wsum = 0.f;
+            for (int t = 0; t < a.n_tiles; ++t) {
+                const TileStat s = st[t];
+                const float w = expf(s.max - m);             // -inf tiles contribute 0
+                sum = fmaf(s.sum, w, sum);
+                wsum = fmaf(s.wsum, w, wsum);
             }
-        }
-
-        // logits of this pass: bias, optional store, mask of the padding classes
-        float wsq[TPW];
-        bool valid[TPW];
-#pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-            const int col = colbase + t * 32 + r;
-            valid[t] = col < a.K;
-            const float bias = valid[t] ? a.b2[col] : 0.f;
-            wsq[t] = valid[t] ? a.ws_prob[col] : 0.f;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const float z = acc[t][j] + bias;
-                acc[t][j] = valid[t] ? z : -INFINITY;
-                const int row = row0 + mfma_row(j, kb);
-                if (a.logits && valid[t] && row < n) a.logits[(long)row * a.K + col] = z;
-            }
-        }
-
-        // (1) row maximum and argmax (lowest index among equals)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            float pm = -INFINITY;
-            int pi = 0x7fffffff;
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                const float v = acc[t][j];
-                if (v > pm) { pm = v; pi = colbase + t * 32 + r; }
-            }
-            const int lr = mfma_row(j, kb);
-            s_f[lr][wave * 32 + r] = pm;
-            s_g[lr][wave * 32 + r] = __int_as_float(pi);
-        }
-        __syncthreads();
-        {
-            float bm = -INFINITY;
-            int bi = 0x7fffffff;
-            for (int c = red_sub; c < npart; c += tpr) {
-                const float v = s_f[red_row][c];
-                const int i = __float_as_int(s_g[red_row][c]);
-                if (v > bm || (v == bm && i < bi)) { bm = v; bi = i; }
-            }
-            for (int m = tpr >> 1; m >= 1; m >>= 1) {
-                const float ov = __shfl_xor(bm, m, 64);
-                const int oi = __shfl_xor(bi, m, 64);
-                if (ov > bm || (ov == bm && oi < bi)) { bm = ov; bi = oi; }
-            }
-            if (red_sub == 0) {
-                const float old = row_max[red_row];
-                if (bm > old) {                      // an earlier pass keeps the class on equality
-                    const float scale = expf(old - bm);   // old = -inf -> 0
-                    row_sum[red_row] *= scale;
-                    row_wsum[red_row] *= scale;
-                    row_max[red_row] = bm;
-                    row_arg[red_row] = bi;
-                }
-            }
-        }
-        __syncthreads();
-
-        // (2) sum of exponentials and selector-weighted sum, relative to the running maximum
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int lr = mfma_row(j, kb);
-            const float m = row_max[lr];
-            float ps = 0.f, pt = 0.f;
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                if (valid[t]) {
-                    const float e = expf(acc[t][j] - m);
-                    ps += e;
-                    pt = fmaf(e, wsq[t], pt);
-                }
-            }
-            s_f[lr][wave * 32 + r] = ps;
-            s_g[lr][wave * 32 + r] = pt;
-        }
-        __syncthreads();
-        {
-            float ss = 0.f, st = 0.f;
-            for (int c = red_sub; c < npart; c += tpr) { ss += s_f[red_row][c]; st += s_g[red_row][c]; }
-            for (int m = tpr >> 1; m >= 1; m >>= 1) {
-                ss += __shfl_xor(ss, m, 64);
-                st += __shfl_xor(st, m, 64);
-            }
-            if (red_sub == 0) { row_sum[red_row] += ss; row_wsum[red_row] += st; }
-        }
-        __syncthreads();
-    }
-
-    if (red_sub == 0) {
-        const int row = row0 + red_row;
-        if (row < n) {
-            const float u = a.bs + a.u_pool[row] + row_wsum[red_row] / row_sum[red_row];
+            const float u = a.bs + a.u_pool[i] + wsum / sum;
             const float conf = 1.f / (1.f + expf(-u));
-            a.pred_class[row] = row_arg[red_row];
-            a.confidence[row] = conf;
-            a.hit[row] = conf > a.tau ? 1 : 0;
+            const bool is_hit = conf > a.tau;
+            a.pred_class[i] = arg;
+            a.confidence[i] = conf;
+            a.hit[i] = is_hit ? 1 : 0;
+            miss = !is_hit;
+        }
+        if (compact) {
+            const unsigned long long mask = __ballot(miss);
+            const int before = __popcll(mask & ((1ull << lane) - 1ull));
+            if (lane == 0) wave_total[wave] = __popcll(mask);
+            __syncthreads();
+            if (tid < 16) {
+                const int v = wave_total[tid];
+                int incl = v;
+#pragma unroll
+                for (int d = 1; d < 16; d <<= 1) {
+                    const int o = __shfl_up(incl, d, 64);
+                    if (tid >= d) incl += o;
+                }
+                wave_offset[tid] = carry + incl - v;
+                if (tid == 15) carry_next = carry + incl;
+            }
+            __syncthreads();
+            if (miss) a.ids_out[wave_offset[wave] + before] = a.ids_in ? a.ids_in[i] : i;
+            if (tid == 0) carry = carry_next;
         }
     }
+    if (compact && tid == 0) *a.n_miss = carry;
 }
 
 }  // namespace gati

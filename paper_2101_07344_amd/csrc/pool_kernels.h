@@ -21,8 +21,15 @@ struct PoolArgs {
     int C, S;
     float inv_S;
     float* out;                // [n, out_stride] fp32
+    __bf16* out16;             // same values rounded to bf16 (nearest even), same stride; or null
     int out_stride;
 };
+
+// Store one pooled mean (and its bf16 copy, the FC1 operand of bf16 caches).
+__device__ __forceinline__ void store_pooled(const PoolArgs& a, long idx, float v) {
+    a.out[idx] = v;
+    if (a.out16) a.out16[idx] = (__bf16)v;
+}
 
 // ---------------------------------------------------------------------------------------
 // [n,C,S], S*elem a multiple of 16 bytes: one wave sums one channel at a time, CPI channels
@@ -83,7 +90,7 @@ __global__ __launch_bounds__(256) void pool_ncs_wave_kernel(PoolArgs a, int vpc)
             mine = (lane == q) ? t : mine;
         }
         if (lane < CPI && c0 + lane < a.C)
-            a.out[(long)i * a.out_stride + c0 + lane] = mine * a.inv_S;
+            store_pooled(a, (long)i * a.out_stride + c0 + lane, mine * a.inv_S);
     }
 }
 
@@ -158,7 +165,7 @@ __global__ __launch_bounds__(256) void pool_ncs_seg_kernel(PoolArgs a, int gt, i
             if (sub == 0 && (start % V) != 0) acc += sB[buf][lo - 1];
         }
         for (int m = tpc >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
-        if (live && sub == 0) a.out[(long)i * a.out_stride + c_first + lc] = acc * a.inv_S;
+        if (live && sub == 0) store_pooled(a, (long)i * a.out_stride + c_first + lc, acc * a.inv_S);
         // The other LDS buffer is written next; the barrier of the next iteration orders
         // this iteration's reads against the writes two iterations ahead.
     }
@@ -219,7 +226,7 @@ __global__ __launch_bounds__(256) void pool_nsc_kernel(PoolArgs a, int cvb_per_r
                 float s = 0.f;
 #pragma unroll
                 for (int g = 0; g < NG; ++g) s += red[g][e];
-                a.out[(long)i * a.out_stride + c] = s * a.inv_S;
+                store_pooled(a, (long)i * a.out_stride + c, s * a.inv_S);
             }
         }
         __syncthreads();
@@ -249,7 +256,7 @@ __global__ __launch_bounds__(256) void pool_generic_kernel(PoolArgs a, int nsc_l
             const uint16_t* x = static_cast<const uint16_t*>(a.act);
             for (int k = 0; k < a.S; ++k) s += __uint_as_float((uint32_t)x[first + k * step] << 16);
         }
-        a.out[i * a.out_stride + c] = s * a.inv_S;
+        store_pooled(a, i * a.out_stride + c, s * a.inv_S);
     }
 }
 

@@ -51,17 +51,19 @@ def test_tiny_config_single_cache():
 
 
 STACKS = [
-    # name, batch (ragged against the 32-row tiles), storage, per-layer hit target
-    ("resnet18", 40, "gather", 0.15),
-    ("resnet50", 37, "gather", 0.10),
-    ("resnet50", 33, "dense", 0.20),
-    ("bert_base", 70, "gather", 0.12),
-    ("bert_base", 45, "dense", 0.25),
+    # name, batch (ragged against the 32-row tiles), storage, per-layer hit target,
+    # fused (gati_cache_lookup_compact) or gati_cache_lookup + gati_compact_misses
+    ("resnet18", 40, "gather", 0.15, True),
+    ("resnet18", 40, "gather", 0.15, False),
+    ("resnet50", 37, "gather", 0.10, True),
+    ("resnet50", 33, "dense", 0.20, False),
+    ("bert_base", 70, "gather", 0.12, True),
+    ("bert_base", 45, "dense", 0.25, True),
 ]
 
 
-@pytest.mark.parametrize("name,batch,storage,rate", STACKS)
-def test_stack_matches_oracle(name, batch, storage, rate):
+@pytest.mark.parametrize("name,batch,storage,rate,fused", STACKS)
+def test_stack_matches_oracle(name, batch, storage, rate, fused):
     """Every layer's class / hit / miss list bit-exact, logits and confidences within
     tolerance, with the miss counts chained on the device."""
     base = W.get_workload(name)
@@ -79,7 +81,7 @@ def test_stack_matches_oracle(name, batch, storage, rate):
         dev_acts = [a.cuda() for a in acts]
     caches = [make_cache(g, L, w, batch) for L, w in zip(spec.layers, weights)]
     stack = g.CacheStack(caches, batch, storage=storage, keep_logits=True)
-    stack.run(dev_acts)
+    stack.run(dev_acts, fused=fused)
     torch.cuda.synchronize()
     counts = stack.counts.cpu().numpy()
     total_hits = 0
@@ -153,6 +155,15 @@ def test_empty_and_degenerate_active_sets():
     got = _lookup_gpu(cache, act, one, 1, None, L.K)
     want = oracle.lookup(defs[0], weights[0], W.to_host_array(acts[0]), row_index=np.array([63], np.int32))
     compare_lookup(got, want, None, "f32", "one row")
+    # fused call with nothing to look up: empty miss list
+    cnt = torch.tensor([5], dtype=torch.int32, device="cuda")
+    ids_out = torch.zeros(4, dtype=torch.int32, device="cuda")
+    assert g.gati_cache_lookup_compact(cache.handle, act, None, 0, None, None, None, None, None, None,
+                                       ids_out, cnt) == g.GATI_OK
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == 0
+    assert g.gati_cache_lookup_compact(cache.handle, act, None, 4, None, 16, 16, 16, None, None,
+                                       None, cnt) == g.GATI_ERR_INVALID_ARG
     # rejected arguments leave outputs alone
     assert g.gati_cache_lookup(cache.handle, act, None, spec.batch + 1, None, 16, 16, 16) == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_lookup(cache.handle, act, None, 4, None, None, 16, 16) == g.GATI_ERR_INVALID_ARG
