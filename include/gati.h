@@ -152,8 +152,8 @@ gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, co
 /* Static, never-NULL description of a status code. */
 const char *gati_status_string(gati_status_t status);
 
-/* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_seg",
- * "nsc_vec", "generic"); static string, for reports and profiles. */
+/* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_segw",
+ * "ncs_seg", "nsc_vec", "generic"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
 
 #ifdef __cplusplus

@@ -19,7 +19,7 @@ using namespace gati;
 
 namespace {
 
-enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3 };
+enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -70,7 +70,7 @@ struct gati_cache {
     int gt = 0, tiles_per_row = 0, tpc_log2 = 0;  // ncs_seg
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
-    int pool_blocks_per_cu = 8;
+    int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
     // head plan: column tiles per workgroup of the output layer
     int fc2_nt = 1;
 };
@@ -124,6 +124,27 @@ void plan_pool(gati_cache* c) {
         // smallest channel count whose byte size is a multiple of 16
         int g0 = 1;
         while (((long)g0 * S) % V != 0) ++g0;
+        c->magic_S = (unsigned)(((1ull << 32) / (unsigned long long)S) + 1ull);
+        // wave-granular tiles: at most 256 vectors and 64 channels per wave
+        {
+            int max_mult = (int)((256L * V) / ((long)g0 * S));
+            if (max_mult * g0 > 64) max_mult = 64 / g0;
+            if (max_mult >= 1) {
+                int mult = max_mult;
+                for (int m = max_mult; m >= (max_mult + 1) / 2; --m)
+                    if (C % (m * g0) == 0) { mult = m; break; }
+                int gt = mult * g0;
+                if (gt > C) gt = round_up(C, g0);
+                c->gt = gt;
+                c->tiles_per_row = (C + gt - 1) / gt;
+                int tpc_log2 = 0;
+                const int partials = (S + V - 1) / V + 1;
+                while ((gt << (tpc_log2 + 1)) <= 64 && (2 << tpc_log2) <= partials / 2) ++tpc_log2;
+                c->tpc_log2 = tpc_log2;
+                c->variant = POOL_NCS_SEGW;
+                return;
+            }
+        }
         const int max_mult = (int)((1024L * V) / ((long)g0 * S));   // tile <= 1024 vectors
         if (max_mult >= 1) {
             int mult = max_mult;
@@ -181,6 +202,12 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
         }
         break;
     }
+    case POOL_NCS_SEGW: {
+        const long tiles = (long)a.n_max * c->tiles_per_row;
+        const int blocks = (int)std::min<long>((tiles + 3) / 4, max_blocks);
+        pool_ncs_segw_kernel<Tag><<<blocks, 256, 0, st>>>(a, c->gt, c->tiles_per_row, c->tpc_log2, c->magic_S);
+        break;
+    }
     case POOL_NCS_SEG: {
         const long tiles = (long)a.n_max * c->tiles_per_row;
         const int blocks = (int)std::min<long>(tiles, max_blocks);
@@ -189,7 +216,7 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
     }
     case POOL_NSC_VEC: {
         const long items = (long)a.n_max * c->cvb_per_row;
-        const int blocks = (int)std::min<long>(items, max_blocks);
+        const int blocks = (int)std::min<long>((items + 3) / 4, max_blocks);
         if (c->gw == 64) pool_nsc_kernel<Tag, 64><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
         else if (c->gw == 32) pool_nsc_kernel<Tag, 32><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
         else pool_nsc_kernel<Tag, 16><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
@@ -229,7 +256,7 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
     f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
     f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
     f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp;
-    fc_kernel<BF16, 1, true><<<dim3(c->Hp / 32 + 1, row_tiles), 256, 0, st>>>(f1);
+    fc_kernel<BF16, 1, true><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -304,7 +331,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         c->num_cu = cus;
     else
         (void)hipGetLastError();
-    c->pool_blocks_per_cu = env_int("GATI_POOL_BLOCKS_PER_CU", 8);
+    c->pool_blocks_per_cu = env_int("GATI_POOL_BLOCKS_PER_CU", 16);
 
     plan_pool(c);
 
@@ -436,6 +463,7 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     switch (c->variant) {
     case POOL_NCS_WAVE: return "ncs_wave";
     case POOL_NCS_SEG: return "ncs_seg";
+    case POOL_NCS_SEGW: return "ncs_segw";
     case POOL_NSC_VEC: return "nsc_vec";
     default: return "generic";
     }

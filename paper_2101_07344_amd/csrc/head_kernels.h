@@ -80,9 +80,9 @@ struct FcArgs {
     TileStat* stats;       // [rows_pad, N/(32*NT)]
 };
 
-// grid = (N/(32*NT) [+1 when HIDDEN], ceil(n_max/32)), block = 256.
-// HIDDEN: epilogue bias + ReLU -> h; the extra column block computes the pooled-feature half
-// of the selector's dot product in fp32, overlapping with the MFMA tiles.
+// grid = (N/(32*NT), ceil(n_max/32)), block = 256.
+// HIDDEN: epilogue bias + ReLU -> h, plus a share of the pooled-feature half of the selector's
+// dot product (fp32).
 // !HIDDEN: epilogue bias -> logits (optional store) and the tile's softmax/argmax summary.
 template <bool BF16, int NT, bool HIDDEN>
 __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
@@ -99,31 +99,14 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     const int r = lane & 31, kb = lane >> 5;
     const int n_tiles_x = a.N / (32 * NT);
 
-    if (HIDDEN && (int)blockIdx.x == n_tiles_x) {
-        const f32x4_t* wv = reinterpret_cast<const f32x4_t*>(a.ws_pool);
-        const int nvec = a.ldp / 4;
-        for (int rr = wave * 8; rr < wave * 8 + 8 && row0 + rr < n; ++rr) {
-            const f32x4_t* pr = reinterpret_cast<const f32x4_t*>(a.p32 + (long)(row0 + rr) * a.ldp);
-            float acc = 0.f;
-            for (int k = lane; k < nvec; k += 64) {
-                const f32x4_t x = pr[k], w = wv[k];
-                acc = fmaf(x[0], w[0], acc); acc = fmaf(x[1], w[1], acc);
-                acc = fmaf(x[2], w[2], acc); acc = fmaf(x[3], w[3], acc);
-            }
-            acc = wave_sum(acc);
-            if (lane == 0) a.u_pool[row0 + rr] = acc;
-        }
-        return;
-    }
-
     // ---- split-K MFMA over this wave's quarter of the reduction axis ----
     const int KS = a.Kdim / kStep;
     const int ksw = KS >> 2;                    // k-steps per wave
     const int ks0 = wave * ksw;
     const int nt0 = blockIdx.x * NT;
+    // A advances kStep elements = 2 fragments of 16 bytes per k-step
     const frag_t* ap = reinterpret_cast<const frag_t*>(
         static_cast<const char*>(a.A) + ((long)(row0 + r) * a.Kdim + (long)ks0 * kStep + kb * kLane) * (BF16 ? 2 : 4));
-    // A advances kStep elements = 2 fragments of 16 bytes per k-step
     const frag_t* bp = reinterpret_cast<const frag_t*>(a.Wp) + ((long)nt0 * KS + ks0) * 64 + lane;
     const long b_tile = (long)KS * 64;          // fragments between consecutive column tiles
 
@@ -133,24 +116,41 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
 
-    int ks = 0;
-    for (; ks + 4 <= ksw; ks += 4) {
-        frag_t af[4], bf[NT][4];
+    // Software pipeline, U k-steps per stage: the loads of stage s+1 are issued before the
+    // MFMAs of stage s, so a wave always has a full stage of fragments in flight.  Slots past
+    // the end re-read the last k-step (in bounds) and are skipped by the MFMA loop.
+    constexpr int U = 4;
+    frag_t af[2][U], bf[2][NT][U];
+    const int last = ksw - 1;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            af[u] = ap[(ks + u) * 2];
+    for (int u = 0; u < U; ++u) {
+        const int k = min(u, last);
+        af[0][u] = ap[k * 2];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) bf[t][u] = bp[t * b_tile + (long)(ks + u) * 64];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t] = M::mma(af[u], bf[t][u], acc[t]);
+        for (int t = 0; t < NT; ++t) bf[0][t][u] = bp[t * b_tile + (long)k * 64];
     }
-    for (; ks < ksw; ++ks) {
-        const frag_t af = ap[ks * 2];
+    for (int ks = 0; ks < ksw; ks += 2 * U) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[t] = M::mma(af, bp[t * b_tile + (long)ks * 64], acc[t]);
+        for (int half = 0; half < 2; ++half) {
+            const int cur = ks + half * U;          // first k-step of the stage in buffer `half`
+            const int nxt = cur + U;
+            if (nxt < ksw) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int k = min(nxt + u, last);
+                    af[half ^ 1][u] = ap[k * 2];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) bf[half ^ 1][t][u] = bp[t * b_tile + (long)k * 64];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (cur + u < ksw) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc[t] = M::mma(af[half][u], bf[half][t][u], acc[t]);
+                }
+            }
+        }
     }
 
 #pragma unroll
@@ -178,6 +178,29 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
                 static_cast<__bf16*>(a.h)[(long)row * a.N + col] = (__bf16)v;
             else
                 static_cast<float*>(a.h)[(long)row * a.N + col] = v;
+        }
+        // Pooled-feature half of the selector, fp32: the 32 rows of the tile are shared out
+        // over the column blocks of the grid row; a block's 256 lanes stride over one row at a
+        // time and add up in a fixed order (lane partials -> wave butterfly -> 4 wave totals).
+        __shared__ float upart[4];
+        const int rpb = (32 + n_tiles_x - 1) / n_tiles_x;   // rows per block
+        const f32x4_t* wv = reinterpret_cast<const f32x4_t*>(a.ws_pool);
+        const int nvec = a.ldp / 4;
+        for (int q = 0; q < rpb; ++q) {
+            const int rr = blockIdx.x * rpb + q;            // block-uniform
+            if (rr >= 32 || row0 + rr >= n) break;
+            const f32x4_t* pr = reinterpret_cast<const f32x4_t*>(a.p32 + (long)(row0 + rr) * a.ldp);
+            float s = 0.f;
+            for (int k = tid; k < nvec; k += 256) {
+                const f32x4_t x = pr[k], w = wv[k];
+                s = fmaf(x[0], w[0], s); s = fmaf(x[1], w[1], s);
+                s = fmaf(x[2], w[2], s); s = fmaf(x[3], w[3], s);
+            }
+            s = wave_sum(s);
+            __syncthreads();                                // previous row's upart has been read
+            if (lane == 0) upart[wave] = s;
+            __syncthreads();
+            if (tid == 0) a.u_pool[row0 + rr] = (upart[0] + upart[1]) + (upart[2] + upart[3]);
         }
     } else {
         constexpr int TW = 32 * NT;                 // tile width in classes
@@ -268,18 +291,27 @@ __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
         bool miss = false;
         if (i < n) {
             const TileStat* st = a.stats + (long)i * a.n_tiles;
-            float m = -INFINITY;
+            float m = -INFINITY, sum = 0.f, wsum = 0.f;
             int arg = 0;
-            for (int t = 0; t < a.n_tiles; ++t) {
-                const TileStat s = st[t];
-                if (s.max > m) { m = s.max; arg = s.arg; }   // earlier tile keeps the class on equality
-            }
-            float sum = 0.f, wsum = 0.f;
-            for (int t = 0; t < a.n_tiles; ++t) {
-                const TileStat s = st[t];
-                const float w = expf(s.max - m);             // -inf tiles contribute 0
-                sum = fmaf(s.sum, w, sum);
-                wsum = fmaf(s.wsum, w, wsum);
+            // tiles in order, 8 at a time so their loads are in flight together; the running
+            // (max, sum, wsum) is rescaled when a later tile raises the maximum
+            for (int t0 = 0; t0 < a.n_tiles; t0 += 8) {
+                TileStat s[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s[u] = st[min(t0 + u, a.n_tiles - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (t0 + u < a.n_tiles && s[u].max > -INFINITY) {
+                        if (s[u].max > m) {                   // an earlier tile keeps the class on equality
+                            const float w = expf(m - s[u].max);   // m = -inf -> 0
+                            sum *= w; wsum *= w;
+                            m = s[u].max; arg = s[u].arg;
+                        }
+                        const float w = expf(s[u].max - m);
+                        sum = fmaf(s[u].sum, w, sum);
+                        wsum = fmaf(s[u].wsum, w, wsum);
+                    }
+                }
             }
             const float u = a.bs + a.u_pool[i] + wsum / sum;
             const float conf = 1.f / (1.f + expf(-u));

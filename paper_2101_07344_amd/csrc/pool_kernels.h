@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void pool_ncs_wave_kernel(PoolArgs a, int vpc)
 #pragma unroll
                 for (int u = 0; u < LPC; ++u) {
                     const int idx = b + u * 64 + lane;
-                    v[q][u] = base[(long)qc * vpc + min(idx, vpc - 1)];
+                    v[q][u] = load_stream(base + (long)qc * vpc + min(idx, vpc - 1));
                 }
             }
 #pragma unroll
@@ -91,6 +91,113 @@ __global__ __launch_bounds__(256) void pool_ncs_wave_kernel(PoolArgs a, int vpc)
         }
         if (lane < CPI && c0 + lane < a.C)
             store_pooled(a, (long)i * a.out_stride + c0 + lane, mine * a.inv_S);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// [n,C,S] with short or 16-byte-unaligned channels (S = 49, 196, 64, ...), wave-granular.
+// A sample's channels are one flat, contiguous stream, so a wave takes a tile of `gt` whole
+// channels whose byte size is a multiple of 16 (at most 256 vectors) and reads it with fully
+// coalesced 16-byte loads.  A vector may straddle one channel boundary (S >= elements per
+// vector): each lane splits its vector into the part that belongs to the channel of its
+// first element (a) and the part that belongs to the next channel (b) and parks both in the
+// wave's own LDS strip; then `tpc` lanes per channel add up that channel's partial sums in a
+// fixed order.  Nothing is shared between waves, so there is no workgroup barrier: the LDS
+// unit serves one wave's instructions in order.  The next tile's loads are issued before the
+// current tile's second phase, so every wave keeps a tile in flight.
+// Requirements (checked on the host): gt*S % kVec == 0, C*S % kVec == 0, gt*S/kVec <= 256,
+// S >= kVec, gt << tpc_log2 <= 64.
+// ---------------------------------------------------------------------------------------
+template <typename Tag>
+__global__ __launch_bounds__(256) void pool_ncs_segw_kernel(PoolArgs a, int gt, int tiles_per_row,
+                                                            int tpc_log2, unsigned magic_S) {
+    constexpr int V = Tag::kVec;
+    constexpr int J = 4;                 // loads per lane per tile
+    constexpr int kMaxVec = 64 * J;
+    __shared__ float sA[4][kMaxVec];
+    __shared__ float sB[4][kMaxVec];
+
+    const int n = active_rows(a.n_dev, a.n_max);
+    const unsigned total = (unsigned)n * (unsigned)tiles_per_row;
+    const int lane = threadIdx.x & 63;
+    const int wib = threadIdx.x >> 6;
+    const unsigned wave = blockIdx.x * (blockDim.x >> 6) + wib;
+    const unsigned nwaves = gridDim.x * (blockDim.x >> 6);
+    float* A = sA[wib];
+    float* B = sB[wib];
+    const int tpc = 1 << tpc_log2;
+    const int lc = lane >> tpc_log2;     // tile-local channel this lane helps to finish
+    const int sub = lane & (tpc - 1);
+
+    // tile w -> (active row i, first channel, channel count, base pointer)
+    auto tile_of = [&](unsigned w, unsigned& i, int& c_first, int& nch) -> const u32x4_t* {
+        i = w / (unsigned)tiles_per_row;
+        const int t = (int)(w - i * (unsigned)tiles_per_row);
+        const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+        c_first = t * gt;
+        nch = min(gt, a.C - c_first);
+        return reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) +
+                                                ((r * a.C + c_first) * (long)a.S) * Tag::kBytes);
+    };
+
+    u32x4_t v[J];
+    unsigned i = 0;
+    int c_first = 0, nch = 0;
+    if (wave < total) {
+        const u32x4_t* base = tile_of(wave, i, c_first, nch);
+        const int tv = (nch * a.S) / V;
+#pragma unroll
+        for (int j = 0; j < J; ++j) v[j] = load_stream(base + min(lane + 64 * j, tv - 1));
+    }
+    for (unsigned w = wave; w < total; w += nwaves) {
+        const int tile_vecs = (nch * a.S) / V;
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const int idx = lane + 64 * j;
+            if (idx < tile_vecs) {
+                const unsigned o = (unsigned)idx * V;            // first element, tile-local
+                const unsigned ch = __umulhi(o, magic_S);        // o / S
+                const int cnt = a.S - (int)(o - ch * (unsigned)a.S);  // elements left in that channel
+                float e[V];
+                vec_unpack<Tag>(v[j], e);
+                float pa = 0.f, pb = 0.f;
+#pragma unroll
+                for (int k = 0; k < V; ++k) {
+                    pa += (k < cnt) ? e[k] : 0.f;
+                    pb += (k < cnt) ? 0.f : e[k];
+                }
+                A[idx] = pa;
+                B[idx] = pb;
+            }
+        }
+        // this tile's identity, then start the next tile's loads
+        const unsigned ci = i;
+        const int cc = c_first, cn = nch;
+        const unsigned wn = w + nwaves;
+        if (wn < total) {
+            const u32x4_t* base = tile_of(wn, i, c_first, nch);
+            const int tv = (nch * a.S) / V;
+#pragma unroll
+            for (int j = 0; j < J; ++j) v[j] = load_stream(base + min(lane + 64 * j, tv - 1));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        float acc = 0.f;
+        const bool live = lc < cn;
+        if (live) {
+            const int start = lc * a.S;
+            const int lo = (start + V - 1) / V;
+            const int hi = (start + a.S + V - 1) / V;
+            for (int k = lo + sub; k < hi; k += tpc) acc += A[k];
+            if (sub == 0 && (start % V) != 0) acc += B[lo - 1];
+        }
+        for (int m = tpc >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+        if (live && sub == 0) store_pooled(a, (long)ci * a.out_stride + cc + lc, acc * a.inv_S);
+        // keep the next tile's LDS writes behind this tile's reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
@@ -134,7 +241,7 @@ __global__ __launch_bounds__(256) void pool_ncs_seg_kernel(PoolArgs a, int gt, i
         u32x4_t v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)   // unconditional, clamped into the tile; extras are ignored below
-            v[j] = base[min(tid + 256 * j, tile_vecs - 1)];
+            v[j] = load_stream(base + min(tid + 256 * j, tile_vecs - 1));
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int idx = tid + 256 * j;
@@ -172,25 +279,27 @@ __global__ __launch_bounds__(256) void pool_ncs_seg_kernel(PoolArgs a, int gt, i
 }
 
 // ---------------------------------------------------------------------------------------
-// [n,S,C] (tokens / channels-last): a lane owns one 16-byte vector of channels and walks
-// down the token axis.  A workgroup covers GW channel-vectors and splits the tokens over
-// its 256/GW lane groups; the groups' partial sums meet in LDS and are added in group order.
-// Requires C % kVec == 0.
+// [n,S,C] (tokens / channels-last), wave-granular: a lane owns one 16-byte vector of channels
+// and walks down the token axis.  A wave covers GW channel-vectors of one row and splits the
+// tokens over its 64/GW lane groups, whose partial sums are added with lane shuffles in a
+// fixed order; no LDS, no barrier.  Requires C % kVec == 0.
 // ---------------------------------------------------------------------------------------
 template <typename Tag, int GW>
 __global__ __launch_bounds__(256) void pool_nsc_kernel(PoolArgs a, int cvb_per_row) {
     constexpr int V = Tag::kVec;
-    constexpr int NG = 256 / GW;   // token slices
+    constexpr int NG = 64 / GW;    // token slices per wave
     constexpr int UN = 8;          // loads in flight per lane
-    __shared__ float red[NG][V * GW];
 
     const int n = active_rows(a.n_dev, a.n_max);
     const unsigned total = (unsigned)n * (unsigned)cvb_per_row;
-    const int gl = threadIdx.x % GW;
-    const int grp = threadIdx.x / GW;
+    const int lane = threadIdx.x & 63;
+    const unsigned wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const unsigned nwaves = gridDim.x * (blockDim.x >> 6);
+    const int gl = lane % GW;
+    const int grp = lane / GW;
     const int CV = a.C / V;
 
-    for (unsigned w = blockIdx.x; w < total; w += gridDim.x) {
+    for (unsigned w = wave; w < total; w += nwaves) {
         const unsigned i = w / (unsigned)cvb_per_row;
         const int cb = (int)(w - i * (unsigned)cvb_per_row);
         const long r = a.row_index ? (long)a.row_index[i] : (long)i;
@@ -206,7 +315,7 @@ __global__ __launch_bounds__(256) void pool_nsc_kernel(PoolArgs a, int cvb_per_r
             u32x4_t v[UN];
 #pragma unroll
             for (int u = 0; u < UN; ++u)   // unconditional, clamped to the last token
-                v[u] = base[(long)min(s0 + u * NG, a.S - 1) * CV];
+                v[u] = load_stream(base + (long)min(s0 + u * NG, a.S - 1) * CV);
 #pragma unroll
             for (int u = 0; u < UN; ++u) {
                 v[u] = keep_or_zero(v[u], ok && (s0 + u * NG < a.S));
@@ -216,20 +325,17 @@ __global__ __launch_bounds__(256) void pool_nsc_kernel(PoolArgs a, int cvb_per_r
                 for (int k = 0; k < V; ++k) acc[k] += e[k];
             }
         }
+        // add the token slices: lanes gl, gl+GW, gl+2GW, ... hold the same channels
 #pragma unroll
-        for (int k = 0; k < V; ++k) red[grp][k * GW + gl] = acc[k];
-        __syncthreads();
-        for (int e = threadIdx.x; e < V * GW; e += 256) {
-            const int k = e / GW, l = e - k * GW;
-            const int c = (cb * GW + l) * V + k;
-            if (c < a.C) {
-                float s = 0.f;
+        for (int m = 32; m >= GW; m >>= 1) {
 #pragma unroll
-                for (int g = 0; g < NG; ++g) s += red[g][e];
-                store_pooled(a, (long)i * a.out_stride + c, s * a.inv_S);
-            }
+            for (int k = 0; k < V; ++k) acc[k] += __shfl_xor(acc[k], m, 64);
         }
-        __syncthreads();
+        if (grp == 0 && ok) {
+            const long o = (long)i * a.out_stride + (long)cv * V;
+#pragma unroll
+            for (int k = 0; k < V; ++k) store_pooled(a, o + k, acc[k] * a.inv_S);
+        }
     }
 }
 

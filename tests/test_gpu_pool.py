@@ -30,18 +30,19 @@ def _act(n, C, S, dtype, layout, seed):
 
 SHAPES = [
     # (C, S, dtype, layout, expected variant)  -- every shape of the five workloads
-    (64, 64, "f32", "ncs", "ncs_seg"),
+    (64, 64, "f32", "ncs", "ncs_segw"),
     (64, 3136, "f32", "ncs", "ncs_wave"), (128, 784, "f32", "ncs", "ncs_wave"),
-    (256, 196, "f32", "ncs", "ncs_wave"), (512, 49, "f32", "ncs", "ncs_seg"),
+    (256, 196, "f32", "ncs", "ncs_wave"), (512, 49, "f32", "ncs", "ncs_segw"),
     (256, 3136, "bf16", "ncs", "ncs_wave"), (512, 784, "bf16", "ncs", "ncs_wave"),
-    (1024, 196, "bf16", "ncs", "ncs_seg"), (2048, 49, "bf16", "ncs", "ncs_seg"),
+    (1024, 196, "bf16", "ncs", "ncs_segw"), (2048, 49, "bf16", "ncs", "ncs_segw"),
     (768, 128, "bf16", "nsc", "nsc_vec"), (768, 128, "f32", "nsc", "nsc_vec"),
     # ragged / odd shapes
-    (24, 50, "bf16", "ncs", "ncs_seg"), (40, 49, "bf16", "ncs", "ncs_seg"), (12, 9, "f32", "ncs", "ncs_seg"),
+    (24, 50, "bf16", "ncs", "ncs_segw"), (40, 49, "bf16", "ncs", "ncs_segw"), (12, 9, "f32", "ncs", "ncs_segw"),
+    (16, 1001, "bf16", "ncs", "ncs_seg"), (24, 333, "f32", "ncs", "ncs_seg"),
     (7, 33, "f32", "ncs", "generic"), (5, 3, "bf16", "ncs", "generic"), (3, 5000, "bf16", "ncs", "ncs_wave"),
     (10, 1024 + 8, "bf16", "ncs", "ncs_wave"), (100, 37, "bf16", "nsc", "generic"),
     (104, 37, "bf16", "nsc", "nsc_vec"), (2056, 5, "f32", "nsc", "nsc_vec"), (8, 1, "bf16", "nsc", "nsc_vec"),
-    (130, 64, "f32", "ncs", "ncs_seg"),
+    (130, 64, "f32", "ncs", "ncs_segw"),
 ]
 
 
