@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
 
 # HBM traffic of the dominant pooling kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs (summaries under profiles/); keyed by workload.  None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"resnet50": 820_010_000}
 
 
 def log(*a):
@@ -138,9 +138,15 @@ def cpu_baseline(spec, weights, acts, stack, counts, budget_requests, torch, W):
                       f"({lookups} lookups, {dt:.1f} s, single thread, gcc -O2, fp64 accumulation)"}
 
 
-def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W):
+def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False):
     t_build = time.perf_counter()
     spec, labels, weights, caches, stack, acts = build_workload(name, torch, g, W)
+    if copy_probe:
+        dst = torch.empty_like(acts[0])
+        dst.copy_(acts[0])
+        torch.cuda.synchronize()
+        log(f"[{name}] copy probe: {acts[0].numel() * acts[0].element_size()} bytes read, same written")
+        del dst
     log(f"[{name}] inputs ready in {time.perf_counter() - t_build:.1f}s "
         f"({sum(a.numel() * a.element_size() for a in acts) / 1e9:.2f} GB of activations)")
     ms_step, wall_ms = time_stack(stack, acts, steps, warmup, torch)
@@ -211,6 +217,9 @@ def main():
                     help="requests of the batch the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", action="store_true", help="include the per-layer table in the JSON line")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain tensor copy of layer 0's activations (known size), the reference "
+                         "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -231,7 +240,7 @@ def main():
     stream = torch.cuda.Stream()          # default priority; every launch and event goes here
     with torch.cuda.stream(stream):
         spec, main_res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
-                                      args.cpu_requests, torch, g, W)
+                                      args.cpu_requests, torch, g, W, copy_probe=args.copy_probe)
         others = {}
         for name in [n for n in args.also.split(",") if n and n != args.workload]:
             _, r = run_workload(name, args.steps, args.warmup, False, 0, torch, g, W)

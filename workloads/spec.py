@@ -105,7 +105,12 @@ def _build():
 # resnet50: linear ramp whose product of miss rates leaves ~40 % after layer 16.
 # resnet152: 2 % -> 70 % linear ramp over the 50 layers.
 HIT_TARGETS = {
+    # resnet18 / bert_base: the configs leave the rate open; with random weights the
+    # un-tuned rate is degenerate (all or nothing), so a ramp in the shape of the paper's
+    # per-block hit-rate table is used: ~84 % and ~75 % cumulative by the last layer.
+    "resnet18": _linear_ramp(0.05, 0.35, 8),
     "resnet50": [0.0065 * (i + 1) for i in range(16)],
+    "bert_base": _linear_ramp(0.02, 0.20, 12),
     "resnet152": _linear_ramp(0.02, 0.70, 50),
 }
 
