@@ -167,6 +167,7 @@ class Cache:
                  max_rows: int, weights: dict):
         self.C, self.S, self.H, self.K = C_, S, H, K
         self.dtype, self.layout, self.max_rows = dtype, layout, max_rows
+        self.threshold = float(threshold)
         desc = CacheDesc(C_, S, H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
                          GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows)
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in ("W1", "b1", "W2", "b2", "ws")}
@@ -194,6 +195,7 @@ class Cache:
 
     def set_selector(self, bs: float, threshold: float):
         _check(gati_cache_set_selector(self.handle, bs, threshold), "gati_cache_set_selector")
+        self.threshold = float(threshold)
 
     @property
     def pool_variant(self) -> str:

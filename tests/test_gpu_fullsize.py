@@ -1,0 +1,136 @@
+"""Full-size workloads in the launch configuration bench.py times (device-chained fused
+stack over GPU-generated tensors): sampled rows against the oracle, plus properties that
+hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2101_07344_amd as g
+import workloads as W
+from oracle import admit
+
+from helpers import TOL, TOL_MIRROR_BF16
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-3
+
+
+def _build(name):
+    spec = W.get_workload(name)
+    labels = W.zipf_labels(spec.batch, spec.layers[0].K, spec.zipf_s, spec.seed)
+    weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
+    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w)
+              for L, w in zip(spec.layers, weights)]
+    return spec, labels, weights, caches
+
+
+def _check_sampled_rows(spec, l, d, w, act, rows_in_act, got, rng_rows):
+    """Oracle on a handful of rows of layer l.  rows_in_act[j] = row of `act` holding active row j."""
+    host = W.to_host_array(act[torch.from_numpy(rows_in_act[rng_rows].astype(np.int64)).cuda()])
+    want = oracle.lookup(d, w, host)
+    z = np.sort(want["logits"].astype(np.float64), axis=1)
+    gap = z[:, -1] - z[:, -2]
+    dist = np.abs(want["confidence"].astype(np.float64) - d.threshold)
+    tol = TOL_MIRROR_BF16 if spec.layers[l].dtype == "bf16" else TOL["f32"]
+    assert np.max(np.abs(got["logits"][rng_rows] - want["logits"])) <= tol, f"layer {l} logits"
+    assert np.max(np.abs(got["confidence"][rng_rows] - want["confidence"])) <= tol, f"layer {l} confidence"
+    sure_c, sure_h = gap >= MARGIN, dist >= MARGIN
+    assert np.array_equal(got["pred_class"][rng_rows][sure_c], want["pred_class"][sure_c]), f"layer {l} class"
+    assert np.array_equal(got["hit"][rng_rows][sure_h], want["hit"][sure_h]), f"layer {l} hit"
+    return int(sure_c.sum()), int(sure_h.sum())
+
+
+def _check_chain_properties(stack, batch, n_layers):
+    counts = stack.counts.cpu().numpy()
+    assert counts[0] == batch
+    seen = []
+    for l in range(n_layers):
+        n, m = int(counts[l]), int(counts[l + 1])
+        ids = stack.ids[l].cpu().numpy()[:n]
+        hit = stack.hit[l].cpu().numpy()[:n]
+        nxt = stack.ids[l + 1].cpu().numpy()[:m]
+        assert m == n - int((hit != 0).sum()), f"layer {l}: miss count"
+        assert np.array_equal(nxt, ids[hit == 0]), f"layer {l}: miss list is not the stable compaction"
+        cls = stack.pred_class[l].cpu().numpy()[:n]
+        assert cls.min(initial=0) >= 0 and cls.max(initial=0) < stack.caches[l].K
+        conf = stack.confidence[l].cpu().numpy()[:n]
+        assert np.all((conf >= 0) & (conf <= 1))
+        assert np.array_equal(hit, (conf > np.float32(stack.caches[l].threshold)).astype(np.uint8))
+        seen.append(ids[hit != 0])
+    seen.append(stack.ids[n_layers].cpu().numpy()[:int(counts[n_layers])])
+    allv = np.concatenate(seen)
+    assert np.array_equal(np.sort(allv), np.arange(batch)), "every request ends in exactly one place"
+    return counts
+
+
+@pytest.mark.parametrize("name,rows_per_layer", [("resnet18", 6), ("resnet50", 5), ("bert_base", 8)])
+def test_full_batch_gather_stack(name, rows_per_layer):
+    spec, labels, weights, caches = _build(name)
+    defs = admit.cache_defs(spec, mirror=True)
+    acts = [W.activation_bulk(spec, l, labels, np.arange(spec.batch), device="cuda")
+            for l in range(len(spec.layers))]
+    stack = g.CacheStack(caches, spec.batch, storage="gather", keep_logits=True)
+    stack.run(acts)
+    stack.run(acts)                      # a second pass over the same state gives the same result
+    torch.cuda.synchronize()
+    counts = _check_chain_properties(stack, spec.batch, len(caches))
+    rng = np.random.default_rng(7)
+    checked = 0
+    for l in range(len(caches)):
+        n = int(counts[l])
+        if n == 0:
+            continue
+        pick = rng.choice(n, size=min(rows_per_layer, n), replace=False)
+        ids = stack.ids[l].cpu().numpy()[:n]
+        got = {"logits": stack.logits[l].cpu().numpy(), "confidence": stack.confidence[l].cpu().numpy(),
+               "pred_class": stack.pred_class[l].cpu().numpy(), "hit": stack.hit[l].cpu().numpy()}
+        c, h = _check_sampled_rows(spec, l, defs[l], weights[l], acts[l], ids, got, pick)
+        checked += c + h
+    assert checked > 0
+    hit_total = spec.batch - int(counts[len(caches)])
+    assert 0.3 * spec.batch < hit_total < 0.95 * spec.batch     # the fitted ramps land in range
+    stack.close()
+
+
+def test_resnet152_streaming_dense_stack():
+    """4096 requests over 50 caches, each layer stored only for the rows still active."""
+    spec, labels, weights, caches = _build("resnet152")
+    defs = admit.cache_defs(spec, mirror=True)
+    stack = g.CacheStack(caches, spec.batch, storage="dense", keep_logits=False)
+    es, base = stack.counts.element_size(), stack.counts.data_ptr()
+    acts, active = [], np.arange(spec.batch)
+    for l, cache in enumerate(caches):            # pass 1: build the dense tensors layer by layer
+        a = W.activation_bulk(spec, l, labels, active if len(active) else np.arange(1), device="cuda")
+        acts.append(a)
+        cache.lookup_compact(a, None, spec.batch, base + l * es, stack.pred_class[l], stack.confidence[l],
+                             stack.hit[l], None, stack.ids[l], stack.ids[l + 1], base + (l + 1) * es)
+        torch.cuda.synchronize()
+        m = int(stack.counts[l + 1].item())
+        active = stack.ids[l + 1][:m].cpu().numpy().astype(np.int64)
+    first = [stack.hit[l].clone() for l in range(len(caches))]
+    stack.run(acts)                                # pass 2: the chained replay bench.py times
+    torch.cuda.synchronize()
+    counts = _check_chain_properties(stack, spec.batch, len(caches))
+    for l in range(len(caches)):
+        n = int(counts[l])
+        assert torch.equal(first[l][:n], stack.hit[l][:n])
+    assert counts[len(caches)] < 8 and counts[10] > 1000      # 2 % -> 70 % ramp: runs dry near layer 30
+    assert (counts[:len(caches)] == 0).any()                   # the empty-set case is exercised
+    # sampled rows against the oracle on a few layers (dense: active row j is row j of the tensor)
+    rng = np.random.default_rng(3)
+    for l in (0, 3, 12, 20):
+        n = int(counts[l])
+        if n == 0:
+            continue
+        pick = rng.choice(n, size=min(4, n), replace=False)
+        logits = torch.zeros(spec.batch, spec.layers[l].K, device="cuda")
+        pc, cf, ht = (torch.zeros(spec.batch, dtype=torch.int32, device="cuda"), torch.zeros(spec.batch, device="cuda"),
+                      torch.zeros(spec.batch, dtype=torch.uint8, device="cuda"))
+        caches[l].lookup(acts[l], None, spec.batch, base + l * es, pc, cf, ht, logits)
+        torch.cuda.synchronize()
+        got = {"logits": logits.cpu().numpy(), "confidence": cf.cpu().numpy(), "pred_class": pc.cpu().numpy(),
+               "hit": ht.cpu().numpy()}
+        _check_sampled_rows(spec, l, defs[l], weights[l], acts[l], np.arange(n), got, pick)
+    stack.close()
