@@ -85,26 +85,36 @@ def time_stack(stack, acts, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def time_pool_launches(spec, caches, stack, acts, counts, reps, torch):
-    """HIP events around every pooling launch, all layers in stack order so that no layer
-    is re-read from cache; same kernel, launch shape, row lists and device counts as in a
-    stack pass.  Returns per-layer mean duration in ms."""
+def time_pool_launches(spec, caches, stack, acts, keys, reps, torch):
+    """HIP events around the pooling launches, all layers in stack order so that no layer is
+    re-read from cache; same kernels, launch shapes, row lists and device counts as in a stack
+    pass.  Consecutive layers that run the same kernel instance share one event pair (their
+    launches queue back to back, as they do behind the head kernels in a real pass), so the
+    figure is kernel time plus launch-to-launch gaps, not host enqueue latency.
+    Returns per-layer mean duration in ms (a group's time is split by algorithmic bytes)."""
     L = len(caches)
     pooled = [torch.empty(spec.batch, c.C, dtype=torch.float32, device="cuda") for c in caches]
     es, base = stack.counts.element_size(), stack.counts.data_ptr()
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+    groups = []                         # [first, last] layer index of each run of equal keys
+    for l in range(L):
+        if groups and keys[groups[-1][0]] == keys[l]:
+            groups[-1][1] = l
+        else:
+            groups.append([l, l])
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in groups]
           for _ in range(reps)]
     for r in range(-1, reps):           # r = -1: warm-up
-        for l, c in enumerate(caches):
-            row_index = stack.ids[l] if spec.storage == "gather" else None
+        for gi, (lo, hi) in enumerate(groups):
             if r >= 0:
-                ev[r][l][0].record()
-            c.pool(acts[l], row_index, spec.batch, base + l * es, pooled[l])
+                ev[r][gi][0].record()
+            for l in range(lo, hi + 1):
+                row_index = stack.ids[l] if spec.storage == "gather" else None
+                caches[l].pool(acts[l], row_index, spec.batch, base + l * es, pooled[l])
             if r >= 0:
-                ev[r][l][1].record()
+                ev[r][gi][1].record()
     torch.cuda.synchronize()
-    ms = np.array([[a.elapsed_time(b) for a, b in row] for row in ev])
-    return ms.mean(axis=0)
+    ms = np.array([[a.elapsed_time(b) for a, b in row] for row in ev]).mean(axis=0)
+    return groups, ms
 
 
 def cpu_baseline(spec, weights, acts, stack, counts, budget_requests, torch, W):
@@ -155,21 +165,26 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
     lookups = int(counts[:n_layers].sum())
     hits = [(int(counts[l] - counts[l + 1]) / int(counts[l])) if counts[l] else None for l in range(n_layers)]
 
-    pool_ms = time_pool_launches(spec, caches, stack, acts, counts, max(3, min(steps, 20)), torch)
     elem = spec.layers[0].elem_bytes
+    keys = [f"{c.pool_variant}[C={L.C},S={L.S},{L.dtype}]" for L, c in zip(spec.layers, caches)]
+    algo = [int(counts[l]) * L.C * L.S * elem + int(counts[l]) * L.C * 4      # activation read + pooled write
+            for l, L in enumerate(spec.layers)]
+    groups, group_ms = time_pool_launches(spec, caches, stack, acts, keys, max(3, min(steps, 20)), torch)
     per_layer, by_kernel = [], {}
-    for l, (L, c) in enumerate(zip(spec.layers, caches)):
-        n = int(counts[l])
-        algo = n * L.C * L.S * elem + n * L.C * 4          # activation read + pooled write
-        gbs = algo / (pool_ms[l] * 1e-3) / 1e9 if n else 0.0
-        key = f"{c.pool_variant}[C={L.C},S={L.S},{L.dtype}]"
-        per_layer.append({"layer": l, "n": n, "kernel": key, "pool_us": round(float(pool_ms[l]) * 1e3, 2),
-                          "pool_GBps": round(gbs, 1), "hit_rate": None if hits[l] is None else round(hits[l], 4)})
-        k = by_kernel.setdefault(key, {"bytes": 0, "ms": 0.0, "launches": 0})
-        if n:
-            k["bytes"] += algo
-            k["ms"] += float(pool_ms[l])
-            k["launches"] += 1
+    for (lo, hi), gms in zip(groups, group_ms):
+        gbytes = sum(algo[lo:hi + 1])
+        k = by_kernel.setdefault(keys[lo], {"bytes": 0, "ms": 0.0, "launches": 0})
+        for l in range(lo, hi + 1):
+            n = int(counts[l])
+            share = float(gms) * (algo[l] / gbytes) if gbytes else 0.0
+            per_layer.append({"layer": l, "n": n, "kernel": keys[l], "pool_us": round(share * 1e3, 2),
+                              "pool_GBps": round(algo[l] / (share * 1e-3) / 1e9, 1) if share else 0.0,
+                              "hit_rate": None if hits[l] is None else round(hits[l], 4)})
+            if n:
+                k["bytes"] += algo[l]
+                k["launches"] += 1
+        if gbytes:
+            k["ms"] += float(gms)
     # dominant kernel = the pooling instance that takes the most time in a pass
     dom_key = max(by_kernel, key=lambda kk: by_kernel[kk]["ms"])
     dom = by_kernel[dom_key]

@@ -153,7 +153,7 @@ gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, co
 const char *gati_status_string(gati_status_t status);
 
 /* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_segw",
- * "ncs_seg", "nsc_vec", "generic"); static string, for reports and profiles. */
+ * "ncs_seg", "nsc_row", "nsc_vec", "generic"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
 
 #ifdef __cplusplus

@@ -217,13 +217,16 @@ class CacheStack:
     """A stack of caches with the device buffers one pass needs, chained on the device:
     layer l+1 looks up only layer l's misses, and the miss count never visits the host."""
 
-    def __init__(self, caches: Sequence[Cache], batch: int, storage: str = "gather", keep_logits: bool = False):
+    def __init__(self, caches: Sequence[Cache], batch: int, storage: str = "gather", keep_logits: bool = False,
+                 first_id: int = 0):
+        """first_id: request id of this stack's first row (a stack may own a slice of a larger
+        batch whose activation tensors are indexed by global request id)."""
         import torch
         self.caches, self.batch, self.storage = list(caches), batch, storage
         dev = "cuda"
         L = len(self.caches)
         self.ids = [torch.empty(batch, dtype=torch.int32, device=dev) for _ in range(L + 1)]
-        self.ids[0].copy_(torch.arange(batch, dtype=torch.int32))
+        self.ids[0].copy_(torch.arange(first_id, first_id + batch, dtype=torch.int32))
         self.counts = torch.zeros(L + 1, dtype=torch.int32, device=dev)
         self.counts[0] = batch
         self.pred_class = [torch.zeros(batch, dtype=torch.int32, device=dev) for _ in range(L)]
@@ -237,20 +240,25 @@ class CacheStack:
         the full batch indexed by request id ("gather"), or the rows still active in
         miss-list order ("dense").  fused: one gati_cache_lookup_compact per layer instead of
         gati_cache_lookup + gati_compact_misses (same results)."""
+        for l in range(len(self.caches)):
+            self.run_layer(l, acts[l], stream, fused)
+
+    def run_layer(self, l: int, act, stream=None, fused: bool = True):
+        """Enqueue layer l alone (lookup of the rows still active + compaction of its misses)."""
         es = self.counts.element_size()
         cbase = self.counts.data_ptr()
-        for l, cache in enumerate(self.caches):
-            n_dev = cbase + l * es
-            row_index = self.ids[l] if self.storage == "gather" else None
-            if fused:
-                cache.lookup_compact(acts[l], row_index, self.batch, n_dev, self.pred_class[l],
-                                     self.confidence[l], self.hit[l], self.logits[l], self.ids[l],
-                                     self.ids[l + 1], cbase + (l + 1) * es, stream)
-            else:
-                cache.lookup(acts[l], row_index, self.batch, n_dev, self.pred_class[l], self.confidence[l],
-                             self.hit[l], self.logits[l], stream)
-                cache.compact(self.hit[l], self.ids[l], self.batch, n_dev, self.ids[l + 1],
-                              cbase + (l + 1) * es, stream)
+        cache = self.caches[l]
+        n_dev = cbase + l * es
+        row_index = self.ids[l] if self.storage == "gather" else None
+        if fused:
+            cache.lookup_compact(act, row_index, self.batch, n_dev, self.pred_class[l],
+                                 self.confidence[l], self.hit[l], self.logits[l], self.ids[l],
+                                 self.ids[l + 1], cbase + (l + 1) * es, stream)
+        else:
+            cache.lookup(act, row_index, self.batch, n_dev, self.pred_class[l], self.confidence[l],
+                         self.hit[l], self.logits[l], stream)
+            cache.compact(self.hit[l], self.ids[l], self.batch, n_dev, self.ids[l + 1],
+                          cbase + (l + 1) * es, stream)
 
     def close(self):
         for c in self.caches:

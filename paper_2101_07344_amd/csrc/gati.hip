@@ -3,6 +3,7 @@
 // the choice of kernel variant per shape.  gfx950 only.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -19,7 +20,7 @@ using namespace gati;
 
 namespace {
 
-enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4 };
+enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_ROW = 5 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -70,6 +71,7 @@ struct gati_cache {
     int gt = 0, tiles_per_row = 0, tpc_log2 = 0;  // ncs_seg
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
+    int nsc_lpt = 1, cb_per_row = 0, nsc_nw = 4;  // nsc_row
     int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
     // head plan: column tiles per workgroup of the output layer
     int fc2_nt = 1;
@@ -108,6 +110,13 @@ void plan_pool(gati_cache* c) {
             c->gw = best;
             c->cvb_per_row = (CV + best - 1) / best;
             c->variant = POOL_NSC_VEC;
+            // enough tokens for four slices of several tokens each: stream whole token rows
+            if (S >= 32 && env_int("GATI_NSC_ROW", 1) == 1) {
+                c->nsc_lpt = std::min(4, (CV + 63) / 64);
+                c->cb_per_row = (CV + 64 * c->nsc_lpt - 1) / (64 * c->nsc_lpt);
+                c->nsc_nw = (S >= 128 && env_int("GATI_NSC_NW", 4) == 16) ? 16 : 4;
+                c->variant = POOL_NSC_ROW;
+            }
         }
         return;
     }
@@ -220,6 +229,26 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
         if (c->gw == 64) pool_nsc_kernel<Tag, 64><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
         else if (c->gw == 32) pool_nsc_kernel<Tag, 32><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
         else pool_nsc_kernel<Tag, 16><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
+        break;
+    }
+    case POOL_NSC_ROW: {
+        const long items = (long)a.n_max * c->cb_per_row;
+        const int blocks = (int)std::min<long>(items, max_blocks);
+        if (c->nsc_nw == 16) {
+            switch (c->nsc_lpt) {
+            case 1: pool_nsc_row_kernel<Tag, 1, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
+            case 2: pool_nsc_row_kernel<Tag, 2, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
+            case 3: pool_nsc_row_kernel<Tag, 3, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
+            default: pool_nsc_row_kernel<Tag, 4, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
+            }
+        } else {
+            switch (c->nsc_lpt) {
+            case 1: pool_nsc_row_kernel<Tag, 1, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
+            case 2: pool_nsc_row_kernel<Tag, 2, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
+            case 3: pool_nsc_row_kernel<Tag, 3, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
+            default: pool_nsc_row_kernel<Tag, 4, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
+            }
+        }
         break;
     }
     default: {
@@ -465,6 +494,7 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     case POOL_NCS_SEG: return "ncs_seg";
     case POOL_NCS_SEGW: return "ncs_segw";
     case POOL_NSC_VEC: return "nsc_vec";
+    case POOL_NSC_ROW: return "nsc_row";
     default: return "generic";
     }
 }

@@ -22,6 +22,7 @@
 #pragma once
 
 #include "common.h"
+#include "compact_kernels.h"
 
 namespace gati {
 
@@ -80,6 +81,40 @@ struct FcArgs {
     TileStat* stats;       // [rows_pad, N/(32*NT)]
 };
 
+// One row's class, confidence and hit flag from its per-tile summaries: tiles in order, the
+// running (max, sum, wsum) rescaled when a later tile raises the maximum;
+// confidence = logistic(bs + u_pool + sum_k ws[k] softmax(z)[k]).
+__device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, float u_pool, float bs, float tau,
+                                           int32_t* cls_out, float* conf_out, uint8_t* hit_out) {
+    float m = -INFINITY, sum = 0.f, wsum = 0.f;
+    int arg = 0;
+    for (int t0 = 0; t0 < n_tiles; t0 += 8) {
+        TileStat s[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s[u] = st[min(t0 + u, n_tiles - 1)];   // 8 loads in flight together
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (t0 + u < n_tiles && s[u].max > -INFINITY) {
+                if (s[u].max > m) {                       // an earlier tile keeps the class on equality
+                    const float w = expf(m - s[u].max);   // m = -inf -> 0
+                    sum *= w; wsum *= w;
+                    m = s[u].max; arg = s[u].arg;
+                }
+                const float w = expf(s[u].max - m);
+                sum = fmaf(s[u].sum, w, sum);
+                wsum = fmaf(s[u].wsum, w, wsum);
+            }
+        }
+    }
+    const float u = bs + u_pool + wsum / sum;
+    const float conf = 1.f / (1.f + expf(-u));
+    const bool is_hit = conf > tau;
+    *cls_out = arg;
+    *conf_out = conf;
+    *hit_out = is_hit ? 1 : 0;
+    return is_hit;
+}
+
 // grid = (N/(32*NT), ceil(n_max/32)), block = 256.
 // HIDDEN: epilogue bias + ReLU -> h, plus a share of the pooled-feature half of the selector's
 // dot product (fp32).
@@ -93,8 +128,8 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
 
     const int n = active_rows(a.n_dev, a.n_max);
     const int row0 = blockIdx.y * 32;
-    if (row0 >= n) return;
     const int tid = threadIdx.x;
+    if (row0 >= n) return;
     const int wave = tid >> 6, lane = tid & 63;
     const int r = lane & 31, kb = lane >> 5;
     const int n_tiles_x = a.N / (32 * NT);
@@ -272,77 +307,28 @@ struct FinalizeArgs {
     int32_t* n_miss;         // device scalar, may alias n_dev
 };
 
-// Combine the per-tile summaries of each row into class, confidence and hit flag
-// (confidence = logistic(bs + u_pool + sum_k ws[k] softmax(z)[k])), and, when asked, compact the
-// misses in the same pass: one workgroup of 1024 lanes, 1024 rows per step, wave ballots and a
-// scan of the 16 wave totals, order preserved.
+// The finish: one workgroup of 1024 lanes, 1024 rows per step, turns each row's tile summaries
+// into class / confidence / hit; with ids_out it also compacts the misses in the same pass.
+// (Folding this into the output-layer kernel through last-arriver tickets was tried and lost:
+// device-scope fences between workgroups on different XCDs cost more than the extra launch.)
 __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
-    __shared__ int wave_total[16];
-    __shared__ int wave_offset[16];
-    __shared__ int carry, carry_next;
+    __shared__ CompactState<16> st;
     const int n = active_rows(a.n_dev, a.n_max);   // read before n_miss is written (they may alias)
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
     const bool compact = a.ids_out != nullptr;
-    if (tid == 0) carry = 0;
-
+    if (tid == 0) st.carry = 0;
     for (int base = 0; base < n; base += 1024) {
         const int i = base + tid;
         bool miss = false;
-        if (i < n) {
-            const TileStat* st = a.stats + (long)i * a.n_tiles;
-            float m = -INFINITY, sum = 0.f, wsum = 0.f;
-            int arg = 0;
-            // tiles in order, 8 at a time so their loads are in flight together; the running
-            // (max, sum, wsum) is rescaled when a later tile raises the maximum
-            for (int t0 = 0; t0 < a.n_tiles; t0 += 8) {
-                TileStat s[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) s[u] = st[min(t0 + u, a.n_tiles - 1)];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if (t0 + u < a.n_tiles && s[u].max > -INFINITY) {
-                        if (s[u].max > m) {                   // an earlier tile keeps the class on equality
-                            const float w = expf(m - s[u].max);   // m = -inf -> 0
-                            sum *= w; wsum *= w;
-                            m = s[u].max; arg = s[u].arg;
-                        }
-                        const float w = expf(s[u].max - m);
-                        sum = fmaf(s[u].sum, w, sum);
-                        wsum = fmaf(s[u].wsum, w, wsum);
-                    }
-                }
-            }
-            const float u = a.bs + a.u_pool[i] + wsum / sum;
-            const float conf = 1.f / (1.f + expf(-u));
-            const bool is_hit = conf > a.tau;
-            a.pred_class[i] = arg;
-            a.confidence[i] = conf;
-            a.hit[i] = is_hit ? 1 : 0;
-            miss = !is_hit;
-        }
+        if (i < n)
+            miss = !finish_row(a.stats + (long)i * a.n_tiles, a.n_tiles, a.u_pool[i], a.bs, a.tau,
+                                      &a.pred_class[i], &a.confidence[i], &a.hit[i]);
         if (compact) {
-            const unsigned long long mask = __ballot(miss);
-            const int before = __popcll(mask & ((1ull << lane) - 1ull));
-            if (lane == 0) wave_total[wave] = __popcll(mask);
-            __syncthreads();
-            if (tid < 16) {
-                const int v = wave_total[tid];
-                int incl = v;
-#pragma unroll
-                for (int d = 1; d < 16; d <<= 1) {
-                    const int o = __shfl_up(incl, d, 64);
-                    if (tid >= d) incl += o;
-                }
-                wave_offset[tid] = carry + incl - v;
-                if (tid == 15) carry_next = carry + incl;
-            }
-            __syncthreads();
-            if (miss) a.ids_out[wave_offset[wave] + before] = a.ids_in ? a.ids_in[i] : i;
-            if (tid == 0) carry = carry_next;
+            const int slot = compact_step<16>(st, miss, tid);
+            if (slot >= 0) a.ids_out[slot] = a.ids_in ? a.ids_in[i] : i;
         }
     }
-    if (compact && tid == 0) *a.n_miss = carry;
+    if (compact && tid == 0) *a.n_miss = st.carry;
 }
 
 }  // namespace gati
