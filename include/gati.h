@@ -56,6 +56,13 @@ typedef enum {
     GATI_LAYOUT_NSC = 1  /* [n, S, C]: token-major / channels-last, C contiguous              */
 } gati_layout_t;
 
+/* How a hit is decided.
+ *   GATI_SEL_LINEAR   the selector network: logistic of an affine map over [pooled ; prob]
+ *   GATI_SEL_SOFTMAX  no selector network: confidence = largest class probability, the
+ *                     softmax-threshold baseline the paper compares against (Appendix,
+ *                     "Decoupling prediction and selection"); ws and bs are ignored      */
+typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1 } gati_selector_t;
+
 /* Shape of one learned cache (Section 3: predictor Input -> Hidden(h) -> Output, selector).
  *   C, S       activation channels and reduced length (pool extent = all of S)
  *   H, K       predictor hidden width and number of classes
@@ -64,13 +71,15 @@ typedef enum {
  *              operands (pooled, hidden) rounded to bf16 (nearest even), fp32 accumulation.
  *              Pooling, biases, softmax, selector and sigmoid are fp32 in both.
  *   threshold  tau; a row is a hit iff confidence > tau (strictly)
- *   max_rows   largest n_max any later call may pass (sizes the library's workspace)   */
+ *   max_rows   largest n_max any later call may pass (sizes the library's workspace)
+ *   selector   how the hit flag is decided, see gati_selector_t                              */
 typedef struct {
     int32_t C, S, H, K;
     gati_dtype_t act_dtype;
     gati_layout_t layout;
     float threshold;
     int32_t max_rows;
+    gati_selector_t selector;
 } gati_cache_desc_t;
 
 /* Weights, HOST pointers, fp32, row-major [out, in].  Copied (and converted) by

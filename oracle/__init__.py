@@ -33,7 +33,7 @@ def build(force: bool = False) -> str:
 class _Desc(C.Structure):
     _fields_ = [("C", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("K", C.c_int32),
                 ("act_dtype", C.c_int32), ("layout", C.c_int32), ("round_operands", C.c_int32),
-                ("threshold", C.c_float)]
+                ("threshold", C.c_float), ("selector", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -83,11 +83,12 @@ class CacheDef:
     layout: str = "ncs"         # "ncs" | "nsc"
     threshold: float = 0.5
     round_operands: bool = False  # bf16 cache arithmetic (see gati_oracle.c)
+    selector: str = "linear"    # "linear": selector network; "softmax": threshold on the top class probability
 
     def _c(self) -> _Desc:
         return _Desc(self.C, self.S, self.H, self.K, BF16 if self.dtype == "bf16" else F32,
                      NSC if self.layout == "nsc" else NCS, 1 if self.round_operands else 0,
-                     float(self.threshold))
+                     float(self.threshold), 1 if self.selector == "softmax" else 0)
 
 
 def _weights_c(w: dict, keep: list) -> _Weights:

@@ -38,6 +38,9 @@ typedef struct {
                                 are rounded to bf16 (nearest even) before each product;
                                 0: nothing is rounded ("ideal" arithmetic)                 */
     float   threshold;       /* tau: hit iff confidence > tau (strict)                    */
+    int32_t selector;        /* 0: selector network (affine map over [pooled ; prob], logistic)
+                                1: no selector network: confidence = largest class probability
+                                   (the softmax-threshold baseline of the design analysis)     */
 } oracle_desc_t;
 
 typedef struct {
@@ -226,8 +229,18 @@ int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void 
         operand_f64(d, h, d->H, hop);
         fc2(d, W2op, w->b2, hop, z);
         int32_t cls = oracle_softmax_argmax(d->K, z, q);
-        double u = oracle_selector_score(d, w, p, q);
-        float conf = (float)logistic(u);
+        double u, c;
+        if (d->selector == 1) {
+            /* Appendix, "Decoupling prediction and selection": only the predictor, with a
+             * threshold over its softmax scores.  score = confidence = max_k q[k]. */
+            c = q[0];
+            for (int k = 1; k < d->K; ++k) if (q[k] > c) c = q[k];
+            u = c;
+        } else {
+            u = oracle_selector_score(d, w, p, q);
+            c = logistic(u);
+        }
+        float conf = (float)c;
         if (pooled) memcpy(pooled + (int64_t)i * d->C, p, sizeof(float) * (size_t)d->C);
         if (logits) for (int k = 0; k < d->K; ++k) logits[(int64_t)i * d->K + k] = (float)z[k];
         if (probs)  memcpy(probs + (int64_t)i * d->K, q, sizeof(double) * (size_t)d->K);

@@ -13,6 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libgati.so")
 GATI_OK, GATI_ERR_INVALID_ARG, GATI_ERR_UNSUPPORTED, GATI_ERR_OOM, GATI_ERR_DEVICE = range(5)
 GATI_F32, GATI_BF16 = 0, 1
 GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
+GATI_SEL_LINEAR, GATI_SEL_SOFTMAX = 0, 1
 
 # every extern "C" symbol include/gati.h declares
 exported_symbols = (
@@ -24,7 +25,7 @@ exported_symbols = (
 class CacheDesc(C.Structure):
     _fields_ = [("C", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("K", C.c_int32),
                 ("act_dtype", C.c_int), ("layout", C.c_int), ("threshold", C.c_float),
-                ("max_rows", C.c_int32)]
+                ("max_rows", C.c_int32), ("selector", C.c_int)]
 
 
 class CacheWeights(C.Structure):
@@ -164,12 +165,13 @@ class Cache:
     """Owns one gati_cache_t."""
 
     def __init__(self, C_: int, S: int, H: int, K: int, dtype: str, layout: str, threshold: float,
-                 max_rows: int, weights: dict):
+                 max_rows: int, weights: dict, selector: str = "linear"):
         self.C, self.S, self.H, self.K = C_, S, H, K
         self.dtype, self.layout, self.max_rows = dtype, layout, max_rows
         self.threshold = float(threshold)
         desc = CacheDesc(C_, S, H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
-                         GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows)
+                         GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows,
+                         GATI_SEL_SOFTMAX if selector == "softmax" else GATI_SEL_LINEAR)
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in ("W1", "b1", "W2", "b2", "ws")}
         assert keep["W1"].shape == (H, C_) and keep["W2"].shape == (K, H) and keep["ws"].shape == (C_ + K,)
         w = CacheWeights(*(keep[k].ctypes.data for k in ("W1", "b1", "W2", "b2", "ws")), float(weights["bs"]))

@@ -301,6 +301,7 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
 
     FinalizeArgs fa = {};
     fa.stats = c->stats; fa.n_tiles = n_tiles; fa.u_pool = c->u_pool; fa.bs = c->bs; fa.tau = c->tau;
+    fa.softmax_only = c->desc.selector == GATI_SEL_SOFTMAX ? 1 : 0;
     fa.n_max = n_max; fa.n_dev = n_dev; fa.pred_class = pred_class; fa.confidence = confidence; fa.hit = hit;
     fa.ids_in = ids_in; fa.ids_out = ids_out; fa.n_miss = n_miss;
     finalize_kernel<<<1, 1024, 0, st>>>(fa);
@@ -334,6 +335,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         return GATI_ERR_INVALID_ARG;
     if (desc->act_dtype != GATI_F32 && desc->act_dtype != GATI_BF16) return GATI_ERR_INVALID_ARG;
     if (desc->layout != GATI_LAYOUT_NCS && desc->layout != GATI_LAYOUT_NSC) return GATI_ERR_INVALID_ARG;
+    if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_SOFTMAX) return GATI_ERR_INVALID_ARG;
     if (!w->W1 || !w->b1 || !w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
     if (!(desc->threshold == desc->threshold)) return GATI_ERR_INVALID_ARG;   // NaN
     // sizes whose padded products still fit the kernels' 32-bit tile arithmetic

@@ -84,8 +84,10 @@ struct FcArgs {
 // One row's class, confidence and hit flag from its per-tile summaries: tiles in order, the
 // running (max, sum, wsum) rescaled when a later tile raises the maximum;
 // confidence = logistic(bs + u_pool + sum_k ws[k] softmax(z)[k]).
+// softmax_only: no selector network, confidence = largest class probability = 1 / sum_k exp(z_k - max).
 __device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, float u_pool, float bs, float tau,
-                                           int32_t* cls_out, float* conf_out, uint8_t* hit_out) {
+                                           bool softmax_only, int32_t* cls_out, float* conf_out,
+                                           uint8_t* hit_out) {
     float m = -INFINITY, sum = 0.f, wsum = 0.f;
     int arg = 0;
     for (int t0 = 0; t0 < n_tiles; t0 += 8) {
@@ -107,7 +109,7 @@ __device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, floa
         }
     }
     const float u = bs + u_pool + wsum / sum;
-    const float conf = 1.f / (1.f + expf(-u));
+    const float conf = softmax_only ? 1.f / sum : 1.f / (1.f + expf(-u));
     const bool is_hit = conf > tau;
     *cls_out = arg;
     *conf_out = conf;
@@ -296,6 +298,7 @@ struct FinalizeArgs {
     int n_tiles;
     const float* u_pool;     // [rows_pad]
     float bs, tau;
+    int softmax_only;        // 1: no selector network, threshold on the top class probability
     int n_max;
     const int32_t* n_dev;
     int32_t* pred_class;     // [n]
@@ -321,8 +324,8 @@ __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
         const int i = base + tid;
         bool miss = false;
         if (i < n)
-            miss = !finish_row(a.stats + (long)i * a.n_tiles, a.n_tiles, a.u_pool[i], a.bs, a.tau,
-                                      &a.pred_class[i], &a.confidence[i], &a.hit[i]);
+            miss = !finish_row(a.stats + (long)i * a.n_tiles, a.n_tiles, a.u_pool[i], a.bs, a.tau, a.softmax_only != 0,
+                               &a.pred_class[i], &a.confidence[i], &a.hit[i]);
         if (compact) {
             const int slot = compact_step<16>(st, miss, tid);
             if (slot >= 0) a.ids_out[slot] = a.ids_in ? a.ids_in[i] : i;

@@ -38,7 +38,7 @@ def test_create_rejects_bad_arguments_on_the_host():
     good = dict(C=4, S=4, H=4, K=4, act_dtype=g.GATI_F32, layout=g.GATI_LAYOUT_NCS, threshold=0.5, max_rows=8)
     assert g.gati_cache_create(None, w)[0] == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_create(g.CacheDesc(**good), None)[0] == g.GATI_ERR_INVALID_ARG
-    for key, bad in (("C", 0), ("S", -1), ("H", 0), ("K", 0), ("max_rows", 0), ("act_dtype", 7), ("layout", 3),
+    for key, bad in (("C", 0), ("S", -1), ("H", 0), ("K", 0), ("max_rows", 0), ("act_dtype", 7), ("layout", 3), ("selector", 5),
                      ("threshold", float("nan"))):
         st, h = g.gati_cache_create(g.CacheDesc(**{**good, key: bad}), w)
         assert st == g.GATI_ERR_INVALID_ARG and h is None, key

@@ -199,3 +199,29 @@ def test_odd_shapes(C, S, H, K, dtype, layout):
     want_ideal = oracle.lookup(ideal_def(d), w, host, row_index=ok) if dtype == "bf16" else None
     compare_lookup(got, want, want_ideal, dtype, f"odd {C}x{S}x{H}x{K}")
     cache.close()
+
+
+@pytest.mark.parametrize("dtype,K", [("f32", 10), ("bf16", 1000)])
+def test_softmax_threshold_selector(dtype, K):
+    """No selector network: hit iff the top class probability exceeds the threshold."""
+    rng = np.random.default_rng(K)
+    n, C, S, H = 70, 128, 49, 96
+    x = torch.from_numpy(np.maximum(rng.standard_normal((n, C, S)) + 0.3, 0).astype(np.float32))
+    x = x.bfloat16() if dtype == "bf16" else x
+    w = {"W1": (rng.standard_normal((H, C)) * np.sqrt(2 / C)).astype(np.float32), "b1": np.zeros(H, np.float32),
+         "W2": (rng.standard_normal((K, H)) * np.sqrt(2 / H)).astype(np.float32), "b2": np.zeros(K, np.float32),
+         "ws": (rng.standard_normal(C + K) * 3).astype(np.float32), "bs": 2.0}
+    host = W.to_host_array(x)
+    probe = oracle.CacheDef(C=C, S=S, H=H, K=K, dtype=dtype, threshold=0.0, round_operands=(dtype == "bf16"),
+                            selector="softmax")
+    tau = float(np.float32(np.median(oracle.lookup(probe, w, host)["confidence"])))   # about half the rows hit
+    d = oracle.CacheDef(C=C, S=S, H=H, K=K, dtype=dtype, threshold=tau, round_operands=(dtype == "bf16"),
+                        selector="softmax")
+    ok = np.setdiff1d(np.arange(n), admit.inadmissible_rows(d, w, host)).astype(np.int32)
+    want = oracle.lookup(d, w, host, row_index=ok)
+    assert 0 < want["hit"].sum() < len(ok)
+    cache = g.Cache(C, S, H, K, dtype, "ncs", tau, n, w, selector="softmax")
+    got = _lookup_gpu(cache, x.cuda(), torch.from_numpy(ok).cuda(), len(ok), None, K)
+    want_ideal = oracle.lookup(ideal_def(d), w, host, row_index=ok) if dtype == "bf16" else None
+    compare_lookup(got, want, want_ideal, dtype, f"softmax selector {dtype}")
+    cache.close()

@@ -125,3 +125,34 @@ def test_lookup_composes_the_steps_against_library_ops(oracle):
     assert np.allclose(out["score"], u.numpy(), rtol=0, atol=1e-12)
     assert np.allclose(out["confidence"], conf.numpy(), rtol=0, atol=1e-7)
     assert np.array_equal(out["hit"], (conf.float().numpy() > np.float32(0.55)).astype(np.uint8))
+
+
+def test_softmax_threshold_mode(oracle):
+    """No selector network: confidence is the top class probability (Appendix, design analysis:
+    the baseline that thresholds the predictor's softmax scores)."""
+    import torch
+    g = np.random.default_rng(21)
+    n, C, S, H, K = 7, 6, 4, 5, 9
+    x = g.standard_normal((n, C, S)).astype(np.float32)
+    w = _w(C, H, K, W1=g.standard_normal((H, C)), b1=g.standard_normal(H) * 0.1,
+           W2=g.standard_normal((K, H)), b2=g.standard_normal(K) * 0.1,
+           ws=g.standard_normal(C + K) * 5, bs=3.0)          # selector weights must be ignored
+    d = CacheDef(C=C, S=S, H=H, K=K, threshold=0.5, selector="softmax")
+    out = oracle.lookup(d, w, x)
+    z = torch.from_numpy(out["logits"].astype(np.float64))
+    assert np.allclose(out["confidence"], out["probs"].max(axis=1), rtol=0, atol=1e-7)
+    assert np.allclose(out["confidence"], torch.softmax(z, dim=1).max(dim=1).values.numpy(), atol=1e-6)
+    assert np.array_equal(out["hit"], (out["confidence"] > np.float32(0.5)).astype(np.uint8))
+    assert np.array_equal(out["pred_class"], out["probs"].argmax(axis=1))
+    # K = 2: top probability = logistic(|z0 - z1|); with |z0 - z1| = ln 3 it is exactly 3/4
+    d2 = CacheDef(C=2, S=3, H=2, K=2, threshold=0.7, selector="softmax")
+    w2 = _w(2, 2, 2, W1=[[1, -1], [0.5, 2]], b1=[0, -5], W2=[[2, -7], [1, 3]], b2=[LN3, 1], ws=[9, 9, 9, 9], bs=9)
+    x2 = np.array([[[1, 2, 3], [-1, 0, 4]]], np.float32)
+    o2 = oracle.lookup(d2, w2, x2)
+    assert abs(float(o2["confidence"][0]) - 0.75) < 1e-6 and o2["hit"][0] == 1
+    # hit set shrinks monotonically as the threshold rises; a uniform distribution gives 1/K
+    hits = [int(oracle.lookup(CacheDef(C=C, S=S, H=H, K=K, threshold=t, selector="softmax"), w, x)["hit"].sum())
+            for t in (0.0, 0.2, 0.5, 0.9, 1.0)]
+    assert hits[0] == n and hits[-1] == 0 and all(a >= b for a, b in zip(hits, hits[1:]))
+    w0 = _w(C, H, K)
+    assert np.allclose(oracle.lookup(d, w0, x)["confidence"], 1.0 / K, atol=1e-7)
