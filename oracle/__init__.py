@@ -33,7 +33,8 @@ def build(force: bool = False) -> str:
 class _Desc(C.Structure):
     _fields_ = [("C", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("K", C.c_int32),
                 ("act_dtype", C.c_int32), ("layout", C.c_int32), ("round_operands", C.c_int32),
-                ("threshold", C.c_float), ("selector", C.c_int32)]
+                ("threshold", C.c_float), ("selector", C.c_int32), ("predictor", C.c_int32),
+                ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -57,6 +58,8 @@ def _load():
         _lib.oracle_compact_misses.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         _lib.oracle_pool_row.restype = None
         _lib.oracle_pool_row.argtypes = [C.POINTER(_Desc), C.c_void_p, C.c_int64, C.c_void_p]
+        _lib.oracle_pool_adaptive_row.restype = None
+        _lib.oracle_pool_adaptive_row.argtypes = [C.POINTER(_Desc), C.c_void_p, C.c_int64, C.c_void_p]
         _lib.oracle_fc1_relu.restype = C.c_int
         _lib.oracle_fc1_relu.argtypes = [C.POINTER(_Desc), C.POINTER(_Weights), C.c_void_p, C.c_void_p]
         _lib.oracle_fc2.restype = C.c_int
@@ -84,23 +87,37 @@ class CacheDef:
     threshold: float = 0.5
     round_operands: bool = False  # bf16 cache arithmetic (see gati_oracle.c)
     selector: str = "linear"    # "linear": selector network; "softmax": threshold on the top class probability
+    predictor: str = "gap_mlp"  # "gap_mlp": global pool -> FC -> ReLU -> FC; "pool_fc": the paper's Pool(h)
+    in_hw: tuple = (0, 0)       # pool_fc: input map (in_h, in_w), S = in_h*in_w
+    out_hw: tuple = (0, 0)      # pool_fc: pooled map (out_h, out_w); features F = C*out_h*out_w
+
+    @property
+    def F(self) -> int:
+        return self.C * self.out_hw[0] * self.out_hw[1] if self.predictor == "pool_fc" else self.C
 
     def _c(self) -> _Desc:
         return _Desc(self.C, self.S, self.H, self.K, BF16 if self.dtype == "bf16" else F32,
                      NSC if self.layout == "nsc" else NCS, 1 if self.round_operands else 0,
-                     float(self.threshold), 1 if self.selector == "softmax" else 0)
+                     float(self.threshold), 1 if self.selector == "softmax" else 0,
+                     1 if self.predictor == "pool_fc" else 0, int(self.in_hw[0]), int(self.in_hw[1]),
+                     int(self.out_hw[0]), int(self.out_hw[1]))
 
 
 def _weights_c(w: dict, keep: list) -> _Weights:
     arrs = {}
     for k in ("W1", "b1", "W2", "b2", "ws"):
-        arrs[k] = np.ascontiguousarray(w[k], dtype=np.float32)
+        v = w.get(k)
+        arrs[k] = np.ascontiguousarray(v if v is not None else np.zeros(1), dtype=np.float32)
         keep.append(arrs[k])
     return _Weights(_ptr(arrs["W1"]), _ptr(arrs["b1"]), _ptr(arrs["W2"]), _ptr(arrs["b2"]),
                     _ptr(arrs["ws"]), float(w["bs"]))
 
 
 def _check_act(d: CacheDef, act: np.ndarray):
+    if d.predictor == "pool_fc":
+        if d.layout != "ncs" or d.in_hw[0] * d.in_hw[1] != d.S or min(d.out_hw) < 1 or \
+                d.out_hw[0] > d.in_hw[0] or d.out_hw[1] > d.in_hw[1]:
+            raise ValueError("pool_fc needs layout ncs, S = in_h*in_w and 1 <= out <= in")
     want = np.uint16 if d.dtype == "bf16" else np.float32
     if act.dtype != want:
         raise TypeError(f"activation dtype {act.dtype}, cache wants {want}")
@@ -132,7 +149,7 @@ def lookup(d: CacheDef, w: dict, act: np.ndarray, row_index: Optional[np.ndarray
         if n > rows_avail:
             raise ValueError("n exceeds rows in activation")
     out = {
-        "pooled": np.zeros((n, d.C), np.float32),
+        "pooled": np.zeros((n, d.F), np.float32),
         "logits": np.zeros((n, d.K), np.float32),
         "probs": np.zeros((n, d.K), np.float64),
         "pred_class": np.zeros(n, np.int32),
@@ -171,9 +188,10 @@ def pool(d: CacheDef, act: np.ndarray, rows=None) -> np.ndarray:
     _check_act(d, act)
     rows = range(act.size // (d.C * d.S)) if rows is None else rows
     dc = d._c()
-    out = np.zeros((len(rows), d.C), np.float32)
+    out = np.zeros((len(rows), d.F), np.float32)
+    fn = lib.oracle_pool_adaptive_row if d.predictor == "pool_fc" else lib.oracle_pool_row
     for i, r in enumerate(rows):
-        lib.oracle_pool_row(C.byref(dc), _ptr(act), int(r), _ptr(out[i]))
+        fn(C.byref(dc), _ptr(act), int(r), _ptr(out[i]))
     return out
 
 

@@ -41,7 +41,18 @@ typedef struct {
     int32_t selector;        /* 0: selector network (affine map over [pooled ; prob], logistic)
                                 1: no selector network: confidence = largest class probability
                                    (the softmax-threshold baseline of the design analysis)     */
+    int32_t predictor;       /* 0: global average pool -> FC -> ReLU -> FC
+                                1: the paper's Pool(h): adaptive average pool of the in_h x in_w
+                                   map to out_h x out_w -> ReLU -> one FC over the
+                                   F = C*out_h*out_w features (H, W1, b1 unused)                */
+    int32_t in_h, in_w, out_h, out_w;   /* predictor 1 only; S = in_h*in_w, layout NCS        */
 } oracle_desc_t;
+
+/* Number of features the pooling step produces per row. */
+static int n_features(const oracle_desc_t *d)
+{
+    return d->predictor == 1 ? d->C * d->out_h * d->out_w : d->C;
+}
 
 typedef struct {
     const float *W1;  /* [H,C] */
@@ -98,6 +109,26 @@ void oracle_pool_row(const oracle_desc_t *d, const void *act, int64_t r, float *
         for (int s = 0; s < d->S; ++s) sum += act_at(d, act, r, c, s);
         p[c] = (float)(sum / (double)d->S);
     }
+}
+
+/* Adaptive average pool of one row: window i of an axis of length In pooled to Out covers
+ * [floor(i*In/Out), ceil((i+1)*In/Out)) (windows overlap when Out does not divide In; they
+ * are the plain In/Out blocks when it does).  f[(c*out_h + oy)*out_w + ox] = relu(mean over
+ * the window), the mean rounded once to fp32.  (Pooling predictor, table of predictor
+ * architectures: Input -Pool-> Hidden Layer(h), ReLU activation; h is the size after pooling.) */
+void oracle_pool_adaptive_row(const oracle_desc_t *d, const void *act, int64_t r, float *f)
+{
+    for (int c = 0; c < d->C; ++c)
+        for (int oy = 0; oy < d->out_h; ++oy)
+            for (int ox = 0; ox < d->out_w; ++ox) {
+                int y0 = (oy * d->in_h) / d->out_h, y1 = ((oy + 1) * d->in_h + d->out_h - 1) / d->out_h;
+                int x0 = (ox * d->in_w) / d->out_w, x1 = ((ox + 1) * d->in_w + d->out_w - 1) / d->out_w;
+                double sum = 0.0;
+                for (int y = y0; y < y1; ++y)
+                    for (int x = x0; x < x1; ++x) sum += act_at(d, act, r, c, y * d->in_w + x);
+                float m = (float)(sum / (double)((y1 - y0) * (x1 - x0)));
+                f[(c * d->out_h + oy) * d->out_w + ox] = m > 0.f ? m : 0.f;
+            }
 }
 
 /* Operand preparation for the bf16 cache arithmetic: a vector rounded element by
@@ -192,9 +223,10 @@ int32_t oracle_softmax_argmax(int K, const double *z, double *q)
 double oracle_selector_score(const oracle_desc_t *d, const oracle_weights_t *w,
                              const float *p, const double *q)
 {
+    const int F = n_features(d);
     double u = (double)w->bs;
-    for (int c = 0; c < d->C; ++c) u += (double)w->ws[c] * (double)p[c];
-    for (int k = 0; k < d->K; ++k) u += (double)w->ws[d->C + k] * q[k];
+    for (int c = 0; c < F; ++c) u += (double)w->ws[c] * (double)p[c];
+    for (int k = 0; k < d->K; ++k) u += (double)w->ws[F + k] * q[k];
     return u;
 }
 
@@ -204,30 +236,40 @@ static double logistic(double u) { return 1.0 / (1.0 + exp(-u)); }
  * Any output pointer may be NULL.  Returns 0, or -1 on allocation failure. */
 int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void *act,
                   const int32_t *row_index, int32_t n,
-                  float *pooled /*[n,C]*/, float *logits /*[n,K]*/, double *probs /*[n,K]*/,
+                  float *pooled /*[n,F]*/, float *logits /*[n,K]*/, double *probs /*[n,K]*/,
                   int32_t *pred_class /*[n]*/, double *score /*[n]*/, float *confidence /*[n]*/,
                   uint8_t *hit /*[n]*/)
 {
-    int64_t n1 = (int64_t)d->H * d->C, n2 = (int64_t)d->K * d->H;
-    float  *p    = (float *)malloc(sizeof(float) * (size_t)d->C);
-    double *pop  = (double *)malloc(sizeof(double) * (size_t)d->C);
-    double *h    = (double *)malloc(sizeof(double) * (size_t)d->H);
-    double *hop  = (double *)malloc(sizeof(double) * (size_t)d->H);
+    const int F = n_features(d);
+    const int pool_fc = d->predictor == 1;
+    const int H = pool_fc ? F : d->H;          /* width of the layer that feeds the output FC */
+    int64_t n1 = pool_fc ? 1 : (int64_t)d->H * d->C, n2 = (int64_t)d->K * H;
+    float  *p    = (float *)malloc(sizeof(float) * (size_t)F);
+    double *pop  = (double *)malloc(sizeof(double) * (size_t)F);
+    double *h    = (double *)malloc(sizeof(double) * (size_t)H);
+    double *hop  = (double *)malloc(sizeof(double) * (size_t)H);
     double *z    = (double *)malloc(sizeof(double) * (size_t)d->K);
     double *q    = (double *)malloc(sizeof(double) * (size_t)d->K);
     double *W1op = (double *)malloc(sizeof(double) * (size_t)n1);
     double *W2op = (double *)malloc(sizeof(double) * (size_t)n2);
     int rc = -1;
     if (!p || !pop || !h || !hop || !z || !q || !W1op || !W2op) goto done;
-    operand_f32(d, w->W1, n1, W1op);
+    if (!pool_fc) operand_f32(d, w->W1, n1, W1op);
     operand_f32(d, w->W2, n2, W2op);
+    oracle_desc_t dh = *d;                     /* the output FC reads H inputs */
+    dh.H = H;
     for (int32_t i = 0; i < n; ++i) {
         int64_t r = row_index ? (int64_t)row_index[i] : (int64_t)i;
-        oracle_pool_row(d, act, r, p);
-        operand_f32(d, p, d->C, pop);
-        fc1_relu(d, W1op, w->b1, pop, h);
-        operand_f64(d, h, d->H, hop);
-        fc2(d, W2op, w->b2, hop, z);
+        if (pool_fc) {
+            oracle_pool_adaptive_row(d, act, r, p);          /* hidden layer = relu(pooled) */
+            for (int c = 0; c < F; ++c) h[c] = (double)p[c];
+        } else {
+            oracle_pool_row(d, act, r, p);
+            operand_f32(d, p, d->C, pop);
+            fc1_relu(d, W1op, w->b1, pop, h);
+        }
+        operand_f64(d, h, H, hop);
+        fc2(&dh, W2op, w->b2, hop, z);
         int32_t cls = oracle_softmax_argmax(d->K, z, q);
         double u, c;
         if (d->selector == 1) {
@@ -241,7 +283,7 @@ int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void 
             c = logistic(u);
         }
         float conf = (float)c;
-        if (pooled) memcpy(pooled + (int64_t)i * d->C, p, sizeof(float) * (size_t)d->C);
+        if (pooled) memcpy(pooled + (int64_t)i * F, p, sizeof(float) * (size_t)F);
         if (logits) for (int k = 0; k < d->K; ++k) logits[(int64_t)i * d->K + k] = (float)z[k];
         if (probs)  memcpy(probs + (int64_t)i * d->K, q, sizeof(double) * (size_t)d->K);
         if (pred_class) pred_class[i] = cls;
