@@ -63,6 +63,16 @@ typedef enum {
  *                     "Decoupling prediction and selection"); ws and bs are ignored      */
 typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1 } gati_selector_t;
 
+/* Which predictor network the cache holds (paper, Section 3, table of predictor architectures).
+ *   GATI_PRED_GAP_MLP  global average pool -> FC(C->H) -> ReLU -> FC(H->K): the fully connected
+ *                      topology applied to the globally pooled features
+ *   GATI_PRED_POOL_FC  the paper's Pool(h): adaptive average pool of the in_h x in_w feature map to
+ *                      out_h x out_w (window i of an axis covers [floor(i*in/out), ceil((i+1)*in/out)),
+ *                      the PyTorch rule), ReLU, then one FC over the F = C*out_h*out_w features
+ *                      (feature order [c][oy][ox]).  Needs GATI_LAYOUT_NCS and S = in_h*in_w.
+ *                      H, W1 and b1 are unused; W2 is [K, F] and ws is [F + K].                  */
+typedef enum { GATI_PRED_GAP_MLP = 0, GATI_PRED_POOL_FC = 1 } gati_predictor_t;
+
 /* Shape of one learned cache (Section 3: predictor Input -> Hidden(h) -> Output, selector).
  *   C, S       activation channels and reduced length (pool extent = all of S)
  *   H, K       predictor hidden width and number of classes
@@ -72,7 +82,8 @@ typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1 } gati_selector_t;
  *              Pooling, biases, softmax, selector and sigmoid are fp32 in both.
  *   threshold  tau; a row is a hit iff confidence > tau (strictly)
  *   max_rows   largest n_max any later call may pass (sizes the library's workspace)
- *   selector   how the hit flag is decided, see gati_selector_t                              */
+ *   selector   how the hit flag is decided, see gati_selector_t
+ *   predictor  which predictor network and its in/out map sizes, see gati_predictor_t          */
 typedef struct {
     int32_t C, S, H, K;
     gati_dtype_t act_dtype;
@@ -80,6 +91,8 @@ typedef struct {
     float threshold;
     int32_t max_rows;
     gati_selector_t selector;
+    gati_predictor_t predictor;
+    int32_t in_h, in_w, out_h, out_w; /* GATI_PRED_POOL_FC only */
 } gati_cache_desc_t;
 
 /* Weights, HOST pointers, fp32, row-major [out, in].  Copied (and converted) by
@@ -129,7 +142,8 @@ gati_status_t gati_cache_lookup(gati_cache_t *cache, const void *act, const int3
                                 float *logits, void *stream);
 
 /* The pooling step alone (pooling predictor, Section 3): pooled[i, c] = mean over s of the
- * activation of active row i, fp32.  pooled is device [n_max, C].  Same row_index / n_max /
+ * activation of active row i, fp32.  pooled is device [n_max, F] with F = C (or the
+ * C*out_h*out_w ReLU'd window means of GATI_PRED_POOL_FC).  Same row_index / n_max /
  * n_dev meaning as gati_cache_lookup. */
 gati_status_t gati_cache_pool(gati_cache_t *cache, const void *act, const int32_t *row_index,
                               int32_t n_max, const int32_t *n_dev, float *pooled, void *stream);
@@ -162,7 +176,7 @@ gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, co
 const char *gati_status_string(gati_status_t status);
 
 /* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_segw",
- * "ncs_seg", "nsc_row", "nsc_vec", "generic"); static string, for reports and profiles. */
+ * "ncs_seg", "nsc_row", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
 
 #ifdef __cplusplus

@@ -14,6 +14,7 @@ GATI_OK, GATI_ERR_INVALID_ARG, GATI_ERR_UNSUPPORTED, GATI_ERR_OOM, GATI_ERR_DEVI
 GATI_F32, GATI_BF16 = 0, 1
 GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
 GATI_SEL_LINEAR, GATI_SEL_SOFTMAX = 0, 1
+GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC = 0, 1
 
 # every extern "C" symbol include/gati.h declares
 exported_symbols = (
@@ -25,7 +26,8 @@ exported_symbols = (
 class CacheDesc(C.Structure):
     _fields_ = [("C", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("K", C.c_int32),
                 ("act_dtype", C.c_int), ("layout", C.c_int), ("threshold", C.c_float),
-                ("max_rows", C.c_int32), ("selector", C.c_int)]
+                ("max_rows", C.c_int32), ("selector", C.c_int), ("predictor", C.c_int),
+                ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32)]
 
 
 class CacheWeights(C.Structure):
@@ -165,16 +167,25 @@ class Cache:
     """Owns one gati_cache_t."""
 
     def __init__(self, C_: int, S: int, H: int, K: int, dtype: str, layout: str, threshold: float,
-                 max_rows: int, weights: dict, selector: str = "linear"):
+                 max_rows: int, weights: dict, selector: str = "linear", predictor: str = "gap_mlp",
+                 in_hw=(0, 0), out_hw=(0, 0)):
         self.C, self.S, self.H, self.K = C_, S, H, K
         self.dtype, self.layout, self.max_rows = dtype, layout, max_rows
         self.threshold = float(threshold)
-        desc = CacheDesc(C_, S, H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
+        pool_fc = predictor == "pool_fc"
+        self.F = C_ * out_hw[0] * out_hw[1] if pool_fc else C_      # pooled features per row
+        desc = CacheDesc(C_, S, 0 if pool_fc else H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
                          GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows,
-                         GATI_SEL_SOFTMAX if selector == "softmax" else GATI_SEL_LINEAR)
-        keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in ("W1", "b1", "W2", "b2", "ws")}
-        assert keep["W1"].shape == (H, C_) and keep["W2"].shape == (K, H) and keep["ws"].shape == (C_ + K,)
-        w = CacheWeights(*(keep[k].ctypes.data for k in ("W1", "b1", "W2", "b2", "ws")), float(weights["bs"]))
+                         GATI_SEL_SOFTMAX if selector == "softmax" else GATI_SEL_LINEAR,
+                         GATI_PRED_POOL_FC if pool_fc else GATI_PRED_GAP_MLP,
+                         int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]))
+        names = ("W2", "b2", "ws") if pool_fc else ("W1", "b1", "W2", "b2", "ws")
+        keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
+        if not pool_fc:
+            assert keep["W1"].shape == (H, C_)
+        assert keep["W2"].shape == (K, self.F if pool_fc else H) and keep["ws"].shape == (self.F + K,)
+        ptr = lambda k: keep[k].ctypes.data if k in keep else None
+        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]))
         st, self.handle = gati_cache_create(desc, w)
         _check(st, "gati_cache_create")
 

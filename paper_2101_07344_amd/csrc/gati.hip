@@ -20,7 +20,8 @@ using namespace gati;
 
 namespace {
 
-enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_ROW = 5 };
+enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_ROW = 5,
+                   POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -47,8 +48,10 @@ struct gati_cache {
     int num_cu = 256;
     bool bf16 = false;
     int elem = 4;
-    // padded sizes: Cp % 64 == 0 and Hp % 64 == 0 (reduction axes: 4 waves x whole k-steps),
-    // Kp % (32*fc2_nt) == 0, rows_pad % 32 == 0
+    bool pool_fc = false;     // the paper's Pool(h) predictor: no hidden FC, the pooled features feed the output FC
+    int F = 0;                // features the pooling step produces per row (C, or C*out_h*out_w)
+    // padded sizes: Cp % 64 == 0 (Cp pads F) and Hp % 64 == 0 (reduction axes: 4 waves x whole
+    // k-steps), Kp % (32*fc2_nt) == 0, rows_pad % 32 == 0
     int Cp = 0, Hp = 0, Kp = 0, rows_pad = 0;
     // device weights, packed in MFMA fragment order (head_kernels.h)
     void* W1 = nullptr;       // [Hp/32][Cp/kStep][64][kLane] bf16 | f32
@@ -72,6 +75,7 @@ struct gati_cache {
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
     int nsc_lpt = 1, cb_per_row = 0, nsc_nw = 4;  // nsc_row
+    int ad_j = 4, ad_tpo_log2 = 0;                // ncs_adaptive (tile in gt / tiles_per_row)
     int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
     // head plan: column tiles per workgroup of the output layer
     int fc2_nt = 1;
@@ -98,6 +102,34 @@ void plan_pool(gati_cache* c) {
     const int C = c->desc.C, S = c->desc.S;
     const int V = 16 / c->elem;
     c->variant = POOL_GENERIC;
+    if (c->pool_fc) {
+        c->variant = POOL_ADAPTIVE_GENERIC;
+        if (S >= V && ((long)C * S) % V == 0) {
+            int g0 = 1;
+            while (((long)g0 * S) % V != 0) ++g0;
+            const long vec0 = (long)g0 * S / V;            // vectors of the smallest aligned tile
+            const int J = vec0 <= 256 ? 4 : vec0 <= 512 ? 8 : vec0 <= 1024 ? 16 : 0;
+            if (J) {
+                const int max_mult = (int)((64L * J) / vec0);
+                int mult = max_mult;
+                for (int m = max_mult; m >= (max_mult + 1) / 2; --m)
+                    if (C % (m * g0) == 0) { mult = m; break; }
+                int gt = mult * g0;
+                if (gt > C) gt = round_up(C, g0);
+                c->gt = gt;
+                c->tiles_per_row = (C + gt - 1) / gt;
+                c->ad_j = J;
+                // lanes per output window: split the window's rows when windows are big
+                const int win_rows = (c->desc.in_h + c->desc.out_h - 1) / c->desc.out_h;
+                const int win_cols = (c->desc.in_w + c->desc.out_w - 1) / c->desc.out_w;
+                int t = 0;
+                while (win_rows * win_cols > 16 && (2 << t) <= win_rows && t < 3) ++t;
+                c->ad_tpo_log2 = t;
+                c->variant = POOL_NCS_ADAPTIVE;
+            }
+        }
+        return;
+    }
     if (c->desc.layout == GATI_LAYOUT_NSC) {
         if (C % V == 0) {
             const int CV = C / V;
@@ -251,6 +283,30 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
         }
         break;
     }
+    case POOL_NCS_ADAPTIVE:
+    case POOL_ADAPTIVE_GENERIC: {
+        AdaptiveArgs g;
+        g.in_h = c->desc.in_h; g.in_w = c->desc.in_w; g.out_h = c->desc.out_h; g.out_w = c->desc.out_w;
+        g.gt = c->gt; g.tiles_per_row = c->tiles_per_row; g.tpo_log2 = c->ad_tpo_log2;
+        if (variant == POOL_ADAPTIVE_GENERIC) {
+            const long items = (long)a.n_max * c->F;
+            const int blocks = (int)std::min<long>((items + 255) / 256, max_blocks);
+            pool_adaptive_generic_kernel<Tag><<<blocks, 256, 0, st>>>(a, g);
+            break;
+        }
+        const long tiles = (long)a.n_max * c->tiles_per_row;
+        if (c->ad_j == 4) {
+            const int blocks = (int)std::min<long>((tiles + 3) / 4, max_blocks);
+            pool_ncs_adaptive_kernel<Tag, 4, 4><<<blocks, 256, 0, st>>>(a, g);
+        } else if (c->ad_j == 8) {
+            const int blocks = (int)std::min<long>((tiles + 3) / 4, max_blocks);
+            pool_ncs_adaptive_kernel<Tag, 8, 4><<<blocks, 256, 0, st>>>(a, g);
+        } else {
+            const int blocks = (int)std::min<long>((tiles + 1) / 2, max_blocks);
+            pool_ncs_adaptive_kernel<Tag, 16, 2><<<blocks, 128, 0, st>>>(a, g);
+        }
+        break;
+    }
     default: {
         const long items = (long)a.n_max * a.C;
         const int blocks = (int)std::min<long>((items + 255) / 256, max_blocks);
@@ -270,7 +326,10 @@ hipError_t launch_pool(const gati_cache* c, const void* act, const int32_t* row_
     a.out = out; a.out_stride = out_stride;
     // the vector kernels need 16-byte aligned rows; rows are multiples of 16 bytes by plan
     PoolVariant v = c->variant;
-    if (v != POOL_GENERIC && (reinterpret_cast<uintptr_t>(act) & 15u) != 0) v = POOL_GENERIC;
+    if ((reinterpret_cast<uintptr_t>(act) & 15u) != 0) {
+        if (v == POOL_NCS_ADAPTIVE) v = POOL_ADAPTIVE_GENERIC;
+        else if (v != POOL_ADAPTIVE_GENERIC) v = POOL_GENERIC;
+    }
     return c->bf16 ? launch_pool_t<BF16Tag>(c, a, v, st) : launch_pool_t<F32Tag>(c, a, v, st);
 }
 
@@ -281,16 +340,25 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
                          float* confidence, uint8_t* hit, float* logits, const int32_t* ids_in,
                          int32_t* ids_out, int32_t* n_miss, hipStream_t st) {
     const int row_tiles = (n_max + 31) / 32;
-    FcArgs f1 = {};
-    f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
-    f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
-    f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp;
-    fc_kernel<BF16, 1, true><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-
+    hipError_t e = hipSuccess;
     FcArgs f2 = {};
-    f2.A = c->h; f2.Wp = c->W2; f2.bias = c->b2; f2.Kdim = c->Hp; f2.N = c->Kp;
+    if (!c->pool_fc) {
+        FcArgs f1 = {};
+        f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
+        f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
+        f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp;
+        fc_kernel<BF16, 1, true><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        f2.A = c->h; f2.Kdim = c->Hp;
+    } else {
+        // Pool(h): the ReLU'd pooled features are the hidden layer; the output-layer kernel also
+        // computes the selector's pooled half
+        f2.A = BF16 ? c->p16 : (const void*)c->p; f2.Kdim = c->Cp;
+        f2.p32 = c->p; f2.ws_pool = c->ws_pool; f2.ldp = c->Cp;
+    }
+    f2.u_pool = c->u_pool;
+    f2.Wp = c->W2; f2.bias = c->b2; f2.N = c->Kp;
     f2.n_max = n_max; f2.n_dev = n_dev;
     f2.K = c->desc.K; f2.ws_prob = c->ws_prob; f2.logits = logits; f2.stats = c->stats;
     const int n_tiles = c->Kp / (32 * c->fc2_nt);
@@ -331,17 +399,28 @@ const char* gati_status_string(gati_status_t s) {
 gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_weights_t* w,
                                 gati_cache_t** out) {
     if (!desc || !w || !out) return GATI_ERR_INVALID_ARG;
-    if (desc->C <= 0 || desc->S <= 0 || desc->H <= 0 || desc->K <= 0 || desc->max_rows <= 0)
-        return GATI_ERR_INVALID_ARG;
+    if (desc->predictor != GATI_PRED_GAP_MLP && desc->predictor != GATI_PRED_POOL_FC) return GATI_ERR_INVALID_ARG;
+    const bool pool_fc = desc->predictor == GATI_PRED_POOL_FC;
+    if (desc->C <= 0 || desc->S <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
+    if (!pool_fc && desc->H <= 0) return GATI_ERR_INVALID_ARG;
+    if (pool_fc) {
+        if (desc->layout != GATI_LAYOUT_NCS) return GATI_ERR_INVALID_ARG;
+        if (desc->in_h <= 0 || desc->in_w <= 0 || desc->out_h <= 0 || desc->out_w <= 0) return GATI_ERR_INVALID_ARG;
+        if (desc->out_h > desc->in_h || desc->out_w > desc->in_w) return GATI_ERR_INVALID_ARG;
+        if ((long)desc->in_h * desc->in_w != (long)desc->S) return GATI_ERR_INVALID_ARG;
+        if ((long)desc->C * desc->out_h * desc->out_w > (1L << 20)) return GATI_ERR_UNSUPPORTED;
+    }
     if (desc->act_dtype != GATI_F32 && desc->act_dtype != GATI_BF16) return GATI_ERR_INVALID_ARG;
     if (desc->layout != GATI_LAYOUT_NCS && desc->layout != GATI_LAYOUT_NSC) return GATI_ERR_INVALID_ARG;
     if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_SOFTMAX) return GATI_ERR_INVALID_ARG;
-    if (!w->W1 || !w->b1 || !w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
+    if (!w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
+    if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
     if (!(desc->threshold == desc->threshold)) return GATI_ERR_INVALID_ARG;   // NaN
     // sizes whose padded products still fit the kernels' 32-bit tile arithmetic
     if (desc->C > (1 << 20) || desc->H > (1 << 20) || desc->K > (1 << 20) || desc->max_rows > (1 << 22))
         return GATI_ERR_UNSUPPORTED;
-    if ((long)desc->max_rows * desc->C >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
+    const long F_l = pool_fc ? (long)desc->C * desc->out_h * desc->out_w : (long)desc->C;
+    if ((long)desc->max_rows * (F_l + 64) >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
 
     gati_cache* c = new (std::nothrow) gati_cache();
     if (!c) return GATI_ERR_OOM;
@@ -350,8 +429,10 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     c->elem = c->bf16 ? 2 : 4;
     c->bs = w->bs;
     c->tau = desc->threshold;
-    c->Cp = round_up(desc->C, 64);
-    c->Hp = round_up(desc->H, 64);
+    c->pool_fc = pool_fc;
+    c->F = (int)F_l;
+    c->Cp = round_up(c->F, 64);
+    c->Hp = pool_fc ? c->Cp : round_up(desc->H, 64);   // width of the layer that feeds the output FC
     c->fc2_nt = desc->K > 96 ? 2 : 1;
     c->Kp = round_up(desc->K, 32 * c->fc2_nt);
     c->rows_pad = round_up(desc->max_rows, 32);
@@ -366,26 +447,30 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
 
     plan_pool(c);
 
-    const int C = desc->C, H = desc->H, K = desc->K;
+    const int C = c->F, H = pool_fc ? c->F : desc->H, K = desc->K;   // C: pooled features; H: inputs of the output FC
     gati_status_t st = GATI_OK;
     try {
         // weights in MFMA fragment order, zero padded
         if (c->bf16) {
             std::vector<uint16_t> t1, t2;
-            pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
+            if (!pool_fc) {
+                pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
+                st = upload(&c->W1, t1.data(), t1.size() * 2);
+            }
             pack_weights(w->W2, K, H, c->Kp, c->Hp, 16, t2, f32_to_bf16_rne);
-            st = upload(&c->W1, t1.data(), t1.size() * 2);
             if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 2);
         } else {
             std::vector<float> t1, t2;
             auto same = [](float x) { return x; };
-            pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);
+            if (!pool_fc) {
+                pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);
+                st = upload(&c->W1, t1.data(), t1.size() * 4);
+            }
             pack_weights(w->W2, K, H, c->Kp, c->Hp, 8, t2, same);
-            st = upload(&c->W1, t1.data(), t1.size() * 4);
             if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 4);
         }
         std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
-        std::memcpy(b1.data(), w->b1, (size_t)H * 4);
+        if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)H * 4);
         std::memcpy(b2.data(), w->b2, (size_t)K * 4);
         std::memcpy(wp.data(), w->ws, (size_t)C * 4);
         std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
@@ -399,7 +484,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     // workspace, zeroed once: the padding columns of p are never written and must read as 0
     if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
     if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);
-    if (st == GATI_OK) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
+    if (st == GATI_OK && !pool_fc) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
     if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
     if (st == GATI_OK)
         st = upload((void**)&c->stats, nullptr, (size_t)c->rows_pad * (c->Kp / (32 * c->fc2_nt)) * sizeof(TileStat));
@@ -430,7 +515,7 @@ gati_status_t gati_cache_pool(gati_cache_t* c, const void* act, const int32_t* r
     if (n_max == 0) return GATI_OK;
     if (!act || !pooled) return GATI_ERR_INVALID_ARG;
     if (!on_cache_device(c)) return GATI_ERR_DEVICE;
-    const hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, pooled, nullptr, c->desc.C, (hipStream_t)stream);
+    const hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, pooled, nullptr, c->F, (hipStream_t)stream);
     return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
 }
 
@@ -497,6 +582,8 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     case POOL_NCS_SEGW: return "ncs_segw";
     case POOL_NSC_VEC: return "nsc_vec";
     case POOL_NSC_ROW: return "nsc_row";
+    case POOL_NCS_ADAPTIVE: return "ncs_adaptive";
+    case POOL_ADAPTIVE_GENERIC: return "adaptive_generic";
     default: return "generic";
     }
 }

@@ -70,7 +70,7 @@ struct FcArgs {
     const int32_t* n_dev;
     // epilogue of the hidden layer
     void* h;               // [rows_pad, N] bf16 or f32: relu(A W^T + bias)
-    const float* p32;      // [rows_pad, ldp] fp32 pooled features (selector half)
+    const float* p32;      // [rows_pad, ldp] fp32 pooled features (selector half); null = not this kernel's job
     const float* ws_pool;  // [ldp]
     float* u_pool;         // [rows_pad] out: ws_pool . p32[row]
     int ldp;
@@ -115,6 +115,35 @@ __device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, floa
     *conf_out = conf;
     *hit_out = is_hit ? 1 : 0;
     return is_hit;
+}
+
+// Pooled-feature half of the selector, fp32: u_pool[row] = ws_pool . p32[row].  The 32 rows of a
+// row tile are shared out over the column blocks of the grid row; a block's 256 lanes stride
+// over one row at a time and add up in a fixed order (lane partials -> wave butterfly -> 4 wave
+// totals).  Called by all 256 lanes of every block of the grid row.
+__device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, int n, int n_tiles_x) {
+    __shared__ float upart[4];
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int rpb = (32 + n_tiles_x - 1) / n_tiles_x;   // rows per block
+    const f32x4_t* wv = reinterpret_cast<const f32x4_t*>(a.ws_pool);
+    const int nvec = a.ldp / 4;
+    for (int q = 0; q < rpb; ++q) {
+        const int rr = blockIdx.x * rpb + q;            // block-uniform
+        if (rr >= 32 || row0 + rr >= n) break;
+        const f32x4_t* pr = reinterpret_cast<const f32x4_t*>(a.p32 + (long)(row0 + rr) * a.ldp);
+        float s = 0.f;
+        for (int k = tid; k < nvec; k += 256) {
+            const f32x4_t x = pr[k], w = wv[k];
+            s = fmaf(x[0], w[0], s); s = fmaf(x[1], w[1], s);
+            s = fmaf(x[2], w[2], s); s = fmaf(x[3], w[3], s);
+        }
+        s = wave_sum(s);
+        __syncthreads();                                // previous row's upart has been read
+        if (lane == 0) upart[wave] = s;
+        __syncthreads();
+        if (tid == 0) a.u_pool[row0 + rr] = (upart[0] + upart[1]) + (upart[2] + upart[3]);
+    }
 }
 
 // grid = (N/(32*NT), ceil(n_max/32)), block = 256.
@@ -216,29 +245,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             else
                 static_cast<float*>(a.h)[(long)row * a.N + col] = v;
         }
-        // Pooled-feature half of the selector, fp32: the 32 rows of the tile are shared out
-        // over the column blocks of the grid row; a block's 256 lanes stride over one row at a
-        // time and add up in a fixed order (lane partials -> wave butterfly -> 4 wave totals).
-        __shared__ float upart[4];
-        const int rpb = (32 + n_tiles_x - 1) / n_tiles_x;   // rows per block
-        const f32x4_t* wv = reinterpret_cast<const f32x4_t*>(a.ws_pool);
-        const int nvec = a.ldp / 4;
-        for (int q = 0; q < rpb; ++q) {
-            const int rr = blockIdx.x * rpb + q;            // block-uniform
-            if (rr >= 32 || row0 + rr >= n) break;
-            const f32x4_t* pr = reinterpret_cast<const f32x4_t*>(a.p32 + (long)(row0 + rr) * a.ldp);
-            float s = 0.f;
-            for (int k = tid; k < nvec; k += 256) {
-                const f32x4_t x = pr[k], w = wv[k];
-                s = fmaf(x[0], w[0], s); s = fmaf(x[1], w[1], s);
-                s = fmaf(x[2], w[2], s); s = fmaf(x[3], w[3], s);
-            }
-            s = wave_sum(s);
-            __syncthreads();                                // previous row's upart has been read
-            if (lane == 0) upart[wave] = s;
-            __syncthreads();
-            if (tid == 0) a.u_pool[row0 + rr] = (upart[0] + upart[1]) + (upart[2] + upart[3]);
-        }
+        selector_pool_part(a, row0, n, n_tiles_x);
     } else {
         constexpr int TW = 32 * NT;                 // tile width in classes
         __shared__ float zt[32][TW + 1];
@@ -290,6 +297,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             s.max = bm; s.sum = ps; s.wsum = pt; s.arg = bi;
             a.stats[(long)(row0 + lr) * n_tiles_x + blockIdx.x] = s;
         }
+        if (a.p32) selector_pool_part(a, row0, n, n_tiles_x);   // predictors without a hidden-layer kernel
     }
 }
 

@@ -414,6 +414,137 @@ __global__ __launch_bounds__(NW * 64) void pool_nsc_row_kernel(PoolArgs a, int c
 }
 
 // ---------------------------------------------------------------------------------------
+// Adaptive average pool of [n,C,in_h*in_w] to [n,C,out_h,out_w] with ReLU (the hidden layer of
+// the paper's Pool(h) predictor).  Same flat-stream tiling as pool_ncs_segw: a wave loads a
+// tile of whole channels (16-byte coalesced, at most 64*J vectors) and parks the raw elements
+// in its own LDS strip; then `tpo` lanes per output window add up the window's rows in a fixed
+// order.  Window i of an axis covers [floor(i*in/out), ceil((i+1)*in/out)).
+// ---------------------------------------------------------------------------------------
+struct AdaptiveArgs {
+    int in_h, in_w, out_h, out_w;
+    int gt, tiles_per_row, tpo_log2;
+};
+
+template <typename Tag> __device__ __forceinline__ float lds_elem(const u32x4_t* raw, int idx);
+template <> __device__ __forceinline__ float lds_elem<F32Tag>(const u32x4_t* raw, int idx) {
+    return reinterpret_cast<const float*>(raw)[idx];
+}
+template <> __device__ __forceinline__ float lds_elem<BF16Tag>(const u32x4_t* raw, int idx) {
+    return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(raw)[idx] << 16);
+}
+
+template <typename Tag, int J, int WPB>
+__global__ __launch_bounds__(WPB * 64) void pool_ncs_adaptive_kernel(PoolArgs a, AdaptiveArgs g) {
+    constexpr int V = Tag::kVec;
+    __shared__ u32x4_t raw_all[WPB][64 * J];
+
+    const int n = active_rows(a.n_dev, a.n_max);
+    const unsigned total = (unsigned)n * (unsigned)g.tiles_per_row;
+    const int lane = threadIdx.x & 63;
+    const int wib = threadIdx.x >> 6;
+    const unsigned wave = blockIdx.x * WPB + wib;
+    const unsigned nwaves = gridDim.x * WPB;
+    u32x4_t* raw = raw_all[wib];
+    const int OO = g.out_h * g.out_w;
+    const int tpo = 1 << g.tpo_log2;
+    const int sub = lane & (tpo - 1);
+
+    auto tile_of = [&](unsigned w, unsigned& i, int& c_first, int& nch) -> const u32x4_t* {
+        i = w / (unsigned)g.tiles_per_row;
+        const int t = (int)(w - i * (unsigned)g.tiles_per_row);
+        const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+        c_first = t * g.gt;
+        nch = min(g.gt, a.C - c_first);
+        return reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) +
+                                                ((r * a.C + c_first) * (long)a.S) * Tag::kBytes);
+    };
+
+    u32x4_t v[J];
+    unsigned i = 0;
+    int c_first = 0, nch = 0;
+    if (wave < total) {
+        const u32x4_t* base = tile_of(wave, i, c_first, nch);
+        const int tv = (nch * a.S) / V;
+#pragma unroll
+        for (int j = 0; j < J; ++j) v[j] = load_stream(base + min(lane + 64 * j, tv - 1));
+    }
+    for (unsigned w = wave; w < total; w += nwaves) {
+        const int tile_vecs = (nch * a.S) / V;
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const int idx = lane + 64 * j;
+            if (idx < tile_vecs) raw[idx] = v[j];
+        }
+        const unsigned ci = i;
+        const int cc = c_first, cn = nch;
+        const unsigned wn = w + nwaves;
+        if (wn < total) {          // next tile's loads fly while this tile's windows are summed
+            const u32x4_t* base = tile_of(wn, i, c_first, nch);
+            const int tv = (nch * a.S) / V;
+#pragma unroll
+            for (int j = 0; j < J; ++j) v[j] = load_stream(base + min(lane + 64 * j, tv - 1));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int n_out = cn * OO;
+        for (int ob = 0; ob < n_out; ob += 64 >> g.tpo_log2) {
+            const int o = ob + (lane >> g.tpo_log2);
+            const bool live = o < n_out;
+            const int oc = live ? o : 0;
+            const int lc = oc / OO;
+            const int wi = oc - lc * OO;
+            const int oy = wi / g.out_w, ox = wi - oy * g.out_w;
+            const int y0 = (oy * g.in_h) / g.out_h, y1 = ((oy + 1) * g.in_h + g.out_h - 1) / g.out_h;
+            const int x0 = (ox * g.in_w) / g.out_w, x1 = ((ox + 1) * g.in_w + g.out_w - 1) / g.out_w;
+            float acc = 0.f;
+            if (live) {
+                for (int y = y0 + sub; y < y1; y += tpo) {
+                    const int rb = lc * a.S + y * g.in_w;
+                    for (int x = x0; x < x1; ++x) acc += lds_elem<Tag>(raw, rb + x);
+                }
+            }
+            for (int m = tpo >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+            if (live && sub == 0) {
+                const float mean = acc / (float)((y1 - y0) * (x1 - x0));
+                store_pooled(a, (long)ci * a.out_stride + (long)(cc + lc) * OO + wi, fmaxf(mean, 0.f));
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// Adaptive pool for shapes the tiled kernel cannot take: one lane per output window, scalar loads.
+template <typename Tag>
+__global__ __launch_bounds__(256) void pool_adaptive_generic_kernel(PoolArgs a, AdaptiveArgs g) {
+    const int n = active_rows(a.n_dev, a.n_max);
+    const int OO = g.out_h * g.out_w;
+    const long F = (long)a.C * OO;
+    const long total = (long)n * F;
+    const long stride = (long)gridDim.x * blockDim.x;
+    for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const long i = idx / F;
+        const int f = (int)(idx - i * F);
+        const int c = f / OO, wi = f - c * OO;
+        const int oy = wi / g.out_w, ox = wi - oy * g.out_w;
+        const int y0 = (oy * g.in_h) / g.out_h, y1 = ((oy + 1) * g.in_h + g.out_h - 1) / g.out_h;
+        const int x0 = (ox * g.in_w) / g.out_w, x1 = ((ox + 1) * g.in_w + g.out_w - 1) / g.out_w;
+        const long r = a.row_index ? (long)a.row_index[i] : i;
+        const long first = (r * a.C + c) * (long)a.S;
+        float s = 0.f;
+        for (int y = y0; y < y1; ++y)
+            for (int x = x0; x < x1; ++x) {
+                const long e = first + y * g.in_w + x;
+                if (Tag::kBytes == 4) s += static_cast<const float*>(a.act)[e];
+                else s += __uint_as_float((uint32_t)static_cast<const uint16_t*>(a.act)[e] << 16);
+            }
+        store_pooled(a, i * a.out_stride + f, fmaxf(s / (float)((y1 - y0) * (x1 - x0)), 0.f));
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Any shape, layout and alignment: one lane per (row, channel), scalar loads.  Slow; only
 // for shapes the vector kernels cannot take.
 // ---------------------------------------------------------------------------------------

@@ -38,7 +38,7 @@ def test_create_rejects_bad_arguments_on_the_host():
     good = dict(C=4, S=4, H=4, K=4, act_dtype=g.GATI_F32, layout=g.GATI_LAYOUT_NCS, threshold=0.5, max_rows=8)
     assert g.gati_cache_create(None, w)[0] == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_create(g.CacheDesc(**good), None)[0] == g.GATI_ERR_INVALID_ARG
-    for key, bad in (("C", 0), ("S", -1), ("H", 0), ("K", 0), ("max_rows", 0), ("act_dtype", 7), ("layout", 3), ("selector", 5),
+    for key, bad in (("C", 0), ("S", -1), ("H", 0), ("K", 0), ("max_rows", 0), ("act_dtype", 7), ("layout", 3), ("selector", 5), ("predictor", 4),
                      ("threshold", float("nan"))):
         st, h = g.gati_cache_create(g.CacheDesc(**{**good, key: bad}), w)
         assert st == g.GATI_ERR_INVALID_ARG and h is None, key
@@ -46,6 +46,10 @@ def test_create_rejects_bad_arguments_on_the_host():
                             keep[4].ctypes.data, 0.0)
     assert g.gati_cache_create(g.CacheDesc(**good), w_null)[0] == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_create(g.CacheDesc(**{**good, "C": 1 << 21}), w)[0] == g.GATI_ERR_UNSUPPORTED
+    # Pool(h): the map sizes must multiply to S, the pooled map must fit in the input map, layout NCS
+    pool = {**good, "predictor": g.GATI_PRED_POOL_FC, "H": 0, "S": 16, "in_h": 4, "in_w": 4, "out_h": 2, "out_w": 2}
+    for key, bad in (("in_h", 5), ("out_h", 0), ("out_w", 5), ("layout", g.GATI_LAYOUT_NSC)):
+        assert g.gati_cache_create(g.CacheDesc(**{**pool, key: bad}), w)[0] == g.GATI_ERR_INVALID_ARG, key
 
 
 def test_calls_reject_null_handles_and_bad_counts_on_the_host():

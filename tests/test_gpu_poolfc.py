@@ -1,0 +1,102 @@
+"""GPU parity of the paper's Pool(h) predictor: adaptive average pool -> ReLU -> one FC."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2101_07344_amd as g
+import workloads as W
+from oracle import CacheDef, admit
+
+from helpers import compare_lookup, ideal_def
+
+pytestmark = pytest.mark.gpu
+
+POOL_ATOL = 2e-6
+
+
+def _weights(F, K, rng=None, scale=1.0):
+    if rng is None:
+        return {"W2": np.zeros((K, F), np.float32), "b2": np.zeros(K, np.float32),
+                "ws": np.zeros(F + K, np.float32), "bs": 0.0}
+    return {"W2": (rng.standard_normal((K, F)) * np.sqrt(2 / F) * scale).astype(np.float32),
+            "b2": (rng.standard_normal(K) * 0.1).astype(np.float32),
+            "ws": (rng.standard_normal(F + K) * np.sqrt(2 / (F + K))).astype(np.float32), "bs": 0.05}
+
+
+SHAPES = [
+    # C, in_h, in_w, out_h, out_w, dtype, variant -- the shapes of the ResNet stages pooled to 4096 / 8192 features
+    (256, 56, 56, 4, 4, "bf16", "ncs_adaptive"), (512, 28, 28, 4, 4, "bf16", "ncs_adaptive"),
+    (1024, 14, 14, 2, 2, "bf16", "ncs_adaptive"), (2048, 7, 7, 2, 2, "bf16", "ncs_adaptive"),
+    (64, 56, 56, 8, 8, "f32", "ncs_adaptive"), (128, 28, 28, 4, 4, "f32", "ncs_adaptive"),
+    (512, 7, 7, 2, 2, "f32", "ncs_adaptive"), (128, 16, 16, 8, 8, "f32", "ncs_adaptive"),
+    # ragged: overlapping windows, non-square maps, identity and 1x1 pooling, shapes the tiled kernel cannot take
+    (24, 5, 10, 3, 4, "bf16", "ncs_adaptive"), (10, 9, 9, 9, 9, "f32", "adaptive_generic"), (12, 9, 9, 9, 9, "f32", "ncs_adaptive"),
+    (40, 7, 7, 1, 1, "bf16", "ncs_adaptive"), (7, 3, 11, 2, 5, "f32", "adaptive_generic"),
+    (3, 80, 80, 5, 5, "f32", "adaptive_generic"), (8, 13, 3, 13, 1, "bf16", "ncs_adaptive"),
+]
+
+
+@pytest.mark.parametrize("C,ih,iw,oh,ow,dtype,variant", SHAPES)
+def test_adaptive_pool_matches_oracle(C, ih, iw, oh, ow, dtype, variant):
+    n, S, F = 9, ih * iw, C * oh * ow
+    gen = torch.Generator().manual_seed(C + ih + oh)
+    x = torch.randn((n, C, S), generator=gen) + 0.3
+    x = x.bfloat16() if dtype == "bf16" else x
+    cache = g.Cache(C, S, 0, 4, dtype, "ncs", 0.5, 32, _weights(F, 4), predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+    assert cache.pool_variant == variant
+    d = CacheDef(C=C, S=S, H=0, K=4, dtype=dtype, predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+    want = oracle.pool(d, W.to_host_array(x))
+    xd = x.cuda()
+    idx = torch.tensor([8, 0, 3, 3, 5, 1, 7], dtype=torch.int32, device="cuda")
+    n_dev = torch.tensor([5], dtype=torch.int32, device="cuda")
+    out = torch.full((7, F), -7.0, device="cuda")
+    cache.pool(xd, idx, 7, n_dev, out)
+    out_all = torch.full((n, F), -7.0, device="cuda")
+    cache.pool(xd, None, n, None, out_all)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.max(np.abs(got[:5] - want[[8, 0, 3, 3, 5]])) <= POOL_ATOL
+    assert np.all(got[5:] == -7.0)
+    assert np.max(np.abs(out_all.cpu().numpy() - want)) <= POOL_ATOL
+    cache.close()
+
+
+@pytest.mark.parametrize("C,ih,iw,oh,ow,K,dtype", [
+    (256, 14, 14, 4, 4, 1000, "bf16"),     # F = 4096, overlapping 14 -> 4 windows
+    (64, 16, 16, 8, 8, 10, "f32"),         # F = 4096: the paper's 16x16 -> 8x8 shape
+    (2048, 7, 7, 2, 2, 1000, "bf16"),      # F = 8192
+    (24, 5, 10, 3, 4, 33, "bf16"),
+])
+def test_pool_fc_lookup_matches_oracle(C, ih, iw, oh, ow, K, dtype):
+    rng = np.random.default_rng(C + K)
+    n, S, F = 45, ih * iw, C * oh * ow
+    x = torch.from_numpy((rng.standard_normal((n, C, S)) + 0.4).astype(np.float32))
+    x = x.bfloat16() if dtype == "bf16" else x
+    w = _weights(F, K, rng)
+    d = CacheDef(C=C, S=S, H=0, K=K, dtype=dtype, threshold=0.5, round_operands=(dtype == "bf16"),
+                 predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+    host = W.to_host_array(x)
+    s0 = oracle.lookup(d, {**w, "bs": 0.0}, host)["score"]
+    w["bs"] = float(np.float32(-np.median(s0)))                 # about half the rows hit
+    ok = np.setdiff1d(np.arange(n), admit.inadmissible_rows(d, w, host)).astype(np.int32)
+    assert len(ok) > n // 2
+    want = oracle.lookup(d, w, host, row_index=ok)
+    assert 0 < want["hit"].sum() < len(ok)
+    cache = g.Cache(C, S, 0, K, dtype, "ncs", 0.5, n, w, predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+    m = len(ok)
+    out = {"pred_class": torch.zeros(m, dtype=torch.int32, device="cuda"), "confidence": torch.zeros(m, device="cuda"),
+           "hit": torch.zeros(m, dtype=torch.uint8, device="cuda"), "logits": torch.zeros(m, K, device="cuda")}
+    ids_out = torch.zeros(m, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    okd = torch.from_numpy(ok).cuda()
+    cache.lookup_compact(x.cuda(), okd, m, None, out["pred_class"], out["confidence"], out["hit"], out["logits"],
+                         okd, ids_out, cnt)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    want_ideal = oracle.lookup(ideal_def(d), w, host, row_index=ok) if dtype == "bf16" else None
+    compare_lookup(got, want, want_ideal, dtype, f"pool_fc {C}x{ih}x{iw}->{oh}x{ow}")
+    want_ids = oracle.compact_misses(want["hit"], ok)
+    assert int(cnt.item()) == len(want_ids)
+    assert np.array_equal(ids_out.cpu().numpy()[:len(want_ids)], want_ids)
+    cache.close()
