@@ -45,7 +45,8 @@ def build_workload(name, torch, g, W):
     K = spec.layers[0].K
     labels = W.zipf_labels(spec.batch, K, spec.zipf_s, spec.seed)
     weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
-    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w)
+    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w,
+                      predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw)
               for L, w in zip(spec.layers, weights)]
     stack = g.CacheStack(caches, spec.batch, storage=spec.storage)
     acts = []
@@ -93,7 +94,7 @@ def time_pool_launches(spec, caches, stack, acts, keys, reps, torch):
     figure is kernel time plus launch-to-launch gaps, not host enqueue latency.
     Returns per-layer mean duration in ms (a group's time is split by algorithmic bytes)."""
     L = len(caches)
-    pooled = [torch.empty(spec.batch, c.C, dtype=torch.float32, device="cuda") for c in caches]
+    pooled = [torch.empty(spec.batch, c.F, dtype=torch.float32, device="cuda") for c in caches]
     es, base = stack.counts.element_size(), stack.counts.data_ptr()
     groups = []                         # [first, last] layer index of each run of equal keys
     for l in range(L):
@@ -167,7 +168,7 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
 
     elem = spec.layers[0].elem_bytes
     keys = [f"{c.pool_variant}[C={L.C},S={L.S},{L.dtype}]" for L, c in zip(spec.layers, caches)]
-    algo = [int(counts[l]) * L.C * L.S * elem + int(counts[l]) * L.C * 4      # activation read + pooled write
+    algo = [int(counts[l]) * L.C * L.S * elem + int(counts[l]) * L.F * 4      # activation read + pooled write
             for l, L in enumerate(spec.layers)]
     groups, group_ms = time_pool_launches(spec, caches, stack, acts, keys, max(3, min(steps, 20)), torch)
     per_layer, by_kernel = [], {}

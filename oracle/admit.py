@@ -23,7 +23,8 @@ def cache_defs(spec: W.WorkloadSpec, mirror: bool = True) -> List[CacheDef]:
     """Oracle-side description of every cache in a workload.  ``mirror`` selects the
     bf16-operand arithmetic for bf16 caches (the grading reference)."""
     return [CacheDef(C=L.C, S=L.S, H=L.H, K=L.K, dtype=L.dtype, layout=L.layout,
-                     threshold=L.threshold, round_operands=(mirror and L.dtype == "bf16"))
+                     threshold=L.threshold, round_operands=(mirror and L.dtype == "bf16"),
+                     predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw)
             for L in spec.layers]
 
 

@@ -21,7 +21,8 @@ def _build(name):
     spec = W.get_workload(name)
     labels = W.zipf_labels(spec.batch, spec.layers[0].K, spec.zipf_s, spec.seed)
     weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
-    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w)
+    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w,
+                      predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw)
               for L, w in zip(spec.layers, weights)]
     return spec, labels, weights, caches
 
@@ -65,7 +66,7 @@ def _check_chain_properties(stack, batch, n_layers):
     return counts
 
 
-@pytest.mark.parametrize("name,rows_per_layer", [("resnet18", 6), ("resnet50", 5), ("bert_base", 8)])
+@pytest.mark.parametrize("name,rows_per_layer", [("resnet18", 6), ("resnet50", 5), ("bert_base", 8), ("resnet50_pool", 3)])
 def test_full_batch_gather_stack(name, rows_per_layer):
     spec, labels, weights, caches = _build(name)
     defs = admit.cache_defs(spec, mirror=True)

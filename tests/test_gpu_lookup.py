@@ -59,6 +59,7 @@ STACKS = [
     ("resnet50", 33, "dense", 0.20, False),
     ("bert_base", 70, "gather", 0.12, True),
     ("bert_base", 45, "dense", 0.25, True),
+    ("resnet50_pool", 35, "gather", 0.12, True),       # the paper's Pool(h) predictor on the same shapes
 ]
 
 

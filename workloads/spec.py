@@ -26,6 +26,14 @@ class LayerSpec:
     relu: bool        # ReLU-Gaussian (CNN block outputs) or plain Gaussian (tokens)
     bs: float = 0.0   # selector bias (calibrated per layer for the hit-rate ramps)
     target_hit: Optional[float] = None  # per-layer hit-rate target the bias was fitted to
+    predictor: str = "gap_mlp"   # "gap_mlp" | "pool_fc" (the paper's Pool(h): adaptive pool -> ReLU -> FC)
+    in_hw: tuple = (0, 0)        # pool_fc: feature-map size, S = in_h*in_w
+    out_hw: tuple = (0, 0)       # pool_fc: pooled map; F = C*out_h*out_w features
+
+    @property
+    def F(self) -> int:
+        """Features the pooling step hands to the FC layers."""
+        return self.C * self.out_hw[0] * self.out_hw[1] if self.predictor == "pool_fc" else self.C
 
     @property
     def elem_bytes(self) -> int:
@@ -52,15 +60,19 @@ class WorkloadSpec:
         return replace(self, batch=batch, name=name or f"{self.name}@{batch}")
 
 
-def _resnet_stack(blocks, H, K, dtype, tau, gammas):
+def _resnet_stack(blocks, H, K, dtype, tau, gammas, pool_out=None):
+    """pool_out: None for the global-pool predictor, else {hw: pooled side} for Pool(h)."""
     layers = []
     idx = 0
     total = sum(b for _, _, b in blocks)
     for (C, hw, reps) in blocks:
         for _ in range(reps):
             g = gammas[0] + (gammas[1] - gammas[0]) * (idx / max(1, total - 1))
-            layers.append(LayerSpec(C=C, S=hw * hw, H=H, K=K, layout="ncs", dtype=dtype,
-                                    threshold=tau, gamma=g, relu=True))
+            extra = {}
+            if pool_out is not None:
+                extra = dict(predictor="pool_fc", in_hw=(hw, hw), out_hw=(pool_out[hw], pool_out[hw]))
+            layers.append(LayerSpec(C=C, S=hw * hw, H=0 if pool_out is not None else H, K=K, layout="ncs",
+                                    dtype=dtype, threshold=tau, gamma=g, relu=True, **extra))
             idx += 1
     return layers
 
@@ -98,6 +110,13 @@ def _build():
         name="resnet152", batch=4096, zipf_s=1.1, seed=0, storage="dense",
         layers=_resnet_stack([(256, 56, 3), (512, 28, 8), (1024, 14, 36), (2048, 7, 3)],
                              H=512, K=1000, dtype="bf16", tau=0.6, gammas=(8.0, 32.0)))
+    # The paper's own Pool(h) variant on the ResNet-50 shapes: pooled maps chosen so that
+    # h = C*s*s is the paper's 4096 / 8192 (Section 7 "Default Parameters")
+    w["resnet50_pool"] = WorkloadSpec(
+        name="resnet50_pool", batch=512, zipf_s=1.1, seed=0,
+        layers=_resnet_stack([(256, 56, 3), (512, 28, 4), (1024, 14, 6), (2048, 7, 3)],
+                             H=0, K=1000, dtype="bf16", tau=0.6, gammas=(8.0, 32.0),
+                             pool_out={56: 4, 28: 4, 14: 2, 7: 2}))
     return w
 
 
@@ -110,6 +129,7 @@ HIT_TARGETS = {
     # per-block hit-rate table is used: ~84 % and ~75 % cumulative by the last layer.
     "resnet18": _linear_ramp(0.05, 0.35, 8),
     "resnet50": [0.0065 * (i + 1) for i in range(16)],
+    "resnet50_pool": [0.0065 * (i + 1) for i in range(16)],
     "bert_base": _linear_ramp(0.02, 0.20, 12),
     "resnet152": _linear_ramp(0.02, 0.70, 50),
 }

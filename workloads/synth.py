@@ -52,6 +52,11 @@ def cache_weights(spec: WorkloadSpec, layer: int) -> dict:
     """
     L = spec.layers[layer]
     g = _rng(spec.seed, _TAG_WEIGHTS, layer)
+    if L.predictor == "pool_fc":
+        # Pool(h): no hidden FC; the output FC reads the F pooled features
+        W2 = (g.standard_normal((L.K, L.F)) * np.sqrt(2.0 / L.F)).astype(np.float32)
+        ws = (g.standard_normal(L.F + L.K) * np.sqrt(2.0 / (L.F + L.K))).astype(np.float32)
+        return {"W1": None, "b1": None, "W2": W2, "b2": np.zeros(L.K, np.float32), "ws": ws, "bs": float(L.bs)}
     W1 = (g.standard_normal((L.H, L.C)) * np.sqrt(2.0 / L.C)).astype(np.float32)
     W2 = (g.standard_normal((L.K, L.H)) * np.sqrt(2.0 / L.H)).astype(np.float32)
     ws = (g.standard_normal(L.C + L.K) * np.sqrt(2.0 / (L.C + L.K))).astype(np.float32)
