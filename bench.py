@@ -118,6 +118,72 @@ def time_pool_launches(spec, caches, stack, acts, keys, reps, torch):
     return groups, ms
 
 
+def time_graph(stack, acts, steps, warmup, torch):
+    """The same pass captured once into a HIP graph and replayed."""
+    stream = torch.cuda.current_stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        stack.run(acts)
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def time_overlap(stack, acts, steps, warmup, torch, gemm_dim=4096):
+    """Lookups beside a stand-in for the base DNN (the paper's serving arrangement, Section 6:
+    base model on one stream, cache lookups on a second one).  The stand-in is one bf16
+    gemm_dim^3 library GEMM per layer; layer l's lookup may start when 'its' GEMM is done.
+    Returns ms per pass for: the stand-in alone, everything on one stream, lookups on a side stream."""
+    a = torch.randn(gemm_dim, gemm_dim, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(gemm_dim, gemm_dim, device="cuda", dtype=torch.bfloat16)
+    out = torch.empty(gemm_dim, gemm_dim, device="cuda", dtype=torch.bfloat16)
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    L = len(stack.caches)
+    done = [torch.cuda.Event() for _ in range(L)]
+
+    def base_only():
+        for _ in range(L):
+            torch.matmul(a, b, out=out)
+
+    def sync_pass():
+        for l in range(L):
+            torch.matmul(a, b, out=out)
+            stack.run_layer(l, acts[l], stream=main)
+
+    def async_pass():
+        for l in range(L):
+            torch.matmul(a, b, out=out)
+            done[l].record(main)
+            side.wait_event(done[l])
+            stack.run_layer(l, acts[l], stream=side)
+        main.wait_stream(side)
+
+    res = {}
+    for name, fn in (("base_only_ms", base_only), ("same_stream_ms", sync_pass), ("side_stream_ms", async_pass)):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = round(e0.elapsed_time(e1) / steps, 4)
+    res["standin"] = f"{L} x bf16 GEMM {gemm_dim}^3 (torch.matmul), one per layer"
+    res["lookup_cost_same_stream_ms"] = round(res["same_stream_ms"] - res["base_only_ms"], 4)
+    res["lookup_cost_side_stream_ms"] = round(res["side_stream_ms"] - res["base_only_ms"], 4)
+    return res
+
+
 def cpu_baseline(spec, weights, acts, stack, counts, budget_requests, torch, W):
     """The CPU oracle, one thread, on the first `budget_requests` requests of the same batch
     through the whole stack (its own hits and compaction).  TEST INFRASTRUCTURE timed as a
@@ -149,7 +215,8 @@ def cpu_baseline(spec, weights, acts, stack, counts, budget_requests, torch, W):
                       f"({lookups} lookups, {dt:.1f} s, single thread, gcc -O2, fp64 accumulation)"}
 
 
-def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False):
+def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False,
+                 graph=False, overlap=False):
     t_build = time.perf_counter()
     spec, labels, weights, caches, stack, acts = build_workload(name, torch, g, W)
     if copy_probe:
@@ -212,6 +279,10 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
                              "launches": v["launches"]} for k, v in by_kernel.items()},
         "layers": per_layer,
     }
+    if graph:
+        out["graph_ms_per_step"] = round(time_graph(stack, acts, steps, warmup, torch), 4)
+    if overlap and spec.storage == "gather":
+        out["overlap"] = time_overlap(stack, acts, steps, warmup, torch)
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(spec, weights, acts, stack, counts, cpu_requests, torch, W)
     stack.close()
@@ -229,10 +300,13 @@ def main():
                     help="tiny | resnet18 | resnet50 | bert_base | resnet152")
     ap.add_argument("--also", default="bert_base",
                     help="comma-separated further workloads reported under 'others' ('' for none)")
-    ap.add_argument("--cpu-requests", type=int, default=192,
+    ap.add_argument("--cpu-requests", type=int, default=512,
                     help="requests of the batch the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", action="store_true", help="include the per-layer table in the JSON line")
+    ap.add_argument("--graph", action="store_true", help="also time the pass replayed from a captured HIP graph")
+    ap.add_argument("--overlap", action="store_true",
+                    help="also time the lookups beside a synthetic base-DNN stand-in, same stream vs side stream")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain tensor copy of layer 0's activations (known size), the reference "
                          "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -256,7 +330,8 @@ def main():
     stream = torch.cuda.Stream()          # default priority; every launch and event goes here
     with torch.cuda.stream(stream):
         spec, main_res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
-                                      args.cpu_requests, torch, g, W, copy_probe=args.copy_probe)
+                                      args.cpu_requests, torch, g, W, copy_probe=args.copy_probe,
+                                      graph=args.graph, overlap=args.overlap)
         others = {}
         for name in [n for n in args.also.split(",") if n and n != args.workload]:
             _, r = run_workload(name, args.steps, args.warmup, False, 0, torch, g, W)
@@ -283,6 +358,9 @@ def main():
         "pool_kernels": main_res["pool_kernels"],
         "others": others,
     }
+    for key in ("graph_ms_per_step", "overlap"):
+        if key in main_res:
+            line[key] = main_res[key]
     if args.layers:
         line["layers"] = main_res["layers"]
     else:
