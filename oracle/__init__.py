@@ -87,19 +87,22 @@ class CacheDef:
     threshold: float = 0.5
     round_operands: bool = False  # bf16 cache arithmetic (see gati_oracle.c)
     selector: str = "linear"    # "linear": selector network; "softmax": threshold on the top class probability
-    predictor: str = "gap_mlp"  # "gap_mlp": global pool -> FC -> ReLU -> FC; "pool_fc": the paper's Pool(h)
+    predictor: str = "gap_mlp"  # "gap_mlp": global pool -> FC -> ReLU -> FC; "pool_fc": the paper's Pool(h);
+                                # "fc_mlp": the paper's FC(h) on the flattened activation
     in_hw: tuple = (0, 0)       # pool_fc: input map (in_h, in_w), S = in_h*in_w
     out_hw: tuple = (0, 0)      # pool_fc: pooled map (out_h, out_w); features F = C*out_h*out_w
 
     @property
     def F(self) -> int:
-        return self.C * self.out_hw[0] * self.out_hw[1] if self.predictor == "pool_fc" else self.C
+        if self.predictor == "pool_fc":
+            return self.C * self.out_hw[0] * self.out_hw[1]
+        return self.H if self.predictor == "fc_mlp" else self.C
 
     def _c(self) -> _Desc:
         return _Desc(self.C, self.S, self.H, self.K, BF16 if self.dtype == "bf16" else F32,
                      NSC if self.layout == "nsc" else NCS, 1 if self.round_operands else 0,
                      float(self.threshold), 1 if self.selector == "softmax" else 0,
-                     1 if self.predictor == "pool_fc" else 0, int(self.in_hw[0]), int(self.in_hw[1]),
+                     {"gap_mlp": 0, "pool_fc": 1, "fc_mlp": 2}[self.predictor], int(self.in_hw[0]), int(self.in_hw[1]),
                      int(self.out_hw[0]), int(self.out_hw[1]))
 
 

@@ -44,24 +44,20 @@ typedef struct {
     int32_t predictor;       /* 0: global average pool -> FC -> ReLU -> FC
                                 1: the paper's Pool(h): adaptive average pool of the in_h x in_w
                                    map to out_h x out_w -> ReLU -> one FC over the
-                                   F = C*out_h*out_w features (H, W1, b1 unused)                */
+                                   F = C*out_h*out_w features (H, W1, b1 unused)
+                                2: the paper's FC(h): the whole activation row, flattened in
+                                   storage order (D = C*S values), -> FC(D->H) -> ReLU -> FC(H->K);
+                                   the selector reads [hidden ; prob]                           */
     int32_t in_h, in_w, out_h, out_w;   /* predictor 1 only; S = in_h*in_w, layout NCS        */
 } oracle_desc_t;
 
 /* Number of features the pooling step produces per row. */
 static int n_features(const oracle_desc_t *d)
 {
-    return d->predictor == 1 ? d->C * d->out_h * d->out_w : d->C;
+    if (d->predictor == 1) return d->C * d->out_h * d->out_w;
+    if (d->predictor == 2) return d->H;
+    return d->C;
 }
-
-typedef struct {
-    const float *W1;  /* [H,C] */
-    const float *b1;  /* [H]   */
-    const float *W2;  /* [K,H] */
-    const float *b2;  /* [K]   */
-    const float *ws;  /* [C+K], pooled features first, class probabilities after */
-    float bs;
-} oracle_weights_t;
 
 /* ---- number formats ------------------------------------------------------------ */
 
@@ -96,6 +92,24 @@ static double act_at(const oracle_desc_t *d, const void *act, int64_t r, int c, 
     if (d->act_dtype == ORACLE_BF16) return bf16_bits_to_double(((const uint16_t *)act)[idx]);
     return (double)((const float *)act)[idx];
 }
+
+/* Element e of the flattened activation row r, in storage order (no layout arithmetic: the
+ * FC(h) predictor sees the hidden layer output as one vector). */
+static double act_flat(const oracle_desc_t *d, const void *act, int64_t r, int64_t e)
+{
+    int64_t idx = r * (int64_t)d->C * d->S + e;
+    if (d->act_dtype == ORACLE_BF16) return bf16_bits_to_double(((const uint16_t *)act)[idx]);
+    return (double)((const float *)act)[idx];
+}
+
+typedef struct {
+    const float *W1;  /* [H,C] */
+    const float *b1;  /* [H]   */
+    const float *W2;  /* [K,H] */
+    const float *b2;  /* [K]   */
+    const float *ws;  /* [C+K], pooled features first, class probabilities after */
+    float bs;
+} oracle_weights_t;
 
 /* ---- the steps ------------------------------------------------------------------- */
 
@@ -241,9 +255,10 @@ int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void 
                   uint8_t *hit /*[n]*/)
 {
     const int F = n_features(d);
-    const int pool_fc = d->predictor == 1;
+    const int pool_fc = d->predictor == 1, flat_fc = d->predictor == 2;
     const int H = pool_fc ? F : d->H;          /* width of the layer that feeds the output FC */
-    int64_t n1 = pool_fc ? 1 : (int64_t)d->H * d->C, n2 = (int64_t)d->K * H;
+    const int64_t D = (int64_t)d->C * d->S;    /* inputs of the first FC of the FC(h) predictor */
+    int64_t n1 = pool_fc ? 1 : (flat_fc ? (int64_t)d->H * D : (int64_t)d->H * d->C), n2 = (int64_t)d->K * H;
     float  *p    = (float *)malloc(sizeof(float) * (size_t)F);
     double *pop  = (double *)malloc(sizeof(double) * (size_t)F);
     double *h    = (double *)malloc(sizeof(double) * (size_t)H);
@@ -263,6 +278,17 @@ int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void 
         if (pool_fc) {
             oracle_pool_adaptive_row(d, act, r, p);          /* hidden layer = relu(pooled) */
             for (int c = 0; c < F; ++c) h[c] = (double)p[c];
+        } else if (flat_fc) {
+            /* hidden[j] = relu(b1[j] + sum_e W1[j,e] x[e]) over the whole flattened row; the
+             * activation values are exact in either element type, W1 is an operand (rounded
+             * in the bf16 arithmetic).  The hidden layer is kept as fp32 features. */
+            for (int j = 0; j < d->H; ++j) {
+                double acc = 0.0;
+                for (int64_t e = 0; e < D; ++e) acc += W1op[(int64_t)j * D + e] * act_flat(d, act, r, e);
+                acc += (double)w->b1[j];
+                p[j] = (float)(acc > 0.0 ? acc : 0.0);
+                h[j] = (double)p[j];
+            }
         } else {
             oracle_pool_row(d, act, r, p);
             operand_f32(d, p, d->C, pop);
