@@ -70,8 +70,13 @@ typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1 } gati_selector_t;
  *                      out_h x out_w (window i of an axis covers [floor(i*in/out), ceil((i+1)*in/out)),
  *                      the PyTorch rule), ReLU, then one FC over the F = C*out_h*out_w features
  *                      (feature order [c][oy][ox]).  Needs GATI_LAYOUT_NCS and S = in_h*in_w.
- *                      H, W1 and b1 are unused; W2 is [K, F] and ws is [F + K].                  */
-typedef enum { GATI_PRED_GAP_MLP = 0, GATI_PRED_POOL_FC = 1 } gati_predictor_t;
+ *                      H, W1 and b1 are unused; W2 is [K, F] and ws is [F + K].
+ *   GATI_PRED_FC_MLP   the paper's FC(h): the activation row flattened in storage order (D = C*S
+ *                      values) -> FC(D->H) -> ReLU -> FC(H->K).  W1 is [H, D]; the selector reads
+ *                      [hidden ; prob], so ws is [H + K]; the "pooled" features reported by
+ *                      gati_cache_pool are the H hidden activations.  D must be a multiple of 16
+ *                      (GATI_ERR_UNSUPPORTED otherwise).                                           */
+typedef enum { GATI_PRED_GAP_MLP = 0, GATI_PRED_POOL_FC = 1, GATI_PRED_FC_MLP = 2 } gati_predictor_t;
 
 /* Shape of one learned cache (Section 3: predictor Input -> Hidden(h) -> Output, selector).
  *   C, S       activation channels and reduced length (pool extent = all of S)
@@ -176,7 +181,7 @@ gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, co
 const char *gati_status_string(gati_status_t status);
 
 /* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_segw",
- * "ncs_seg", "nsc_row", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic"); static string, for reports and profiles. */
+ * "ncs_seg", "nsc_row", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
 
 #ifdef __cplusplus

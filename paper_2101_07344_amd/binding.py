@@ -14,7 +14,7 @@ GATI_OK, GATI_ERR_INVALID_ARG, GATI_ERR_UNSUPPORTED, GATI_ERR_OOM, GATI_ERR_DEVI
 GATI_F32, GATI_BF16 = 0, 1
 GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
 GATI_SEL_LINEAR, GATI_SEL_SOFTMAX = 0, 1
-GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC = 0, 1
+GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC, GATI_PRED_FC_MLP = 0, 1, 2
 
 # every extern "C" symbol include/gati.h declares
 exported_symbols = (
@@ -172,17 +172,18 @@ class Cache:
         self.C, self.S, self.H, self.K = C_, S, H, K
         self.dtype, self.layout, self.max_rows = dtype, layout, max_rows
         self.threshold = float(threshold)
-        pool_fc = predictor == "pool_fc"
-        self.F = C_ * out_hw[0] * out_hw[1] if pool_fc else C_      # pooled features per row
+        pool_fc, fc_mlp = predictor == "pool_fc", predictor == "fc_mlp"
+        # features per row that the selector sees and gati_cache_pool reports
+        self.F = C_ * out_hw[0] * out_hw[1] if pool_fc else (H if fc_mlp else C_)
         desc = CacheDesc(C_, S, 0 if pool_fc else H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
                          GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows,
                          GATI_SEL_SOFTMAX if selector == "softmax" else GATI_SEL_LINEAR,
-                         GATI_PRED_POOL_FC if pool_fc else GATI_PRED_GAP_MLP,
+                         {"gap_mlp": GATI_PRED_GAP_MLP, "pool_fc": GATI_PRED_POOL_FC, "fc_mlp": GATI_PRED_FC_MLP}[predictor],
                          int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]))
         names = ("W2", "b2", "ws") if pool_fc else ("W1", "b1", "W2", "b2", "ws")
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
         if not pool_fc:
-            assert keep["W1"].shape == (H, C_)
+            assert keep["W1"].shape == (H, C_ * S if fc_mlp else C_)
         assert keep["W2"].shape == (K, self.F if pool_fc else H) and keep["ws"].shape == (self.F + K,)
         ptr = lambda k: keep[k].ctypes.data if k in keep else None
         w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]))

@@ -13,6 +13,7 @@
 #include "../../include/gati.h"
 #include "common.h"
 #include "compact_kernels.h"
+#include "flat_kernels.h"
 #include "head_kernels.h"
 #include "pool_kernels.h"
 
@@ -21,7 +22,7 @@ using namespace gati;
 namespace {
 
 enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_ROW = 5,
-                   POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7 };
+                   POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7, POOL_FC_FLAT = 8 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -48,7 +49,11 @@ struct gati_cache {
     int num_cu = 256;
     bool bf16 = false;
     int elem = 4;
-    bool pool_fc = false;     // the paper's Pool(h) predictor: no hidden FC, the pooled features feed the output FC
+    bool pool_fc = false;     // no separate hidden-FC kernel: the features feed the output FC (Pool(h), FC(h))
+    bool flat_fc = false;     // the paper's FC(h): the features are relu(W1 x + b1) over the flattened row
+    // FC(h) plan: wave register tile MT=NT=flat_t, padded sizes, split-K
+    int flat_t = 1, Hb = 0, rows_b = 0, flat_KS = 0, flat_splits = 1, flat_ks_per = 0, flat_tiles_m = 0, flat_tiles_n = 0;
+    float* flat_partial = nullptr;   // [splits][rows_b][Hb]
     int F = 0;                // features the pooling step produces per row (C, or C*out_h*out_w)
     // padded sizes: Cp % 64 == 0 (Cp pads F) and Hp % 64 == 0 (reduction axes: 4 waves x whole
     // k-steps), Kp % (32*fc2_nt) == 0, rows_pad % 32 == 0
@@ -84,7 +89,7 @@ struct gati_cache {
 namespace {
 
 void free_all(gati_cache* c) {
-    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats};
+    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats, c->flat_partial};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
 }
@@ -317,8 +322,39 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
     return hipGetLastError();
 }
 
+// FC(h): features = relu(W1 x + b1) over the flattened rows: split-K MFMA tiles, then the
+// fixed-order reduction of the splits.
+template <bool BF16>
+hipError_t launch_flat_t(const gati_cache* c, const void* act, const int32_t* row_index, int n_max,
+                         const int32_t* n_dev, float* out, void* out16, int out_stride, hipStream_t st) {
+    FlatArgs f;
+    f.act = act; f.row_index = row_index; f.n_dev = n_dev; f.n_max = n_max;
+    f.D = (long)c->desc.C * c->desc.S; f.Wp = c->W1; f.KS = c->flat_KS; f.Hb = c->Hb; f.rows_b = c->rows_b;
+    f.splits = c->flat_splits; f.ks_per_split = c->flat_ks_per;
+    f.tiles_n = c->flat_tiles_n;
+    f.tiles_m = std::min(c->flat_tiles_m, (n_max + 64 * c->flat_t - 1) / (64 * c->flat_t));
+    f.partial = c->flat_partial;
+    const int grid = f.tiles_m * f.tiles_n * f.splits;
+    if (c->flat_t == 4) fc_flat_kernel<BF16, 4, 4><<<grid, 256, 0, st>>>(f);
+    else if (c->flat_t == 2) fc_flat_kernel<BF16, 2, 2><<<grid, 256, 0, st>>>(f);
+    else fc_flat_kernel<BF16, 1, 1><<<grid, 256, 0, st>>>(f);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    FlatReduceArgs r;
+    r.partial = c->flat_partial; r.bias = c->b1; r.n_dev = n_dev; r.n_max = n_max;
+    r.splits = c->flat_splits; r.rows_b = c->rows_b; r.Hb = c->Hb;
+    r.p = out; r.p16 = static_cast<__bf16*>(out16); r.ldp = out_stride;
+    const long vecs = (long)n_max * (out_stride / 4);
+    const int blocks = (int)std::min<long>((vecs + 255) / 256, c->num_cu * 8);
+    fc_flat_reduce_kernel<<<blocks, 256, 0, st>>>(r);
+    return hipGetLastError();
+}
+
 hipError_t launch_pool(const gati_cache* c, const void* act, const int32_t* row_index, int n_max,
                        const int32_t* n_dev, float* out, void* out16, int out_stride, hipStream_t st) {
+    if (c->flat_fc)
+        return c->bf16 ? launch_flat_t<true>(c, act, row_index, n_max, n_dev, out, out16, out_stride, st)
+                       : launch_flat_t<false>(c, act, row_index, n_max, n_dev, out, out16, out_stride, st);
     PoolArgs a;
     a.out16 = static_cast<__bf16*>(out16);
     a.act = act; a.row_index = row_index; a.n_dev = n_dev; a.n_max = n_max;
@@ -399,8 +435,12 @@ const char* gati_status_string(gati_status_t s) {
 gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_weights_t* w,
                                 gati_cache_t** out) {
     if (!desc || !w || !out) return GATI_ERR_INVALID_ARG;
-    if (desc->predictor != GATI_PRED_GAP_MLP && desc->predictor != GATI_PRED_POOL_FC) return GATI_ERR_INVALID_ARG;
+    if (desc->predictor != GATI_PRED_GAP_MLP && desc->predictor != GATI_PRED_POOL_FC &&
+        desc->predictor != GATI_PRED_FC_MLP)
+        return GATI_ERR_INVALID_ARG;
+    const bool flat_fc = desc->predictor == GATI_PRED_FC_MLP;
     const bool pool_fc = desc->predictor == GATI_PRED_POOL_FC;
+    const bool no_hidden_kernel = pool_fc || flat_fc;
     if (desc->C <= 0 || desc->S <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && desc->H <= 0) return GATI_ERR_INVALID_ARG;
     if (pool_fc) {
@@ -415,11 +455,13 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_SOFTMAX) return GATI_ERR_INVALID_ARG;
     if (!w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
+    if (flat_fc && ((long)desc->C * desc->S) % 16 != 0) return GATI_ERR_UNSUPPORTED;
+    if (flat_fc && (long)desc->C * desc->S >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
     if (!(desc->threshold == desc->threshold)) return GATI_ERR_INVALID_ARG;   // NaN
     // sizes whose padded products still fit the kernels' 32-bit tile arithmetic
     if (desc->C > (1 << 20) || desc->H > (1 << 20) || desc->K > (1 << 20) || desc->max_rows > (1 << 22))
         return GATI_ERR_UNSUPPORTED;
-    const long F_l = pool_fc ? (long)desc->C * desc->out_h * desc->out_w : (long)desc->C;
+    const long F_l = pool_fc ? (long)desc->C * desc->out_h * desc->out_w : (flat_fc ? (long)desc->H : (long)desc->C);
     if ((long)desc->max_rows * (F_l + 64) >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
 
     gati_cache* c = new (std::nothrow) gati_cache();
@@ -429,10 +471,11 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     c->elem = c->bf16 ? 2 : 4;
     c->bs = w->bs;
     c->tau = desc->threshold;
-    c->pool_fc = pool_fc;
+    c->pool_fc = no_hidden_kernel;
+    c->flat_fc = flat_fc;
     c->F = (int)F_l;
     c->Cp = round_up(c->F, 64);
-    c->Hp = pool_fc ? c->Cp : round_up(desc->H, 64);   // width of the layer that feeds the output FC
+    c->Hp = no_hidden_kernel ? c->Cp : round_up(desc->H, 64);   // width of the layer that feeds the output FC
     c->fc2_nt = desc->K > 96 ? 2 : 1;
     c->Kp = round_up(desc->K, 32 * c->fc2_nt);
     c->rows_pad = round_up(desc->max_rows, 32);
@@ -445,15 +488,38 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         (void)hipGetLastError();
     c->pool_blocks_per_cu = env_int("GATI_POOL_BLOCKS_PER_CU", 16);
 
-    plan_pool(c);
+    if (flat_fc) {
+        const int k_step = c->bf16 ? 16 : 8;
+        const long D = (long)desc->C * desc->S;
+        c->flat_t = (desc->max_rows >= 256 && desc->H >= 256) ? 4 : (desc->max_rows >= 128 && desc->H >= 128) ? 2 : 1;
+        c->flat_KS = (int)(D / k_step);
+        c->Hb = round_up(desc->H, 64 * c->flat_t);
+        c->rows_b = round_up(desc->max_rows, 64 * c->flat_t);
+        c->flat_tiles_m = c->rows_b / (64 * c->flat_t);
+        c->flat_tiles_n = c->Hb / (64 * c->flat_t);
+        const int tiles = c->flat_tiles_m * c->flat_tiles_n;
+        // enough workgroups for every CU, each with at least 16 k-steps; multiples of 8 keep the XCD mapping
+        int splits = std::max(1, std::min(c->num_cu / tiles, c->flat_KS / 16));
+        if (splits >= 8) splits = splits / 8 * 8;
+        splits = std::min(splits, env_int("GATI_FLAT_MAX_SPLITS", 64));
+        c->flat_ks_per = (c->flat_KS + splits - 1) / splits;
+        c->flat_splits = (c->flat_KS + c->flat_ks_per - 1) / c->flat_ks_per;
+        c->variant = POOL_FC_FLAT;
+    } else {
+        plan_pool(c);
+    }
 
-    const int C = c->F, H = pool_fc ? c->F : desc->H, K = desc->K;   // C: pooled features; H: inputs of the output FC
+    const int C = c->F, H = no_hidden_kernel ? c->F : desc->H, K = desc->K;   // C: features; H: inputs of the output FC
     gati_status_t st = GATI_OK;
     try {
         // weights in MFMA fragment order, zero padded
         if (c->bf16) {
             std::vector<uint16_t> t1, t2;
-            if (!pool_fc) {
+            if (flat_fc) {
+                const int D = desc->C * desc->S;
+                pack_weights(w->W1, desc->H, D, c->Hb, D, 16, t1, f32_to_bf16_rne);
+                st = upload(&c->W1, t1.data(), t1.size() * 2);
+            } else if (!pool_fc) {
                 pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
                 st = upload(&c->W1, t1.data(), t1.size() * 2);
             }
@@ -462,7 +528,11 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         } else {
             std::vector<float> t1, t2;
             auto same = [](float x) { return x; };
-            if (!pool_fc) {
+            if (flat_fc) {
+                const int D = desc->C * desc->S;
+                pack_weights(w->W1, desc->H, D, c->Hb, D, 8, t1, same);
+                st = upload(&c->W1, t1.data(), t1.size() * 4);
+            } else if (!pool_fc) {
                 pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);
                 st = upload(&c->W1, t1.data(), t1.size() * 4);
             }
@@ -470,7 +540,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
             if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 4);
         }
         std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
-        if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)H * 4);
+        if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)desc->H * 4);
         std::memcpy(b2.data(), w->b2, (size_t)K * 4);
         std::memcpy(wp.data(), w->ws, (size_t)C * 4);
         std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
@@ -484,7 +554,9 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     // workspace, zeroed once: the padding columns of p are never written and must read as 0
     if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
     if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);
-    if (st == GATI_OK && !pool_fc) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
+    if (st == GATI_OK && !no_hidden_kernel) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
+    if (st == GATI_OK && flat_fc)
+        st = upload((void**)&c->flat_partial, nullptr, (size_t)c->flat_splits * c->rows_b * c->Hb * 4);
     if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
     if (st == GATI_OK)
         st = upload((void**)&c->stats, nullptr, (size_t)c->rows_pad * (c->Kp / (32 * c->fc2_nt)) * sizeof(TileStat));
@@ -514,6 +586,9 @@ gati_status_t gati_cache_pool(gati_cache_t* c, const void* act, const int32_t* r
     if (!c || n_max < 0 || n_max > c->desc.max_rows) return GATI_ERR_INVALID_ARG;
     if (n_max == 0) return GATI_OK;
     if (!act || !pooled) return GATI_ERR_INVALID_ARG;
+    if (c->flat_fc && ((reinterpret_cast<uintptr_t>(act) | reinterpret_cast<uintptr_t>(pooled)) & 15u) != 0)
+        return GATI_ERR_UNSUPPORTED;
+    if (c->flat_fc && c->F % 4 != 0) return GATI_ERR_UNSUPPORTED;
     if (!on_cache_device(c)) return GATI_ERR_DEVICE;
     const hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, pooled, nullptr, c->F, (hipStream_t)stream);
     return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
@@ -524,6 +599,7 @@ gati_status_t lookup_impl(gati_cache_t* c, const void* act, const int32_t* row_i
                           const int32_t* n_dev, int32_t* pred_class, float* confidence, uint8_t* hit,
                           float* logits, const int32_t* ids_in, int32_t* ids_out, int32_t* n_miss,
                           hipStream_t st) {
+    if (c->flat_fc && (reinterpret_cast<uintptr_t>(act) & 15u) != 0) return GATI_ERR_UNSUPPORTED;
     hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, c->p, c->p16, c->Cp, st);
     if (e != hipSuccess) return GATI_ERR_DEVICE;
     e = c->bf16 ? launch_head_t<true>(c, n_max, n_dev, pred_class, confidence, hit, logits, ids_in, ids_out, n_miss, st)
@@ -584,6 +660,7 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     case POOL_NSC_ROW: return "nsc_row";
     case POOL_NCS_ADAPTIVE: return "ncs_adaptive";
     case POOL_ADAPTIVE_GENERIC: return "adaptive_generic";
+    case POOL_FC_FLAT: return "fc_flat";
     default: return "generic";
     }
 }
