@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X published dense matrix peaks
 
 # HBM traffic of the dominant pooling kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs (summaries under profiles/); keyed by workload.  None until measured.
@@ -227,6 +228,8 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
         del dst
     log(f"[{name}] inputs ready in {time.perf_counter() - t_build:.1f}s "
         f"({sum(a.numel() * a.element_size() for a in acts) / 1e9:.2f} GB of activations)")
+    if spec.layers[0].predictor == "fc_mlp":
+        cpu_requests = min(cpu_requests, 4)         # the oracle needs ~1 G multiply-adds per row and layer
     ms_step, wall_ms = time_stack(stack, acts, steps, warmup, torch)
     counts = stack.counts.cpu().numpy().astype(np.int64)
     n_layers = len(caches)
@@ -236,12 +239,14 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
     elem = spec.layers[0].elem_bytes
     keys = [f"{c.pool_variant}[C={L.C},S={L.S},{L.dtype}]" for L, c in zip(spec.layers, caches)]
     algo = [int(counts[l]) * L.C * L.S * elem + int(counts[l]) * L.F * 4      # activation read + pooled write
+            + (L.H * L.C * L.S * elem if L.predictor == "fc_mlp" else 0)      # FC(h): W1 is streamed once too
             for l, L in enumerate(spec.layers)]
+    flops = [2 * int(counts[l]) * L.C * L.S * L.H if L.predictor == "fc_mlp" else 0 for l, L in enumerate(spec.layers)]
     groups, group_ms = time_pool_launches(spec, caches, stack, acts, keys, max(3, min(steps, 20)), torch)
     per_layer, by_kernel = [], {}
     for (lo, hi), gms in zip(groups, group_ms):
         gbytes = sum(algo[lo:hi + 1])
-        k = by_kernel.setdefault(keys[lo], {"bytes": 0, "ms": 0.0, "launches": 0})
+        k = by_kernel.setdefault(keys[lo], {"bytes": 0, "flops": 0, "ms": 0.0, "launches": 0})
         for l in range(lo, hi + 1):
             n = int(counts[l])
             share = float(gms) * (algo[l] / gbytes) if gbytes else 0.0
@@ -250,6 +255,7 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
                               "hit_rate": None if hits[l] is None else round(hits[l], 4)})
             if n:
                 k["bytes"] += algo[l]
+                k["flops"] += flops[l]
                 k["launches"] += 1
         if gbytes:
             k["ms"] += float(gms)
@@ -263,6 +269,14 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
                 "bytes_per_launch": int(dom["bytes"] / max(1, dom["launches"])),
                 "avg_launch_us": round(dom["ms"] / max(1, dom["launches"]) * 1e3, 2),
                 "launches_per_step": dom["launches"]}
+    if dom["flops"]:
+        # FC(h): a dense contraction (split-K MFMA kernel + split reduction); report it against the
+        # matrix-core peak of its dtype, and keep the byte rate beside it
+        tf = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        peak = MFMA_PEAK_TFLOPS[spec.layers[0].dtype]
+        roofline.update({"bound": "mfma", "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s",
+                         "frac": round(tf / peak, 4), "flops_per_launch": int(dom["flops"] / max(1, dom["launches"])),
+                         "hbm_GBps": round(achieved, 1), "traffic": None})
     pool_total_bytes = sum(k["bytes"] for k in by_kernel.values())
     pool_total_ms = sum(k["ms"] for k in by_kernel.values())
     out = {

@@ -74,7 +74,7 @@ typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1 } gati_selector_t;
  *   GATI_PRED_FC_MLP   the paper's FC(h): the activation row flattened in storage order (D = C*S
  *                      values) -> FC(D->H) -> ReLU -> FC(H->K).  W1 is [H, D]; the selector reads
  *                      [hidden ; prob], so ws is [H + K]; the "pooled" features reported by
- *                      gati_cache_pool are the H hidden activations.  D must be a multiple of 16
+ *                      gati_cache_pool are the H hidden activations.  D must be a multiple of 64
  *                      (GATI_ERR_UNSUPPORTED otherwise).                                           */
 typedef enum { GATI_PRED_GAP_MLP = 0, GATI_PRED_POOL_FC = 1, GATI_PRED_FC_MLP = 2 } gati_predictor_t;
 

@@ -231,6 +231,26 @@ void pack_weights(const float* W, int rows, int cols, int rows_p, int cols_p, in
                 }
 }
 
+// W1 of the FC(h) predictor: as pack_weights, but within every block of 4 k-steps lane half kb
+// owns 2*k_step consecutive inputs (see flat_kernels.h): fragment (nt, ks, lane, e) holds
+// W[nt*32 + lane%32][(ks/4)*4*k_step + (lane/32)*2*k_step + (ks%4)*k_lane + e].
+template <typename T, typename Conv>
+void pack_weights_flat(const float* W, int rows, long cols, int rows_p, int k_step, std::vector<T>& out, Conv conv) {
+    const int k_lane = k_step / 2;
+    const long KS = cols / k_step;
+    out.assign((size_t)rows_p * cols, conv(0.f));
+    for (int nt = 0; nt < rows_p / 32; ++nt)
+        for (long ks = 0; ks < KS; ++ks)
+            for (int l = 0; l < 64; ++l) {
+                const int row = nt * 32 + (l & 31);
+                if (row >= rows) continue;
+                const long col0 = (ks >> 2) * 4 * k_step + (long)(l >> 5) * 2 * k_step + (ks & 3) * k_lane;
+                T* dst = &out[(((size_t)nt * KS + ks) * 64 + l) * k_lane];
+                const float* src = &W[(size_t)row * cols + col0];
+                for (int e = 0; e < k_lane; ++e) dst[e] = conv(src[e]);
+            }
+}
+
 template <typename Tag>
 hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, hipStream_t st) {
     const int max_blocks = c->num_cu * c->pool_blocks_per_cu;
@@ -335,9 +355,19 @@ hipError_t launch_flat_t(const gati_cache* c, const void* act, const int32_t* ro
     f.tiles_m = std::min(c->flat_tiles_m, (n_max + 64 * c->flat_t - 1) / (64 * c->flat_t));
     f.partial = c->flat_partial;
     const int grid = f.tiles_m * f.tiles_n * f.splits;
-    if (c->flat_t == 4) fc_flat_kernel<BF16, 4, 4><<<grid, 256, 0, st>>>(f);
-    else if (c->flat_t == 2) fc_flat_kernel<BF16, 2, 2><<<grid, 256, 0, st>>>(f);
-    else fc_flat_kernel<BF16, 1, 1><<<grid, 256, 0, st>>>(f);
+    if (c->flat_t == 4 && env_int("GATI_FLAT_LDS", 1) == 1) {
+        const int depth = env_int("GATI_FLAT_DEPTH", 3);
+        if (depth == 1) fc_flat_lds_kernel<BF16, 1><<<grid, 256, 0, st>>>(f);
+        else if (depth == 2) fc_flat_lds_kernel<BF16, 2><<<grid, 256, 0, st>>>(f);
+        else if (depth == 4) fc_flat_lds_kernel<BF16, 4><<<grid, 256, 0, st>>>(f);
+        else fc_flat_lds_kernel<BF16, 3><<<grid, 256, 0, st>>>(f);
+    } else if (c->flat_t == 4) {
+        const int ring = env_int("GATI_FLAT_RING", 5);
+        if (ring == 4) fc_flat_kernel<BF16, 4, 4, 4><<<grid, 256, 0, st>>>(f);
+        else if (ring == 6) fc_flat_kernel<BF16, 4, 4, 6><<<grid, 256, 0, st>>>(f);
+        else fc_flat_kernel<BF16, 4, 4, 5><<<grid, 256, 0, st>>>(f);
+    } else if (c->flat_t == 2) fc_flat_kernel<BF16, 2, 2, 6><<<grid, 256, 0, st>>>(f);
+    else fc_flat_kernel<BF16, 1, 1, 8><<<grid, 256, 0, st>>>(f);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     FlatReduceArgs r;
@@ -455,7 +485,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_SOFTMAX) return GATI_ERR_INVALID_ARG;
     if (!w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
-    if (flat_fc && ((long)desc->C * desc->S) % 16 != 0) return GATI_ERR_UNSUPPORTED;
+    if (flat_fc && ((long)desc->C * desc->S) % 64 != 0) return GATI_ERR_UNSUPPORTED;
     if (flat_fc && (long)desc->C * desc->S >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
     if (!(desc->threshold == desc->threshold)) return GATI_ERR_INVALID_ARG;   // NaN
     // sizes whose padded products still fit the kernels' 32-bit tile arithmetic
@@ -492,6 +522,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         const int k_step = c->bf16 ? 16 : 8;
         const long D = (long)desc->C * desc->S;
         c->flat_t = (desc->max_rows >= 256 && desc->H >= 256) ? 4 : (desc->max_rows >= 128 && desc->H >= 128) ? 2 : 1;
+        c->flat_t = std::min(c->flat_t, env_int("GATI_FLAT_TILE", 4));
         c->flat_KS = (int)(D / k_step);
         c->Hb = round_up(desc->H, 64 * c->flat_t);
         c->rows_b = round_up(desc->max_rows, 64 * c->flat_t);
@@ -499,10 +530,10 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         c->flat_tiles_n = c->Hb / (64 * c->flat_t);
         const int tiles = c->flat_tiles_m * c->flat_tiles_n;
         // enough workgroups for every CU, each with at least 16 k-steps; multiples of 8 keep the XCD mapping
-        int splits = std::max(1, std::min(c->num_cu / tiles, c->flat_KS / 16));
+        int splits = std::max(1, std::min(env_int("GATI_FLAT_WGS", c->num_cu) / tiles, c->flat_KS / 16));
         if (splits >= 8) splits = splits / 8 * 8;
         splits = std::min(splits, env_int("GATI_FLAT_MAX_SPLITS", 64));
-        c->flat_ks_per = (c->flat_KS + splits - 1) / splits;
+        c->flat_ks_per = round_up((c->flat_KS + splits - 1) / splits, 4);   // whole permutation blocks
         c->flat_splits = (c->flat_KS + c->flat_ks_per - 1) / c->flat_ks_per;
         c->variant = POOL_FC_FLAT;
     } else {
@@ -517,7 +548,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
             std::vector<uint16_t> t1, t2;
             if (flat_fc) {
                 const int D = desc->C * desc->S;
-                pack_weights(w->W1, desc->H, D, c->Hb, D, 16, t1, f32_to_bf16_rne);
+                pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 16, t1, f32_to_bf16_rne);
                 st = upload(&c->W1, t1.data(), t1.size() * 2);
             } else if (!pool_fc) {
                 pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
@@ -530,7 +561,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
             auto same = [](float x) { return x; };
             if (flat_fc) {
                 const int D = desc->C * desc->S;
-                pack_weights(w->W1, desc->H, D, c->Hb, D, 8, t1, same);
+                pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 8, t1, same);
                 st = upload(&c->W1, t1.data(), t1.size() * 4);
             } else if (!pool_fc) {
                 pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);

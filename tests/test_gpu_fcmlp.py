@@ -25,7 +25,7 @@ def _weights(D, H, K, rng):
     (8, 16, 40, 7, 45, "bf16", "ncs"),        # 1x1 wave tiles, one split
     (64, 64, 128, 33, 150, "f32", "ncs"),     # 2x2 wave tiles, fp32 MFMA
     (32, 196, 256, 100, 300, "bf16", "ncs"),  # 4x4 wave tiles, several splits, ragged rows
-    (48, 50, 256, 20, 260, "bf16", "nsc"),    # token-major storage: flattened as stored
+    (48, 64, 256, 20, 260, "bf16", "nsc"),    # token-major storage: flattened as stored
 ])
 def test_fc_mlp_lookup_matches_oracle(C, S, H, K, n, dtype, layout):
     rng = np.random.default_rng(C * S + H)
@@ -86,4 +86,4 @@ def test_fc_mlp_rejects_unaligned_width():
     desc = g.CacheDesc(5, 7, 8, 3, g.GATI_F32, g.GATI_LAYOUT_NCS, 0.5, 4, g.GATI_SEL_LINEAR, g.GATI_PRED_FC_MLP, 0, 0, 0, 0)
     keep = [np.ascontiguousarray(w[k]) for k in ("W1", "b1", "W2", "b2", "ws")]
     cw = g.CacheWeights(*(a.ctypes.data for a in keep), 0.0)
-    assert g.gati_cache_create(desc, cw)[0] == g.GATI_ERR_UNSUPPORTED      # D = 35 is not a multiple of 16
+    assert g.gati_cache_create(desc, cw)[0] == g.GATI_ERR_UNSUPPORTED      # D = 35 is not a multiple of 64

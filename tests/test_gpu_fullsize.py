@@ -135,3 +135,30 @@ def test_resnet152_streaming_dense_stack():
                "hit": ht.cpu().numpy()}
         _check_sampled_rows(spec, l, defs[l], weights[l], acts[l], np.arange(n), got, pick)
     stack.close()
+
+
+def test_resnet50_fc_full_batch():
+    """The paper's FC(h) predictor at full batch on three of the six blocks of the resnet50_fc
+    workload (D = 401408, 200704, 100352 inputs per row): chain properties and sampled rows."""
+    base = W.get_workload("resnet50_fc")
+    spec = W.WorkloadSpec(name="resnet50_fc[1,3,5]", batch=base.batch, zipf_s=base.zipf_s, seed=base.seed,
+                          layers=[base.layers[i] for i in (1, 3, 5)], storage="gather")
+    labels = W.zipf_labels(spec.batch, spec.layers[0].K, spec.zipf_s, spec.seed)
+    weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
+    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w, predictor=L.predictor)
+              for L, w in zip(spec.layers, weights)]
+    defs = admit.cache_defs(spec, mirror=True)
+    acts = [W.activation_bulk(spec, l, labels, np.arange(spec.batch), device="cuda") for l in range(len(spec.layers))]
+    stack = g.CacheStack(caches, spec.batch, storage="gather", keep_logits=True)
+    stack.run(acts)
+    torch.cuda.synchronize()
+    counts = _check_chain_properties(stack, spec.batch, len(caches))
+    rng = np.random.default_rng(11)
+    for l in range(len(caches)):
+        n = int(counts[l])
+        pick = rng.choice(n, size=2, replace=False)
+        ids = stack.ids[l].cpu().numpy()[:n]
+        got = {"logits": stack.logits[l].cpu().numpy(), "confidence": stack.confidence[l].cpu().numpy(),
+               "pred_class": stack.pred_class[l].cpu().numpy(), "hit": stack.hit[l].cpu().numpy()}
+        _check_sampled_rows(spec, l, defs[l], weights[l], acts[l], ids, got, pick)
+    stack.close()

@@ -27,13 +27,16 @@ class LayerSpec:
     bs: float = 0.0   # selector bias (calibrated per layer for the hit-rate ramps)
     target_hit: Optional[float] = None  # per-layer hit-rate target the bias was fitted to
     predictor: str = "gap_mlp"   # "gap_mlp" | "pool_fc" (the paper's Pool(h): adaptive pool -> ReLU -> FC)
+                                 # | "fc_mlp" (the paper's FC(h): flattened activation -> FC -> ReLU -> FC)
     in_hw: tuple = (0, 0)        # pool_fc: feature-map size, S = in_h*in_w
     out_hw: tuple = (0, 0)       # pool_fc: pooled map; F = C*out_h*out_w features
 
     @property
     def F(self) -> int:
         """Features the pooling step hands to the FC layers."""
-        return self.C * self.out_hw[0] * self.out_hw[1] if self.predictor == "pool_fc" else self.C
+        if self.predictor == "pool_fc":
+            return self.C * self.out_hw[0] * self.out_hw[1]
+        return self.H if self.predictor == "fc_mlp" else self.C
 
     @property
     def elem_bytes(self) -> int:
@@ -117,6 +120,14 @@ def _build():
         layers=_resnet_stack([(256, 56, 3), (512, 28, 4), (1024, 14, 6), (2048, 7, 3)],
                              H=0, K=1000, dtype="bf16", tau=0.6, gammas=(8.0, 32.0),
                              pool_out={56: 4, 28: 4, 14: 2, 7: 2}))
+    # The paper's FC(h) variant (h = 1024, its default) at six ResNet-50 blocks -- the paper's GPU
+    # composition for ResNet-50 ends up with six FC caches (Section 7.1).  Blocks 3, 6, 9, 11, 13, 16.
+    fc_blocks = [(256, 56), (512, 28), (1024, 14), (1024, 14), (1024, 14), (2048, 7)]
+    w["resnet50_fc"] = WorkloadSpec(
+        name="resnet50_fc", batch=512, zipf_s=1.1, seed=0,
+        layers=[LayerSpec(C=C, S=hw * hw, H=1024, K=1000, layout="ncs", dtype="bf16", threshold=0.6,
+                          gamma=8.0 + 4.8 * i, relu=True, predictor="fc_mlp")
+                for i, (C, hw) in enumerate(fc_blocks)])
     return w
 
 
@@ -130,6 +141,7 @@ HIT_TARGETS = {
     "resnet18": _linear_ramp(0.05, 0.35, 8),
     "resnet50": [0.0065 * (i + 1) for i in range(16)],
     "resnet50_pool": [0.0065 * (i + 1) for i in range(16)],
+    "resnet50_fc": _linear_ramp(0.05, 0.20, 6),
     "bert_base": _linear_ramp(0.02, 0.20, 12),
     "resnet152": _linear_ramp(0.02, 0.70, 50),
 }

@@ -57,6 +57,18 @@ def cache_weights(spec: WorkloadSpec, layer: int) -> dict:
         W2 = (g.standard_normal((L.K, L.F)) * np.sqrt(2.0 / L.F)).astype(np.float32)
         ws = (g.standard_normal(L.F + L.K) * np.sqrt(2.0 / (L.F + L.K))).astype(np.float32)
         return {"W1": None, "b1": None, "W2": W2, "b2": np.zeros(L.K, np.float32), "ws": ws, "bs": float(L.bs)}
+    if L.predictor == "fc_mlp":
+        # FC(h): the first FC reads the whole flattened row (D = C*S inputs); drawn in float32
+        # row blocks to keep the host footprint at one copy of the matrix
+        D = L.C * L.S
+        W1 = np.empty((L.H, D), np.float32)
+        scale = np.float32(np.sqrt(2.0 / D))
+        for j0 in range(0, L.H, 64):
+            W1[j0:j0 + 64] = g.standard_normal((min(64, L.H - j0), D), dtype=np.float32) * scale
+        W2 = (g.standard_normal((L.K, L.H)) * np.sqrt(2.0 / L.H)).astype(np.float32)
+        ws = (g.standard_normal(L.H + L.K) * np.sqrt(2.0 / (L.H + L.K))).astype(np.float32)
+        return {"W1": W1, "b1": np.zeros(L.H, np.float32), "W2": W2, "b2": np.zeros(L.K, np.float32),
+                "ws": ws, "bs": float(L.bs)}
     W1 = (g.standard_normal((L.H, L.C)) * np.sqrt(2.0 / L.C)).astype(np.float32)
     W2 = (g.standard_normal((L.K, L.H)) * np.sqrt(2.0 / L.H)).astype(np.float32)
     ws = (g.standard_normal(L.C + L.K) * np.sqrt(2.0 / (L.C + L.K))).astype(np.float32)
