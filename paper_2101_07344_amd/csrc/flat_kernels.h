@@ -9,12 +9,13 @@
 // to fill 256 CUs otherwise).  Each wave keeps an MT x NT grid of 32x32 accumulators (256
 // AGPRs at MT = NT = 4), so one A fragment feeds NT MFMAs and one B fragment MT MFMAs.  Both
 // operands are contiguous along the reduction axis -- the activation row as stored, the
-// weights repacked at creation into MFMA fragment order -- so fragments are 16-byte loads
-// straight from global memory into a register ring several k-steps deep; the 4 waves of a workgroup share them through
-// L1/L2.  Within every block of 4 k-steps the reduction index is permuted so that a lane's four
-// A fragments are 64 contiguous bytes of its row (lanes kb = 0 / 1 take the two halves of a
-// 128-byte line): the line is requested whole while the four loads are in flight, instead of
-// in 32-byte pieces.  The weights are packed with the same permutation (pack_weights_flat).
+// weights repacked at creation into MFMA fragment order.  Within every block of 4 k-steps the
+// reduction index is permuted so that the eight 16-byte chunks of a row's 128-byte line are
+// (k-step j&3, lane half j>>2): a lane's four A fragments of the block are 64 contiguous bytes
+// of its row.  The weights are packed with the same permutation (pack_weights_flat).
+// Two kernels: fc_flat_kernel (small tiles, MT = NT = 1 or 2: 16-byte fragment loads straight
+// from global memory into a register ring several k-steps deep, the waves sharing them through
+// L1/L2) and fc_flat_lds_kernel (the full 256 x 256 tile, operands staged through LDS).
 // Split partial tiles go to a workspace and are added in split order by a second
 // kernel (bias, ReLU, fp32 + bf16 features), which keeps the result bit-reproducible.
 // The grid is linear and XCD-aware: the workgroups that share an operand slice (same split,
@@ -140,23 +141,40 @@ __global__ __launch_bounds__(256) void fc_flat_kernel(FlatArgs a) {
 }
 
 // The same contraction with the operands shared through LDS, for the full-size 256 x 256
-// workgroup tile (MT = NT = 4).  Loading every fragment straight into the registers of each
-// wave that needs it makes the two waves of a tile row (column) fetch the same A (B) fragments
-// twice, and the vector memory pipeline -- 32 scattered 128-byte lines per A fragment -- then
-// caps the MFMA duty cycle near a quarter.  Here the 4 waves split the 16 fragments of a k-step
-// (8 row blocks of A, 8 column blocks of B) four each, park them in LDS in fragment order
-// (lane i's 16 bytes at slot 16*i, so both the store and the later ds_read_b128 are
-// conflict-free), and after one barrier per stage every wave reads the 4 + 4 fragments of its
-// own 128 x 128 quadrant.  Two LDS slots of U = 2 k-steps (64 KB) and P stages of global loads
-// in flight in registers, so a load has P stages of MFMA work to cover its latency.
+// workgroup tile (four waves, each a 128 x 128 quadrant held in 16 accumulator tiles).
+//
+// Why not load fragments straight into the registers of each wave that needs them: the two waves
+// of a tile row (column) then fetch the same A (B) fragments twice, and -- worse -- an A fragment
+// load touches 32 rows x 32 bytes, a quarter of each 128-byte line.  The other three quarters are
+// wanted by the next three k-steps, but by then 64 KB has passed through the 32 KB vector L1 and
+// the line is gone: counters showed every activation line crossing L2 -> L1 four times and the
+// MFMA pipe busy a third of the time.
+//
+// Here a stage is U = 4 k-steps = one whole 128-byte line per activation row.  The four waves
+// split the stage's loads (64 rows x 128 B of A and 2 column blocks x 4 k-steps of packed B
+// each, all full lines), park them in one of two 64 KB LDS slots, and after ONE barrier per
+// stage every wave reads the 4 + 4 fragments per k-step of its quadrant with ds_read_b128.
+//
+// LDS slot layout: fragment (u, f) -- k-step u of the stage, f = 0..7 the A row blocks, 8..15 the
+// B column blocks -- is 1 KB at u*16 KB + f*1 KB.  A B fragment is stored lane-major (lane l at
+// 16*l).  An A fragment is two 512-byte halves (kb = 0, 1), and inside a half row r sits at
+// (r>>3)*128 + (((r&7) + u + 4*kb) & 7)*16: the rotation by the chunk number u + 4*kb makes the
+// eight lanes that hold the eight 16-byte chunks of ONE row (a loader's natural, coalesced
+// assignment) hit eight different bank groups, while a reader's eight consecutive rows still
+// cover one whole 128-byte group.  Neither side has bank conflicts.
+//
+// P stages of global loads (16 x 16 bytes per lane each) are in flight in registers; each group of
+// four registers is reloaded P+1 stages ahead right after its LDS stores, so a load has P whole
+// stages of MFMA work (P x 2048 MFMA cycles per wave) to cover its latency.
 template <bool BF16, int P>
 __global__ __launch_bounds__(256) void fc_flat_lds_kernel(FlatArgs a) {
     using M = Mma<BF16>;
     using frag_t = typename M::frag_t;
     constexpr int kStep = M::kStep;
     constexpr int kElem = BF16 ? 2 : 4;
-    constexpr int U = 2;
-    __shared__ frag_t lds[2][U][16][64];          // [slot][k-step][A row blocks 0-7, B column blocks 8-15][lane]
+    constexpr int U = 4;
+    constexpr int kSlot = U * 16 * 1024;                     // bytes per LDS slot
+    extern __shared__ __align__(16) unsigned char flat_lds[];   // 2 slots
 
     const int n = active_rows(a.n_dev, a.n_max);
     const int tid = threadIdx.x;
@@ -180,41 +198,61 @@ __global__ __launch_bounds__(256) void fc_flat_lds_kernel(FlatArgs a) {
 
     const int ks0 = split * a.ks_per_split;
     const int ks1 = min(a.KS, ks0 + a.ks_per_split);
-    const int steps = ks1 - ks0;                             // a multiple of 4
-    const int stages = (steps + U - 1) / U;
-    const int last = steps - 1;
+    const int steps = ks1 - ks0;                             // a multiple of 4: whole stages
+    const int stages = steps / U;
 
-    // loader role: this wave fetches row blocks 2*wave, 2*wave+1 of A and the same column blocks of B
-    const frag_t* apg[2];
+    // ---- loader role: rows [64*wave, 64*wave+64) of A, column blocks 2*wave, 2*wave+1 of B ----
+    // load i of a stage covers 8 rows x 128 B: lane -> (row lane>>3, 16-byte chunk j = lane&7).
+    // Chunk j of a line belongs to k-step j&3, half j>>2 (the k order inside a block of 4 k-steps
+    // is the permuted one fc_flat_kernel documents; the packed weights follow it).
+    const int row_in = lane >> 3, j = lane & 7;
+    const frag_t* apg[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = min(tile_row0 + wave * 64 + i * 8 + row_in, n - 1);   // rows past n re-read row n-1
+        const long src = a.row_index ? (long)a.row_index[row] : (long)row;
+        apg[i] = reinterpret_cast<const frag_t*>(static_cast<const char*>(a.act) +
+                                                 (src * a.D + (long)ks0 * kStep) * kElem) + j;
+    }
     const frag_t* bpg[2];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int row = min(tile_row0 + (2 * wave + q) * 32 + r, n - 1);   // rows past n re-read row n-1
-        const long src = a.row_index ? (long)a.row_index[row] : (long)row;
-        apg[q] = reinterpret_cast<const frag_t*>(static_cast<const char*>(a.act) +
-                                                 (src * a.D + (long)ks0 * kStep) * kElem) + kb * 4;
+    for (int q = 0; q < 2; ++q)
         bpg[q] = reinterpret_cast<const frag_t*>(a.Wp) + ((long)(tile_n * 8 + 2 * wave + q) * a.KS + ks0) * 64 + lane;
-    }
-    frag_t g[P][U][4];                                      // stage q waits in g[q % P]
-    auto gload = [&](frag_t (&gs)[U][4], int first_k) {
+    // LDS store offsets: A load i goes to row block 2*wave + (i>>2), rows (i&3)*8 + row_in
+    const int wa_off = (j & 3) * 16384 + wave * 2048 + (j >> 2) * 512 + ((row_in + j) & 7) * 16;
+    const int wb_off = (8 + 2 * wave) * 1024 + lane * 16;
+    // LDS read offsets of this wave's quadrant
+    int ra_off[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int k = min(first_k + u, last);
-            const int fa = (k >> 2) * 8 + (k & 3);           // see fc_flat_kernel: permuted k within blocks of 4
-            gs[u][0] = apg[0][fa];
-            gs[u][1] = apg[1][fa];
-            gs[u][2] = bpg[0][(long)k * 64];
-            gs[u][3] = bpg[1][(long)k * 64];
+    for (int u = 0; u < U; ++u)
+        ra_off[u] = u * 16384 + wm * 4096 + kb * 512 + (r >> 3) * 128 + (((r & 7) + u + 4 * kb) & 7) * 16;
+    const int rb_off = (8 + 4 * wn) * 1024 + lane * 16;
+
+    frag_t g[P][16];                                         // stage q waits in g[q % P]: 8 A loads, 2 x 4 B loads
+    auto gload = [&](frag_t (&g)[16], int t_raw, int first, int count) {
+        const int t = min(t_raw, stages - 1);                // the tail re-reads the last stage
+#pragma unroll
+        for (int e = first; e < first + count; ++e) {
+            if (e < 8) g[e] = apg[e][(long)t * 8];
+            else g[e] = bpg[(e - 8) >> 2][(long)(t * U + ((e - 8) & 3)) * 64];
         }
     };
-    auto lwrite = [&](int slot, const frag_t (&gs)[U][4]) {
+    auto lstore = [&](int slot, const frag_t (&g)[16], int first, int count) {
+        unsigned char* base = flat_lds + slot * kSlot;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            lds[slot][u][2 * wave][lane] = gs[u][0];
-            lds[slot][u][2 * wave + 1][lane] = gs[u][1];
-            lds[slot][u][8 + 2 * wave][lane] = gs[u][2];
-            lds[slot][u][8 + 2 * wave + 1][lane] = gs[u][3];
+        for (int e = first; e < first + count; ++e) {
+            if (e < 8)
+                *reinterpret_cast<frag_t*>(base + wa_off + (e >> 2) * 1024 + (e & 3) * 128) = g[e];
+            else
+                *reinterpret_cast<frag_t*>(base + wb_off + ((e - 8) & 3) * 16384 + ((e - 8) >> 2) * 1024) = g[e];
         }
+    };
+    auto lread = [&](frag_t (&af)[4], frag_t (&bf)[4], int slot, int u) {
+        const unsigned char* base = flat_lds + slot * kSlot;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) af[m] = *reinterpret_cast<const frag_t*>(base + ra_off[u] + m * 1024);
+#pragma unroll
+        for (int nn = 0; nn < 4; ++nn) bf[nn] = *reinterpret_cast<const frag_t*>(base + u * 16384 + rb_off + nn * 1024);
     };
 
     f32x16_t acc[4][4];
@@ -223,44 +261,77 @@ __global__ __launch_bounds__(256) void fc_flat_lds_kernel(FlatArgs a) {
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+            for (int jj = 0; jj < 16; ++jj) acc[mt][nt][jj] = 0.f;
 
-    if (stages > 0) {
-        gload(g[0], 0);
-        lwrite(0, g[0]);
+    frag_t ax[4], bx[4], ay[4], by[4];                       // fragments of even / odd k-steps
+    auto mma_rows = [&](const frag_t (&af)[4], const frag_t (&bf)[4], int m0) {
 #pragma unroll
-        for (int q = 1; q <= P; ++q)
-            if (q < stages) gload(g[q % P], q * U);
-    }
-    __syncthreads();
-    for (int s0 = 0; s0 < stages; s0 += P) {
+        for (int m = m0; m < m0 + 2; ++m)
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const int s = s0 + p;
-            if (s < stages) {                                // uniform over the workgroup
-                const int slot = s & 1;
+            for (int nn = 0; nn < 4; ++nn) acc[m][nn] = M::mma(af[m], bf[nn], acc[m][nn]);
+    };
+    // One stage, order fixed by hand with scheduling fences: every LDS read is issued half a k-step
+    // or more before its MFMAs, the LDS stores of stage s+1 and the reloads for stage s+2 are spread
+    // between MFMA groups, and the single barrier sits inside the last k-step.  A slot is overwritten
+    // only after the barrier that follows the last MFMA-consumed read of it, and read only after the
+    // barrier that follows its stores.  Every global load is issued unconditionally: a load under a
+    // branch would make the compiler wait for ALL outstanding loads before each LDS store, because
+    // the wait counter only orders loads that are certain to have been issued.
+    auto stage = [&](int s, frag_t (&gs)[16]) {
+        const int slot = s & 1;
+        lread(ay, by, slot, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ax, bx, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        lstore(slot ^ 1, gs, 0, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ax, bx, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        lread(ax, bx, slot, 2);
+        gload(gs, s + 1 + P, 0, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ay, by, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        lstore(slot ^ 1, gs, 4, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ay, by, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        lread(ay, by, slot, 3);
+        gload(gs, s + 1 + P, 4, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ax, bx, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        lstore(slot ^ 1, gs, 8, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ax, bx, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        lstore(slot ^ 1, gs, 12, 4);
+        gload(gs, s + 1 + P, 8, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ay, by, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        lread(ax, bx, slot ^ 1, 0);
+        gload(gs, s + 1 + P, 12, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_rows(ay, by, 2);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    if (stages > 0) {                                        // uniform over the workgroup
+        gload(g[0], 0, 0, 16);
+        lstore(0, g[0], 0, 16);
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (s * U + u < steps) {
-                        frag_t af[4], bf[4];
+        for (int q = 1; q <= P; ++q) gload(g[q % P], q, 0, 16);
+        __syncthreads();
+        lread(ax, bx, 0, 0);
+        int s0 = 0;
+        for (; s0 + P <= stages; s0 += P) {
 #pragma unroll
-                        for (int m = 0; m < 4; ++m) af[m] = lds[slot][u][4 * wm + m][lane];
-#pragma unroll
-                        for (int nn = 0; nn < 4; ++nn) bf[nn] = lds[slot][u][8 + 4 * wn + nn][lane];
-#pragma unroll
-                        for (int m = 0; m < 4; ++m)
-#pragma unroll
-                            for (int nn = 0; nn < 4; ++nn) acc[m][nn] = M::mma(af[m], bf[nn], acc[m][nn]);
-                    }
-                }
-                if (s + 1 < stages) {
-                    // every wave finished reading that slot before the previous barrier
-                    lwrite(slot ^ 1, g[(p + 1) % P]);
-                    if (s + 1 + P < stages) gload(g[(p + 1) % P], (s + 1 + P) * U);
-                }
-                __syncthreads();
-            }
+            for (int p = 0; p < P; ++p) stage(s0 + p, g[(p + 1) % P]);
         }
+#pragma unroll
+        for (int p = 0; p < P - 1; ++p)                      // the last stages % P stages
+            if (s0 + p < stages) stage(s0 + p, g[(p + 1) % P]);
     }
 
     const int row_base = tile_row0 + wm * 128;
@@ -271,10 +342,10 @@ __global__ __launch_bounds__(256) void fc_flat_lds_kernel(FlatArgs a) {
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int row = row_base + mt * 32 + mfma_row(j, kb);
+            for (int jj = 0; jj < 16; ++jj) {
+                const int row = row_base + mt * 32 + mfma_row(jj, kb);
                 const int col = (col_tile0 + nt) * 32 + r;
-                out[(long)row * a.Hb + col] = acc[mt][nt][j];
+                out[(long)row * a.Hb + col] = acc[mt][nt][jj];
             }
 }
 

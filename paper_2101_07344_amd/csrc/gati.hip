@@ -342,6 +342,16 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
     return hipGetLastError();
 }
 
+// Two 64 KB LDS slots of the 256 x 256 FC(h) kernel: above the 64 KB a kernel gets by default, so
+// the limit is raised for the device when a cache that uses the kernel is created.
+constexpr int kFlatLdsBytes = 2 * 4 * 16 * 1024;
+
+hipError_t raise_flat_lds_limit(bool bf16) {
+    const void* kern = bf16 ? reinterpret_cast<const void*>(fc_flat_lds_kernel<true, 2>)
+                            : reinterpret_cast<const void*>(fc_flat_lds_kernel<false, 2>);
+    return hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kFlatLdsBytes);
+}
+
 // FC(h): features = relu(W1 x + b1) over the flattened rows: split-K MFMA tiles, then the
 // fixed-order reduction of the splits.
 template <bool BF16>
@@ -355,18 +365,8 @@ hipError_t launch_flat_t(const gati_cache* c, const void* act, const int32_t* ro
     f.tiles_m = std::min(c->flat_tiles_m, (n_max + 64 * c->flat_t - 1) / (64 * c->flat_t));
     f.partial = c->flat_partial;
     const int grid = f.tiles_m * f.tiles_n * f.splits;
-    if (c->flat_t == 4 && env_int("GATI_FLAT_LDS", 1) == 1) {
-        const int depth = env_int("GATI_FLAT_DEPTH", 3);
-        if (depth == 1) fc_flat_lds_kernel<BF16, 1><<<grid, 256, 0, st>>>(f);
-        else if (depth == 2) fc_flat_lds_kernel<BF16, 2><<<grid, 256, 0, st>>>(f);
-        else if (depth == 4) fc_flat_lds_kernel<BF16, 4><<<grid, 256, 0, st>>>(f);
-        else fc_flat_lds_kernel<BF16, 3><<<grid, 256, 0, st>>>(f);
-    } else if (c->flat_t == 4) {
-        const int ring = env_int("GATI_FLAT_RING", 5);
-        if (ring == 4) fc_flat_kernel<BF16, 4, 4, 4><<<grid, 256, 0, st>>>(f);
-        else if (ring == 6) fc_flat_kernel<BF16, 4, 4, 6><<<grid, 256, 0, st>>>(f);
-        else fc_flat_kernel<BF16, 4, 4, 5><<<grid, 256, 0, st>>>(f);
-    } else if (c->flat_t == 2) fc_flat_kernel<BF16, 2, 2, 6><<<grid, 256, 0, st>>>(f);
+    if (c->flat_t == 4) fc_flat_lds_kernel<BF16, 2><<<grid, 256, kFlatLdsBytes, st>>>(f);
+    else if (c->flat_t == 2) fc_flat_kernel<BF16, 2, 2, 6><<<grid, 256, 0, st>>>(f);
     else fc_flat_kernel<BF16, 1, 1, 8><<<grid, 256, 0, st>>>(f);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -522,7 +522,9 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         const int k_step = c->bf16 ? 16 : 8;
         const long D = (long)desc->C * desc->S;
         c->flat_t = (desc->max_rows >= 256 && desc->H >= 256) ? 4 : (desc->max_rows >= 128 && desc->H >= 128) ? 2 : 1;
-        c->flat_t = std::min(c->flat_t, env_int("GATI_FLAT_TILE", 4));
+        if (c->flat_t == 4 && raise_flat_lds_limit(c->bf16) != hipSuccess) {
+            (void)hipGetLastError(); delete c; return GATI_ERR_DEVICE;
+        }
         c->flat_KS = (int)(D / k_step);
         c->Hb = round_up(desc->H, 64 * c->flat_t);
         c->rows_b = round_up(desc->max_rows, 64 * c->flat_t);
@@ -530,7 +532,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         c->flat_tiles_n = c->Hb / (64 * c->flat_t);
         const int tiles = c->flat_tiles_m * c->flat_tiles_n;
         // enough workgroups for every CU, each with at least 16 k-steps; multiples of 8 keep the XCD mapping
-        int splits = std::max(1, std::min(env_int("GATI_FLAT_WGS", c->num_cu) / tiles, c->flat_KS / 16));
+        int splits = std::max(1, std::min(c->num_cu / tiles, c->flat_KS / 16));
         if (splits >= 8) splits = splits / 8 * 8;
         splits = std::min(splits, env_int("GATI_FLAT_MAX_SPLITS", 64));
         c->flat_ks_per = round_up((c->flat_KS + splits - 1) / splits, 4);   // whole permutation blocks

@@ -26,6 +26,7 @@ def _weights(D, H, K, rng):
     (64, 64, 128, 33, 150, "f32", "ncs"),     # 2x2 wave tiles, fp32 MFMA
     (32, 196, 256, 100, 300, "bf16", "ncs"),  # 4x4 wave tiles, several splits, ragged rows
     (48, 64, 256, 20, 260, "bf16", "nsc"),    # token-major storage: flattened as stored
+    (16, 72, 256, 12, 270, "f32", "ncs"),     # 4x4 wave tiles through LDS, fp32 MFMA, odd stage count
 ])
 def test_fc_mlp_lookup_matches_oracle(C, S, H, K, n, dtype, layout):
     rng = np.random.default_rng(C * S + H)
