@@ -34,12 +34,14 @@ class _Desc(C.Structure):
     _fields_ = [("C", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("K", C.c_int32),
                 ("act_dtype", C.c_int32), ("layout", C.c_int32), ("round_operands", C.c_int32),
                 ("threshold", C.c_float), ("selector", C.c_int32), ("predictor", C.c_int32),
-                ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32)]
+                ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32),
+                ("sel_hidden", C.c_int32)]
 
 
 class _Weights(C.Structure):
     _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
-                ("ws", C.c_void_p), ("bs", C.c_float)]
+                ("ws", C.c_void_p), ("bs", C.c_float),
+                ("Ws", C.c_void_p), ("cs", C.c_void_p), ("vs", C.c_void_p)]
 
 
 _lib = None
@@ -68,6 +70,8 @@ def _load():
         _lib.oracle_softmax_argmax.argtypes = [C.c_int, C.c_void_p, C.c_void_p]
         _lib.oracle_selector_score.restype = C.c_double
         _lib.oracle_selector_score.argtypes = [C.POINTER(_Desc), C.POINTER(_Weights), C.c_void_p, C.c_void_p]
+        _lib.oracle_selector_hidden_score.restype = C.c_double
+        _lib.oracle_selector_hidden_score.argtypes = [C.POINTER(_Desc), C.POINTER(_Weights), C.c_void_p, C.c_void_p]
     return _lib
 
 
@@ -86,11 +90,13 @@ class CacheDef:
     layout: str = "ncs"         # "ncs" | "nsc"
     threshold: float = 0.5
     round_operands: bool = False  # bf16 cache arithmetic (see gati_oracle.c)
-    selector: str = "linear"    # "linear": selector network; "softmax": threshold on the top class probability
+    selector: str = "linear"    # "linear": selector network; "softmax": threshold on the top class probability;
+                                # "hidden": selector network with one hidden layer of sel_hidden units
     predictor: str = "gap_mlp"  # "gap_mlp": global pool -> FC -> ReLU -> FC; "pool_fc": the paper's Pool(h);
                                 # "fc_mlp": the paper's FC(h) on the flattened activation
     in_hw: tuple = (0, 0)       # pool_fc: input map (in_h, in_w), S = in_h*in_w
     out_hw: tuple = (0, 0)      # pool_fc: pooled map (out_h, out_w); features F = C*out_h*out_w
+    sel_hidden: int = 0         # selector "hidden": units in the selector's hidden layer
 
     @property
     def F(self) -> int:
@@ -101,19 +107,19 @@ class CacheDef:
     def _c(self) -> _Desc:
         return _Desc(self.C, self.S, self.H, self.K, BF16 if self.dtype == "bf16" else F32,
                      NSC if self.layout == "nsc" else NCS, 1 if self.round_operands else 0,
-                     float(self.threshold), 1 if self.selector == "softmax" else 0,
+                     float(self.threshold), {"linear": 0, "softmax": 1, "hidden": 2}[self.selector],
                      {"gap_mlp": 0, "pool_fc": 1, "fc_mlp": 2}[self.predictor], int(self.in_hw[0]), int(self.in_hw[1]),
-                     int(self.out_hw[0]), int(self.out_hw[1]))
+                     int(self.out_hw[0]), int(self.out_hw[1]), int(self.sel_hidden))
 
 
 def _weights_c(w: dict, keep: list) -> _Weights:
     arrs = {}
-    for k in ("W1", "b1", "W2", "b2", "ws"):
+    for k in ("W1", "b1", "W2", "b2", "ws", "Ws", "cs", "vs"):
         v = w.get(k)
         arrs[k] = np.ascontiguousarray(v if v is not None else np.zeros(1), dtype=np.float32)
         keep.append(arrs[k])
     return _Weights(_ptr(arrs["W1"]), _ptr(arrs["b1"]), _ptr(arrs["W2"]), _ptr(arrs["b2"]),
-                    _ptr(arrs["ws"]), float(w["bs"]))
+                    _ptr(arrs["ws"]), float(w["bs"]), _ptr(arrs["Ws"]), _ptr(arrs["cs"]), _ptr(arrs["vs"]))
 
 
 def _check_act(d: CacheDef, act: np.ndarray):
@@ -233,6 +239,15 @@ def selector_score(d: CacheDef, w: dict, p: np.ndarray, q: np.ndarray) -> float:
     p = np.ascontiguousarray(p, np.float32)
     q = np.ascontiguousarray(q, np.float64)
     return float(lib.oracle_selector_score(C.byref(dc), C.byref(wc), _ptr(p), _ptr(q)))
+
+
+def selector_hidden_score(d: CacheDef, w: dict, p: np.ndarray, q: np.ndarray) -> float:
+    lib = _load()
+    keep: list = []
+    dc, wc = d._c(), _weights_c(w, keep)
+    p = np.ascontiguousarray(p, np.float32)
+    q = np.ascontiguousarray(q, np.float64)
+    return float(lib.oracle_selector_hidden_score(C.byref(dc), C.byref(wc), _ptr(p), _ptr(q)))
 
 
 # -- a stack of caches: layer l+1 looks up only layer l's misses -------------------------

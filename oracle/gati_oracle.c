@@ -40,7 +40,10 @@ typedef struct {
     float   threshold;       /* tau: hit iff confidence > tau (strict)                    */
     int32_t selector;        /* 0: selector network (affine map over [pooled ; prob], logistic)
                                 1: no selector network: confidence = largest class probability
-                                   (the softmax-threshold baseline of the design analysis)     */
+                                   (the softmax-threshold baseline of the design analysis)
+                                2: selector network with one hidden layer of sel_hidden units
+                                   (Section 3, "Selector Network Design"): affine map over
+                                   [features ; prob] -> ReLU -> affine map to one score -> logistic */
     int32_t predictor;       /* 0: global average pool -> FC -> ReLU -> FC
                                 1: the paper's Pool(h): adaptive average pool of the in_h x in_w
                                    map to out_h x out_w -> ReLU -> one FC over the
@@ -49,6 +52,7 @@ typedef struct {
                                    storage order (D = C*S values), -> FC(D->H) -> ReLU -> FC(H->K);
                                    the selector reads [hidden ; prob]                           */
     int32_t in_h, in_w, out_h, out_w;   /* predictor 1 only; S = in_h*in_w, layout NCS        */
+    int32_t sel_hidden;      /* selector 2 only: units in the selector's hidden layer      */
 } oracle_desc_t;
 
 /* Number of features the pooling step produces per row. */
@@ -109,6 +113,10 @@ typedef struct {
     const float *b2;  /* [K]   */
     const float *ws;  /* [C+K], pooled features first, class probabilities after */
     float bs;
+    /* selector 2 (hidden layer): */
+    const float *Ws;  /* [sel_hidden, F+K] first layer, features first, probabilities after */
+    const float *cs;  /* [sel_hidden] first-layer bias                                      */
+    const float *vs;  /* [sel_hidden] second layer; its bias is bs                          */
 } oracle_weights_t;
 
 /* ---- the steps ------------------------------------------------------------------- */
@@ -244,6 +252,38 @@ double oracle_selector_score(const oracle_desc_t *d, const oracle_weights_t *w,
     return u;
 }
 
+/* Selector with one hidden layer (Section 3, "Selector Network Design": a network with one
+ * hidden layer that projects the predictor's output onto a binary decision; ReLU as in every
+ * hidden layer of the cache's networks):
+ *   g[j] = relu(cs[j] + sum_c Ws[j,c] p[c] + sum_k Ws[j,F+k] q[k]),  u = bs + sum_j vs[j] g[j].
+ * In the bf16 cache arithmetic the first layer is a matrix product like the predictor's, so
+ * its weights and operands (p, q) are rounded to bf16 and so is the hidden vector g that it
+ * hands on; the one-output second layer is plain fp32 arithmetic on unrounded vs. */
+double oracle_selector_hidden_score(const oracle_desc_t *d, const oracle_weights_t *w,
+                                    const float *p, const double *q)
+{
+    const int F = n_features(d), In = F + d->K;
+    double u = (double)w->bs;
+    for (int j = 0; j < d->sel_hidden; ++j) {
+        double acc = 0.0;
+        for (int c = 0; c < F; ++c) {
+            double wv = (double)w->Ws[(int64_t)j * In + c], x = (double)p[c];
+            if (d->round_operands) { wv = oracle_round_bf16(wv); x = oracle_round_bf16(x); }
+            acc += wv * x;
+        }
+        for (int k = 0; k < d->K; ++k) {
+            double wv = (double)w->Ws[(int64_t)j * In + F + k], x = q[k];
+            if (d->round_operands) { wv = oracle_round_bf16(wv); x = oracle_round_bf16(x); }
+            acc += wv * x;
+        }
+        acc += (double)w->cs[j];
+        double g = acc > 0.0 ? acc : 0.0;
+        if (d->round_operands) g = oracle_round_bf16(g);
+        u += (double)w->vs[j] * g;
+    }
+    return u;
+}
+
 static double logistic(double u) { return 1.0 / (1.0 + exp(-u)); }
 
 /* One lookup per active row i (source row r = row_index ? row_index[i] : i).
@@ -304,6 +344,9 @@ int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void 
             c = q[0];
             for (int k = 1; k < d->K; ++k) if (q[k] > c) c = q[k];
             u = c;
+        } else if (d->selector == 2) {
+            u = oracle_selector_hidden_score(d, w, p, q);
+            c = logistic(u);
         } else {
             u = oracle_selector_score(d, w, p, q);
             c = logistic(u);

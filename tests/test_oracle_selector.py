@@ -156,3 +156,78 @@ def test_softmax_threshold_mode(oracle):
     assert hits[0] == n and hits[-1] == 0 and all(a >= b for a, b in zip(hits, hits[1:]))
     w0 = _w(C, H, K)
     assert np.allclose(oracle.lookup(d, w0, x)["confidence"], 1.0 / K, atol=1e-7)
+
+
+# ---- the selector with one hidden layer (Section 3, "Selector Network Design") ----
+
+def test_hidden_selector_hand_case(oracle):
+    """F = 2, K = 2, two hidden units; p = (1, 2), q = (3/4, 1/4).
+
+    g0 = relu(0 + 1*1 + 0*2 + 4*.75 + 0*.25) = 4
+    g1 = relu(-1 - 1*1 + 1*2 + 0*.75 + 4*.25) = 1
+    u  = 0.5 + 2*4 - 1*1 = 7.5
+    """
+    d = CacheDef(C=2, S=1, H=1, K=2, selector="hidden", sel_hidden=2)
+    w = _w(2, 1, 2, Ws=[[1, 0, 4, 0], [-1, 1, 0, 4]], cs=[0, -1], vs=[2, -1], bs=0.5)
+    p, q = np.array([1, 2], np.float32), np.array([0.75, 0.25])
+    assert oracle.selector_hidden_score(d, w, p, q) == 7.5
+    # the ReLU clamps: push unit 1 below zero and it drops out (u = 0.5 + 8)
+    w["cs"] = np.asarray([0, -3], np.float32)
+    assert oracle.selector_hidden_score(d, w, p, q) == 8.5
+    # features come first in a row of Ws, and rows are hidden units: probe both with an index pattern
+    Ws = np.array([[10 * j + i for i in range(4)] for j in range(2)], np.float32)      # Ws[j,i] = 10j+i
+    w = _w(2, 1, 2, Ws=Ws, cs=[0, 0], vs=[1, 100], bs=0.0)
+    for i in range(4):                      # one-hot input i picks column i of both rows
+        x = np.zeros(4)
+        x[i] = 1.0
+        got = oracle.selector_hidden_score(d, w, x[:2].astype(np.float32), x[2:])
+        assert got == i + 100 * (10 + i)
+
+
+def test_hidden_selector_against_library_ops_and_linear_limit(oracle):
+    rng = np.random.default_rng(5)
+    F, K, Hs = 7, 5, 6
+    d = CacheDef(C=F, S=1, H=1, K=K, selector="hidden", sel_hidden=Hs)
+    Ws = rng.standard_normal((Hs, F + K)).astype(np.float32)
+    cs = rng.standard_normal(Hs).astype(np.float32)
+    vs = rng.standard_normal(Hs).astype(np.float32)
+    p = rng.standard_normal(F).astype(np.float32)
+    q = rng.random(K)
+    q /= q.sum()
+    w = _w(F, 1, K, Ws=Ws, cs=cs, vs=vs, bs=0.25)
+    x = np.concatenate([p.astype(np.float64), q])
+    want = 0.25 + vs.astype(np.float64) @ np.maximum(Ws.astype(np.float64) @ x + cs, 0.0)
+    assert abs(oracle.selector_hidden_score(d, w, p, q) - want) < 1e-12
+    # one always-active unit with unit output weight is the single-layer selector
+    ws = rng.standard_normal(F + K).astype(np.float32)
+    d1 = CacheDef(C=F, S=1, H=1, K=K, selector="hidden", sel_hidden=1)
+    w1 = _w(F, 1, K, Ws=ws[None, :], cs=[64.0], vs=[1.0], bs=-64.0 + 0.5)
+    lin = oracle.selector_score(CacheDef(C=F, S=1, H=1, K=K), _w(F, 1, K, ws=ws, bs=0.5), p, q)
+    assert abs(oracle.selector_hidden_score(d1, w1, p, q) - lin) < 1e-12
+
+
+def test_hidden_selector_bf16_rounding_points(oracle):
+    """bf16 cache arithmetic: first-layer weights, its operands and the hidden vector are rounded
+    (nearest even); the second layer is not.  1 + 2^-8 is a tie and rounds to 1:
+    Ws = 1+2^-8 -> 1, p = 3 -> g = 3, vs = 1+2^-8 stays: u = 3*(1+2^-8)."""
+    d = CacheDef(C=1, S=1, H=1, K=1, selector="hidden", sel_hidden=1, round_operands=True)
+    e = 2.0 ** -8
+    w = _w(1, 1, 1, Ws=[[1 + e, 0]], cs=[0], vs=[1 + e], bs=0.0)
+    assert oracle.selector_hidden_score(d, w, np.array([3], np.float32), np.array([1.0])) == 3 * (1 + e)
+    d0 = CacheDef(C=1, S=1, H=1, K=1, selector="hidden", sel_hidden=1)
+    assert oracle.selector_hidden_score(d0, w, np.array([3], np.float32), np.array([1.0])) == 3 * (1 + e) * (1 + e)
+    # the hidden vector itself is rounded: g = 1 + 2^-8 + 2^-9 (exact sum of bf16 products) -> 1 + 2^-7
+    w = _w(1, 1, 1, Ws=[[1, 0]], cs=[e / 2], vs=[1], bs=0.0)
+    got = oracle.selector_hidden_score(d, w, np.array([1 + 2 * e], np.float32), np.array([1.0]))
+    assert got == 1 + 2 * e          # 1 + 2^-7 + 2^-9 rounds down to 1 + 2^-7
+
+
+def test_hidden_selector_in_lookup(oracle):
+    """The full-lookup hand case (see test_full_lookup_hand_case), row 0, with a hidden-layer selector:
+    p = (2, 1), q = (3/4, 1/4); g = relu(.5*2 - 1*1 + 4*.75 + 8*.25 - 4) = 1; u = ln3 * 1 -> conf 3/4."""
+    d = CacheDef(C=2, S=3, H=2, K=2, threshold=0.7, selector="hidden", sel_hidden=1)
+    x = np.array([[[1, 2, 3], [0, 1, 2]]], np.float32)
+    w = _w(2, 2, 2, W1=[[1, -1], [1, 2]], b1=[0, -5], W2=[[2, 0], [1, 0]], b2=[LN3, 1],
+           Ws=[[0.5, -1, 4, 8]], cs=[-4.0], vs=[LN3], bs=0.0)
+    out = oracle.lookup(d, w, x)
+    assert abs(float(out["confidence"][0]) - 0.75) < 1e-7 and out["hit"][0] == 1 and out["pred_class"][0] == 0
