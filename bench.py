@@ -46,9 +46,7 @@ def build_workload(name, torch, g, W):
     K = spec.layers[0].K
     labels = W.zipf_labels(spec.batch, K, spec.zipf_s, spec.seed)
     weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
-    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w,
-                      predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw)
-              for L, w in zip(spec.layers, weights)]
+    caches = [g.Cache.from_layer(L, w, spec.batch) for L, w in zip(spec.layers, weights)]
     stack = g.CacheStack(caches, spec.batch, storage=spec.storage)
     acts = []
     if spec.storage == "gather":

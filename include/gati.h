@@ -60,8 +60,13 @@ typedef enum {
  *   GATI_SEL_LINEAR   the selector network: logistic of an affine map over [pooled ; prob]
  *   GATI_SEL_SOFTMAX  no selector network: confidence = largest class probability, the
  *                     softmax-threshold baseline the paper compares against (Appendix,
- *                     "Decoupling prediction and selection"); ws and bs are ignored      */
-typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1 } gati_selector_t;
+ *                     "Decoupling prediction and selection"); ws and bs are ignored
+ *   GATI_SEL_HIDDEN   the selector network with one hidden layer (Section 3, "Selector Network
+ *                     Design"): g = relu(Ws [features ; prob] + cs), confidence =
+ *                     logistic(vs . g + bs).  selector_hidden units, 1..1024.  The first layer is
+ *                     a matrix product like the predictor's: in a GATI_BF16 cache Ws, its operands
+ *                     and g are rounded to bf16; the second layer is fp32.  ws is ignored.        */
+typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1, GATI_SEL_HIDDEN = 2 } gati_selector_t;
 
 /* Which predictor network the cache holds (paper, Section 3, table of predictor architectures).
  *   GATI_PRED_GAP_MLP  global average pool -> FC(C->H) -> ReLU -> FC(H->K): the fully connected
@@ -98,6 +103,7 @@ typedef struct {
     gati_selector_t selector;
     gati_predictor_t predictor;
     int32_t in_h, in_w, out_h, out_w; /* GATI_PRED_POOL_FC only */
+    int32_t selector_hidden;          /* GATI_SEL_HIDDEN only: units in the selector's hidden layer */
 } gati_cache_desc_t;
 
 /* Weights, HOST pointers, fp32, row-major [out, in].  Copied (and converted) by
@@ -108,7 +114,11 @@ typedef struct {
     const float *W2; /* [K, H]                                                    */
     const float *b2; /* [K]                                                       */
     const float *ws; /* [C + K]: weights of the pooled features first, then of the class probabilities */
-    float bs;        /* selector bias                                             */
+    float bs;        /* selector bias (GATI_SEL_HIDDEN: bias of its second layer)  */
+    /* GATI_SEL_HIDDEN only (may be NULL otherwise); F = number of features, as for ws: */
+    const float *Ws; /* [selector_hidden, F + K]: features first, then class probabilities */
+    const float *cs; /* [selector_hidden] first-layer bias                        */
+    const float *vs; /* [selector_hidden] second-layer weights                    */
 } gati_cache_weights_t;
 
 /* Build a cache on the current HIP device: uploads the weights in the library's private

@@ -24,7 +24,8 @@ def cache_defs(spec: W.WorkloadSpec, mirror: bool = True) -> List[CacheDef]:
     bf16-operand arithmetic for bf16 caches (the grading reference)."""
     return [CacheDef(C=L.C, S=L.S, H=L.H, K=L.K, dtype=L.dtype, layout=L.layout,
                      threshold=L.threshold, round_operands=(mirror and L.dtype == "bf16"),
-                     predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw)
+                     predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw,
+                     selector=L.selector, sel_hidden=L.sel_hidden)
             for L in spec.layers]
 
 

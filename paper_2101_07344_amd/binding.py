@@ -13,7 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libgati.so")
 GATI_OK, GATI_ERR_INVALID_ARG, GATI_ERR_UNSUPPORTED, GATI_ERR_OOM, GATI_ERR_DEVICE = range(5)
 GATI_F32, GATI_BF16 = 0, 1
 GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
-GATI_SEL_LINEAR, GATI_SEL_SOFTMAX = 0, 1
+GATI_SEL_LINEAR, GATI_SEL_SOFTMAX, GATI_SEL_HIDDEN = 0, 1, 2
 GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC, GATI_PRED_FC_MLP = 0, 1, 2
 
 # every extern "C" symbol include/gati.h declares
@@ -27,12 +27,14 @@ class CacheDesc(C.Structure):
     _fields_ = [("C", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("K", C.c_int32),
                 ("act_dtype", C.c_int), ("layout", C.c_int), ("threshold", C.c_float),
                 ("max_rows", C.c_int32), ("selector", C.c_int), ("predictor", C.c_int),
-                ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32)]
+                ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32),
+                ("selector_hidden", C.c_int32)]
 
 
 class CacheWeights(C.Structure):
     _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
-                ("ws", C.c_void_p), ("bs", C.c_float)]
+                ("ws", C.c_void_p), ("bs", C.c_float),
+                ("Ws", C.c_void_p), ("cs", C.c_void_p), ("vs", C.c_void_p)]
 
 
 class GatiError(RuntimeError):
@@ -168,7 +170,7 @@ class Cache:
 
     def __init__(self, C_: int, S: int, H: int, K: int, dtype: str, layout: str, threshold: float,
                  max_rows: int, weights: dict, selector: str = "linear", predictor: str = "gap_mlp",
-                 in_hw=(0, 0), out_hw=(0, 0)):
+                 in_hw=(0, 0), out_hw=(0, 0), sel_hidden: int = 0):
         self.C, self.S, self.H, self.K = C_, S, H, K
         self.dtype, self.layout, self.max_rows = dtype, layout, max_rows
         self.threshold = float(threshold)
@@ -177,18 +179,35 @@ class Cache:
         self.F = C_ * out_hw[0] * out_hw[1] if pool_fc else (H if fc_mlp else C_)
         desc = CacheDesc(C_, S, 0 if pool_fc else H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
                          GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows,
-                         GATI_SEL_SOFTMAX if selector == "softmax" else GATI_SEL_LINEAR,
+                         {"linear": GATI_SEL_LINEAR, "softmax": GATI_SEL_SOFTMAX, "hidden": GATI_SEL_HIDDEN}[selector],
                          {"gap_mlp": GATI_PRED_GAP_MLP, "pool_fc": GATI_PRED_POOL_FC, "fc_mlp": GATI_PRED_FC_MLP}[predictor],
-                         int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]))
-        names = ("W2", "b2", "ws") if pool_fc else ("W1", "b1", "W2", "b2", "ws")
+                         int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]), int(sel_hidden))
+        hidden_sel = selector == "hidden"
+        names = ("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")
+        names += ("Ws", "cs", "vs") if hidden_sel else ("ws",)
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
         if not pool_fc:
             assert keep["W1"].shape == (H, C_ * S if fc_mlp else C_)
-        assert keep["W2"].shape == (K, self.F if pool_fc else H) and keep["ws"].shape == (self.F + K,)
+        assert keep["W2"].shape == (K, self.F if pool_fc else H)
+        if hidden_sel:
+            assert keep["Ws"].shape == (sel_hidden, self.F + K) and keep["cs"].shape == (sel_hidden,) \
+                and keep["vs"].shape == (sel_hidden,)
+        else:
+            assert keep["ws"].shape == (self.F + K,)
         ptr = lambda k: keep[k].ctypes.data if k in keep else None
-        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]))
+        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]),
+                         ptr("Ws"), ptr("cs"), ptr("vs"))
         st, self.handle = gati_cache_create(desc, w)
         _check(st, "gati_cache_create")
+
+    @classmethod
+    def from_layer(cls, L, weights: dict, max_rows: int) -> "Cache":
+        """Build from any record with the fields C, S, H, K, dtype, layout, threshold and,
+        optionally, predictor, in_hw, out_hw, selector, sel_hidden."""
+        return cls(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, max_rows, weights,
+                   selector=getattr(L, "selector", "linear"), predictor=getattr(L, "predictor", "gap_mlp"),
+                   in_hw=getattr(L, "in_hw", (0, 0)), out_hw=getattr(L, "out_hw", (0, 0)),
+                   sel_hidden=getattr(L, "sel_hidden", 0))
 
     def lookup(self, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits=None, stream=None):
         _check(gati_cache_lookup(self.handle, act, row_index, n_max, n_dev, pred_class, confidence, hit,

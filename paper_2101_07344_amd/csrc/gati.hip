@@ -84,12 +84,21 @@ struct gati_cache {
     int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
     // head plan: column tiles per workgroup of the output layer
     int fc2_nt = 1;
+    // selector with a hidden layer: Hs units (padded Hsp), operand rows [features(Cp) ; prob] of width Sin
+    int Hs = 0, Hsp = 0, Sin = 0;
+    void* Ws = nullptr;       // [Hsp/32][Sin/kStep][64][kLane] bf16 | f32
+    float* cs = nullptr;      // [Hsp]
+    float* vs = nullptr;      // [Hsp]
+    void* sel_in = nullptr;   // [rows_pad, Sin]
+    void* sel_g = nullptr;    // [rows_pad, Hsp]
+    float* zbuf = nullptr;    // [max_rows, K] logits when the caller keeps none
 };
 
 namespace {
 
 void free_all(gati_cache* c) {
-    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats, c->flat_partial};
+    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats,
+                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
 }
@@ -407,12 +416,14 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
                          int32_t* ids_out, int32_t* n_miss, hipStream_t st) {
     const int row_tiles = (n_max + 31) / 32;
     hipError_t e = hipSuccess;
+    const bool sel_hidden = c->desc.selector == GATI_SEL_HIDDEN;
+    if (sel_hidden && !logits) logits = c->zbuf;     // the selector's first layer reads the class probabilities
     FcArgs f2 = {};
     if (!c->pool_fc) {
         FcArgs f1 = {};
         f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
         f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
-        f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp;
+        if (!sel_hidden) { f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp; }
         fc_kernel<BF16, 1, true><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -421,7 +432,7 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
         // Pool(h): the ReLU'd pooled features are the hidden layer; the output-layer kernel also
         // computes the selector's pooled half
         f2.A = BF16 ? c->p16 : (const void*)c->p; f2.Kdim = c->Cp;
-        f2.p32 = c->p; f2.ws_pool = c->ws_pool; f2.ldp = c->Cp;
+        if (!sel_hidden) { f2.p32 = c->p; f2.ws_pool = c->ws_pool; f2.ldp = c->Cp; }
     }
     f2.u_pool = c->u_pool;
     f2.Wp = c->W2; f2.bias = c->b2; f2.N = c->Kp;
@@ -434,6 +445,23 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
     if (e != hipSuccess) return e;
 
     FinalizeArgs fa = {};
+    if (sel_hidden) {
+        // [features ; prob] operand rows, then the selector's first layer as one more FC launch
+        SelInArgs si = {};
+        si.stats = c->stats; si.n_tiles = n_tiles; si.logits = logits;
+        si.feat = BF16 ? c->p16 : (const void*)c->p; si.sel_in = c->sel_in;
+        si.Cp = c->Cp; si.K = c->desc.K; si.ld = c->Sin; si.n_max = n_max; si.n_dev = n_dev;
+        selector_input_kernel<BF16><<<std::max(1, std::min(n_max, c->num_cu * 4)), 256, 0, st>>>(si);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        FcArgs fs = {};
+        fs.A = c->sel_in; fs.Wp = c->Ws; fs.bias = c->cs; fs.Kdim = c->Sin; fs.N = c->Hsp;
+        fs.n_max = n_max; fs.n_dev = n_dev; fs.h = c->sel_g;
+        fc_kernel<BF16, 1, true><<<dim3(c->Hsp / 32, row_tiles), 256, 0, st>>>(fs);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        fa.sel_g = c->sel_g; fa.sel_vs = c->vs; fa.sel_hs = c->Hs; fa.ldg = c->Hsp; fa.g_bf16 = BF16 ? 1 : 0;
+    }
     fa.stats = c->stats; fa.n_tiles = n_tiles; fa.u_pool = c->u_pool; fa.bs = c->bs; fa.tau = c->tau;
     fa.softmax_only = c->desc.selector == GATI_SEL_SOFTMAX ? 1 : 0;
     fa.n_max = n_max; fa.n_dev = n_dev; fa.pred_class = pred_class; fa.confidence = confidence; fa.hit = hit;
@@ -482,8 +510,12 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     }
     if (desc->act_dtype != GATI_F32 && desc->act_dtype != GATI_BF16) return GATI_ERR_INVALID_ARG;
     if (desc->layout != GATI_LAYOUT_NCS && desc->layout != GATI_LAYOUT_NSC) return GATI_ERR_INVALID_ARG;
-    if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_SOFTMAX) return GATI_ERR_INVALID_ARG;
-    if (!w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
+    if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_SOFTMAX && desc->selector != GATI_SEL_HIDDEN)
+        return GATI_ERR_INVALID_ARG;
+    const bool sel_hidden = desc->selector == GATI_SEL_HIDDEN;
+    if (sel_hidden && (desc->selector_hidden < 1 || desc->selector_hidden > 1024 || !w->Ws || !w->cs || !w->vs))
+        return GATI_ERR_INVALID_ARG;
+    if (!w->W2 || !w->b2 || (!sel_hidden && !w->ws)) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
     if (flat_fc && ((long)desc->C * desc->S) % 64 != 0) return GATI_ERR_UNSUPPORTED;
     if (flat_fc && (long)desc->C * desc->S >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
@@ -575,12 +607,38 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
         if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)desc->H * 4);
         std::memcpy(b2.data(), w->b2, (size_t)K * 4);
-        std::memcpy(wp.data(), w->ws, (size_t)C * 4);
-        std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
+        if (!sel_hidden) {      // otherwise both halves stay zero: the per-tile selector sums are unused
+            std::memcpy(wp.data(), w->ws, (size_t)C * 4);
+            std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
+        }
         if (st == GATI_OK) st = upload((void**)&c->b1, b1.data(), b1.size() * 4);
         if (st == GATI_OK) st = upload((void**)&c->b2, b2.data(), b2.size() * 4);
         if (st == GATI_OK) st = upload((void**)&c->ws_pool, wp.data(), wp.size() * 4);
         if (st == GATI_OK) st = upload((void**)&c->ws_prob, wq.data(), wq.size() * 4);
+        if (sel_hidden) {
+            // first layer over operand rows [features padded to Cp ; probabilities padded to Sin - Cp]
+            c->Hs = desc->selector_hidden;
+            c->Hsp = round_up(c->Hs, 32);
+            c->Sin = c->Cp + round_up(K, 64);
+            std::vector<float> wide((size_t)c->Hs * c->Sin, 0.f), cs(c->Hsp, 0.f), vs(c->Hsp, 0.f);
+            for (int j = 0; j < c->Hs; ++j) {
+                std::memcpy(&wide[(size_t)j * c->Sin], w->Ws + (size_t)j * (C + K), (size_t)C * 4);
+                std::memcpy(&wide[(size_t)j * c->Sin + c->Cp], w->Ws + (size_t)j * (C + K) + C, (size_t)K * 4);
+            }
+            std::memcpy(cs.data(), w->cs, (size_t)c->Hs * 4);
+            std::memcpy(vs.data(), w->vs, (size_t)c->Hs * 4);
+            if (c->bf16) {
+                std::vector<uint16_t> t;
+                pack_weights(wide.data(), c->Hs, c->Sin, c->Hsp, c->Sin, 16, t, f32_to_bf16_rne);
+                if (st == GATI_OK) st = upload(&c->Ws, t.data(), t.size() * 2);
+            } else {
+                std::vector<float> t;
+                pack_weights(wide.data(), c->Hs, c->Sin, c->Hsp, c->Sin, 8, t, [](float x) { return x; });
+                if (st == GATI_OK) st = upload(&c->Ws, t.data(), t.size() * 4);
+            }
+            if (st == GATI_OK) st = upload((void**)&c->cs, cs.data(), cs.size() * 4);
+            if (st == GATI_OK) st = upload((void**)&c->vs, vs.data(), vs.size() * 4);
+        }
     } catch (const std::bad_alloc&) {
         st = GATI_ERR_OOM;
     }
@@ -591,6 +649,9 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     if (st == GATI_OK && flat_fc)
         st = upload((void**)&c->flat_partial, nullptr, (size_t)c->flat_splits * c->rows_b * c->Hb * 4);
     if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
+    if (st == GATI_OK && sel_hidden) st = upload(&c->sel_in, nullptr, (size_t)c->rows_pad * c->Sin * c->elem);
+    if (st == GATI_OK && sel_hidden) st = upload(&c->sel_g, nullptr, (size_t)c->rows_pad * c->Hsp * c->elem);
+    if (st == GATI_OK && sel_hidden) st = upload((void**)&c->zbuf, nullptr, (size_t)desc->max_rows * K * 4);
     if (st == GATI_OK)
         st = upload((void**)&c->stats, nullptr, (size_t)c->rows_pad * (c->Kp / (32 * c->fc2_nt)) * sizeof(TileStat));
     if (st == GATI_OK && hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); st = GATI_ERR_DEVICE; }

@@ -81,13 +81,10 @@ struct FcArgs {
     TileStat* stats;       // [rows_pad, N/(32*NT)]
 };
 
-// One row's class, confidence and hit flag from its per-tile summaries: tiles in order, the
-// running (max, sum, wsum) rescaled when a later tile raises the maximum;
-// confidence = logistic(bs + u_pool + sum_k ws[k] softmax(z)[k]).
-// softmax_only: no selector network, confidence = largest class probability = 1 / sum_k exp(z_k - max).
-__device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, float u_pool, float bs, float tau,
-                                           bool softmax_only, int32_t* cls_out, float* conf_out,
-                                           uint8_t* hit_out) {
+// One row's per-tile softmax summaries merged in tile order: the running (max, sum, wsum) is
+// rescaled when a later tile raises the maximum; an earlier tile keeps the class on equality.
+__device__ __forceinline__ void merge_tile_stats(const TileStat* st, int n_tiles, float* m_out, float* sum_out,
+                                                 float* wsum_out, int* arg_out) {
     float m = -INFINITY, sum = 0.f, wsum = 0.f;
     int arg = 0;
     for (int t0 = 0; t0 < n_tiles; t0 += 8) {
@@ -97,7 +94,7 @@ __device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, floa
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             if (t0 + u < n_tiles && s[u].max > -INFINITY) {
-                if (s[u].max > m) {                       // an earlier tile keeps the class on equality
+                if (s[u].max > m) {
                     const float w = expf(m - s[u].max);   // m = -inf -> 0
                     sum *= w; wsum *= w;
                     m = s[u].max; arg = s[u].arg;
@@ -108,6 +105,18 @@ __device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, floa
             }
         }
     }
+    *m_out = m; *sum_out = sum; *wsum_out = wsum; *arg_out = arg;
+}
+
+// One row's class, confidence and hit flag from its per-tile summaries;
+// confidence = logistic(bs + u_pool + sum_k ws[k] softmax(z)[k]).
+// softmax_only: no selector network, confidence = largest class probability = 1 / sum_k exp(z_k - max).
+__device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, float u_pool, float bs, float tau,
+                                           bool softmax_only, int32_t* cls_out, float* conf_out,
+                                           uint8_t* hit_out) {
+    float m, sum, wsum;
+    int arg;
+    merge_tile_stats(st, n_tiles, &m, &sum, &wsum, &arg);
     const float u = bs + u_pool + wsum / sum;
     const float conf = softmax_only ? 1.f / sum : 1.f / (1.f + expf(-u));
     const bool is_hit = conf > tau;
@@ -245,7 +254,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             else
                 static_cast<float*>(a.h)[(long)row * a.N + col] = v;
         }
-        selector_pool_part(a, row0, n, n_tiles_x);
+        if (a.p32) selector_pool_part(a, row0, n, n_tiles_x);   // null: this launch has no selector half
     } else {
         constexpr int TW = 32 * NT;                 // tile width in classes
         __shared__ float zt[32][TW + 1];
@@ -301,12 +310,53 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     }
 }
 
+// Input of the hidden-layer selector (Section 3, "Selector Network Design"): one operand row
+// [features ; class probabilities] per active row, in the element type of the cache's matrix
+// products, so that the selector's first layer is one more fc_kernel launch.
+struct SelInArgs {
+    const TileStat* stats;   // [rows_pad, n_tiles]
+    int n_tiles;
+    const float* logits;     // [n, K]
+    const void* feat;        // [rows_pad, Cp] features as the predictor's FC reads them (bf16 or f32)
+    void* sel_in;            // [rows_pad, ld] out: features in columns [0, Cp), q in [Cp, Cp+K), zeros after
+    int Cp, K, ld;
+    int n_max;
+    const int32_t* n_dev;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void selector_input_kernel(SelInArgs a) {
+    const int n = active_rows(a.n_dev, a.n_max);
+    constexpr int kElem = BF16 ? 2 : 4;
+    for (int row = blockIdx.x; row < n; row += gridDim.x) {
+        float m, sum, wsum;
+        int arg;
+        merge_tile_stats(a.stats + (long)row * a.n_tiles, a.n_tiles, &m, &sum, &wsum, &arg);   // every lane: same values
+        const float inv = 1.f / sum;
+        char* dst = static_cast<char*>(a.sel_in) + (long)row * a.ld * kElem;
+        const u32x4_t* src = reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.feat) + (long)row * a.Cp * kElem);
+        const int nvec = a.Cp * kElem / 16;                   // Cp is a multiple of 64 elements
+        for (int v = threadIdx.x; v < nvec; v += 256) reinterpret_cast<u32x4_t*>(dst)[v] = src[v];
+        const float* z = a.logits + (long)row * a.K;
+        const int nq = a.ld - a.Cp;
+        for (int k = threadIdx.x; k < nq; k += 256) {
+            const float q = k < a.K ? expf(z[k] - m) * inv : 0.f;
+            if constexpr (BF16) reinterpret_cast<__bf16*>(dst)[a.Cp + k] = (__bf16)q;
+            else reinterpret_cast<float*>(dst)[a.Cp + k] = q;
+        }
+    }
+}
+
 struct FinalizeArgs {
     const TileStat* stats;   // [rows_pad, n_tiles]
     int n_tiles;
     const float* u_pool;     // [rows_pad]
     float bs, tau;
     int softmax_only;        // 1: no selector network, threshold on the top class probability
+    // selector with a hidden layer: u = bs + vs . g[row] replaces u_pool (null = not that selector)
+    const void* sel_g;       // [rows_pad, ldg] hidden vector, bf16 or f32
+    const float* sel_vs;     // [Hs]
+    int sel_hs, ldg, g_bf16;
     int n_max;
     const int32_t* n_dev;
     int32_t* pred_class;     // [n]
@@ -331,9 +381,23 @@ __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
     for (int base = 0; base < n; base += 1024) {
         const int i = base + tid;
         bool miss = false;
-        if (i < n)
-            miss = !finish_row(a.stats + (long)i * a.n_tiles, a.n_tiles, a.u_pool[i], a.bs, a.tau, a.softmax_only != 0,
+        if (i < n) {
+            float u_in;
+            if (a.sel_g) {                                  // second layer of the selector, in unit order
+                u_in = 0.f;
+                if (a.g_bf16) {
+                    const __bf16* g = static_cast<const __bf16*>(a.sel_g) + (long)i * a.ldg;
+                    for (int j = 0; j < a.sel_hs; ++j) u_in = fmaf(a.sel_vs[j], (float)g[j], u_in);
+                } else {
+                    const float* g = static_cast<const float*>(a.sel_g) + (long)i * a.ldg;
+                    for (int j = 0; j < a.sel_hs; ++j) u_in = fmaf(a.sel_vs[j], g[j], u_in);
+                }
+            } else {
+                u_in = a.u_pool[i];
+            }
+            miss = !finish_row(a.stats + (long)i * a.n_tiles, a.n_tiles, u_in, a.bs, a.tau, a.softmax_only != 0,
                                &a.pred_class[i], &a.confidence[i], &a.hit[i]);
+        }
         if (compact) {
             const int slot = compact_step<16>(st, miss, tid);
             if (slot >= 0) a.ids_out[slot] = a.ids_in ? a.ids_in[i] : i;

@@ -17,8 +17,7 @@ TOL_MIRROR_BF16 = 5e-3
 
 
 def make_cache(g, L, weights, max_rows):
-    return g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, max_rows, weights,
-                   predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw)
+    return g.Cache.from_layer(L, weights, max_rows)
 
 
 def admissible_stack_inputs(spec: W.WorkloadSpec, calibrate_to=None):

@@ -21,9 +21,7 @@ def _build(name):
     spec = W.get_workload(name)
     labels = W.zipf_labels(spec.batch, spec.layers[0].K, spec.zipf_s, spec.seed)
     weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
-    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w,
-                      predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw)
-              for L, w in zip(spec.layers, weights)]
+    caches = [g.Cache.from_layer(L, w, spec.batch) for L, w in zip(spec.layers, weights)]
     return spec, labels, weights, caches
 
 
@@ -66,7 +64,7 @@ def _check_chain_properties(stack, batch, n_layers):
     return counts
 
 
-@pytest.mark.parametrize("name,rows_per_layer", [("resnet18", 6), ("resnet50", 5), ("bert_base", 8), ("resnet50_pool", 3)])
+@pytest.mark.parametrize("name,rows_per_layer", [("resnet18", 6), ("resnet50", 5), ("bert_base", 8), ("resnet50_pool", 3), ("resnet50_hsel", 3)])
 def test_full_batch_gather_stack(name, rows_per_layer):
     spec, labels, weights, caches = _build(name)
     defs = admit.cache_defs(spec, mirror=True)
@@ -145,8 +143,7 @@ def test_resnet50_fc_full_batch():
                           layers=[base.layers[i] for i in (1, 3, 5)], storage="gather")
     labels = W.zipf_labels(spec.batch, spec.layers[0].K, spec.zipf_s, spec.seed)
     weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
-    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, spec.batch, w, predictor=L.predictor)
-              for L, w in zip(spec.layers, weights)]
+    caches = [g.Cache.from_layer(L, w, spec.batch) for L, w in zip(spec.layers, weights)]
     defs = admit.cache_defs(spec, mirror=True)
     acts = [W.activation_bulk(spec, l, labels, np.arange(spec.batch), device="cuda") for l in range(len(spec.layers))]
     stack = g.CacheStack(caches, spec.batch, storage="gather", keep_logits=True)

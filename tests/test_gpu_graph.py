@@ -35,7 +35,7 @@ def test_graph_replay_equals_eager(name, batch):
                           layers=base.layers[:6], storage="gather")
     labels = W.zipf_labels(batch, spec.layers[0].K, spec.zipf_s, spec.seed)
     weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
-    caches = [g.Cache(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, batch, w) for L, w in zip(spec.layers, weights)]
+    caches = [g.Cache.from_layer(L, w, batch) for L, w in zip(spec.layers, weights)]
     stack = g.CacheStack(caches, batch, storage="gather")
     acts = [W.activation_bulk(spec, l, labels, np.arange(batch), device="cuda") for l in range(len(spec.layers))]
     side = torch.cuda.Stream()

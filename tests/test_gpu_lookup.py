@@ -60,6 +60,7 @@ STACKS = [
     ("bert_base", 70, "gather", 0.12, True),
     ("bert_base", 45, "dense", 0.25, True),
     ("resnet50_pool", 35, "gather", 0.12, True),       # the paper's Pool(h) predictor on the same shapes
+    ("resnet50_hsel", 37, "gather", 0.12, True),       # selector network with one hidden layer
 ]
 
 
@@ -225,4 +226,61 @@ def test_softmax_threshold_selector(dtype, K):
     got = _lookup_gpu(cache, x.cuda(), torch.from_numpy(ok).cuda(), len(ok), None, K)
     want_ideal = oracle.lookup(ideal_def(d), w, host, row_index=ok) if dtype == "bf16" else None
     compare_lookup(got, want, want_ideal, dtype, f"softmax selector {dtype}")
+    cache.close()
+
+
+@pytest.mark.parametrize("dtype,predictor,K,Hs,want_logits", [
+    ("f32", "gap_mlp", 10, 8, True),        # fp32 MFMA first layer, one partial tile of units
+    ("bf16", "gap_mlp", 1000, 64, False),   # probabilities from the library's own logits buffer
+    ("bf16", "pool_fc", 100, 33, True),     # features = ReLU'd window means
+    ("bf16", "fc_mlp", 37, 130, True),      # features = the FC(h) hidden layer
+])
+def test_hidden_layer_selector(dtype, predictor, K, Hs, want_logits):
+    """Selector network with one hidden layer over [features ; class probabilities]."""
+    rng = np.random.default_rng(K + Hs)
+    n, C, ih, iw, H = 90, 32, 8, 8, 96
+    S = ih * iw
+    kw = dict(predictor=predictor)
+    if predictor == "pool_fc":
+        kw.update(in_hw=(ih, iw), out_hw=(2, 2))
+    d0 = oracle.CacheDef(C=C, S=S, H=0 if predictor == "pool_fc" else H, K=K, dtype=dtype, threshold=0.5,
+                         round_operands=(dtype == "bf16"), selector="hidden", sel_hidden=Hs, **kw)
+    F = d0.F
+    x = torch.from_numpy(np.maximum(rng.standard_normal((n, C, S)) + 0.3, 0).astype(np.float32))
+    x = x.bfloat16() if dtype == "bf16" else x
+    fan1 = C * S if predictor == "fc_mlp" else C
+    Hin = F if predictor == "pool_fc" else H
+    w = {"W1": (rng.standard_normal((H, fan1)) * np.sqrt(2 / fan1)).astype(np.float32), "b1": np.zeros(H, np.float32),
+         "W2": (rng.standard_normal((K, Hin)) * np.sqrt(2 / Hin)).astype(np.float32),
+         "b2": (rng.standard_normal(K) * 0.1).astype(np.float32),
+         "Ws": (rng.standard_normal((Hs, F + K)) * 4 * np.sqrt(2 / (F + K))).astype(np.float32),
+         "cs": (rng.standard_normal(Hs) * 0.1).astype(np.float32),
+         "vs": (rng.standard_normal(Hs) * np.sqrt(2 / Hs)).astype(np.float32), "bs": 0.0}
+    host = W.to_host_array(x)
+    s0 = oracle.lookup(d0, w, host)["score"]
+    w["bs"] = float(np.float32(-np.median(s0)))          # about half the rows hit
+    ok = np.setdiff1d(np.arange(n), admit.inadmissible_rows(d0, w, host)).astype(np.int32)
+    assert len(ok) > n // 2
+    want = oracle.lookup(d0, w, host, row_index=ok)
+    assert 0 < want["hit"].sum() < len(ok)
+    cache = g.Cache(C, S, d0.H, K, dtype, "ncs", 0.5, n, w, selector="hidden", sel_hidden=Hs,
+                    in_hw=kw.get("in_hw", (0, 0)), out_hw=kw.get("out_hw", (0, 0)), predictor=predictor)
+    m = len(ok)
+    okd = torch.from_numpy(ok).cuda()
+    got = _lookup_gpu(cache, x.cuda(), okd, m, None, K, want_logits=want_logits)
+    want_ideal = oracle.lookup(ideal_def(d0), w, host, row_index=ok) if dtype == "bf16" else None
+    compare_lookup(got, want, want_ideal, dtype, f"hidden selector {dtype} {predictor}",
+                   tol_ideal=5e-2 if predictor == "fc_mlp" else None)
+    # fused compaction gives the same flags and the oracle's miss list
+    out = {"pred_class": torch.zeros(m, dtype=torch.int32, device="cuda"), "confidence": torch.zeros(m, device="cuda"),
+           "hit": torch.zeros(m, dtype=torch.uint8, device="cuda")}
+    ids_out = torch.zeros(m, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    cache.lookup_compact(x.cuda(), okd, m, None, out["pred_class"], out["confidence"], out["hit"], None,
+                         okd, ids_out, cnt)
+    torch.cuda.synchronize()
+    assert np.array_equal(out["hit"].cpu().numpy(), got["hit"]) and \
+        np.array_equal(out["confidence"].cpu().numpy(), got["confidence"])
+    want_ids = oracle.compact_misses(want["hit"], ok)
+    assert int(cnt.item()) == len(want_ids) and np.array_equal(ids_out.cpu().numpy()[:len(want_ids)], want_ids)
     cache.close()

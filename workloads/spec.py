@@ -30,6 +30,8 @@ class LayerSpec:
                                  # | "fc_mlp" (the paper's FC(h): flattened activation -> FC -> ReLU -> FC)
     in_hw: tuple = (0, 0)        # pool_fc: feature-map size, S = in_h*in_w
     out_hw: tuple = (0, 0)       # pool_fc: pooled map; F = C*out_h*out_w features
+    selector: str = "linear"     # "linear" | "softmax" | "hidden" (selector network with one hidden layer)
+    sel_hidden: int = 0          # units of that hidden layer
 
     @property
     def F(self) -> int:
@@ -128,6 +130,10 @@ def _build():
         layers=[LayerSpec(C=C, S=hw * hw, H=1024, K=1000, layout="ncs", dtype="bf16", threshold=0.6,
                           gamma=8.0 + 4.8 * i, relu=True, predictor="fc_mlp")
                 for i, (C, hw) in enumerate(fc_blocks)])
+    # The resnet50 stack with the paper's selector shape: one hidden layer (Section 3, "Selector
+    # Network Design") of 64 units over [pooled ; class probabilities]
+    w["resnet50_hsel"] = replace(w["resnet50"], name="resnet50_hsel",
+                                 layers=[replace(l, selector="hidden", sel_hidden=64) for l in w["resnet50"].layers])
     return w
 
 
@@ -141,6 +147,7 @@ HIT_TARGETS = {
     "resnet18": _linear_ramp(0.05, 0.35, 8),
     "resnet50": [0.0065 * (i + 1) for i in range(16)],
     "resnet50_pool": [0.0065 * (i + 1) for i in range(16)],
+    "resnet50_hsel": [0.0065 * (i + 1) for i in range(16)],
     "resnet50_fc": _linear_ramp(0.05, 0.20, 6),
     "bert_base": _linear_ramp(0.02, 0.20, 12),
     "resnet152": _linear_ramp(0.02, 0.70, 50),

@@ -14,7 +14,7 @@ import torch
 
 from .spec import LayerSpec, WorkloadSpec
 
-_TAG_LABELS, _TAG_DIRS, _TAG_WEIGHTS, _TAG_ROW, _TAG_BULK = 1, 2, 3, 4, 5
+_TAG_LABELS, _TAG_DIRS, _TAG_WEIGHTS, _TAG_ROW, _TAG_BULK, _TAG_SELECTOR = 1, 2, 3, 4, 5, 6
 
 
 def _rng(seed: int, *key: int) -> np.random.Generator:
@@ -50,6 +50,19 @@ def cache_weights(spec: WorkloadSpec, layer: int) -> dict:
     Shapes follow the [out, in] convention: W1 [H,C], W2 [K,H], ws [C+K] with the
     pooled features first and the class probabilities after them.
     """
+    w = _predictor_and_linear_selector(spec, layer)
+    L = spec.layers[layer]
+    if L.selector == "hidden":
+        # drawn from a stream of its own so the predictor weights equal those of the linear-selector stack
+        g = _rng(spec.seed, _TAG_SELECTOR, layer)
+        n_in = L.F + L.K
+        w["Ws"] = (g.standard_normal((L.sel_hidden, n_in)) * np.sqrt(2.0 / n_in)).astype(np.float32)
+        w["cs"] = np.zeros(L.sel_hidden, np.float32)
+        w["vs"] = (g.standard_normal(L.sel_hidden) * np.sqrt(2.0 / L.sel_hidden)).astype(np.float32)
+    return w
+
+
+def _predictor_and_linear_selector(spec: WorkloadSpec, layer: int) -> dict:
     L = spec.layers[layer]
     g = _rng(spec.seed, _TAG_WEIGHTS, layer)
     if L.predictor == "pool_fc":
