@@ -80,7 +80,7 @@ struct gati_cache {
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
     int nsc_lpt = 1, cb_per_row = 0, nsc_nw = 4;  // nsc_row
-    int ad_j = 4, ad_tpo_log2 = 0;                // ncs_adaptive (tile in gt / tiles_per_row)
+    int ad_j = 4, ad_tpo_log2 = 0, ad_ww = 0, ad_pair = 0;   // ncs_adaptive (tile in gt / tiles_per_row; common window width or 0; LDS read mode)
     int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
     // head plan: column tiles per workgroup of the output layer
     int fc2_nt = 1;
@@ -139,6 +139,21 @@ void plan_pool(gati_cache* c) {
                 int t = 0;
                 while (win_rows * win_cols > 16 && (2 << t) <= win_rows && t < 3) ++t;
                 c->ad_tpo_log2 = t;
+                // a window width shared by every window lets the kernel unroll a window row
+                int ww = -1;
+                for (int ox = 0; ox < c->desc.out_w; ++ox) {
+                    const int x0 = (ox * c->desc.in_w) / c->desc.out_w;
+                    const int x1 = ((ox + 1) * c->desc.in_w + c->desc.out_w - 1) / c->desc.out_w;
+                    ww = (ww == -1 || ww == x1 - x0) ? x1 - x0 : 0;
+                }
+                c->ad_ww = (ww == 4 || ww == 7 || ww == 14) ? ww : 0;
+                // bf16 LDS read mode of the kernel: aligned pairs for the 14-wide windows of an even map
+                // that out_w divides (row starts 14*ox + even), offset pairs for the narrow ones
+                c->ad_pair = 0;
+                if (c->bf16 && c->ad_ww == 14 && c->desc.in_w % 2 == 0 && S % 2 == 0 && c->desc.in_w % c->desc.out_w == 0)
+                    c->ad_pair = 1;
+                else if (c->bf16 && c->ad_ww == 4)
+                    c->ad_pair = 2;
                 c->variant = POOL_NCS_ADAPTIVE;
             }
         }
@@ -329,16 +344,21 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
             break;
         }
         const long tiles = (long)a.n_max * c->tiles_per_row;
-        if (c->ad_j == 4) {
-            const int blocks = (int)std::min<long>((tiles + 3) / 4, max_blocks);
-            pool_ncs_adaptive_kernel<Tag, 4, 4><<<blocks, 256, 0, st>>>(a, g);
-        } else if (c->ad_j == 8) {
-            const int blocks = (int)std::min<long>((tiles + 3) / 4, max_blocks);
-            pool_ncs_adaptive_kernel<Tag, 8, 4><<<blocks, 256, 0, st>>>(a, g);
-        } else {
-            const int blocks = (int)std::min<long>((tiles + 1) / 2, max_blocks);
-            pool_ncs_adaptive_kernel<Tag, 16, 2><<<blocks, 128, 0, st>>>(a, g);
-        }
+        const int wpb = c->ad_j == 16 ? 2 : 4;
+        const int blocks = (int)std::min<long>((tiles + wpb - 1) / wpb, max_blocks);
+#define GATI_ADAPTIVE(JJ, WPB)                                                                                  \
+    switch (c->ad_ww * 4 + c->ad_pair) {                                                                        \
+    case 4 * 4 + 2: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 4, 2><<<blocks, WPB * 64, 0, st>>>(a, g); break;    \
+    case 4 * 4: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 4, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;        \
+    case 7 * 4: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 7, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;        \
+    case 14 * 4 + 1: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 14, 1><<<blocks, WPB * 64, 0, st>>>(a, g); break;  \
+    case 14 * 4: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 14, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;      \
+    default: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 0, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;           \
+    }
+        if (c->ad_j == 4) { GATI_ADAPTIVE(4, 4) }
+        else if (c->ad_j == 8) { GATI_ADAPTIVE(8, 4) }
+        else { GATI_ADAPTIVE(16, 2) }
+#undef GATI_ADAPTIVE
         break;
     }
     default: {

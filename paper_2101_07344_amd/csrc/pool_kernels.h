@@ -433,7 +433,14 @@ template <> __device__ __forceinline__ float lds_elem<BF16Tag>(const u32x4_t* ra
     return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(raw)[idx] << 16);
 }
 
-template <typename Tag, int J, int WPB>
+// WW > 0: every window is WW columns wide (known on the host), so a window row's LDS reads are
+// unrolled and all in flight together; with a run-time width each element's read waits for the
+// one before it and the kernel is bound by LDS latency instead of HBM.  (Also unrolling the
+// window rows, with clamped reads for the rows a lane does not own, was slower.)
+// PAIR (bf16 only): 1 = every window row starts on an even element and WW is even, two elements
+// per 32-bit LDS read; 2 = 32-bit reads from the even element at or before the row start, the
+// candidate outside the window added as zero (pays for narrow windows only); 0 = 16-bit reads.
+template <typename Tag, int J, int WPB, int WW, int PAIR>
 __global__ __launch_bounds__(WPB * 64) void pool_ncs_adaptive_kernel(PoolArgs a, AdaptiveArgs g) {
     constexpr int V = Tag::kVec;
     __shared__ u32x4_t raw_all[WPB][64 * J];
@@ -501,7 +508,45 @@ __global__ __launch_bounds__(WPB * 64) void pool_ncs_adaptive_kernel(PoolArgs a,
             if (live) {
                 for (int y = y0 + sub; y < y1; y += tpo) {
                     const int rb = lc * a.S + y * g.in_w;
-                    for (int x = x0; x < x1; ++x) acc += lds_elem<Tag>(raw, rb + x);
+                    if constexpr (WW > 0 && PAIR == 1) {
+                        uint32_t e2[WW / 2];
+                        const uint32_t* r2 = reinterpret_cast<const uint32_t*>(raw) + ((rb + x0) >> 1);
+#pragma unroll
+                        for (int x = 0; x < WW / 2; ++x) e2[x] = r2[x];
+#pragma unroll
+                        for (int x = 0; x < WW / 2; ++x) {                 // same order as the loop below
+                            acc += __uint_as_float(e2[x] << 16);
+                            acc += __uint_as_float(e2[x] & 0xffff0000u);
+                        }
+                    } else if constexpr (WW > 0 && PAIR == 2) {
+                        // The pairs hold WW+1 or WW+2 candidates; the first is skipped when the row starts
+                        // on an odd element, the one after the window is added only then.  Skipped
+                        // candidates are added as zero: the sum and its left-to-right order stay.
+                        constexpr int NP = WW / 2 + 1;
+                        const int first = rb + x0;
+                        const bool odd = first & 1;
+                        const uint32_t* r2 = reinterpret_cast<const uint32_t*>(raw);
+                        const int last_pair = tile_vecs * 4 - 1;              // 8 elements per vector
+                        uint32_t e2[NP];
+#pragma unroll
+                        for (int x = 0; x < NP; ++x) e2[x] = r2[min((first >> 1) + x, last_pair)];
+#pragma unroll
+                        for (int k = 0; k <= WW; ++k) {
+                            const uint32_t w = e2[k >> 1];
+                            const float v = __uint_as_float((k & 1) ? (w & 0xffff0000u) : (w << 16));
+                            if (k == 0) acc += odd ? 0.f : v;
+                            else if (k == WW) acc += odd ? v : 0.f;
+                            else acc += v;
+                        }
+                    } else if constexpr (WW > 0) {
+                        float e[WW];
+#pragma unroll
+                        for (int x = 0; x < WW; ++x) e[x] = lds_elem<Tag>(raw, rb + x0 + x);
+#pragma unroll
+                        for (int x = 0; x < WW; ++x) acc += e[x];          // same order as the loop below
+                    } else {
+                        for (int x = x0; x < x1; ++x) acc += lds_elem<Tag>(raw, rb + x);
+                    }
                 }
             }
             for (int m = tpo >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);

@@ -34,6 +34,8 @@ SHAPES = [
     (24, 5, 10, 3, 4, "bf16", "ncs_adaptive"), (10, 9, 9, 9, 9, "f32", "adaptive_generic"), (12, 9, 9, 9, 9, "f32", "ncs_adaptive"),
     (40, 7, 7, 1, 1, "bf16", "ncs_adaptive"), (7, 3, 11, 2, 5, "f32", "adaptive_generic"),
     (3, 80, 80, 5, 5, "f32", "adaptive_generic"), (8, 13, 3, 13, 1, "bf16", "ncs_adaptive"),
+    # 14-wide windows on an odd-width map (rows start on odd elements) and on a 14-wide map
+    (16, 6, 27, 2, 2, "bf16", "ncs_adaptive"), (32, 4, 14, 2, 1, "bf16", "ncs_adaptive"),
 ]
 
 
