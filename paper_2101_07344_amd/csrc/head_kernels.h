@@ -384,13 +384,27 @@ __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
         if (i < n) {
             float u_in;
             if (a.sel_g) {                                  // second layer of the selector, in unit order
-                u_in = 0.f;
+                u_in = 0.f;                                 // rows are padded to 32 units: whole 16-byte loads
                 if (a.g_bf16) {
-                    const __bf16* g = static_cast<const __bf16*>(a.sel_g) + (long)i * a.ldg;
-                    for (int j = 0; j < a.sel_hs; ++j) u_in = fmaf(a.sel_vs[j], (float)g[j], u_in);
+                    const u32x4_t* g = reinterpret_cast<const u32x4_t*>(static_cast<const __bf16*>(a.sel_g) + (long)i * a.ldg);
+                    for (int j0 = 0; j0 < a.sel_hs; j0 += 16) {
+                        const u32x4_t v0 = g[j0 / 8], v1 = g[j0 / 8 + 1];
+                        const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const float gv = __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+                            if (j0 + e < a.sel_hs) u_in = fmaf(a.sel_vs[j0 + e], gv, u_in);
+                        }
+                    }
                 } else {
-                    const float* g = static_cast<const float*>(a.sel_g) + (long)i * a.ldg;
-                    for (int j = 0; j < a.sel_hs; ++j) u_in = fmaf(a.sel_vs[j], g[j], u_in);
+                    const f32x4_t* g = reinterpret_cast<const f32x4_t*>(static_cast<const float*>(a.sel_g) + (long)i * a.ldg);
+                    for (int j0 = 0; j0 < a.sel_hs; j0 += 8) {
+                        const f32x4_t v0 = g[j0 / 4], v1 = g[j0 / 4 + 1];
+                        const float w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (j0 + e < a.sel_hs) u_in = fmaf(a.sel_vs[j0 + e], w[e], u_in);
+                    }
                 }
             } else {
                 u_in = a.u_pool[i];
