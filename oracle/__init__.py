@@ -35,7 +35,7 @@ class _Desc(C.Structure):
                 ("act_dtype", C.c_int32), ("layout", C.c_int32), ("round_operands", C.c_int32),
                 ("threshold", C.c_float), ("selector", C.c_int32), ("predictor", C.c_int32),
                 ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32),
-                ("sel_hidden", C.c_int32)]
+                ("sel_hidden", C.c_int32), ("conv_k", C.c_int32), ("conv_s", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -97,19 +97,24 @@ class CacheDef:
     in_hw: tuple = (0, 0)       # pool_fc: input map (in_h, in_w), S = in_h*in_w
     out_hw: tuple = (0, 0)      # pool_fc: pooled map (out_h, out_w); features F = C*out_h*out_w
     sel_hidden: int = 0         # selector "hidden": units in the selector's hidden layer
+    conv_ks: tuple = (0, 0)     # predictor "conv_fc" (the paper's Conv(k,s)): kernel size, stride; H filters
 
     @property
     def F(self) -> int:
         if self.predictor == "pool_fc":
             return self.C * self.out_hw[0] * self.out_hw[1]
+        if self.predictor == "conv_fc":
+            k, s = self.conv_ks
+            return self.H * ((self.in_hw[0] - k) // s + 1) * ((self.in_hw[1] - k) // s + 1)
         return self.H if self.predictor == "fc_mlp" else self.C
 
     def _c(self) -> _Desc:
         return _Desc(self.C, self.S, self.H, self.K, BF16 if self.dtype == "bf16" else F32,
                      NSC if self.layout == "nsc" else NCS, 1 if self.round_operands else 0,
                      float(self.threshold), {"linear": 0, "softmax": 1, "hidden": 2}[self.selector],
-                     {"gap_mlp": 0, "pool_fc": 1, "fc_mlp": 2}[self.predictor], int(self.in_hw[0]), int(self.in_hw[1]),
-                     int(self.out_hw[0]), int(self.out_hw[1]), int(self.sel_hidden))
+                     {"gap_mlp": 0, "pool_fc": 1, "fc_mlp": 2, "conv_fc": 3}[self.predictor], int(self.in_hw[0]), int(self.in_hw[1]),
+                     int(self.out_hw[0]), int(self.out_hw[1]), int(self.sel_hidden),
+                     int(self.conv_ks[0]), int(self.conv_ks[1]))
 
 
 def _weights_c(w: dict, keep: list) -> _Weights:
@@ -127,6 +132,10 @@ def _check_act(d: CacheDef, act: np.ndarray):
         if d.layout != "ncs" or d.in_hw[0] * d.in_hw[1] != d.S or min(d.out_hw) < 1 or \
                 d.out_hw[0] > d.in_hw[0] or d.out_hw[1] > d.in_hw[1]:
             raise ValueError("pool_fc needs layout ncs, S = in_h*in_w and 1 <= out <= in")
+    if d.predictor == "conv_fc":
+        k, s = d.conv_ks
+        if d.layout != "ncs" or d.in_hw[0] * d.in_hw[1] != d.S or k < 1 or s < 1 or k > min(d.in_hw):
+            raise ValueError("conv_fc needs layout ncs, S = in_h*in_w and 1 <= k <= min(in_h, in_w), s >= 1")
     want = np.uint16 if d.dtype == "bf16" else np.float32
     if act.dtype != want:
         raise TypeError(f"activation dtype {act.dtype}, cache wants {want}")

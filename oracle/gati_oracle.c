@@ -50,16 +50,25 @@ typedef struct {
                                    F = C*out_h*out_w features (H, W1, b1 unused)
                                 2: the paper's FC(h): the whole activation row, flattened in
                                    storage order (D = C*S values), -> FC(D->H) -> ReLU -> FC(H->K);
-                                   the selector reads [hidden ; prob]                           */
+                                   the selector reads [hidden ; prob]
+                                3: the paper's Conv(k,s): convolution of the C x in_h x in_w map with
+                                   H filters of conv_k x conv_k, stride conv_s, no padding -> ReLU ->
+                                   one FC over the F = H*out_h*out_w hidden values, out = (in-k)/s+1
+                                   (out_h, out_w are derived, not read); W1 is [H, C, k, k], b1 [H]  */
     int32_t in_h, in_w, out_h, out_w;   /* predictor 1 only; S = in_h*in_w, layout NCS        */
     int32_t sel_hidden;      /* selector 2 only: units in the selector's hidden layer      */
+    int32_t conv_k, conv_s;  /* predictor 3 only                                           */
 } oracle_desc_t;
+
+static int conv_out_h(const oracle_desc_t *d) { return (d->in_h - d->conv_k) / d->conv_s + 1; }
+static int conv_out_w(const oracle_desc_t *d) { return (d->in_w - d->conv_k) / d->conv_s + 1; }
 
 /* Number of features the pooling step produces per row. */
 static int n_features(const oracle_desc_t *d)
 {
     if (d->predictor == 1) return d->C * d->out_h * d->out_w;
     if (d->predictor == 2) return d->H;
+    if (d->predictor == 3) return d->H * conv_out_h(d) * conv_out_w(d);
     return d->C;
 }
 
@@ -150,6 +159,29 @@ void oracle_pool_adaptive_row(const oracle_desc_t *d, const void *act, int64_t r
                     for (int x = x0; x < x1; ++x) sum += act_at(d, act, r, c, y * d->in_w + x);
                 float m = (float)(sum / (double)((y1 - y0) * (x1 - x0)));
                 f[(c * d->out_h + oy) * d->out_w + ox] = m > 0.f ? m : 0.f;
+            }
+}
+
+/* Convolution predictor, hidden layer of one row (table of predictor architectures:
+ * Input -Conv-> Hidden Layer, ReLU; Conv(k,s) = kernel size k, stride s):
+ *   f[(o*oh + oy)*ow + ox] = relu(b1[o] + sum_{c,dy,dx} W1[o,c,dy,dx] * x[c, oy*s+dy, ox*s+dx]),
+ * no padding, rounded once to fp32.  W1op holds the filter weights as operands (rounded to bf16
+ * in the bf16 cache arithmetic); activation values are exact in either element type. */
+void oracle_conv_row(const oracle_desc_t *d, const double *W1op, const float *b1, const void *act,
+                     int64_t r, float *f)
+{
+    const int k = d->conv_k, s = d->conv_s, oh = conv_out_h(d), ow = conv_out_w(d);
+    for (int o = 0; o < d->H; ++o)
+        for (int oy = 0; oy < oh; ++oy)
+            for (int ox = 0; ox < ow; ++ox) {
+                double acc = 0.0;
+                for (int c = 0; c < d->C; ++c)
+                    for (int dy = 0; dy < k; ++dy)
+                        for (int dx = 0; dx < k; ++dx)
+                            acc += W1op[(((int64_t)o * d->C + c) * k + dy) * k + dx] *
+                                   act_at(d, act, r, c, (oy * s + dy) * d->in_w + ox * s + dx);
+                acc += (double)b1[o];
+                f[((int64_t)o * oh + oy) * ow + ox] = (float)(acc > 0.0 ? acc : 0.0);
             }
 }
 
@@ -295,10 +327,11 @@ int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void 
                   uint8_t *hit /*[n]*/)
 {
     const int F = n_features(d);
-    const int pool_fc = d->predictor == 1, flat_fc = d->predictor == 2;
-    const int H = pool_fc ? F : d->H;          /* width of the layer that feeds the output FC */
+    const int pool_fc = d->predictor == 1, flat_fc = d->predictor == 2, conv_fc = d->predictor == 3;
+    const int H = (pool_fc || conv_fc) ? F : d->H;   /* width of the layer that feeds the output FC */
     const int64_t D = (int64_t)d->C * d->S;    /* inputs of the first FC of the FC(h) predictor */
     int64_t n1 = pool_fc ? 1 : (flat_fc ? (int64_t)d->H * D : (int64_t)d->H * d->C), n2 = (int64_t)d->K * H;
+    if (conv_fc) n1 = (int64_t)d->H * d->C * d->conv_k * d->conv_k;
     float  *p    = (float *)malloc(sizeof(float) * (size_t)F);
     double *pop  = (double *)malloc(sizeof(double) * (size_t)F);
     double *h    = (double *)malloc(sizeof(double) * (size_t)H);
@@ -317,6 +350,9 @@ int oracle_lookup(const oracle_desc_t *d, const oracle_weights_t *w, const void 
         int64_t r = row_index ? (int64_t)row_index[i] : (int64_t)i;
         if (pool_fc) {
             oracle_pool_adaptive_row(d, act, r, p);          /* hidden layer = relu(pooled) */
+            for (int c = 0; c < F; ++c) h[c] = (double)p[c];
+        } else if (conv_fc) {
+            oracle_conv_row(d, W1op, w->b1, act, r, p);      /* hidden layer = relu(conv) */
             for (int c = 0; c < F; ++c) h[c] = (double)p[c];
         } else if (flat_fc) {
             /* hidden[j] = relu(b1[j] + sum_e W1[j,e] x[e]) over the whole flattened row; the
