@@ -80,8 +80,14 @@ typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1, GATI_SEL_HIDDEN = 2 } 
  *                      values) -> FC(D->H) -> ReLU -> FC(H->K).  W1 is [H, D]; the selector reads
  *                      [hidden ; prob], so ws is [H + K]; the "pooled" features reported by
  *                      gati_cache_pool are the H hidden activations.  D must be a multiple of 64
- *                      (GATI_ERR_UNSUPPORTED otherwise).                                           */
-typedef enum { GATI_PRED_GAP_MLP = 0, GATI_PRED_POOL_FC = 1, GATI_PRED_FC_MLP = 2 } gati_predictor_t;
+ *                      (GATI_ERR_UNSUPPORTED otherwise).
+ *   GATI_PRED_CONV_FC  the paper's Conv(k,s): convolution of the C x in_h x in_w map with H filters of
+ *                      conv_k x conv_k, stride conv_s, no padding, ReLU, then one FC over the
+ *                      F = H*oh*ow hidden values, oh = (in_h - conv_k)/conv_s + 1 (feature order
+ *                      [filter][oy][ox]).  Needs GATI_LAYOUT_NCS and S = in_h*in_w.  W1 is
+ *                      [H, C, conv_k, conv_k], b1 [H], W2 [K, F], ws [F + K].  H <= 64, conv_k <= 15
+ *                      (GATI_ERR_UNSUPPORTED otherwise).                                            */
+typedef enum { GATI_PRED_GAP_MLP = 0, GATI_PRED_POOL_FC = 1, GATI_PRED_FC_MLP = 2, GATI_PRED_CONV_FC = 3 } gati_predictor_t;
 
 /* Shape of one learned cache (Section 3: predictor Input -> Hidden(h) -> Output, selector).
  *   C, S       activation channels and reduced length (pool extent = all of S)
@@ -102,8 +108,9 @@ typedef struct {
     int32_t max_rows;
     gati_selector_t selector;
     gati_predictor_t predictor;
-    int32_t in_h, in_w, out_h, out_w; /* GATI_PRED_POOL_FC only */
+    int32_t in_h, in_w, out_h, out_w; /* GATI_PRED_POOL_FC (all four); GATI_PRED_CONV_FC (in_h, in_w) */
     int32_t selector_hidden;          /* GATI_SEL_HIDDEN only: units in the selector's hidden layer */
+    int32_t conv_k, conv_s;           /* GATI_PRED_CONV_FC only: filter size and stride */
 } gati_cache_desc_t;
 
 /* Weights, HOST pointers, fp32, row-major [out, in].  Copied (and converted) by
@@ -191,7 +198,8 @@ gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, co
 const char *gati_status_string(gati_status_t status);
 
 /* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_segw",
- * "ncs_seg", "nsc_row", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat"); static string, for reports and profiles. */
+ * "ncs_seg", "nsc_row", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat", "conv_mfma",
+ * "conv_generic"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
 
 #ifdef __cplusplus

@@ -25,7 +25,7 @@ def cache_defs(spec: W.WorkloadSpec, mirror: bool = True) -> List[CacheDef]:
     return [CacheDef(C=L.C, S=L.S, H=L.H, K=L.K, dtype=L.dtype, layout=L.layout,
                      threshold=L.threshold, round_operands=(mirror and L.dtype == "bf16"),
                      predictor=L.predictor, in_hw=L.in_hw, out_hw=L.out_hw,
-                     selector=L.selector, sel_hidden=L.sel_hidden)
+                     selector=L.selector, sel_hidden=L.sel_hidden, conv_ks=L.conv_ks)
             for L in spec.layers]
 
 

@@ -14,7 +14,7 @@ GATI_OK, GATI_ERR_INVALID_ARG, GATI_ERR_UNSUPPORTED, GATI_ERR_OOM, GATI_ERR_DEVI
 GATI_F32, GATI_BF16 = 0, 1
 GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
 GATI_SEL_LINEAR, GATI_SEL_SOFTMAX, GATI_SEL_HIDDEN = 0, 1, 2
-GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC, GATI_PRED_FC_MLP = 0, 1, 2
+GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC, GATI_PRED_FC_MLP, GATI_PRED_CONV_FC = 0, 1, 2, 3
 
 # every extern "C" symbol include/gati.h declares
 exported_symbols = (
@@ -28,7 +28,7 @@ class CacheDesc(C.Structure):
                 ("act_dtype", C.c_int), ("layout", C.c_int), ("threshold", C.c_float),
                 ("max_rows", C.c_int32), ("selector", C.c_int), ("predictor", C.c_int),
                 ("in_h", C.c_int32), ("in_w", C.c_int32), ("out_h", C.c_int32), ("out_w", C.c_int32),
-                ("selector_hidden", C.c_int32)]
+                ("selector_hidden", C.c_int32), ("conv_k", C.c_int32), ("conv_s", C.c_int32)]
 
 
 class CacheWeights(C.Structure):
@@ -170,25 +170,32 @@ class Cache:
 
     def __init__(self, C_: int, S: int, H: int, K: int, dtype: str, layout: str, threshold: float,
                  max_rows: int, weights: dict, selector: str = "linear", predictor: str = "gap_mlp",
-                 in_hw=(0, 0), out_hw=(0, 0), sel_hidden: int = 0):
+                 in_hw=(0, 0), out_hw=(0, 0), sel_hidden: int = 0, conv_ks=(0, 0)):
         self.C, self.S, self.H, self.K = C_, S, H, K
         self.dtype, self.layout, self.max_rows = dtype, layout, max_rows
         self.threshold = float(threshold)
-        pool_fc, fc_mlp = predictor == "pool_fc", predictor == "fc_mlp"
+        pool_fc, fc_mlp, conv_fc = predictor == "pool_fc", predictor == "fc_mlp", predictor == "conv_fc"
         # features per row that the selector sees and gati_cache_pool reports
         self.F = C_ * out_hw[0] * out_hw[1] if pool_fc else (H if fc_mlp else C_)
+        if conv_fc:
+            k, s = conv_ks
+            self.F = H * ((in_hw[0] - k) // s + 1) * ((in_hw[1] - k) // s + 1)
         desc = CacheDesc(C_, S, 0 if pool_fc else H, K, GATI_BF16 if dtype == "bf16" else GATI_F32,
                          GATI_LAYOUT_NSC if layout == "nsc" else GATI_LAYOUT_NCS, float(threshold), max_rows,
                          {"linear": GATI_SEL_LINEAR, "softmax": GATI_SEL_SOFTMAX, "hidden": GATI_SEL_HIDDEN}[selector],
-                         {"gap_mlp": GATI_PRED_GAP_MLP, "pool_fc": GATI_PRED_POOL_FC, "fc_mlp": GATI_PRED_FC_MLP}[predictor],
-                         int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]), int(sel_hidden))
+                         {"gap_mlp": GATI_PRED_GAP_MLP, "pool_fc": GATI_PRED_POOL_FC, "fc_mlp": GATI_PRED_FC_MLP,
+                          "conv_fc": GATI_PRED_CONV_FC}[predictor],
+                         int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]), int(sel_hidden),
+                         int(conv_ks[0]), int(conv_ks[1]))
         hidden_sel = selector == "hidden"
         names = ("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")
         names += ("Ws", "cs", "vs") if hidden_sel else ("ws",)
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
-        if not pool_fc:
+        if conv_fc:
+            assert keep["W1"].shape == (H, C_, conv_ks[0], conv_ks[0])
+        elif not pool_fc:
             assert keep["W1"].shape == (H, C_ * S if fc_mlp else C_)
-        assert keep["W2"].shape == (K, self.F if pool_fc else H)
+        assert keep["W2"].shape == (K, self.F if (pool_fc or conv_fc) else H)
         if hidden_sel:
             assert keep["Ws"].shape == (sel_hidden, self.F + K) and keep["cs"].shape == (sel_hidden,) \
                 and keep["vs"].shape == (sel_hidden,)
@@ -207,7 +214,7 @@ class Cache:
         return cls(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, max_rows, weights,
                    selector=getattr(L, "selector", "linear"), predictor=getattr(L, "predictor", "gap_mlp"),
                    in_hw=getattr(L, "in_hw", (0, 0)), out_hw=getattr(L, "out_hw", (0, 0)),
-                   sel_hidden=getattr(L, "sel_hidden", 0))
+                   sel_hidden=getattr(L, "sel_hidden", 0), conv_ks=getattr(L, "conv_ks", (0, 0)))
 
     def lookup(self, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits=None, stream=None):
         _check(gati_cache_lookup(self.handle, act, row_index, n_max, n_dev, pred_class, confidence, hit,

@@ -13,6 +13,7 @@
 #include "../../include/gati.h"
 #include "common.h"
 #include "compact_kernels.h"
+#include "conv_kernels.h"
 #include "flat_kernels.h"
 #include "head_kernels.h"
 #include "pool_kernels.h"
@@ -22,7 +23,7 @@ using namespace gati;
 namespace {
 
 enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_ROW = 5,
-                   POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7, POOL_FC_FLAT = 8 };
+                   POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7, POOL_FC_FLAT = 8, POOL_CONV = 9, POOL_CONV_GENERIC = 10 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -92,13 +93,17 @@ struct gati_cache {
     void* sel_in = nullptr;   // [rows_pad, Sin]
     void* sel_g = nullptr;    // [rows_pad, Hsp]
     float* zbuf = nullptr;    // [max_rows, K] logits when the caller keeps none
+    // Conv(k,s) predictor: Co = desc.H filters; plan of conv_relu_kernel
+    bool conv_fc = false;
+    int conv_oh = 0, conv_ow = 0, conv_R = 0, conv_nbands = 1, conv_rows_in = 0, conv_whole = 0, conv_tpw = 8, conv_ntc = 1;
+    float* W1plain = nullptr; // [Co, C, k, k] fp32 (rounded to bf16 values in bf16 caches)
 };
 
 namespace {
 
 void free_all(gati_cache* c) {
     void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats,
-                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf};
+                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf, c->W1plain};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
 }
@@ -109,6 +114,60 @@ gati_status_t upload(void** dst, const void* src, size_t bytes) {
     e = src ? hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) : hipMemset(*dst, 0, bytes);
     if (e != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
     return GATI_OK;
+}
+
+// Conv(k,s): staging mode and band height of conv_relu_kernel, or the generic kernel.
+void plan_conv(gati_cache* c) {
+    const gati_cache_desc_t& d = c->desc;
+    const int k_step = c->bf16 ? 16 : 8;
+    const int oh = c->conv_oh, ow = c->conv_ow;
+    c->variant = POOL_CONV_GENERIC;
+    c->conv_ntc = d.H > 32 ? 2 : 1;
+    const int max_pixels = c->conv_ntc == 2 ? 512 : 1024;   // 4 waves x TPW tiles x 32 pixels
+    c->conv_tpw = c->conv_ntc == 2 ? 4 : 8;
+    if (d.C % k_step != 0 || ((long)d.C * d.S * c->elem) % 16 != 0) return;
+    if (d.S <= 1024) {
+        // small map: the whole planes of a channel block are staged; bands only split the output rows
+        c->conv_whole = 1;
+        c->conv_rows_in = d.in_h;
+        c->conv_R = std::min(oh, std::max(1, max_pixels / ow));
+        if (ow > max_pixels) return;
+    } else {
+        if ((d.in_w * c->elem) % 16 != 0 || ((long)d.S * c->elem) % 16 != 0) return;
+        int R = std::min(oh, max_pixels / ow);
+        while (R >= 1 && (long)((R - 1) * d.conv_s + d.conv_k) * d.in_w > 1024) --R;
+        if (R < 1) return;
+        c->conv_whole = 0;
+        c->conv_R = R;
+        c->conv_rows_in = (R - 1) * d.conv_s + d.conv_k;
+    }
+    c->conv_nbands = (oh + c->conv_R - 1) / c->conv_R;
+    c->variant = POOL_CONV;
+}
+
+template <bool BF16>
+hipError_t launch_conv_t(const gati_cache* c, const void* act, const int32_t* row_index, int n_max,
+                         const int32_t* n_dev, float* out, void* out16, int out_stride, hipStream_t st) {
+    const gati_cache_desc_t& d = c->desc;
+    ConvArgs a;
+    a.act = act; a.row_index = row_index; a.n_dev = n_dev; a.n_max = n_max;
+    a.C = d.C; a.S = d.S; a.in_h = d.in_h; a.in_w = d.in_w; a.k = d.conv_k; a.s = d.conv_s;
+    a.oh = c->conv_oh; a.ow = c->conv_ow; a.Co = d.H;
+    a.Wp = c->W1; a.Wplain = c->W1plain; a.bias = c->b1;
+    a.CB = d.C / (BF16 ? 16 : 8);
+    a.R = c->conv_R; a.nbands = c->conv_nbands; a.rows_in = c->conv_rows_in; a.whole = c->conv_whole;
+    a.out = out; a.out16 = static_cast<__bf16*>(out16); a.out_stride = out_stride;
+    if (n_max == 0) return hipSuccess;
+    if (c->variant != POOL_CONV || (reinterpret_cast<uintptr_t>(act) & 15u) != 0) {
+        const long items = (long)n_max * c->F;
+        const int blocks = (int)std::min<long>((items + 255) / 256, (long)c->num_cu * 16);
+        conv_generic_kernel<BF16><<<blocks, 256, 0, st>>>(a);
+    } else {
+        const int grid = n_max * c->conv_nbands;
+        if (c->conv_ntc == 2) conv_relu_kernel<BF16, 4, 2><<<grid, 256, 0, st>>>(a);
+        else conv_relu_kernel<BF16, 8, 1><<<grid, 256, 0, st>>>(a);
+    }
+    return hipGetLastError();
 }
 
 // Pick the pooling kernel for a shape.  Everything the vector kernels assume is checked here.
@@ -275,6 +334,20 @@ void pack_weights_flat(const float* W, int rows, long cols, int rows_p, int k_st
             }
 }
 
+// Filters of the Conv(k,s) predictor as a [Co, Kd] matrix whose reduction index is ordered
+// (channel block, dy, dx, channel in block), channels zero padded to whole blocks: the order
+// conv_relu_kernel walks.  Returns Kd.
+int conv_reorder(const gati_cache_desc_t* d, const float* W1, int k_step, std::vector<float>& out) {
+    const int k = d->conv_k, k2 = k * k, CB = (d->C + k_step - 1) / k_step, Kd = CB * k2 * k_step;
+    out.assign((size_t)d->H * Kd, 0.f);
+    for (int o = 0; o < d->H; ++o)
+        for (int c = 0; c < d->C; ++c)
+            for (int t = 0; t < k2; ++t)
+                out[(size_t)o * Kd + ((size_t)(c / k_step) * k2 + t) * k_step + c % k_step] =
+                    W1[((size_t)o * d->C + c) * k2 + t];
+    return Kd;
+}
+
 template <typename Tag>
 hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, hipStream_t st) {
     const int max_blocks = c->num_cu * c->pool_blocks_per_cu;
@@ -414,6 +487,9 @@ hipError_t launch_pool(const gati_cache* c, const void* act, const int32_t* row_
     if (c->flat_fc)
         return c->bf16 ? launch_flat_t<true>(c, act, row_index, n_max, n_dev, out, out16, out_stride, st)
                        : launch_flat_t<false>(c, act, row_index, n_max, n_dev, out, out16, out_stride, st);
+    if (c->conv_fc)
+        return c->bf16 ? launch_conv_t<true>(c, act, row_index, n_max, n_dev, out, out16, out_stride, st)
+                       : launch_conv_t<false>(c, act, row_index, n_max, n_dev, out, out16, out_stride, st);
     PoolArgs a;
     a.out16 = static_cast<__bf16*>(out16);
     a.act = act; a.row_index = row_index; a.n_dev = n_dev; a.n_max = n_max;
@@ -514,11 +590,24 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
                                 gati_cache_t** out) {
     if (!desc || !w || !out) return GATI_ERR_INVALID_ARG;
     if (desc->predictor != GATI_PRED_GAP_MLP && desc->predictor != GATI_PRED_POOL_FC &&
-        desc->predictor != GATI_PRED_FC_MLP)
+        desc->predictor != GATI_PRED_FC_MLP && desc->predictor != GATI_PRED_CONV_FC)
         return GATI_ERR_INVALID_ARG;
     const bool flat_fc = desc->predictor == GATI_PRED_FC_MLP;
     const bool pool_fc = desc->predictor == GATI_PRED_POOL_FC;
-    const bool no_hidden_kernel = pool_fc || flat_fc;
+    const bool conv_fc = desc->predictor == GATI_PRED_CONV_FC;
+    const bool no_hidden_kernel = pool_fc || flat_fc || conv_fc;
+    int conv_oh = 0, conv_ow = 0;
+    if (conv_fc) {
+        if (desc->layout != GATI_LAYOUT_NCS) return GATI_ERR_INVALID_ARG;
+        if (desc->in_h <= 0 || desc->in_w <= 0 || desc->conv_k <= 0 || desc->conv_s <= 0) return GATI_ERR_INVALID_ARG;
+        if (desc->conv_k > desc->in_h || desc->conv_k > desc->in_w) return GATI_ERR_INVALID_ARG;
+        if ((long)desc->in_h * desc->in_w != (long)desc->S) return GATI_ERR_INVALID_ARG;
+        if (desc->H <= 0) return GATI_ERR_INVALID_ARG;
+        if (desc->H > 64 || desc->conv_k > 15) return GATI_ERR_UNSUPPORTED;
+        conv_oh = (desc->in_h - desc->conv_k) / desc->conv_s + 1;
+        conv_ow = (desc->in_w - desc->conv_k) / desc->conv_s + 1;
+        if ((long)desc->H * conv_oh * conv_ow > (1L << 20)) return GATI_ERR_UNSUPPORTED;
+    }
     if (desc->C <= 0 || desc->S <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && desc->H <= 0) return GATI_ERR_INVALID_ARG;
     if (pool_fc) {
@@ -543,7 +632,8 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     // sizes whose padded products still fit the kernels' 32-bit tile arithmetic
     if (desc->C > (1 << 20) || desc->H > (1 << 20) || desc->K > (1 << 20) || desc->max_rows > (1 << 22))
         return GATI_ERR_UNSUPPORTED;
-    const long F_l = pool_fc ? (long)desc->C * desc->out_h * desc->out_w : (flat_fc ? (long)desc->H : (long)desc->C);
+    const long F_l = pool_fc ? (long)desc->C * desc->out_h * desc->out_w
+                   : conv_fc ? (long)desc->H * conv_oh * conv_ow : (flat_fc ? (long)desc->H : (long)desc->C);
     if ((long)desc->max_rows * (F_l + 64) >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
 
     gati_cache* c = new (std::nothrow) gati_cache();
@@ -555,6 +645,8 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     c->tau = desc->threshold;
     c->pool_fc = no_hidden_kernel;
     c->flat_fc = flat_fc;
+    c->conv_fc = conv_fc;
+    c->conv_oh = conv_oh; c->conv_ow = conv_ow;
     c->F = (int)F_l;
     c->Cp = round_up(c->F, 64);
     c->Hp = no_hidden_kernel ? c->Cp : round_up(desc->H, 64);   // width of the layer that feeds the output FC
@@ -590,6 +682,8 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         c->flat_ks_per = round_up((c->flat_KS + splits - 1) / splits, 4);   // whole permutation blocks
         c->flat_splits = (c->flat_KS + c->flat_ks_per - 1) / c->flat_ks_per;
         c->variant = POOL_FC_FLAT;
+    } else if (conv_fc) {
+        plan_conv(c);
     } else {
         plan_pool(c);
     }
@@ -604,6 +698,17 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
                 const int D = desc->C * desc->S;
                 pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 16, t1, f32_to_bf16_rne);
                 st = upload(&c->W1, t1.data(), t1.size() * 2);
+            } else if (conv_fc) {
+                std::vector<float> wr, plain;
+                const int kd = conv_reorder(desc, w->W1, 16, wr);
+                pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 16, t1, f32_to_bf16_rne);
+                st = upload(&c->W1, t1.data(), t1.size() * 2);
+                plain.resize((size_t)desc->H * desc->C * desc->conv_k * desc->conv_k);
+                for (size_t q = 0; q < plain.size(); ++q) {
+                    const uint32_t bits = (uint32_t)f32_to_bf16_rne(w->W1[q]) << 16;
+                    std::memcpy(&plain[q], &bits, 4);
+                }
+                if (st == GATI_OK) st = upload((void**)&c->W1plain, plain.data(), plain.size() * 4);
             } else if (!pool_fc) {
                 pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
                 st = upload(&c->W1, t1.data(), t1.size() * 2);
@@ -617,6 +722,13 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
                 const int D = desc->C * desc->S;
                 pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 8, t1, same);
                 st = upload(&c->W1, t1.data(), t1.size() * 4);
+            } else if (conv_fc) {
+                std::vector<float> wr;
+                const int kd = conv_reorder(desc, w->W1, 8, wr);
+                pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 8, t1, same);
+                st = upload(&c->W1, t1.data(), t1.size() * 4);
+                if (st == GATI_OK)
+                    st = upload((void**)&c->W1plain, w->W1, (size_t)desc->H * desc->C * desc->conv_k * desc->conv_k * 4);
             } else if (!pool_fc) {
                 pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);
                 st = upload(&c->W1, t1.data(), t1.size() * 4);
@@ -625,7 +737,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
             if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 4);
         }
         std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
-        if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)desc->H * 4);
+        if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)desc->H * 4);   // conv_fc: one bias per filter
         std::memcpy(b2.data(), w->b2, (size_t)K * 4);
         if (!sel_hidden) {      // otherwise both halves stay zero: the per-tile selector sums are unused
             std::memcpy(wp.data(), w->ws, (size_t)C * 4);
@@ -775,6 +887,8 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     case POOL_NCS_ADAPTIVE: return "ncs_adaptive";
     case POOL_ADAPTIVE_GENERIC: return "adaptive_generic";
     case POOL_FC_FLAT: return "fc_flat";
+    case POOL_CONV: return "conv_mfma";
+    case POOL_CONV_GENERIC: return "conv_generic";
     default: return "generic";
     }
 }

@@ -32,12 +32,16 @@ class LayerSpec:
     out_hw: tuple = (0, 0)       # pool_fc: pooled map; F = C*out_h*out_w features
     selector: str = "linear"     # "linear" | "softmax" | "hidden" (selector network with one hidden layer)
     sel_hidden: int = 0          # units of that hidden layer
+    conv_ks: tuple = (0, 0)      # conv_fc (the paper's Conv(k,s)): filter size and stride; H filters, map in_hw
 
     @property
     def F(self) -> int:
         """Features the pooling step hands to the FC layers."""
         if self.predictor == "pool_fc":
             return self.C * self.out_hw[0] * self.out_hw[1]
+        if self.predictor == "conv_fc":
+            k, s = self.conv_ks
+            return self.H * ((self.in_hw[0] - k) // s + 1) * ((self.in_hw[1] - k) // s + 1)
         return self.H if self.predictor == "fc_mlp" else self.C
 
     @property

@@ -70,6 +70,14 @@ def _predictor_and_linear_selector(spec: WorkloadSpec, layer: int) -> dict:
         W2 = (g.standard_normal((L.K, L.F)) * np.sqrt(2.0 / L.F)).astype(np.float32)
         ws = (g.standard_normal(L.F + L.K) * np.sqrt(2.0 / (L.F + L.K))).astype(np.float32)
         return {"W1": None, "b1": None, "W2": W2, "b2": np.zeros(L.K, np.float32), "ws": ws, "bs": float(L.bs)}
+    if L.predictor == "conv_fc":
+        # Conv(k,s): H filters [H, C, k, k] (fan-in C*k*k), then the output FC over the F hidden values
+        k = L.conv_ks[0]
+        W1 = (g.standard_normal((L.H, L.C, k, k)) * np.sqrt(2.0 / (L.C * k * k))).astype(np.float32)
+        W2 = (g.standard_normal((L.K, L.F)) * np.sqrt(2.0 / L.F)).astype(np.float32)
+        ws = (g.standard_normal(L.F + L.K) * np.sqrt(2.0 / (L.F + L.K))).astype(np.float32)
+        return {"W1": W1, "b1": np.zeros(L.H, np.float32), "W2": W2, "b2": np.zeros(L.K, np.float32),
+                "ws": ws, "bs": float(L.bs)}
     if L.predictor == "fc_mlp":
         # FC(h): the first FC reads the whole flattened row (D = C*S inputs); drawn in float32
         # row blocks to keep the host footprint at one copy of the matrix
