@@ -95,7 +95,8 @@ struct gati_cache {
     float* zbuf = nullptr;    // [max_rows, K] logits when the caller keeps none
     // Conv(k,s) predictor: Co = desc.H filters; plan of conv_relu_kernel
     bool conv_fc = false;
-    int conv_oh = 0, conv_ow = 0, conv_R = 0, conv_nbands = 1, conv_rows_in = 0, conv_whole = 0, conv_tpw = 8, conv_ntc = 1;
+    int conv_oh = 0, conv_ow = 0, conv_R = 0, conv_nbands = 1, conv_rows_in = 0, conv_whole = 0, conv_tpw = 8, conv_ntc = 1, conv_tr = 0, conv_ksplit = 1, conv_cb_per = 0, conv_bps = 1;
+    float* conv_partial = nullptr;   // [ksplit][max_rows][Cp] when ksplit > 1
     float* W1plain = nullptr; // [Co, C, k, k] fp32 (rounded to bf16 values in bf16 caches)
 };
 
@@ -103,7 +104,7 @@ namespace {
 
 void free_all(gati_cache* c) {
     void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats,
-                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf, c->W1plain};
+                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf, c->W1plain, c->conv_partial};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
 }
@@ -142,6 +143,25 @@ void plan_conv(gati_cache* c) {
         c->conv_rows_in = (R - 1) * d.conv_s + d.conv_k;
     }
     c->conv_nbands = (oh + c->conv_R - 1) / c->conv_R;
+    // 32-pixel tiles per wave: the smallest of 1, 2, 4, 8 that covers the tallest band
+    const int tiles = (c->conv_R * ow + 31) / 32;
+    int tpw = 1;
+    while (tpw * 4 < tiles) tpw *= 2;
+    c->conv_tpw = tpw;
+    // bf16 maps whose 8-position chunks are 16-byte aligned in every channel: transposed staging
+    c->conv_tr = (c->bf16 && d.S % 8 == 0 && (c->conv_whole || d.in_w % 8 == 0)) ? 1 : 0;
+    // a workgroup walks its channel blocks one after another: when max_rows x bands gives fewer than
+    // ~4 workgroups per CU, split the blocks over several (fixed at creation, so results do not
+    // depend on how many rows a call has)
+    const int CB = d.C / k_step;
+    const long wgs = (long)d.max_rows * c->conv_nbands;
+    int ks = (int)((4L * c->num_cu + wgs - 1) / wgs);
+    if (wgs < 8L * c->num_cu) ks = std::max(ks, CB / 8);     // and keep a workgroup's chain to ~8 blocks
+    ks = std::max(1, std::min(std::min(ks, CB / 2), 16));
+    c->conv_cb_per = (CB + ks - 1) / ks;
+    c->conv_ksplit = (CB + c->conv_cb_per - 1) / c->conv_cb_per;
+    // small maps copied as they lie: as many channel blocks per LDS fill as the 32 KB buffer holds
+    c->conv_bps = (c->conv_whole && !c->conv_tr) ? std::max(1, std::min(c->conv_cb_per, 1024 / d.S)) : 1;
     c->variant = POOL_CONV;
 }
 
@@ -157,15 +177,42 @@ hipError_t launch_conv_t(const gati_cache* c, const void* act, const int32_t* ro
     a.CB = d.C / (BF16 ? 16 : 8);
     a.R = c->conv_R; a.nbands = c->conv_nbands; a.rows_in = c->conv_rows_in; a.whole = c->conv_whole;
     a.out = out; a.out16 = static_cast<__bf16*>(out16); a.out_stride = out_stride;
+    a.ksplit = 1; a.cb_per_split = a.CB; a.partial = nullptr; a.bps = c->conv_bps;
     if (n_max == 0) return hipSuccess;
     if (c->variant != POOL_CONV || (reinterpret_cast<uintptr_t>(act) & 15u) != 0) {
         const long items = (long)n_max * c->F;
         const int blocks = (int)std::min<long>((items + 255) / 256, (long)c->num_cu * 16);
         conv_generic_kernel<BF16><<<blocks, 256, 0, st>>>(a);
     } else {
-        const int grid = n_max * c->conv_nbands;
-        if (c->conv_ntc == 2) conv_relu_kernel<BF16, 4, 2><<<grid, 256, 0, st>>>(a);
-        else conv_relu_kernel<BF16, 8, 1><<<grid, 256, 0, st>>>(a);
+        // the split slabs are laid out for out_stride == Cp (the cache's own feature buffer and
+        // gati_cache_pool's F-wide output both fit: out_stride <= Cp)
+        if (c->conv_ksplit > 1 && out_stride <= c->Cp) {
+            a.ksplit = c->conv_ksplit; a.cb_per_split = c->conv_cb_per; a.partial = c->conv_partial;
+        }
+        const int grid = n_max * c->conv_nbands * a.ksplit;
+        const int key = c->conv_ntc * 16 + c->conv_tpw;
+#define GATI_CONV(TRV)                                                                        \
+    switch (key) {                                                                            \
+    case 16 + 1: conv_relu_kernel<BF16, 1, 1, TRV><<<grid, 256, 0, st>>>(a); break;           \
+    case 16 + 2: conv_relu_kernel<BF16, 2, 1, TRV><<<grid, 256, 0, st>>>(a); break;           \
+    case 16 + 4: conv_relu_kernel<BF16, 4, 1, TRV><<<grid, 256, 0, st>>>(a); break;           \
+    case 16 + 8: conv_relu_kernel<BF16, 8, 1, TRV><<<grid, 256, 0, st>>>(a); break;           \
+    case 32 + 1: conv_relu_kernel<BF16, 1, 2, TRV><<<grid, 256, 0, st>>>(a); break;           \
+    case 32 + 2: conv_relu_kernel<BF16, 2, 2, TRV><<<grid, 256, 0, st>>>(a); break;           \
+    default: conv_relu_kernel<BF16, 4, 2, TRV><<<grid, 256, 0, st>>>(a); break;               \
+    }
+        if constexpr (BF16) {
+            if (c->conv_tr) { GATI_CONV(true) } else { GATI_CONV(false) }
+        } else {
+            GATI_CONV(false)
+        }
+#undef GATI_CONV
+        if (a.ksplit > 1) {
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            const long items = (long)n_max * c->F;
+            conv_reduce_kernel<<<(int)std::min<long>((items + 255) / 256, (long)c->num_cu * 8), 256, 0, st>>>(a);
+        }
     }
     return hipGetLastError();
 }
@@ -335,15 +382,16 @@ void pack_weights_flat(const float* W, int rows, long cols, int rows_p, int k_st
 }
 
 // Filters of the Conv(k,s) predictor as a [Co, Kd] matrix whose reduction index is ordered
-// (channel block, dy, dx, channel in block), channels zero padded to whole blocks: the order
-// conv_relu_kernel walks.  Returns Kd.
+// (channel block, tap dy*k+dx padded with zeros to conv_taps_padded(k), channel in block): the
+// order conv_relu_kernel walks.  Returns Kd.
 int conv_reorder(const gati_cache_desc_t* d, const float* W1, int k_step, std::vector<float>& out) {
-    const int k = d->conv_k, k2 = k * k, CB = (d->C + k_step - 1) / k_step, Kd = CB * k2 * k_step;
+    const int k = d->conv_k, k2 = k * k, IT = conv_taps_padded(k);
+    const int CB = (d->C + k_step - 1) / k_step, Kd = CB * IT * k_step;
     out.assign((size_t)d->H * Kd, 0.f);
     for (int o = 0; o < d->H; ++o)
         for (int c = 0; c < d->C; ++c)
             for (int t = 0; t < k2; ++t)
-                out[(size_t)o * Kd + ((size_t)(c / k_step) * k2 + t) * k_step + c % k_step] =
+                out[(size_t)o * Kd + ((size_t)(c / k_step) * IT + t) * k_step + c % k_step] =
                     W1[((size_t)o * d->C + c) * k2 + t];
     return Kd;
 }
@@ -780,6 +828,8 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     if (st == GATI_OK && !no_hidden_kernel) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
     if (st == GATI_OK && flat_fc)
         st = upload((void**)&c->flat_partial, nullptr, (size_t)c->flat_splits * c->rows_b * c->Hb * 4);
+    if (st == GATI_OK && conv_fc && c->conv_ksplit > 1)
+        st = upload((void**)&c->conv_partial, nullptr, (size_t)c->conv_ksplit * desc->max_rows * c->Cp * 4);
     if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
     if (st == GATI_OK && sel_hidden) st = upload(&c->sel_in, nullptr, (size_t)c->rows_pad * c->Sin * c->elem);
     if (st == GATI_OK && sel_hidden) st = upload(&c->sel_g, nullptr, (size_t)c->rows_pad * c->Hsp * c->elem);

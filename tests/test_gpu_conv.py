@@ -24,6 +24,9 @@ SHAPES = [
     (12, 10, 10, 3, 3, 1, 4, 11, "bf16", "conv_generic"),   # channels not a whole block
     (5, 9, 7, 2, 4, 3, 3, 8, "f32", "conv_generic"),
     (32, 32, 40, 4, 3, 1, 6, 5, "bf16", "conv_mfma"),       # wide rows: 38 output columns, several bands
+    (32, 28, 28, 8, 5, 2, 10, 7, "bf16", "conv_mfma"),      # whole-plane staging with the transposing store
+    (16, 16, 16, 40, 3, 1, 6, 9, "bf16", "conv_mfma"),      # the same with two filter tiles
+    (16, 24, 24, 8, 3, 1, 5, 6, "f32", "conv_mfma"),        # fp32, several tiles per wave
 ]
 
 

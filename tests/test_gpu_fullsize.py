@@ -64,7 +64,7 @@ def _check_chain_properties(stack, batch, n_layers):
     return counts
 
 
-@pytest.mark.parametrize("name,rows_per_layer", [("resnet18", 6), ("resnet50", 5), ("bert_base", 8), ("resnet50_pool", 3), ("resnet50_hsel", 3)])
+@pytest.mark.parametrize("name,rows_per_layer", [("resnet18", 6), ("resnet50", 5), ("bert_base", 8), ("resnet50_pool", 3), ("resnet50_hsel", 3), ("resnet50_conv", 2)])
 def test_full_batch_gather_stack(name, rows_per_layer):
     spec, labels, weights, caches = _build(name)
     defs = admit.cache_defs(spec, mirror=True)

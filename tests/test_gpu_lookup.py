@@ -61,6 +61,7 @@ STACKS = [
     ("bert_base", 45, "dense", 0.25, True),
     ("resnet50_pool", 35, "gather", 0.12, True),       # the paper's Pool(h) predictor on the same shapes
     ("resnet50_hsel", 37, "gather", 0.12, True),       # selector network with one hidden layer
+    ("resnet50_conv", 20, "gather", 0.12, True),       # the paper's Conv(k,s) predictor on the same shapes
 ]
 
 

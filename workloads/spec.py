@@ -134,6 +134,14 @@ def _build():
         layers=[LayerSpec(C=C, S=hw * hw, H=1024, K=1000, layout="ncs", dtype="bf16", threshold=0.6,
                           gamma=8.0 + 4.8 * i, relu=True, predictor="fc_mlp")
                 for i, (C, hw) in enumerate(fc_blocks)])
+    # The paper's Conv(k,s) variant on the ResNet-50 shapes, 8 filters: Conv(5,2) on the 56x56 and 28x28
+    # maps, Conv(3,1) on the 14x14 and 7x7 ones (the two settings of Section 7 "Default Parameters"),
+    # i.e. 5408 / 1152 / 1152 / 200 hidden values
+    conv_layers = []
+    for l in w["resnet50"].layers:
+        hw = int(round(l.S ** 0.5))
+        conv_layers.append(replace(l, H=8, predictor="conv_fc", in_hw=(hw, hw), conv_ks=(5, 2) if hw >= 28 else (3, 1)))
+    w["resnet50_conv"] = replace(w["resnet50"], name="resnet50_conv", layers=conv_layers)
     # The resnet50 stack with the paper's selector shape: one hidden layer (Section 3, "Selector
     # Network Design") of 64 units over [pooled ; class probabilities]
     w["resnet50_hsel"] = replace(w["resnet50"], name="resnet50_hsel",
@@ -152,6 +160,7 @@ HIT_TARGETS = {
     "resnet50": [0.0065 * (i + 1) for i in range(16)],
     "resnet50_pool": [0.0065 * (i + 1) for i in range(16)],
     "resnet50_hsel": [0.0065 * (i + 1) for i in range(16)],
+    "resnet50_conv": [0.0065 * (i + 1) for i in range(16)],
     "resnet50_fc": _linear_ramp(0.05, 0.20, 6),
     "bert_base": _linear_ramp(0.02, 0.20, 12),
     "resnet152": _linear_ramp(0.02, 0.70, 50),
