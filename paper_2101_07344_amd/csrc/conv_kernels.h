@@ -248,22 +248,30 @@ __global__ __launch_bounds__(256, (TPW * NTC <= 2 ? 4 : (TPW * NTC <= 4 ? 3 : 1)
         __syncthreads();
       for (int bj = 0; bj < nblk; ++bj) {
         const unsigned char* xb = reinterpret_cast<const unsigned char*>(xs[0]) + (long)bj * total_vec * 16;
-        int dy = 0, dx = 0;
+        // the A fragments of tap t+1 are read from LDS before the MFMAs of tap t, so the read latency
+        // is covered by arithmetic; (dy, dx) below are those of the NEXT tap
+        auto fragments = [&](frag_t (&f)[TPW], int off) {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                if constexpr (TR) f[t] = conv_a_fragment_tr(xb, pos[t] + off, kb);
+                else f[t] = conv_a_fragment<BF16>(xb, pos[t] + off, pitch, kb);
+            }
+        };
+        frag_t xf[TPW], xn[TPW];
+        fragments(xf, 0);                                    // tap 0
+        int dy = 0, dx = 1;
+        if (dx == a.k) { dx = 0; dy = 1; }
         for (int tap0 = 0; tap0 < IT; tap0 += WD) {
 #pragma unroll
             for (int u = 0; u < WD; ++u) {                   // ring slot = u
                 wload((u + WD - 1) % WD);
-                const int off = tap0 + u < k2 ? dy * a.in_w + dx : 0;
-                frag_t xf[TPW];
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    if constexpr (TR) xf[t] = conv_a_fragment_tr(xb, pos[t] + off, kb);
-                    else xf[t] = conv_a_fragment<BF16>(xb, pos[t] + off, pitch, kb);
-                }
+                fragments(xn, tap0 + u + 1 < k2 ? dy * a.in_w + dx : 0);   // past the last tap: any valid position
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
 #pragma unroll
                     for (int nt = 0; nt < NTC; ++nt) acc[t][nt] = M::mma(xf[t], wring[u][nt], acc[t][nt]);
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) xf[t] = xn[t];
                 if (++dx == a.k) { dx = 0; ++dy; }
             }
         }
