@@ -66,3 +66,23 @@ def test_bert_rows_are_token_major_bf16():
     bulk = W.activation_bulk(spec, 0, lab, [0, 1, 2, 3], device="cpu")
     assert bulk.shape == (4, 128, 768)
     assert torch.equal(bulk, W.activation_bulk(spec, 0, lab, [0, 1, 2, 3], device="cpu"))
+
+
+def test_variant_workloads_have_their_feature_counts_and_fitted_biases():
+    want_F = {"resnet50_pool": [4096] * 3 + [8192] * 4 + [4096] * 6 + [8192] * 3,
+              "resnet50_conv": [5408] * 3 + [1152] * 4 + [1152] * 6 + [200] * 3,
+              "resnet50_fc": [1024] * 6, "resnet50_hsel": [256] * 3 + [512] * 4 + [1024] * 6 + [2048] * 3}
+    for name, fs in want_F.items():
+        spec = W.get_workload(name)
+        assert [l.F for l in spec.layers] == fs, name
+        assert all(l.target_hit is not None for l in spec.layers), name       # the stored calibration was applied
+        assert len({round(l.bs, 6) for l in spec.layers}) > 1, name
+        w = W.cache_weights(spec, len(spec.layers) - 1)
+        L = spec.layers[-1]
+        assert w["W2"].shape == (L.K, L.F if L.predictor in ("pool_fc", "conv_fc") else L.H)
+        if L.selector == "hidden":
+            assert w["Ws"].shape == (L.sel_hidden, L.F + L.K) and w["vs"].shape == (L.sel_hidden,)
+            base = W.cache_weights(W.get_workload("resnet50"), len(spec.layers) - 1)
+            assert np.array_equal(w["W1"], base["W1"])                          # same predictor as the linear stack
+        if L.predictor == "conv_fc":
+            assert w["W1"].shape == (L.H, L.C, L.conv_ks[0], L.conv_ks[0])
