@@ -35,13 +35,6 @@ inline uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-int env_int(const char* name, int dflt) {
-    const char* v = std::getenv(name);
-    if (!v || !*v) return dflt;
-    const int x = std::atoi(v);
-    return x > 0 ? x : dflt;
-}
-
 }  // namespace
 
 struct gati_cache {
@@ -80,7 +73,7 @@ struct gati_cache {
     int gt = 0, tiles_per_row = 0, tpc_log2 = 0;  // ncs_seg
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
-    int nsc_lpt = 1, cb_per_row = 0, nsc_nw = 4;  // nsc_row
+    int nsc_lpt = 1, cb_per_row = 0;              // nsc_row (4 waves per workgroup; 16 measured no faster)
     int ad_j = 4, ad_tpo_log2 = 0, ad_ww = 0, ad_pair = 0;   // ncs_adaptive (tile in gt / tiles_per_row; common window width or 0; LDS read mode)
     int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
     // head plan: column tiles per workgroup of the output layer
@@ -278,10 +271,9 @@ void plan_pool(gati_cache* c) {
             c->cvb_per_row = (CV + best - 1) / best;
             c->variant = POOL_NSC_VEC;
             // enough tokens for four slices of several tokens each: stream whole token rows
-            if (S >= 32 && env_int("GATI_NSC_ROW", 1) == 1) {
+            if (S >= 32) {
                 c->nsc_lpt = std::min(4, (CV + 63) / 64);
                 c->cb_per_row = (CV + 64 * c->nsc_lpt - 1) / (64 * c->nsc_lpt);
-                c->nsc_nw = (S >= 128 && env_int("GATI_NSC_NW", 4) == 16) ? 16 : 4;
                 c->variant = POOL_NSC_ROW;
             }
         }
@@ -436,20 +428,11 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
     case POOL_NSC_ROW: {
         const long items = (long)a.n_max * c->cb_per_row;
         const int blocks = (int)std::min<long>(items, max_blocks);
-        if (c->nsc_nw == 16) {
-            switch (c->nsc_lpt) {
-            case 1: pool_nsc_row_kernel<Tag, 1, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
-            case 2: pool_nsc_row_kernel<Tag, 2, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
-            case 3: pool_nsc_row_kernel<Tag, 3, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
-            default: pool_nsc_row_kernel<Tag, 4, 16><<<blocks, 1024, 0, st>>>(a, c->cb_per_row); break;
-            }
-        } else {
-            switch (c->nsc_lpt) {
-            case 1: pool_nsc_row_kernel<Tag, 1, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-            case 2: pool_nsc_row_kernel<Tag, 2, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-            case 3: pool_nsc_row_kernel<Tag, 3, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-            default: pool_nsc_row_kernel<Tag, 4, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-            }
+        switch (c->nsc_lpt) {
+        case 1: pool_nsc_row_kernel<Tag, 1, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
+        case 2: pool_nsc_row_kernel<Tag, 2, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
+        case 3: pool_nsc_row_kernel<Tag, 3, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
+        default: pool_nsc_row_kernel<Tag, 4, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
         }
         break;
     }
@@ -708,7 +691,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         c->num_cu = cus;
     else
         (void)hipGetLastError();
-    c->pool_blocks_per_cu = env_int("GATI_POOL_BLOCKS_PER_CU", 16);
+    c->pool_blocks_per_cu = 16;
 
     if (flat_fc) {
         const int k_step = c->bf16 ? 16 : 8;
@@ -726,7 +709,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         // enough workgroups for every CU, each with at least 16 k-steps; multiples of 8 keep the XCD mapping
         int splits = std::max(1, std::min(c->num_cu / tiles, c->flat_KS / 16));
         if (splits >= 8) splits = splits / 8 * 8;
-        splits = std::min(splits, env_int("GATI_FLAT_MAX_SPLITS", 64));
+        splits = std::min(splits, 64);
         c->flat_ks_per = round_up((c->flat_KS + splits - 1) / splits, 4);   // whole permutation blocks
         c->flat_splits = (c->flat_KS + c->flat_ks_per - 1) / c->flat_ks_per;
         c->variant = POOL_FC_FLAT;
