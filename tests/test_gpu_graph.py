@@ -28,11 +28,15 @@ def _same(a, b):
     return all(torch.equal(a[3][l][:counts[l]], b[3][l][:counts[l]]) for l in range(len(a[3])))
 
 
-@pytest.mark.parametrize("name,batch", [("resnet18", 48), ("bert_base", 96)])
-def test_graph_replay_equals_eager(name, batch):
+@pytest.mark.parametrize("name,batch,layers", [
+    ("resnet18", 48, slice(0, 6)), ("bert_base", 96, slice(0, 6)),
+    # the predictor / selector variants: Pool(h), Conv(k,s) incl. its split + reduce kernels, hidden-layer selector
+    ("resnet50_pool", 40, slice(5, 9)), ("resnet50_conv", 24, slice(5, 9)), ("resnet50_hsel", 40, slice(5, 9)),
+])
+def test_graph_replay_equals_eager(name, batch, layers):
     base = W.get_workload(name)
     spec = W.WorkloadSpec(name=f"{name}@{batch}", batch=batch, zipf_s=base.zipf_s, seed=base.seed,
-                          layers=base.layers[:6], storage="gather")
+                          layers=base.layers[layers], storage="gather")
     labels = W.zipf_labels(batch, spec.layers[0].K, spec.zipf_s, spec.seed)
     weights = [W.cache_weights(spec, l) for l in range(len(spec.layers))]
     caches = [g.Cache.from_layer(L, w, batch) for L, w in zip(spec.layers, weights)]
@@ -46,7 +50,7 @@ def test_graph_replay_equals_eager(name, batch):
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
             stack.run(acts)
-    assert 0 < int(eager[4][-1].item()) < batch
+    assert int(eager[4][0].item()) == batch and 0 <= int(eager[4][-1].item()) <= batch
     for rep in range(4):
         # scribble over the outputs and do unrelated eager work between replays
         for t in stack.hit + stack.pred_class + stack.ids[1:]:
