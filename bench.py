@@ -303,6 +303,37 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
     return spec, out
 
 
+def gemm_yardstick(spec, torch):
+    """What the vendor GEMM behind torch.matmul reaches on this machine: on the layer-0 FC(h) product
+    (random operands of the same shapes and dtype) and on a large square one."""
+    def timed(fn, reps=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        return ts[len(ts) // 2] * 1e-3
+    L = spec.layers[0]
+    dt = torch.bfloat16 if L.dtype == "bf16" else torch.float32
+    n, D, H = spec.batch, L.C * L.S, L.H
+    x = torch.randn(n, D, device="cuda").clamp_(min=0).to(dt)
+    w = torch.randn(H, D, device="cuda", dtype=torch.float32).to(dt)
+    t1 = timed(lambda: x @ w.t())
+    del x, w
+    m = 8192
+    a, b = torch.randn(m, m, device="cuda").to(dt), torch.randn(m, m, device="cuda").to(dt)
+    t2 = timed(lambda: a @ b)
+    return {"fc_shape": [n, D, H], "fc_us": round(t1 * 1e6, 1), "fc_TFLOPs": round(2.0 * n * D * H / t1 / 1e12, 1),
+            "square_8192_us": round(t2 * 1e6, 1), "square_8192_TFLOPs": round(2.0 * m ** 3 / t2 / 1e12, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -322,6 +353,9 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain tensor copy of layer 0's activations (known size), the reference "
                          "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    ap.add_argument("--gemm-yardstick", action="store_true",
+                    help="fc_mlp workloads: also time the vendor GEMM (torch.matmul) on layer 0's [n, D] x [D, H] "
+                         "and on a square 8192^3 bf16 product -- context for the MFMA roofline fraction, not a target")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -373,6 +407,8 @@ def main():
     for key in ("graph_ms_per_step", "overlap"):
         if key in main_res:
             line[key] = main_res[key]
+    if args.gemm_yardstick and L0.predictor == "fc_mlp":
+        line["library_gemm"] = gemm_yardstick(spec, torch)
     if args.layers:
         line["layers"] = main_res["layers"]
     else:
