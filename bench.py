@@ -334,6 +334,38 @@ def gemm_yardstick(spec, torch):
             "square_8192_us": round(t2 * 1e6, 1), "square_8192_TFLOPs": round(2.0 * m ** 3 / t2 / 1e12, 1)}
 
 
+def conv_yardstick(spec, layers, torch):
+    """The vendor convolution (torch conv2d + relu, NCHW as the library stores it) on random operands of
+    one layer per map size, with that layer's active row count, beside this library's time for it."""
+    out, seen = [], set()
+    for l, L in enumerate(spec.layers):
+        if L.in_hw in seen:
+            continue
+        seen.add(L.in_hw)
+        n = max(1, int(layers[l]["n"]))
+        dt = torch.bfloat16 if L.dtype == "bf16" else torch.float32
+        k, s = L.conv_ks
+        x = torch.randn(n, L.C, L.in_hw[0], L.in_hw[1], device="cuda").to(dt)
+        w = torch.randn(L.H, L.C, k, k, device="cuda").to(dt)
+        fn = lambda: torch.relu(torch.nn.functional.conv2d(x, w, stride=s))
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(10):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        out.append({"layer": l, "n": n, "C": L.C, "map": list(L.in_hw), "conv": [k, s], "filters": L.H,
+                    "library_us": round(ts[len(ts) // 2] * 1e3, 1), "this_us": layers[l]["pool_us"]})
+        del x, w
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -353,9 +385,10 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain tensor copy of layer 0's activations (known size), the reference "
                          "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
-    ap.add_argument("--gemm-yardstick", action="store_true",
-                    help="fc_mlp workloads: also time the vendor GEMM (torch.matmul) on layer 0's [n, D] x [D, H] "
-                         "and on a square 8192^3 bf16 product -- context for the MFMA roofline fraction, not a target")
+    ap.add_argument("--library-yardstick", "--gemm-yardstick", dest="gemm_yardstick", action="store_true",
+                    help="context, not a target: fc_mlp workloads also time the vendor GEMM (torch.matmul) on layer 0's "
+                         "[n, D] x [D, H] and on a square 8192^3 product; conv_fc workloads time the vendor convolution "
+                         "(torch conv2d + relu) on one layer of every map size")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -409,6 +442,8 @@ def main():
             line[key] = main_res[key]
     if args.gemm_yardstick and L0.predictor == "fc_mlp":
         line["library_gemm"] = gemm_yardstick(spec, torch)
+    if args.gemm_yardstick and L0.predictor == "conv_fc":
+        line["library_conv"] = conv_yardstick(spec, main_res["layers"], torch)
     if args.layers:
         line["layers"] = main_res["layers"]
     else:
