@@ -214,8 +214,31 @@ def cpu_baseline(spec, weights, acts, stack, counts, budget_requests, torch, W):
                       f"({lookups} lookups, {dt:.1f} s, single thread, gcc -O2, fp64 accumulation)"}
 
 
+def pool_yardstick(spec, acts, torch):
+    """The vendor reduction (torch mean over the pooled axis, fp32 result) on layer 0's full tensor."""
+    L = spec.layers[0]
+    x = acts[0]
+    dim = 2 if L.layout == "ncs" else 1
+    fn = lambda: x.mean(dim=dim, dtype=torch.float32)
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(10):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ts.sort()
+    t = ts[len(ts) // 2] * 1e-3
+    nbytes = x.numel() * x.element_size()
+    return {"shape": list(x.shape), "library_us": round(t * 1e6, 1), "library_GBps": round(nbytes / t / 1e9, 1)}
+
+
 def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False,
-                 graph=False, overlap=False):
+                 graph=False, overlap=False, yardstick=False):
     t_build = time.perf_counter()
     spec, labels, weights, caches, stack, acts = build_workload(name, torch, g, W)
     if copy_probe:
@@ -297,6 +320,8 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
         out["overlap"] = time_overlap(stack, acts, steps, warmup, torch)
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(spec, weights, acts, stack, counts, cpu_requests, torch, W)
+    if yardstick and spec.layers[0].predictor == "gap_mlp" and spec.storage == "gather":
+        out["library_pool"] = pool_yardstick(spec, acts, torch)
     stack.close()
     del acts
     torch.cuda.empty_cache()
@@ -388,7 +413,8 @@ def main():
     ap.add_argument("--library-yardstick", "--gemm-yardstick", dest="gemm_yardstick", action="store_true",
                     help="context, not a target: fc_mlp workloads also time the vendor GEMM (torch.matmul) on layer 0's "
                          "[n, D] x [D, H] and on a square 8192^3 product; conv_fc workloads time the vendor convolution "
-                         "(torch conv2d + relu) on one layer of every map size")
+                         "(torch conv2d + relu) on one layer of every map size; global-pool workloads time torch's mean "
+                         "over the pooled axis of layer 0's tensor")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -410,7 +436,7 @@ def main():
     with torch.cuda.stream(stream):
         spec, main_res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
                                       args.cpu_requests, torch, g, W, copy_probe=args.copy_probe,
-                                      graph=args.graph, overlap=args.overlap)
+                                      graph=args.graph, overlap=args.overlap, yardstick=args.gemm_yardstick)
         others = {}
         for name in [n for n in args.also.split(",") if n and n != args.workload]:
             _, r = run_workload(name, args.steps, args.warmup, False, 0, torch, g, W)
@@ -437,7 +463,7 @@ def main():
         "pool_kernels": main_res["pool_kernels"],
         "others": others,
     }
-    for key in ("graph_ms_per_step", "overlap"):
+    for key in ("graph_ms_per_step", "overlap", "library_pool"):
         if key in main_res:
             line[key] = main_res[key]
     if args.gemm_yardstick and L0.predictor == "fc_mlp":
