@@ -137,6 +137,14 @@ gati_status_t gati_cache_create(const gati_cache_desc_t *desc, const gati_cache_
  * that uses it.  NULL is GATI_OK. */
 gati_status_t gati_cache_destroy(gati_cache_t *cache);
 
+/* Replace every weight of an existing cache with a new set of the same shapes (Section 5,
+ * "Retraining Learned Caches": the adaptation service periodically retrains predictor and
+ * selector and swaps them in; the retraining itself is not part of this library).  Host fp32
+ * arrays as for gati_cache_create; repacked and copied before the call returns.  The call
+ * waits for all work on the device first, so lookups enqueued earlier use the old weights and
+ * lookups issued afterwards the new ones; no allocation takes place.  The threshold is kept. */
+gati_status_t gati_cache_set_weights(gati_cache_t *cache, const gati_cache_weights_t *weights);
+
 /* Replace the selector bias and threshold of an existing cache (host scalars; takes effect
  * for calls issued afterwards). */
 gati_status_t gati_cache_set_selector(gati_cache_t *cache, float bs, float threshold);

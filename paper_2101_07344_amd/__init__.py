@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     GatiError, CacheDesc, CacheWeights, Cache, CacheStack,
     load_library, library_path, exported_symbols,
     gati_cache_create, gati_cache_destroy, gati_cache_lookup, gati_cache_lookup_compact, gati_cache_pool,
-    gati_compact_misses, gati_cache_set_selector, gati_status_string, gati_cache_pool_variant,
+    gati_compact_misses, gati_cache_set_selector, gati_cache_set_weights, gati_status_string, gati_cache_pool_variant,
 )

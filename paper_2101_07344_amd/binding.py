@@ -18,7 +18,7 @@ GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC, GATI_PRED_FC_MLP, GATI_PRED_CONV_FC = 0, 1
 
 # every extern "C" symbol include/gati.h declares
 exported_symbols = (
-    "gati_cache_create", "gati_cache_destroy", "gati_cache_set_selector", "gati_cache_lookup",
+    "gati_cache_create", "gati_cache_destroy", "gati_cache_set_weights", "gati_cache_set_selector", "gati_cache_lookup",
     "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_status_string", "gati_cache_pool_variant",
 )
 
@@ -69,6 +69,8 @@ def load_library():
     lib.gati_cache_create.argtypes = [C.POINTER(CacheDesc), C.POINTER(CacheWeights), C.POINTER(vp)]
     lib.gati_cache_destroy.restype = C.c_int
     lib.gati_cache_destroy.argtypes = [vp]
+    lib.gati_cache_set_weights.restype = C.c_int
+    lib.gati_cache_set_weights.argtypes = [vp, C.POINTER(CacheWeights)]
     lib.gati_cache_set_selector.restype = C.c_int
     lib.gati_cache_set_selector.argtypes = [vp, C.c_float, C.c_float]
     lib.gati_cache_lookup.restype = C.c_int
@@ -124,6 +126,10 @@ def gati_cache_create(desc: CacheDesc, weights: CacheWeights):
 
 def gati_cache_destroy(handle) -> int:
     return load_library().gati_cache_destroy(handle)
+
+
+def gati_cache_set_weights(handle, weights: CacheWeights) -> int:
+    return load_library().gati_cache_set_weights(handle, C.byref(weights))
 
 
 def gati_cache_set_selector(handle, bs: float, threshold: float) -> int:
@@ -187,7 +193,24 @@ class Cache:
                           "conv_fc": GATI_PRED_CONV_FC}[predictor],
                          int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]), int(sel_hidden),
                          int(conv_ks[0]), int(conv_ks[1]))
-        hidden_sel = selector == "hidden"
+        self._shape = (C_, S, H, K, pool_fc, fc_mlp, conv_fc, selector == "hidden", sel_hidden, tuple(conv_ks))
+        w, _keep = self._marshal(weights)
+        st, self.handle = gati_cache_create(desc, w)
+        _check(st, "gati_cache_create")
+
+    @classmethod
+    def from_layer(cls, L, weights: dict, max_rows: int) -> "Cache":
+        """Build from any record with the fields C, S, H, K, dtype, layout, threshold and,
+        optionally, predictor, in_hw, out_hw, selector, sel_hidden."""
+        return cls(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, max_rows, weights,
+                   selector=getattr(L, "selector", "linear"), predictor=getattr(L, "predictor", "gap_mlp"),
+                   in_hw=getattr(L, "in_hw", (0, 0)), out_hw=getattr(L, "out_hw", (0, 0)),
+                   sel_hidden=getattr(L, "sel_hidden", 0), conv_ks=getattr(L, "conv_ks", (0, 0)))
+
+    def _marshal(self, weights: dict):
+        """Host fp32 arrays of the shapes this cache was created with -> the C struct (and the
+        arrays it points into, which must outlive the call)."""
+        C_, S, H, K, pool_fc, fc_mlp, conv_fc, hidden_sel, sel_hidden, conv_ks = self._shape
         names = ("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")
         names += ("Ws", "cs", "vs") if hidden_sel else ("ws",)
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
@@ -204,17 +227,11 @@ class Cache:
         ptr = lambda k: keep[k].ctypes.data if k in keep else None
         w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]),
                          ptr("Ws"), ptr("cs"), ptr("vs"))
-        st, self.handle = gati_cache_create(desc, w)
-        _check(st, "gati_cache_create")
+        return w, keep
 
-    @classmethod
-    def from_layer(cls, L, weights: dict, max_rows: int) -> "Cache":
-        """Build from any record with the fields C, S, H, K, dtype, layout, threshold and,
-        optionally, predictor, in_hw, out_hw, selector, sel_hidden."""
-        return cls(L.C, L.S, L.H, L.K, L.dtype, L.layout, L.threshold, max_rows, weights,
-                   selector=getattr(L, "selector", "linear"), predictor=getattr(L, "predictor", "gap_mlp"),
-                   in_hw=getattr(L, "in_hw", (0, 0)), out_hw=getattr(L, "out_hw", (0, 0)),
-                   sel_hidden=getattr(L, "sel_hidden", 0), conv_ks=getattr(L, "conv_ks", (0, 0)))
+    def set_weights(self, weights: dict):
+        w, _keep = self._marshal(weights)
+        _check(gati_cache_set_weights(self.handle, w), "gati_cache_set_weights")
 
     def lookup(self, act, row_index, n_max, n_dev, pred_class, confidence, hit, logits=None, stream=None):
         _check(gati_cache_lookup(self.handle, act, row_index, n_max, n_dev, pred_class, confidence, hit,

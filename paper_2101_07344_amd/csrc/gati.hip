@@ -102,9 +102,14 @@ void free_all(gati_cache* c) {
         if (q) (void)hipFree(q);
 }
 
+// Device copy of a host array (src == NULL: zeros).  *dst == NULL allocates; otherwise the existing
+// allocation of the same size is overwritten (weight replacement).
 gati_status_t upload(void** dst, const void* src, size_t bytes) {
-    hipError_t e = hipMalloc(dst, bytes);
-    if (e != hipSuccess) { *dst = nullptr; (void)hipGetLastError(); return GATI_ERR_OOM; }
+    hipError_t e = hipSuccess;
+    if (!*dst) {
+        e = hipMalloc(dst, bytes);
+        if (e != hipSuccess) { *dst = nullptr; (void)hipGetLastError(); return GATI_ERR_OOM; }
+    }
     e = src ? hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) : hipMemset(*dst, 0, bytes);
     if (e != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
     return GATI_OK;
@@ -597,6 +602,103 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
     return hipGetLastError();
 }
 
+// Repack the host weights into the kernels' layouts and copy them to the device (allocating on
+// first use).  Everything the packing needs is already planned in *c.
+gati_status_t upload_weights(gati_cache* c, const gati_cache_weights_t* w) {
+    const gati_cache_desc_t* desc = &c->desc;
+    const bool flat_fc = c->flat_fc, conv_fc = c->conv_fc;
+    const bool pool_fc = desc->predictor == GATI_PRED_POOL_FC;
+    const bool no_hidden_kernel = c->pool_fc;
+    const bool sel_hidden = desc->selector == GATI_SEL_HIDDEN;
+    const int C = c->F, H = no_hidden_kernel ? c->F : desc->H, K = desc->K;   // C: features; H: inputs of the output FC
+    gati_status_t st = GATI_OK;
+    try {
+        // weights in MFMA fragment order, zero padded
+        if (c->bf16) {
+            std::vector<uint16_t> t1, t2;
+            if (flat_fc) {
+                const int D = desc->C * desc->S;
+                pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 16, t1, f32_to_bf16_rne);
+                st = upload(&c->W1, t1.data(), t1.size() * 2);
+            } else if (conv_fc) {
+                std::vector<float> wr, plain;
+                const int kd = conv_reorder(desc, w->W1, 16, wr);
+                pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 16, t1, f32_to_bf16_rne);
+                st = upload(&c->W1, t1.data(), t1.size() * 2);
+                plain.resize((size_t)desc->H * desc->C * desc->conv_k * desc->conv_k);
+                for (size_t q = 0; q < plain.size(); ++q) {
+                    const uint32_t bits = (uint32_t)f32_to_bf16_rne(w->W1[q]) << 16;
+                    std::memcpy(&plain[q], &bits, 4);
+                }
+                if (st == GATI_OK) st = upload((void**)&c->W1plain, plain.data(), plain.size() * 4);
+            } else if (!pool_fc) {
+                pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
+                st = upload(&c->W1, t1.data(), t1.size() * 2);
+            }
+            pack_weights(w->W2, K, H, c->Kp, c->Hp, 16, t2, f32_to_bf16_rne);
+            if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 2);
+        } else {
+            std::vector<float> t1, t2;
+            auto same = [](float x) { return x; };
+            if (flat_fc) {
+                const int D = desc->C * desc->S;
+                pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 8, t1, same);
+                st = upload(&c->W1, t1.data(), t1.size() * 4);
+            } else if (conv_fc) {
+                std::vector<float> wr;
+                const int kd = conv_reorder(desc, w->W1, 8, wr);
+                pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 8, t1, same);
+                st = upload(&c->W1, t1.data(), t1.size() * 4);
+                if (st == GATI_OK)
+                    st = upload((void**)&c->W1plain, w->W1, (size_t)desc->H * desc->C * desc->conv_k * desc->conv_k * 4);
+            } else if (!pool_fc) {
+                pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);
+                st = upload(&c->W1, t1.data(), t1.size() * 4);
+            }
+            pack_weights(w->W2, K, H, c->Kp, c->Hp, 8, t2, same);
+            if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 4);
+        }
+        std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
+        if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)desc->H * 4);   // conv_fc: one bias per filter
+        std::memcpy(b2.data(), w->b2, (size_t)K * 4);
+        if (!sel_hidden) {      // otherwise both halves stay zero: the per-tile selector sums are unused
+            std::memcpy(wp.data(), w->ws, (size_t)C * 4);
+            std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
+        }
+        if (st == GATI_OK) st = upload((void**)&c->b1, b1.data(), b1.size() * 4);
+        if (st == GATI_OK) st = upload((void**)&c->b2, b2.data(), b2.size() * 4);
+        if (st == GATI_OK) st = upload((void**)&c->ws_pool, wp.data(), wp.size() * 4);
+        if (st == GATI_OK) st = upload((void**)&c->ws_prob, wq.data(), wq.size() * 4);
+        if (sel_hidden) {
+            // first layer over operand rows [features padded to Cp ; probabilities padded to Sin - Cp]
+            c->Hs = desc->selector_hidden;
+            c->Hsp = round_up(c->Hs, 32);
+            c->Sin = c->Cp + round_up(K, 64);
+            std::vector<float> wide((size_t)c->Hs * c->Sin, 0.f), cs(c->Hsp, 0.f), vs(c->Hsp, 0.f);
+            for (int j = 0; j < c->Hs; ++j) {
+                std::memcpy(&wide[(size_t)j * c->Sin], w->Ws + (size_t)j * (C + K), (size_t)C * 4);
+                std::memcpy(&wide[(size_t)j * c->Sin + c->Cp], w->Ws + (size_t)j * (C + K) + C, (size_t)K * 4);
+            }
+            std::memcpy(cs.data(), w->cs, (size_t)c->Hs * 4);
+            std::memcpy(vs.data(), w->vs, (size_t)c->Hs * 4);
+            if (c->bf16) {
+                std::vector<uint16_t> t;
+                pack_weights(wide.data(), c->Hs, c->Sin, c->Hsp, c->Sin, 16, t, f32_to_bf16_rne);
+                if (st == GATI_OK) st = upload(&c->Ws, t.data(), t.size() * 2);
+            } else {
+                std::vector<float> t;
+                pack_weights(wide.data(), c->Hs, c->Sin, c->Hsp, c->Sin, 8, t, [](float x) { return x; });
+                if (st == GATI_OK) st = upload(&c->Ws, t.data(), t.size() * 4);
+            }
+            if (st == GATI_OK) st = upload((void**)&c->cs, cs.data(), cs.size() * 4);
+            if (st == GATI_OK) st = upload((void**)&c->vs, vs.data(), vs.size() * 4);
+        }
+    } catch (const std::bad_alloc&) {
+        st = GATI_ERR_OOM;
+    }
+    return st;
+}
+
 bool on_cache_device(const gati_cache* c) {
     int dev = -1;
     return hipGetDevice(&dev) == hipSuccess && dev == c->device;
@@ -719,92 +821,8 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         plan_pool(c);
     }
 
-    const int C = c->F, H = no_hidden_kernel ? c->F : desc->H, K = desc->K;   // C: features; H: inputs of the output FC
-    gati_status_t st = GATI_OK;
-    try {
-        // weights in MFMA fragment order, zero padded
-        if (c->bf16) {
-            std::vector<uint16_t> t1, t2;
-            if (flat_fc) {
-                const int D = desc->C * desc->S;
-                pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 16, t1, f32_to_bf16_rne);
-                st = upload(&c->W1, t1.data(), t1.size() * 2);
-            } else if (conv_fc) {
-                std::vector<float> wr, plain;
-                const int kd = conv_reorder(desc, w->W1, 16, wr);
-                pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 16, t1, f32_to_bf16_rne);
-                st = upload(&c->W1, t1.data(), t1.size() * 2);
-                plain.resize((size_t)desc->H * desc->C * desc->conv_k * desc->conv_k);
-                for (size_t q = 0; q < plain.size(); ++q) {
-                    const uint32_t bits = (uint32_t)f32_to_bf16_rne(w->W1[q]) << 16;
-                    std::memcpy(&plain[q], &bits, 4);
-                }
-                if (st == GATI_OK) st = upload((void**)&c->W1plain, plain.data(), plain.size() * 4);
-            } else if (!pool_fc) {
-                pack_weights(w->W1, H, C, c->Hp, c->Cp, 16, t1, f32_to_bf16_rne);
-                st = upload(&c->W1, t1.data(), t1.size() * 2);
-            }
-            pack_weights(w->W2, K, H, c->Kp, c->Hp, 16, t2, f32_to_bf16_rne);
-            if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 2);
-        } else {
-            std::vector<float> t1, t2;
-            auto same = [](float x) { return x; };
-            if (flat_fc) {
-                const int D = desc->C * desc->S;
-                pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 8, t1, same);
-                st = upload(&c->W1, t1.data(), t1.size() * 4);
-            } else if (conv_fc) {
-                std::vector<float> wr;
-                const int kd = conv_reorder(desc, w->W1, 8, wr);
-                pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 8, t1, same);
-                st = upload(&c->W1, t1.data(), t1.size() * 4);
-                if (st == GATI_OK)
-                    st = upload((void**)&c->W1plain, w->W1, (size_t)desc->H * desc->C * desc->conv_k * desc->conv_k * 4);
-            } else if (!pool_fc) {
-                pack_weights(w->W1, H, C, c->Hp, c->Cp, 8, t1, same);
-                st = upload(&c->W1, t1.data(), t1.size() * 4);
-            }
-            pack_weights(w->W2, K, H, c->Kp, c->Hp, 8, t2, same);
-            if (st == GATI_OK) st = upload(&c->W2, t2.data(), t2.size() * 4);
-        }
-        std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
-        if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)desc->H * 4);   // conv_fc: one bias per filter
-        std::memcpy(b2.data(), w->b2, (size_t)K * 4);
-        if (!sel_hidden) {      // otherwise both halves stay zero: the per-tile selector sums are unused
-            std::memcpy(wp.data(), w->ws, (size_t)C * 4);
-            std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
-        }
-        if (st == GATI_OK) st = upload((void**)&c->b1, b1.data(), b1.size() * 4);
-        if (st == GATI_OK) st = upload((void**)&c->b2, b2.data(), b2.size() * 4);
-        if (st == GATI_OK) st = upload((void**)&c->ws_pool, wp.data(), wp.size() * 4);
-        if (st == GATI_OK) st = upload((void**)&c->ws_prob, wq.data(), wq.size() * 4);
-        if (sel_hidden) {
-            // first layer over operand rows [features padded to Cp ; probabilities padded to Sin - Cp]
-            c->Hs = desc->selector_hidden;
-            c->Hsp = round_up(c->Hs, 32);
-            c->Sin = c->Cp + round_up(K, 64);
-            std::vector<float> wide((size_t)c->Hs * c->Sin, 0.f), cs(c->Hsp, 0.f), vs(c->Hsp, 0.f);
-            for (int j = 0; j < c->Hs; ++j) {
-                std::memcpy(&wide[(size_t)j * c->Sin], w->Ws + (size_t)j * (C + K), (size_t)C * 4);
-                std::memcpy(&wide[(size_t)j * c->Sin + c->Cp], w->Ws + (size_t)j * (C + K) + C, (size_t)K * 4);
-            }
-            std::memcpy(cs.data(), w->cs, (size_t)c->Hs * 4);
-            std::memcpy(vs.data(), w->vs, (size_t)c->Hs * 4);
-            if (c->bf16) {
-                std::vector<uint16_t> t;
-                pack_weights(wide.data(), c->Hs, c->Sin, c->Hsp, c->Sin, 16, t, f32_to_bf16_rne);
-                if (st == GATI_OK) st = upload(&c->Ws, t.data(), t.size() * 2);
-            } else {
-                std::vector<float> t;
-                pack_weights(wide.data(), c->Hs, c->Sin, c->Hsp, c->Sin, 8, t, [](float x) { return x; });
-                if (st == GATI_OK) st = upload(&c->Ws, t.data(), t.size() * 4);
-            }
-            if (st == GATI_OK) st = upload((void**)&c->cs, cs.data(), cs.size() * 4);
-            if (st == GATI_OK) st = upload((void**)&c->vs, vs.data(), vs.size() * 4);
-        }
-    } catch (const std::bad_alloc&) {
-        st = GATI_ERR_OOM;
-    }
+    const int K = desc->K;
+    gati_status_t st = upload_weights(c, w);
     // workspace, zeroed once: the padding columns of p are never written and must read as 0
     if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
     if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);
@@ -829,6 +847,24 @@ gati_status_t gati_cache_destroy(gati_cache_t* c) {
     if (!c) return GATI_OK;
     free_all(c);
     delete c;
+    return GATI_OK;
+}
+
+gati_status_t gati_cache_set_weights(gati_cache_t* c, const gati_cache_weights_t* w) {
+    if (!c || !w) return GATI_ERR_INVALID_ARG;
+    const bool pool_fc = c->desc.predictor == GATI_PRED_POOL_FC;
+    const bool sel_hidden = c->desc.selector == GATI_SEL_HIDDEN;
+    if (sel_hidden && (!w->Ws || !w->cs || !w->vs)) return GATI_ERR_INVALID_ARG;
+    if (!w->W2 || !w->b2 || (!sel_hidden && !w->ws)) return GATI_ERR_INVALID_ARG;
+    if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
+    if (!(w->bs == w->bs)) return GATI_ERR_INVALID_ARG;
+    if (!on_cache_device(c)) return GATI_ERR_DEVICE;
+    // lookups already enqueued must finish with the old weights
+    if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+    const gati_status_t st = upload_weights(c, w);
+    if (st != GATI_OK) return st;
+    c->bs = w->bs;
+    if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
     return GATI_OK;
 }
 

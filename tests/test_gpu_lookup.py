@@ -285,3 +285,62 @@ def test_hidden_layer_selector(dtype, predictor, K, Hs, want_logits):
     want_ids = oracle.compact_misses(want["hit"], ok)
     assert int(cnt.item()) == len(want_ids) and np.array_equal(ids_out.cpu().numpy()[:len(want_ids)], want_ids)
     cache.close()
+
+
+@pytest.mark.parametrize("predictor,selector", [("gap_mlp", "linear"), ("gap_mlp", "hidden"), ("pool_fc", "linear"),
+                                                ("fc_mlp", "linear"), ("conv_fc", "linear")])
+def test_set_weights_swaps_in_a_retrained_cache(predictor, selector):
+    """Weights replaced in place (the paper's periodic cache replacement) behave exactly like a cache
+    created with them, and the lookup follows the oracle before and after."""
+    n, C, hw, H, K, Hs = 48, 32, 8, 24, 11, 9
+    S = hw * hw
+    kw = dict(predictor=predictor)
+    if predictor == "pool_fc":
+        kw.update(in_hw=(hw, hw), out_hw=(2, 2))
+    if predictor == "conv_fc":
+        kw.update(in_hw=(hw, hw), conv_ks=(3, 1))
+        H = 4
+    d = oracle.CacheDef(C=C, S=S, H=0 if predictor == "pool_fc" else H, K=K, dtype="bf16", threshold=0.5, round_operands=True,
+                        selector=selector, sel_hidden=Hs if selector == "hidden" else 0, **kw)
+    F = d.F
+    rng = np.random.default_rng(len(predictor) + len(selector))
+    x = torch.from_numpy(np.maximum(rng.standard_normal((n, C, S)) + 0.3, 0).astype(np.float32)).bfloat16()
+    host = W.to_host_array(x)
+
+    def draw():
+        fan1 = {"fc_mlp": C * S, "conv_fc": C * 9}.get(predictor, C)
+        shape1 = (H, C, 3, 3) if predictor == "conv_fc" else (H, fan1)
+        Hin = F if predictor in ("pool_fc", "conv_fc") else H
+        w = {"W1": (rng.standard_normal(shape1) * np.sqrt(2 / fan1)).astype(np.float32),
+             "b1": (rng.standard_normal(H) * 0.1).astype(np.float32),
+             "W2": (rng.standard_normal((K, Hin)) * np.sqrt(2 / Hin)).astype(np.float32),
+             "b2": (rng.standard_normal(K) * 0.1).astype(np.float32),
+             "ws": (rng.standard_normal(F + K) * 2 * np.sqrt(2 / (F + K))).astype(np.float32), "bs": 0.0}
+        if selector == "hidden":
+            w.update(Ws=(rng.standard_normal((Hs, F + K)) * 4 * np.sqrt(2 / (F + K))).astype(np.float32),
+                     cs=(rng.standard_normal(Hs) * 0.1).astype(np.float32),
+                     vs=(rng.standard_normal(Hs) * np.sqrt(2 / Hs)).astype(np.float32))
+        w["bs"] = float(np.float32(-np.median(oracle.lookup(d, w, host)["score"])))
+        return w
+
+    wa, wb = draw(), draw()
+    mk = lambda w: g.Cache(C, S, d.H, K, "bf16", "ncs", 0.5, n, w, selector=selector, predictor=predictor,
+                           in_hw=kw.get("in_hw", (0, 0)), out_hw=kw.get("out_hw", (0, 0)),
+                           sel_hidden=d.sel_hidden, conv_ks=kw.get("conv_ks", (0, 0)))
+    cache, fresh_b = mk(wa), mk(wb)
+    xd = x.cuda()
+    for w_now, other in ((wa, None), (wb, fresh_b)):
+        if other is not None:
+            cache.set_weights(w_now)
+        ok = np.setdiff1d(np.arange(n), admit.inadmissible_rows(d, w_now, host)).astype(np.int32)
+        okd = torch.from_numpy(ok).cuda()
+        got = _lookup_gpu(cache, xd, okd, len(ok), None, K)
+        want = oracle.lookup(d, w_now, host, row_index=ok)
+        compare_lookup(got, want, None, "bf16", f"set_weights {predictor}/{selector}")
+        if other is not None:
+            ref = _lookup_gpu(other, xd, okd, len(ok), None, K)
+            for key in ("pred_class", "confidence", "hit", "logits"):
+                assert np.array_equal(got[key], ref[key]), key       # bit for bit the cache created with them
+    assert not np.array_equal(oracle.lookup(d, wa, host)["pred_class"], oracle.lookup(d, wb, host)["pred_class"])
+    cache.close()
+    fresh_b.close()
