@@ -56,6 +56,7 @@ def test_calls_reject_null_handles_and_bad_counts_on_the_host():
     assert g.gati_cache_lookup(None, 16, None, 4, None, 16, 16, 16, None, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_pool(None, 16, None, 4, None, 16, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_set_selector(None, 0.0, 0.5) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_cache_set_weights(None, g.CacheWeights()) == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_destroy(None) == g.GATI_OK
     assert g.gati_compact_misses(None, 16, None, -1, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_compact_misses(None, 16, None, 4, None, 16, None, stream=0) == g.GATI_ERR_INVALID_ARG
