@@ -237,6 +237,26 @@ def pool_yardstick(spec, acts, torch):
     return {"shape": list(x.shape), "library_us": round(t * 1e6, 1), "library_GBps": round(nbytes / t / 1e9, 1)}
 
 
+def time_compaction(cache, stack, batch, torch, reps=20):
+    """The stand-alone miss compaction over a full batch of layer 0's hit flags (in the stack it is
+    fused into the finish kernel and costs no launch of its own)."""
+    ids_out = torch.empty(batch, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        cache.compact(stack.hit[0], None, batch, None, ids_out, cnt)
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        cache.compact(stack.hit[0], None, batch, None, ids_out, cnt)
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ts.sort()
+    return round(ts[len(ts) // 2] * 1e3, 2)
+
+
 def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False,
                  graph=False, overlap=False, yardstick=False):
     t_build = time.perf_counter()
@@ -314,6 +334,8 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
                              "launches": v["launches"]} for k, v in by_kernel.items()},
         "layers": per_layer,
     }
+    out["head_us_per_step"] = round((ms_step - pool_total_ms) * 1e3, 1)     # FC layers, softmax, selector, finish + compaction
+    out["compact_alone_us"] = time_compaction(caches[0], stack, spec.batch, torch)
     if graph:
         out["graph_ms_per_step"] = round(time_graph(stack, acts, steps, warmup, torch), 4)
     if overlap and spec.storage == "gather":
@@ -463,7 +485,7 @@ def main():
         "pool_kernels": main_res["pool_kernels"],
         "others": others,
     }
-    for key in ("graph_ms_per_step", "overlap", "library_pool"):
+    for key in ("head_us_per_step", "compact_alone_us", "graph_ms_per_step", "overlap", "library_pool"):
         if key in main_res:
             line[key] = main_res[key]
     if args.gemm_yardstick and L0.predictor == "fc_mlp":
