@@ -1,0 +1,90 @@
+"""CPU oracle for one retraining step of a learned cache.  TEST INFRASTRUCTURE ONLY.
+
+Plain numpy in fp64, written from the paper's description of how predictor and selector are
+trained (Section 3, "Training Learned Caches") and retrained online (Section 5, "Retraining
+Learned Caches"; Section 7 parameters: learning rate 0.002, 5 epochs).  The paper gives the
+ingredients, not the formulas; the reading taken here:
+
+  predictor  global pool -> FC(C->H) -> ReLU -> FC(H->K) -> softmax q.
+             Loss "inspired by distillation ... takes into account the true labels and also the
+             distribution of class probabilities":
+                 t_i = (1 - alpha) * onehot(y_i) + alpha * Y_i        (Y = the base DNN's distribution)
+                 L_p = -(1/n) sum_i sum_k t_ik log q_ik
+  selector   ground truth G_i = [argmax_k z_ik == argmax_k Y_ik] (the paper's G); a cross-entropy
+             that "levies a higher loss penalty" on false positives (fp_weight >= 1):
+                 c_i = logistic(ws . [p_i ; q_i] + bs)
+                 L_s = -(1/n) sum_i [ G_i log c_i + fp_weight (1 - G_i) log(1 - c_i) ]
+             The selector is trained on the predictor's outputs as data: no gradient flows from L_s
+             into the predictor.
+  update     plain SGD, theta <- theta - lr * grad, both networks in the same step, the selector
+             on the predictor's outputs of BEFORE the update.
+
+Every function takes and returns fp64 arrays; `pooled` are the features the lookup oracle reports.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def forward(w: dict, pooled: np.ndarray):
+    p = np.asarray(pooled, np.float64)
+    W1, b1 = np.asarray(w["W1"], np.float64), np.asarray(w["b1"], np.float64)
+    W2, b2 = np.asarray(w["W2"], np.float64), np.asarray(w["b2"], np.float64)
+    a = p @ W1.T + b1
+    h = np.maximum(a, 0.0)
+    z = h @ W2.T + b2
+    e = np.exp(z - z.max(axis=1, keepdims=True))
+    q = e / e.sum(axis=1, keepdims=True)
+    ws = np.asarray(w["ws"], np.float64)
+    u = np.concatenate([p, q], axis=1) @ ws + float(w["bs"])
+    c = 1.0 / (1.0 + np.exp(-u))
+    return {"p": p, "a": a, "h": h, "z": z, "q": q, "u": u, "c": c}
+
+
+def targets(labels: np.ndarray, teacher: np.ndarray, alpha: float) -> np.ndarray:
+    Y = np.asarray(teacher, np.float64)
+    t = alpha * Y
+    t[np.arange(len(labels)), np.asarray(labels)] += 1.0 - alpha
+    return t
+
+
+def losses(w: dict, pooled, labels, teacher, alpha: float, fp_weight: float):
+    f = forward(w, pooled)
+    n = len(labels)
+    t = targets(labels, teacher, alpha)
+    logq = f["z"] - f["z"].max(axis=1, keepdims=True)
+    logq = logq - np.log(np.exp(logq).sum(axis=1, keepdims=True))
+    Lp = -float((t * logq).sum()) / n
+    G = (f["z"].argmax(axis=1) == np.asarray(teacher).argmax(axis=1)).astype(np.float64)
+    # log c and log(1-c) from u, stable for large |u|
+    log_c = -np.logaddexp(0.0, -f["u"])
+    log_1mc = -np.logaddexp(0.0, f["u"])
+    Ls = -float((G * log_c + fp_weight * (1.0 - G) * log_1mc).sum()) / n
+    return Lp, Ls
+
+
+def gradients(w: dict, pooled, labels, teacher, alpha: float, fp_weight: float) -> dict:
+    f = forward(w, pooled)
+    n = len(labels)
+    t = targets(labels, teacher, alpha)
+    dz = (f["q"] - t) / n
+    W2 = np.asarray(w["W2"], np.float64)
+    dW2 = dz.T @ f["h"]
+    db2 = dz.sum(axis=0)
+    dh = (dz @ W2) * (f["a"] > 0.0)
+    dW1 = dh.T @ f["p"]
+    db1 = dh.sum(axis=0)
+    G = (f["z"].argmax(axis=1) == np.asarray(teacher).argmax(axis=1)).astype(np.float64)
+    du = (G * (f["c"] - 1.0) + fp_weight * (1.0 - G) * f["c"]) / n
+    x = np.concatenate([f["p"], f["q"]], axis=1)
+    return {"W1": dW1, "b1": db1, "W2": dW2, "b2": db2, "ws": du @ x, "bs": float(du.sum())}
+
+
+def sgd_step(w: dict, pooled, labels, teacher, lr: float, alpha: float, fp_weight: float):
+    """One step on one batch.  Returns (new weights as fp64 arrays, predictor loss, selector loss),
+    the losses evaluated before the update."""
+    g = gradients(w, pooled, labels, teacher, alpha, fp_weight)
+    Lp, Ls = losses(w, pooled, labels, teacher, alpha, fp_weight)
+    new = {k: np.asarray(w[k], np.float64) - lr * g[k] for k in ("W1", "b1", "W2", "b2", "ws")}
+    new["bs"] = float(w["bs"]) - lr * g["bs"]
+    return new, Lp, Ls

@@ -1,0 +1,100 @@
+"""Pins for the retraining-step oracle (Section 3, "Training Learned Caches"; Section 5,
+"Retraining Learned Caches"): its gradients against finite differences of its own loss and against
+an automatic-differentiation library, closed forms, and the direction of a step."""
+import numpy as np
+import torch
+
+from oracle import train
+
+
+def _case(seed=0, n=9, C=5, H=4, K=3):
+    rng = np.random.default_rng(seed)
+    w = {"W1": rng.standard_normal((H, C)) * 0.7, "b1": rng.standard_normal(H) * 0.2,
+         "W2": rng.standard_normal((K, H)) * 0.7, "b2": rng.standard_normal(K) * 0.2,
+         "ws": rng.standard_normal(C + K) * 0.5, "bs": 0.3}
+    pooled = rng.standard_normal((n, C))
+    labels = rng.integers(0, K, n)
+    Y = rng.random((n, K)) + 0.05
+    Y /= Y.sum(axis=1, keepdims=True)
+    return w, pooled, labels, Y
+
+
+def test_gradients_match_finite_differences_of_the_losses():
+    w, pooled, labels, Y = _case()
+    alpha, lam = 0.3, 2.5
+    g = train.gradients(w, pooled, labels, Y, alpha, lam)
+    eps = 1e-6
+    for key, which in (("W1", 0), ("b1", 0), ("W2", 0), ("b2", 0), ("ws", 1)):
+        flat = np.asarray(w[key], np.float64)
+        for idx in list(np.ndindex(flat.shape))[:: max(1, flat.size // 7)]:
+            wp = {k: np.array(v, np.float64) if k != "bs" else v for k, v in w.items()}
+            wm = {k: np.array(v, np.float64) if k != "bs" else v for k, v in w.items()}
+            wp[key][idx] += eps
+            wm[key][idx] -= eps
+            num = (train.losses(wp, pooled, labels, Y, alpha, lam)[which] -
+                   train.losses(wm, pooled, labels, Y, alpha, lam)[which]) / (2 * eps)
+            assert abs(num - g[key][idx]) < 1e-7, (key, idx, num, g[key][idx])
+    num = (train.losses({**w, "bs": w["bs"] + eps}, pooled, labels, Y, alpha, lam)[1] -
+           train.losses({**w, "bs": w["bs"] - eps}, pooled, labels, Y, alpha, lam)[1]) / (2 * eps)
+    assert abs(num - g["bs"]) < 1e-7
+    # the selector loss depends on W2 through q, yet the step's W2 gradient is the predictor loss's alone
+    bump = np.array(w["W2"], np.float64)
+    bump[0, 0] += 1e-3
+    assert train.losses({**w, "W2": bump}, pooled, labels, Y, alpha, lam)[1] != \
+        train.losses(w, pooled, labels, Y, alpha, lam)[1]
+
+
+def test_against_automatic_differentiation():
+    w, pooled, labels, Y = _case(seed=3, n=12, C=6, H=5, K=4)
+    alpha, lam = 0.5, 3.0
+    tw = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in w.items() if k != "bs"}
+    bs = torch.tensor(float(w["bs"]), dtype=torch.float64, requires_grad=True)
+    p = torch.tensor(pooled)
+    h = torch.relu(p @ tw["W1"].T + tw["b1"])
+    z = h @ tw["W2"].T + tw["b2"]
+    logq = torch.log_softmax(z, dim=1)
+    t = torch.tensor(train.targets(labels, Y, alpha))
+    Lp = -(t * logq).sum() / len(labels)
+    q = torch.softmax(z, dim=1).detach()                       # the selector sees the outputs as data
+    u = torch.cat([p, q], dim=1) @ tw["ws"] + bs
+    G = torch.tensor((z.detach().numpy().argmax(1) == Y.argmax(1)).astype(np.float64))
+    Ls = -(G * torch.nn.functional.logsigmoid(u) + lam * (1 - G) * torch.nn.functional.logsigmoid(-u)).sum() / len(labels)
+    (Lp + Ls).backward()
+    g = train.gradients(w, pooled, labels, Y, alpha, lam)
+    for k in ("W1", "b1", "W2", "b2", "ws"):
+        assert np.max(np.abs(tw[k].grad.numpy() - g[k])) < 1e-12, k
+    assert abs(bs.grad.item() - g["bs"]) < 1e-12
+    lp, ls = train.losses(w, pooled, labels, Y, alpha, lam)
+    assert abs(lp - Lp.item()) < 1e-12 and abs(ls - Ls.item()) < 1e-12
+
+
+def test_closed_forms():
+    w, pooled, labels, Y = _case(seed=5)
+    n, K = Y.shape
+    f = train.forward(w, pooled)
+    # alpha = 0: plain cross-entropy on the labels, dz = (q - onehot) / n; db2 is its column sum
+    g = train.gradients(w, pooled, labels, Y, 0.0, 1.0)
+    one = np.eye(K)[labels]
+    assert np.allclose(g["b2"], ((f["q"] - one) / n).sum(0), atol=1e-15)
+    assert abs(g["b2"].sum()) < 1e-15                          # targets and probabilities both sum to one
+    # alpha = 1 and a teacher equal to the predictor's own distribution: the predictor is at a stationary point
+    g = train.gradients(w, pooled, labels, f["q"], 1.0, 1.0)
+    assert max(np.max(np.abs(g[k])) for k in ("W1", "b1", "W2", "b2")) < 1e-15
+    # fp_weight = 1: ordinary logistic regression on G; a larger weight scales exactly the G = 0 rows
+    G = (f["z"].argmax(1) == Y.argmax(1)).astype(float)
+    g1 = train.gradients(w, pooled, labels, Y, 0.3, 1.0)
+    g4 = train.gradients(w, pooled, labels, Y, 0.3, 4.0)
+    assert abs(g1["bs"] - ((f["c"] - G) / n).sum()) < 1e-15
+    assert abs((g4["bs"] - g1["bs"]) - 3.0 * (((1 - G) * f["c"]) / n).sum()) < 1e-15
+    assert 0 < G.sum() < n
+
+
+def test_a_step_goes_downhill_and_zero_rate_is_the_identity():
+    w, pooled, labels, Y = _case(seed=8, n=40, C=8, H=6, K=5)
+    new, lp, ls = train.sgd_step(w, pooled, labels, Y, 0.0, 0.3, 2.0)
+    assert all(np.array_equal(new[k], np.asarray(w[k], np.float64)) for k in ("W1", "b1", "W2", "b2", "ws"))
+    cur = w
+    for _ in range(5):                                          # the paper retrains for 5 epochs
+        cur, lp1, ls1 = train.sgd_step(cur, pooled, labels, Y, 0.05, 0.3, 2.0)
+    lp2 = train.losses(cur, pooled, labels, Y, 0.3, 2.0)[0]
+    assert lp2 < lp and lp1 < lp
