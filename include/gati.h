@@ -26,7 +26,7 @@
  * current when the cache was created; "host" pointers are ordinary host memory.  The
  * library never frees or keeps caller buffers.  Every call that takes a stream only
  * enqueues work on it and returns; nothing synchronises the device and nothing is
- * allocated after gati_cache_create.  No function throws or aborts: errors come back
+ * allocated after gati_cache_create (gati_trainer_create).  No function throws or aborts: errors come back
  * as a gati_status_t and leave the outputs untouched (argument errors are detected on
  * the host before anything is launched).
  */
@@ -139,7 +139,7 @@ gati_status_t gati_cache_destroy(gati_cache_t *cache);
 
 /* Replace every weight of an existing cache with a new set of the same shapes (Section 5,
  * "Retraining Learned Caches": the adaptation service periodically retrains predictor and
- * selector and swaps them in; the retraining itself is not part of this library).  Host fp32
+ * selector and swaps them in; gati_trainer_* below runs the retraining steps).  Host fp32
  * arrays as for gati_cache_create; repacked and copied before the call returns.  The call
  * waits for all work on the device first, so lookups enqueued earlier use the old weights and
  * lookups issued afterwards the new ones; no allocation takes place.  The threshold is kept. */
@@ -209,6 +209,62 @@ const char *gati_status_string(gati_status_t status);
  * "ncs_seg", "nsc_row", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat", "conv_mfma",
  * "conv_generic"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
+
+/* ---------------------------------------------------------------------------------------------
+ * Retraining (Section 3, "Training Learned Caches"; Section 5, "Retraining Learned Caches":
+ * predictor and selector are retrained periodically on recently served inputs, for which the
+ * base DNN's output is known, and the new weights replace the old ones).  A trainer holds fp32
+ * master weights on the device and runs SGD steps on them; gati_trainer_get_weights +
+ * gati_cache_set_weights move the result into a serving cache.
+ *
+ * One step on a batch of n samples, all arithmetic in fp32:
+ *   p        pooled features of the sample (what gati_cache_pool writes)
+ *   h        = relu(W1 p + b1),  z = W2 h + b2,  q = softmax(z)
+ *   target   t = (1 - alpha) onehot(label) + alpha Y          Y: the base DNN's class distribution
+ *   L_pred   = -(1/n) sum_i sum_k t_ik log q_ik               (the paper's distillation-inspired loss:
+ *                                                               true labels and the class distribution)
+ *   G_i      = [argmax_k z_ik == argmax_k Y_ik], lowest index on ties   (selector ground truth)
+ *   c_i      = 1/(1 + exp(-(ws . [p_i ; q_i] + bs)))
+ *   L_sel    = -(1/n) sum_i [ G_i log c_i + fp_weight (1 - G_i) log(1 - c_i) ]
+ *                                                              (false positives cost fp_weight times more)
+ *   every weight theta <- theta - lr dL/dtheta, with L_pred for W1, b1, W2, b2 and L_sel for ws, bs;
+ *   the selector sees q as data (L_sel has no gradient into the predictor), and uses the q and
+ *   the G of before the update.
+ * Only GATI_PRED_GAP_MLP with GATI_SEL_LINEAR is supported (GATI_ERR_UNSUPPORTED otherwise);
+ * act_dtype, layout, S and threshold of the descriptor are ignored.                               */
+typedef struct gati_trainer gati_trainer_t; /* opaque, owned by the library */
+
+typedef struct {
+    float lr;        /* learning rate, >= 0 (Section 7 uses 0.002)          */
+    float alpha;     /* weight of the base DNN's distribution in the target, in [0, 1] */
+    float fp_weight; /* penalty factor of selector false positives, >= 0   */
+} gati_train_params_t;
+
+/* Build a trainer on the current HIP device from host fp32 weights (as for gati_cache_create)
+ * with a workspace for desc->max_rows samples per step.  *out is set only on GATI_OK. */
+gati_status_t gati_trainer_create(const gati_cache_desc_t *desc, const gati_cache_weights_t *weights,
+                                  gati_trainer_t **out);
+
+/* Free everything the trainer owns; the caller has synchronised its work.  NULL is GATI_OK. */
+gati_status_t gati_trainer_destroy(gati_trainer_t *trainer);
+
+/* Enqueue one SGD step on `stream`.
+ *   pooled      device [n, ld_pooled] fp32, ld_pooled >= C: row i holds sample i's C pooled features
+ *   n           host count, 0 <= n <= max_rows (0: nothing happens)
+ *   labels      device [n] int32 true class, in [0, K)
+ *   teacher     device [n, ld_teacher] fp32, ld_teacher >= K: the base DNN's class probabilities
+ *   losses      device [2] fp32 or NULL: L_pred and L_sel of the batch under the weights of
+ *               BEFORE the update
+ * Nothing is allocated and nothing synchronises.  Steps on one trainer must not overlap in time
+ * (they share its workspace); results do not depend on anything but the arguments. */
+gati_status_t gati_trainer_step(gati_trainer_t *trainer, const float *pooled, int32_t ld_pooled, int32_t n,
+                                const int32_t *labels, const float *teacher, int32_t ld_teacher,
+                                const gati_train_params_t *params, float *losses, void *stream);
+
+/* Copy the current weights to HOST arrays W1 [H, C], b1 [H], W2 [K, H], b2 [K], ws [C + K] and
+ * *bs, after waiting for all work on the device. */
+gati_status_t gati_trainer_get_weights(gati_trainer_t *trainer, float *W1, float *b1, float *W2, float *b2,
+                                       float *ws, float *bs);
 
 #ifdef __cplusplus
 }

@@ -20,6 +20,7 @@ GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC, GATI_PRED_FC_MLP, GATI_PRED_CONV_FC = 0, 1
 exported_symbols = (
     "gati_cache_create", "gati_cache_destroy", "gati_cache_set_weights", "gati_cache_set_selector", "gati_cache_lookup",
     "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_status_string", "gati_cache_pool_variant",
+    "gati_trainer_create", "gati_trainer_destroy", "gati_trainer_step", "gati_trainer_get_weights",
 )
 
 
@@ -35,6 +36,10 @@ class CacheWeights(C.Structure):
     _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
                 ("ws", C.c_void_p), ("bs", C.c_float),
                 ("Ws", C.c_void_p), ("cs", C.c_void_p), ("vs", C.c_void_p)]
+
+
+class TrainParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("alpha", C.c_float), ("fp_weight", C.c_float)]
 
 
 class GatiError(RuntimeError):
@@ -85,6 +90,14 @@ def load_library():
     lib.gati_status_string.argtypes = [C.c_int]
     lib.gati_cache_pool_variant.restype = C.c_char_p
     lib.gati_cache_pool_variant.argtypes = [vp]
+    lib.gati_trainer_create.restype = C.c_int
+    lib.gati_trainer_create.argtypes = [C.POINTER(CacheDesc), C.POINTER(CacheWeights), C.POINTER(vp)]
+    lib.gati_trainer_destroy.restype = C.c_int
+    lib.gati_trainer_destroy.argtypes = [vp]
+    lib.gati_trainer_step.restype = C.c_int
+    lib.gati_trainer_step.argtypes = [vp, vp, i32, i32, vp, vp, i32, C.POINTER(TrainParams), vp, vp]
+    lib.gati_trainer_get_weights.restype = C.c_int
+    lib.gati_trainer_get_weights.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -261,6 +274,74 @@ class Cache:
     def close(self):
         if getattr(self, "handle", None):
             gati_cache_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gati_trainer_create(desc: CacheDesc, weights: CacheWeights):
+    """Returns (status, handle)."""
+    h = C.c_void_p()
+    st = load_library().gati_trainer_create(C.byref(desc) if desc is not None else None,
+                                            C.byref(weights) if weights is not None else None, C.byref(h))
+    return st, h.value
+
+
+def gati_trainer_destroy(handle) -> int:
+    return load_library().gati_trainer_destroy(handle)
+
+
+def gati_trainer_step(handle, pooled, ld_pooled, n, labels, teacher, ld_teacher, params, losses=None, stream=None) -> int:
+    return load_library().gati_trainer_step(handle, _dptr(pooled), ld_pooled, n, _dptr(labels), _dptr(teacher),
+                                            ld_teacher, C.byref(params) if params is not None else None,
+                                            _dptr(losses), _stream(stream))
+
+
+def gati_trainer_get_weights(handle, W1, b1, W2, b2, ws, bs) -> int:
+    """Host numpy fp32 arrays (bs: a 1-element array) filled in place."""
+    a = lambda x: x.ctypes.data if x is not None else None
+    return load_library().gati_trainer_get_weights(handle, a(W1), a(b1), a(W2), a(b2), a(ws), a(bs))
+
+
+class Trainer:
+    """SGD steps on one cache's predictor and selector (pooling predictor, linear selector)."""
+
+    def __init__(self, C_: int, H: int, K: int, weights: dict, max_rows: int):
+        keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in ("W1", "b1", "W2", "b2", "ws")}
+        assert keep["W1"].shape == (H, C_) and keep["b1"].shape == (H,) and keep["W2"].shape == (K, H)
+        assert keep["b2"].shape == (K,) and keep["ws"].shape == (C_ + K,)
+        desc = CacheDesc(C_, 1, H, K, GATI_F32, GATI_LAYOUT_NCS, 0.5, max_rows, GATI_SEL_LINEAR, GATI_PRED_GAP_MLP,
+                         0, 0, 0, 0, 0, 0, 0)
+        w = CacheWeights(*(keep[k].ctypes.data for k in ("W1", "b1", "W2", "b2", "ws")), float(weights["bs"]),
+                         None, None, None)
+        st, self.handle = gati_trainer_create(desc, w)
+        _check(st, "gati_trainer_create")
+        self.C, self.H, self.K, self.max_rows = C_, H, K, max_rows
+
+    def step(self, pooled, labels, teacher, lr: float, alpha: float, fp_weight: float, losses=None, stream=None,
+             n: Optional[int] = None):
+        """pooled [n, >=C] fp32, labels [n] int32, teacher [n, >=K] fp32: device tensors."""
+        n = pooled.shape[0] if n is None else n
+        _check(gati_trainer_step(self.handle, pooled, pooled.stride(0), n, labels, teacher, teacher.stride(0),
+                                 TrainParams(lr, alpha, fp_weight), losses, stream), "gati_trainer_step")
+
+    def get_weights(self) -> dict:
+        out = {"W1": np.empty((self.H, self.C), np.float32), "b1": np.empty(self.H, np.float32),
+               "W2": np.empty((self.K, self.H), np.float32), "b2": np.empty(self.K, np.float32),
+               "ws": np.empty(self.C + self.K, np.float32)}
+        bs = np.empty(1, np.float32)
+        _check(gati_trainer_get_weights(self.handle, out["W1"], out["b1"], out["W2"], out["b2"], out["ws"], bs),
+               "gati_trainer_get_weights")
+        out["bs"] = float(bs[0])
+        return out
+
+    def close(self):
+        if getattr(self, "handle", None):
+            gati_trainer_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

@@ -63,3 +63,20 @@ def test_calls_reject_null_handles_and_bad_counts_on_the_host():
     assert g.gati_compact_misses(None, None, None, 4, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_compact_misses(None, 16, 32, 4, None, 32, 16, stream=0) == g.GATI_ERR_INVALID_ARG   # in/out alias
     assert g.gati_cache_pool_variant(None) == "none"
+
+
+def test_trainer_calls_reject_bad_arguments_on_the_host():
+    keep, w = _weights(4, 4, 4)
+    good = dict(C=4, S=4, H=4, K=4, act_dtype=g.GATI_F32, layout=g.GATI_LAYOUT_NCS, threshold=0.5, max_rows=8)
+    assert g.gati_trainer_create(None, w)[0] == g.GATI_ERR_INVALID_ARG
+    assert g.gati_trainer_create(g.CacheDesc(**good), None)[0] == g.GATI_ERR_INVALID_ARG
+    for key, bad in (("C", 0), ("H", 0), ("K", -2), ("max_rows", 0)):
+        st, h = g.gati_trainer_create(g.CacheDesc(**{**good, key: bad}), w)
+        assert st == g.GATI_ERR_INVALID_ARG and h is None, key
+    # only the pooling predictor with the linear selector can be trained
+    for key, other in (("predictor", g.GATI_PRED_FC_MLP), ("selector", g.GATI_SEL_SOFTMAX)):
+        assert g.gati_trainer_create(g.CacheDesc(**{**good, key: other}), w)[0] == g.GATI_ERR_UNSUPPORTED, key
+    p = g.TrainParams(0.002, 0.5, 2.0)
+    assert g.gati_trainer_step(None, 16, 4, 4, 16, 16, 4, p, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_trainer_get_weights(None, *(keep + [np.zeros(1, np.float32)])) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_trainer_destroy(None) == g.GATI_OK

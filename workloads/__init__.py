@@ -10,6 +10,7 @@ sides can be fed from it without sharing any of the method's code.
 from .spec import LayerSpec, WorkloadSpec, WORKLOADS, get_workload  # noqa: F401
 from .synth import (  # noqa: F401
     zipf_labels,
+    teacher_distribution,
     class_directions,
     cache_weights,
     activation_rows,

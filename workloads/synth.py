@@ -14,7 +14,7 @@ import torch
 
 from .spec import LayerSpec, WorkloadSpec
 
-_TAG_LABELS, _TAG_DIRS, _TAG_WEIGHTS, _TAG_ROW, _TAG_BULK, _TAG_SELECTOR = 1, 2, 3, 4, 5, 6
+_TAG_LABELS, _TAG_DIRS, _TAG_WEIGHTS, _TAG_ROW, _TAG_BULK, _TAG_SELECTOR, _TAG_TEACHER = 1, 2, 3, 4, 5, 6, 7
 
 
 def _rng(seed: int, *key: int) -> np.random.Generator:
@@ -34,6 +34,23 @@ def zipf_labels(batch: int, K: int, s: float, seed: int) -> np.ndarray:
     cdf[-1] = 1.0
     u = _rng(seed, _TAG_LABELS).random(batch)
     return np.searchsorted(cdf, u, side="right").astype(np.int32).clip(0, K - 1)
+
+
+def teacher_distribution(labels: np.ndarray, K: int, seed: int, accuracy: float = 0.9,
+                         peak: float = 0.8) -> np.ndarray:
+    """[n, K] float32 rows on the simplex standing in for the base DNN's output on requests whose
+    true classes are `labels`: mass `peak` on the base model's answer (the true class with
+    probability `accuracy`, else another class drawn uniformly), the rest spread by a seeded
+    Dirichlet draw."""
+    n = len(labels)
+    rng = _rng(seed, _TAG_TEACHER)
+    wrong = rng.random(n) >= accuracy
+    other = (np.asarray(labels) + 1 + rng.integers(0, max(K - 1, 1), n)) % K
+    answer = np.where(wrong, other, labels)
+    Y = rng.dirichlet(np.full(K, 0.3), size=n) * (1.0 - peak)
+    Y[np.arange(n), answer] += peak
+    Y = Y.astype(np.float32)
+    return Y / Y.sum(axis=1, keepdims=True, dtype=np.float32)
 
 
 def class_directions(spec: WorkloadSpec, layer: int) -> np.ndarray:
