@@ -258,7 +258,7 @@ def time_compaction(cache, stack, batch, torch, reps=20):
 
 
 def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False,
-                 graph=False, overlap=False, yardstick=False):
+                 graph=False, overlap=False, yardstick=False, train=False):
     t_build = time.perf_counter()
     spec, labels, weights, caches, stack, acts = build_workload(name, torch, g, W)
     if copy_probe:
@@ -344,6 +344,8 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
         out["cpu_baseline"] = cpu_baseline(spec, weights, acts, stack, counts, cpu_requests, torch, W)
     if yardstick and spec.layers[0].predictor == "gap_mlp" and spec.storage == "gather":
         out["library_pool"] = pool_yardstick(spec, acts, torch)
+    if train:
+        out["train_step"] = time_training(spec, weights, caches, acts, torch, g, W, with_cpu)
     stack.close()
     del acts
     torch.cuda.empty_cache()
@@ -413,6 +415,46 @@ def conv_yardstick(spec, layers, torch):
     return out
 
 
+def time_training(spec, weights, caches, acts, torch, g, W, with_cpu, reps=10):
+    """One retraining step (Section 5, "Retraining Learned Caches") per distinct cache shape of the
+    workload, on a full batch: pooled features from the cache's own pooling kernel, then
+    gati_trainer_step.  Context beside the lookup metric, not part of it."""
+    n = spec.batch
+    labels = W.zipf_labels(n, spec.layers[0].K, spec.zipf_s, spec.seed)
+    Y = W.teacher_distribution(labels, spec.layers[0].K, spec.seed)
+    lab_d, Y_d = torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda()
+    out, seen = [], set()
+    for l, L in enumerate(spec.layers):
+        if L.C in seen or L.predictor != "gap_mlp" or L.selector != "linear":
+            continue
+        seen.add(L.C)
+        pooled = torch.empty((n, L.C), device="cuda")
+        caches[l].pool(acts[l], None, n, None, pooled)
+        tr = g.Trainer(L.C, L.H, L.K, weights[l], max_rows=n)
+        losses = torch.zeros(2, device="cuda")
+        for _ in range(3):
+            tr.step(pooled, lab_d, Y_d, 0.002, 0.5, 2.0, losses)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(reps):
+            tr.step(pooled, lab_d, Y_d, 0.002, 0.5, 2.0, losses)
+        ev[1].record()
+        torch.cuda.synchronize()
+        us = ev[0].elapsed_time(ev[1]) / reps * 1e3
+        flops = 2 * n * (L.C * L.H + L.H * L.K) + 2 * n * L.H * L.K + 2 * n * (L.K * L.H + L.H * L.C)
+        row = {"layer": l, "C": L.C, "H": L.H, "K": L.K, "n": n, "step_us": round(us, 1),
+               "TFLOPs": round(flops / (us * 1e-6) / 1e12, 2), "frac_of_fp32_mfma_peak": round(flops / (us * 1e-6) / 1e12 / 157.3, 4)}
+        if with_cpu and len(out) == 0:            # CPU baseline leg: the fp64 oracle's step on the same batch
+            from oracle import train as otrain
+            p_host = pooled.cpu().numpy()
+            t0 = time.perf_counter()
+            otrain.sgd_step(weights[l], p_host, labels, Y, 0.002, 0.5, 2.0)
+            row["oracle_cpu_ms"] = round((time.perf_counter() - t0) * 1e3, 1)
+        out.append(row)
+        tr.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -437,6 +479,8 @@ def main():
                          "[n, D] x [D, H] and on a square 8192^3 product; conv_fc workloads time the vendor convolution "
                          "(torch conv2d + relu) on one layer of every map size; global-pool workloads time torch's mean "
                          "over the pooled axis of layer 0's tensor")
+    ap.add_argument("--train", action="store_true",
+                    help="also time one retraining step (gati_trainer_step, full batch) per distinct cache shape")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -458,7 +502,8 @@ def main():
     with torch.cuda.stream(stream):
         spec, main_res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
                                       args.cpu_requests, torch, g, W, copy_probe=args.copy_probe,
-                                      graph=args.graph, overlap=args.overlap, yardstick=args.gemm_yardstick)
+                                      graph=args.graph, overlap=args.overlap, yardstick=args.gemm_yardstick,
+                                      train=args.train)
         others = {}
         for name in [n for n in args.also.split(",") if n and n != args.workload]:
             _, r = run_workload(name, args.steps, args.warmup, False, 0, torch, g, W)
@@ -485,7 +530,7 @@ def main():
         "pool_kernels": main_res["pool_kernels"],
         "others": others,
     }
-    for key in ("head_us_per_step", "compact_alone_us", "graph_ms_per_step", "overlap", "library_pool"):
+    for key in ("head_us_per_step", "compact_alone_us", "graph_ms_per_step", "overlap", "library_pool", "train_step"):
         if key in main_res:
             line[key] = main_res[key]
     if args.gemm_yardstick and L0.predictor == "fc_mlp":

@@ -159,7 +159,11 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
         a.z = t->z; a.q = t->q; a.p = pooled; a.ldp = ld_pooled; a.labels = labels; a.Y = teacher; a.ldy = ld_teacher;
         a.ws = t->ws; a.bs = t->bs; a.n = n; a.C = C; a.K = K; a.alpha = params->alpha; a.fp_weight = params->fp_weight;
         a.du = t->du; a.lp = t->lp; a.ls = t->ls;
-        train_row_kernel<<<(n + 3) / 4, 256, 0, st>>>(a);
+        const int blocks = (n + 3) / 4;
+        if (K <= 64) train_row_kernel<1><<<blocks, 256, 0, st>>>(a);
+        else if (K <= 256) train_row_kernel<4><<<blocks, 256, 0, st>>>(a);
+        else if (K <= 1024) train_row_kernel<16><<<blocks, 256, 0, st>>>(a);
+        else train_row_kernel<0><<<blocks, 256, 0, st>>>(a);
         if ((e = hipGetLastError()) != hipSuccess) goto fail;
     }
     // dh = (dz W2) where h > 0      (uses W2 before its update)
@@ -175,10 +179,17 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
     g.out = t->W1; g.ldo = C; g.lr = lr;
     if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
     // biases and selector
-    train_colsum_kernel<<<(K + 63) / 64, 256, 0, st>>>(t->z, K, n, K, nullptr, t->b2, lr);
-    train_colsum_kernel<<<(H + 63) / 64, 256, 0, st>>>(t->dh, H, n, H, nullptr, t->b1, lr);
-    train_colsum_kernel<<<(C + 63) / 64, 256, 0, st>>>(pooled, ld_pooled, n, C, t->du, t->ws, lr);
-    train_colsum_kernel<<<(K + 63) / 64, 256, 0, st>>>(t->q, K, n, K, t->du, t->ws + C, lr);
+    {
+        ColsumArgs c;
+        c.n = n; c.lr = lr;
+        c.job[0] = ColsumJob{t->z, K, K, nullptr, t->b2, 0};
+        c.job[1] = ColsumJob{t->dh, H, H, nullptr, t->b1, 0};
+        c.job[2] = ColsumJob{pooled, ld_pooled, C, t->du, t->ws, 0};
+        c.job[3] = ColsumJob{t->q, K, K, t->du, t->ws + C, 0};
+        int blocks = 0;
+        for (int j = 0; j < 4; ++j) { c.job[j].first_block = blocks; blocks += (c.job[j].cols + 63) / 64; }
+        train_colsums_kernel<<<blocks, 1024, 0, st>>>(c);
+    }
     train_scalar_kernel<<<1, 256, 0, st>>>(t->du, t->lp, t->ls, n, lr, t->bs, losses);
     if ((e = hipGetLastError()) != hipSuccess) goto fail;
     return GATI_OK;

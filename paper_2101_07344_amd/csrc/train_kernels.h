@@ -190,6 +190,9 @@ __device__ __forceinline__ void wave_argmax(float& v, int& i) {
 // log(1 + exp(x)) without overflow.
 __device__ __forceinline__ float softplus(float x) { return fmaxf(x, 0.0f) + log1pf(expf(-fabsf(x))); }
 
+// NK > 0: the row's logits and teacher probabilities stay in registers (K <= 64*NK), so global
+// memory is read once; NK == 0: any K, the row is re-read from memory in each pass.
+template <int NK>
 __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -198,34 +201,61 @@ __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
     float* q = a.q + (size_t)row * a.K;
     const float* Y = a.Y + (size_t)row * a.ldy;
     const float* p = a.p + (size_t)row * a.ldp;
+    constexpr int R = NK > 0 ? NK : 1;
+    float zr[R], yr[R];
+    const int chunks = NK > 0 ? NK : (a.K + 63) / 64;
+
+    if constexpr (NK > 0) {
+#pragma unroll
+        for (int j = 0; j < NK; ++j) {
+            const int k = lane + 64 * j;
+            zr[j] = k < a.K ? z[k] : -INFINITY;
+            yr[j] = k < a.K ? Y[k] : -INFINITY;
+        }
+    }
+    // the selector's feature half does not depend on the softmax: issue its loads early
+    float u = 0.0f;
+    for (int c = lane; c < a.C; c += 64) u += a.ws[c] * p[c];
 
     float zm = -INFINITY, ym = -INFINITY;
     int zi = 0x7fffffff, yi = 0x7fffffff;
-    for (int k = lane; k < a.K; k += 64) {
-        const float zv = z[k], yv = Y[k];
-        if (zv > zm) { zm = zv; zi = k; }
-        if (yv > ym) { ym = yv; yi = k; }
+#pragma unroll
+    for (int j = 0; j < chunks; ++j) {
+        const int k = lane + 64 * j;
+        if (k < a.K) {
+            const float zv = NK > 0 ? zr[NK > 0 ? j : 0] : z[k], yv = NK > 0 ? yr[NK > 0 ? j : 0] : Y[k];
+            if (zv > zm) { zm = zv; zi = k; }
+            if (yv > ym) { ym = yv; yi = k; }
+        }
     }
     wave_argmax(zm, zi);
     wave_argmax(ym, yi);
 
     float se = 0.0f;
-    for (int k = lane; k < a.K; k += 64) se += expf(z[k] - zm);
+#pragma unroll
+    for (int j = 0; j < chunks; ++j) {
+        const int k = lane + 64 * j;
+        if (k < a.K) se += expf((NK > 0 ? zr[NK > 0 ? j : 0] : z[k]) - zm);
+    }
     se = wave_sum(se);
     const float log_se = logf(se), inv_se = 1.0f / se, inv_n = 1.0f / (float)a.n;
 
     const int label = a.labels[row];
-    float lp = 0.0f, u = 0.0f;
-    for (int k = lane; k < a.K; k += 64) {
-        const float zc = z[k] - zm;
-        const float qk = expf(zc) * inv_se;
-        const float tk = a.alpha * Y[k] + (k == label ? 1.0f - a.alpha : 0.0f);
-        lp -= tk * (zc - log_se);
-        u += a.ws[a.C + k] * qk;
-        q[k] = qk;
-        z[k] = (qk - tk) * inv_n;
+    float lp = 0.0f;
+#pragma unroll
+    for (int j = 0; j < chunks; ++j) {
+        const int k = lane + 64 * j;
+        if (k < a.K) {
+            const float zc = (NK > 0 ? zr[NK > 0 ? j : 0] : z[k]) - zm;
+            const float yv = NK > 0 ? yr[NK > 0 ? j : 0] : Y[k];
+            const float qk = expf(zc) * inv_se;
+            const float tk = a.alpha * yv + (k == label ? 1.0f - a.alpha : 0.0f);
+            lp -= tk * (zc - log_se);
+            u += a.ws[a.C + k] * qk;
+            q[k] = qk;
+            z[k] = (qk - tk) * inv_n;
+        }
     }
-    for (int c = lane; c < a.C; c += 64) u += a.ws[c] * p[c];
     lp = wave_sum(lp);
     u = wave_sum(u) + *a.bs;
     if (lane == 0) {
@@ -237,19 +267,45 @@ __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
     }
 }
 
-// out[c] -= lr * sum_i scale_i X[i][c] (scale null: 1): bias gradients and the selector's weight
-// gradient.  64 columns per workgroup, rows dealt round-robin to the 4 waves, fixed order.
-__global__ __launch_bounds__(256) void train_colsum_kernel(const float* __restrict__ X, int ld, int n, int cols,
-                                                           const float* __restrict__ scale, float* out, float lr) {
-    __shared__ float part[4][64];
+// out[c] -= lr * sum_i scale_i X[i][c] (scale null: 1): the two bias gradients and the two halves
+// of the selector's weight gradient, all in one launch.  A workgroup of 16 waves owns 64 columns of
+// one job; rows are dealt round-robin to the waves, four independent partial sums per thread, and
+// the partials are added in a fixed order.
+struct ColsumJob {
+    const float* X; int ld; int cols;
+    const float* scale;
+    float* out;
+    int first_block;     // this job's first workgroup in the launch
+};
+struct ColsumArgs { ColsumJob job[4]; int n; float lr; };
+
+__global__ __launch_bounds__(1024) void train_colsums_kernel(ColsumArgs a) {
+    __shared__ float part[16][64];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + lane;
-    float acc = 0.0f;
-    if (c < cols)
-        for (int i = w; i < n; i += 4) acc += (scale ? scale[i] : 1.0f) * X[(size_t)i * ld + c];
-    part[w][lane] = acc;
+    int j = 0;
+#pragma unroll
+    for (int t = 1; t < 4; ++t)
+        if ((int)blockIdx.x >= a.job[t].first_block) j = t;
+    const ColsumJob job = a.job[j];
+    const int c = (blockIdx.x - job.first_block) * 64 + lane;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (c < job.cols) {
+        for (int i0 = w; i0 < a.n; i0 += 64) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = i0 + 16 * r;
+                if (i < a.n) acc[r] += (job.scale ? job.scale[i] : 1.0f) * job.X[(size_t)i * job.ld + c];
+            }
+        }
+    }
+    part[w][lane] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     __syncthreads();
-    if (w == 0 && c < cols) out[c] -= lr * ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]));
+    if (w == 0 && c < job.cols) {
+        float s = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) s += part[t][lane];
+        job.out[c] -= a.lr * s;
+    }
 }
 
 // bs -= lr * sum du; losses = (sum lp / n, sum ls / n).  One workgroup.
