@@ -329,6 +329,19 @@ class Trainer:
         _check(gati_trainer_step(self.handle, pooled, pooled.stride(0), n, labels, teacher, teacher.stride(0),
                                  TrainParams(lr, alpha, fp_weight), losses, stream), "gati_trainer_step")
 
+    def fit(self, pooled, labels, teacher, epochs: int, batch_size: int, lr: float, alpha: float, fp_weight: float,
+            losses=None, stream=None):
+        """Mini-batch SGD in storage order: `epochs` sweeps over the samples in batches of `batch_size`
+        (the last one may be shorter); the paper retrains for 5 epochs (Section 7).  losses: optional
+        device [epochs, batches, 2] tensor receiving every step's two losses.  Only enqueues."""
+        n = pooled.shape[0]
+        assert 0 < batch_size <= self.max_rows
+        for e in range(epochs):
+            for b, lo in enumerate(range(0, n, batch_size)):
+                hi = min(n, lo + batch_size)
+                self.step(pooled[lo:hi], labels[lo:hi], teacher[lo:hi], lr, alpha, fp_weight,
+                          None if losses is None else losses[e, b], stream)
+
     def get_weights(self) -> dict:
         out = {"W1": np.empty((self.H, self.C), np.float32), "b1": np.empty(self.H, np.float32),
                "W2": np.empty((self.K, self.H), np.float32), "b2": np.empty(self.K, np.float32),

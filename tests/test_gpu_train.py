@@ -126,6 +126,29 @@ def test_five_steps_then_serve(name, layer, n):
     tr.close(); cache.close()
 
 
+def test_minibatch_epochs():
+    """Two epochs over 150 samples in batches of 64 (64 + 64 + 22): sliced inputs, ragged last batch."""
+    lr, alpha, lam = 0.01, 0.4, 2.0
+    spec, L, labels, w, act, Y, pooled_ref = _inputs("resnet18", 5, 150)
+    cache, pooled = _gpu_pooled(L, w, act, 150)
+    tr = g.Trainer(L.C, L.H, L.K, w, max_rows=64)
+    losses = torch.zeros((2, 3, 2), device="cuda")
+    tr.fit(pooled, torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda(), 2, 64, lr, alpha, lam, losses)
+    cur, want, gmax = w, [], None
+    for e in range(2):
+        for lo in range(0, 150, 64):
+            sl = slice(lo, min(150, lo + 64))
+            assert _margin_ok(cur, pooled_ref[sl], Y[sl])
+            grads = train.gradients(cur, pooled_ref[sl], labels[sl], Y[sl], alpha, lam)
+            gmax = grads if gmax is None else {k: np.maximum(np.abs(gmax[k]), np.abs(grads[k])) for k in grads}
+            cur, lp, ls = train.sgd_step(cur, pooled_ref[sl], labels[sl], Y[sl], lr, alpha, lam)
+            want.append((lp, ls))
+    torch.cuda.synchronize()
+    _check_update(tr.get_weights(), cur, w, gmax, lr, steps=6, where="minibatch epochs")
+    assert np.allclose(losses.cpu().numpy().reshape(6, 2), np.array(want), rtol=2e-5, atol=1e-6)
+    tr.close(); cache.close()
+
+
 def test_step_argument_checks_and_empty_batch():
     spec, L, labels, w, act, Y, pooled_ref = _inputs("tiny", 0, 8)
     tr = g.Trainer(L.C, L.H, L.K, w, max_rows=8)
