@@ -74,6 +74,7 @@ struct gati_cache {
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
     int nsc_lpt = 1, cb_per_row = 0;              // nsc_row (4 waves per workgroup; 16 measured no faster)
+    AdaptiveWindow* ad_win = nullptr;   // ncs_adaptive: [gt * out_h * out_w] window table
     int ad_j = 4, ad_tpo_log2 = 0, ad_ww = 0, ad_pair = 0;   // ncs_adaptive (tile in gt / tiles_per_row; common window width or 0; LDS read mode)
     int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
     // head plan: column tiles per workgroup of the output layer
@@ -97,7 +98,8 @@ namespace {
 
 void free_all(gati_cache* c) {
     void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats,
-                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf, c->W1plain, c->conv_partial};
+                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf, c->W1plain, c->conv_partial,
+                    c->ad_win};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
 }
@@ -256,7 +258,7 @@ void plan_pool(gati_cache* c) {
                 c->ad_pair = 0;
                 if (c->bf16 && c->ad_ww == 14 && c->desc.in_w % 2 == 0 && S % 2 == 0 && c->desc.in_w % c->desc.out_w == 0)
                     c->ad_pair = 1;
-                else if (c->bf16 && c->ad_ww == 4)
+                else if (c->bf16 && c->ad_ww > 0)
                     c->ad_pair = 2;
                 c->variant = POOL_NCS_ADAPTIVE;
             }
@@ -445,7 +447,7 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
     case POOL_ADAPTIVE_GENERIC: {
         AdaptiveArgs g;
         g.in_h = c->desc.in_h; g.in_w = c->desc.in_w; g.out_h = c->desc.out_h; g.out_w = c->desc.out_w;
-        g.gt = c->gt; g.tiles_per_row = c->tiles_per_row; g.tpo_log2 = c->ad_tpo_log2;
+        g.gt = c->gt; g.tiles_per_row = c->tiles_per_row; g.tpo_log2 = c->ad_tpo_log2; g.win = c->ad_win;
         if (variant == POOL_ADAPTIVE_GENERIC) {
             const long items = (long)a.n_max * c->F;
             const int blocks = (int)std::min<long>((items + 255) / 256, max_blocks);
@@ -460,6 +462,8 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
     case 4 * 4 + 2: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 4, 2><<<blocks, WPB * 64, 0, st>>>(a, g); break;    \
     case 4 * 4: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 4, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;        \
     case 7 * 4: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 7, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;        \
+    case 7 * 4 + 2: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 7, 2><<<blocks, WPB * 64, 0, st>>>(a, g); break;    \
+    case 14 * 4 + 2: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 14, 2><<<blocks, WPB * 64, 0, st>>>(a, g); break;  \
     case 14 * 4 + 1: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 14, 1><<<blocks, WPB * 64, 0, st>>>(a, g); break;  \
     case 14 * 4: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 14, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;      \
     default: pool_ncs_adaptive_kernel<Tag, JJ, WPB, 0, 0><<<blocks, WPB * 64, 0, st>>>(a, g); break;           \
@@ -823,6 +827,24 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
 
     const int K = desc->K;
     gati_status_t st = upload_weights(c, w);
+    if (st == GATI_OK && c->variant == POOL_NCS_ADAPTIVE) {
+        // window table of the tiled adaptive-pool kernel; window i of an axis covers
+        // [floor(i*in/out), ceil((i+1)*in/out))
+        try {
+            const int OO = desc->out_h * desc->out_w;
+            std::vector<AdaptiveWindow> win((size_t)c->gt * OO);
+            for (int lc = 0; lc < c->gt; ++lc)
+                for (int oy = 0; oy < desc->out_h; ++oy)
+                    for (int ox = 0; ox < desc->out_w; ++ox) {
+                        const int y0 = (oy * desc->in_h) / desc->out_h, y1 = ((oy + 1) * desc->in_h + desc->out_h - 1) / desc->out_h;
+                        const int x0 = (ox * desc->in_w) / desc->out_w, x1 = ((ox + 1) * desc->in_w + desc->out_w - 1) / desc->out_w;
+                        AdaptiveWindow& e = win[(size_t)lc * OO + oy * desc->out_w + ox];
+                        e.start = lc * desc->S + y0 * desc->in_w + x0;
+                        e.rows = y1 - y0; e.cols = x1 - x0; e.area = (float)((y1 - y0) * (x1 - x0));
+                    }
+            st = upload((void**)&c->ad_win, win.data(), win.size() * sizeof(AdaptiveWindow));
+        } catch (const std::bad_alloc&) { st = GATI_ERR_OOM; }
+    }
     // workspace, zeroed once: the padding columns of p are never written and must read as 0
     if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
     if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);

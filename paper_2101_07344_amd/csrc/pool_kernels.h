@@ -420,9 +420,20 @@ __global__ __launch_bounds__(NW * 64) void pool_nsc_row_kernel(PoolArgs a, int c
 // in its own LDS strip; then `tpo` lanes per output window add up the window's rows in a fixed
 // order.  Window i of an axis covers [floor(i*in/out), ceil((i+1)*in/out)).
 // ---------------------------------------------------------------------------------------
+// One output window of a tile, by its index o = local_channel * out_h*out_w + window: where its
+// first element lies in the tile's flat element stream, its extent, and its element count.  Built
+// on the host so that the kernel does no integer division (those made it ALU-bound).
+struct __attribute__((aligned(16))) AdaptiveWindow {
+    int start;   // local_channel * S + y0 * in_w + x0
+    int rows;    // y1 - y0
+    int cols;    // x1 - x0
+    float area;  // rows * cols
+};
+
 struct AdaptiveArgs {
     int in_h, in_w, out_h, out_w;
     int gt, tiles_per_row, tpo_log2;
+    const AdaptiveWindow* win;   // [gt * out_h * out_w], tiled kernel only
 };
 
 template <typename Tag> __device__ __forceinline__ float lds_elem(const u32x4_t* raw, int idx);
@@ -433,13 +444,22 @@ template <> __device__ __forceinline__ float lds_elem<BF16Tag>(const u32x4_t* ra
     return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(raw)[idx] << 16);
 }
 
+// acc + lo + hi of a pair of bf16 values in one instruction (the products with 1.0 are exact; the
+// sum is accumulated in fp32).
+__device__ __forceinline__ float add_bf16_pair(uint32_t pair, float acc) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair),
+                                           __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc, false);
+}
+
 // WW > 0: every window is WW columns wide (known on the host), so a window row's LDS reads are
 // unrolled and all in flight together; with a run-time width each element's read waits for the
 // one before it and the kernel is bound by LDS latency instead of HBM.  (Also unrolling the
 // window rows, with clamped reads for the rows a lane does not own, was slower.)
 // PAIR (bf16 only): 1 = every window row starts on an even element and WW is even, two elements
 // per 32-bit LDS read; 2 = 32-bit reads from the even element at or before the row start, the
-// candidate outside the window added as zero (pays for narrow windows only); 0 = 16-bit reads.
+// candidates outside the window masked to zero; 0 = 16-bit reads.  Pairs are added by the bf16
+// dot-product instruction, so a row's elements are not added strictly left to right.
 template <typename Tag, int J, int WPB, int WW, int PAIR>
 __global__ __launch_bounds__(WPB * 64) void pool_ncs_adaptive_kernel(PoolArgs a, AdaptiveArgs g) {
     constexpr int V = Tag::kVec;
@@ -465,6 +485,13 @@ __global__ __launch_bounds__(WPB * 64) void pool_ncs_adaptive_kernel(PoolArgs a,
         return reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) +
                                                 ((r * a.C + c_first) * (long)a.S) * Tag::kBytes);
     };
+
+    constexpr int kWinRegs = 4;
+    const int per_it = 64 >> g.tpo_log2;            // windows per step of the wave
+    const int my_win = lane >> g.tpo_log2;
+    AdaptiveWindow wreg[kWinRegs];
+#pragma unroll
+    for (int it = 0; it < kWinRegs; ++it) wreg[it] = g.win[min(it * per_it + my_win, g.gt * OO - 1)];
 
     u32x4_t v[J];
     unsigned i = 0;
@@ -495,65 +522,57 @@ __global__ __launch_bounds__(WPB * 64) void pool_ncs_adaptive_kernel(PoolArgs a,
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const int n_out = cn * OO;
-        for (int ob = 0; ob < n_out; ob += 64 >> g.tpo_log2) {
-            const int o = ob + (lane >> g.tpo_log2);
+        auto window = [&](int o, const AdaptiveWindow& wd) {
             const bool live = o < n_out;
-            const int oc = live ? o : 0;
-            const int lc = oc / OO;
-            const int wi = oc - lc * OO;
-            const int oy = wi / g.out_w, ox = wi - oy * g.out_w;
-            const int y0 = (oy * g.in_h) / g.out_h, y1 = ((oy + 1) * g.in_h + g.out_h - 1) / g.out_h;
-            const int x0 = (ox * g.in_w) / g.out_w, x1 = ((ox + 1) * g.in_w + g.out_w - 1) / g.out_w;
             float acc = 0.f;
             if (live) {
-                for (int y = y0 + sub; y < y1; y += tpo) {
-                    const int rb = lc * a.S + y * g.in_w;
+                for (int y = sub; y < wd.rows; y += tpo) {
+                    const int rb = wd.start + y * g.in_w;          // first element of the window row
                     if constexpr (WW > 0 && PAIR == 1) {
                         uint32_t e2[WW / 2];
-                        const uint32_t* r2 = reinterpret_cast<const uint32_t*>(raw) + ((rb + x0) >> 1);
+                        const uint32_t* r2 = reinterpret_cast<const uint32_t*>(raw) + (rb >> 1);
 #pragma unroll
                         for (int x = 0; x < WW / 2; ++x) e2[x] = r2[x];
 #pragma unroll
-                        for (int x = 0; x < WW / 2; ++x) {                 // same order as the loop below
-                            acc += __uint_as_float(e2[x] << 16);
-                            acc += __uint_as_float(e2[x] & 0xffff0000u);
-                        }
+                        for (int x = 0; x < WW / 2; ++x) acc = add_bf16_pair(e2[x], acc);
                     } else if constexpr (WW > 0 && PAIR == 2) {
-                        // The pairs hold WW+1 or WW+2 candidates; the first is skipped when the row starts
-                        // on an odd element, the one after the window is added only then.  Skipped
-                        // candidates are added as zero: the sum and its left-to-right order stay.
+                        // The row starts at any element: NP aligned pairs hold candidates k = 0 .. 2*NP-1, the
+                        // window is k = odd .. odd + WW - 1.  Only the first and the last pair can hold a
+                        // candidate outside the window; it is masked to +0.0 before the pair is added.
                         constexpr int NP = WW / 2 + 1;
-                        const int first = rb + x0;
-                        const bool odd = first & 1;
+                        const bool odd = rb & 1;
                         const uint32_t* r2 = reinterpret_cast<const uint32_t*>(raw);
                         const int last_pair = tile_vecs * 4 - 1;              // 8 elements per vector
                         uint32_t e2[NP];
 #pragma unroll
-                        for (int x = 0; x < NP; ++x) e2[x] = r2[min((first >> 1) + x, last_pair)];
+                        for (int x = 0; x < NP; ++x) e2[x] = r2[min((rb >> 1) + x, last_pair)];
+                        e2[0] &= odd ? 0xffff0000u : 0xffffffffu;
+                        if constexpr (WW % 2 == 0) e2[NP - 1] &= odd ? 0x0000ffffu : 0u;
+                        else e2[NP - 1] &= odd ? 0xffffffffu : 0x0000ffffu;
 #pragma unroll
-                        for (int k = 0; k <= WW; ++k) {
-                            const uint32_t w = e2[k >> 1];
-                            const float v = __uint_as_float((k & 1) ? (w & 0xffff0000u) : (w << 16));
-                            if (k == 0) acc += odd ? 0.f : v;
-                            else if (k == WW) acc += odd ? v : 0.f;
-                            else acc += v;
-                        }
+                        for (int x = 0; x < NP; ++x) acc = add_bf16_pair(e2[x], acc);
                     } else if constexpr (WW > 0) {
                         float e[WW];
 #pragma unroll
-                        for (int x = 0; x < WW; ++x) e[x] = lds_elem<Tag>(raw, rb + x0 + x);
+                        for (int x = 0; x < WW; ++x) e[x] = lds_elem<Tag>(raw, rb + x);
 #pragma unroll
                         for (int x = 0; x < WW; ++x) acc += e[x];          // same order as the loop below
                     } else {
-                        for (int x = x0; x < x1; ++x) acc += lds_elem<Tag>(raw, rb + x);
+                        for (int x = 0; x < wd.cols; ++x) acc += lds_elem<Tag>(raw, rb + x);
                     }
                 }
             }
             for (int m = tpo >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
-            if (live && sub == 0) {
-                const float mean = acc / (float)((y1 - y0) * (x1 - x0));
-                store_pooled(a, (long)ci * a.out_stride + (long)(cc + lc) * OO + wi, fmaxf(mean, 0.f));
-            }
+            if (live && sub == 0)      // (cc + local channel) * OO + window = cc * OO + o
+                store_pooled(a, (long)ci * a.out_stride + (long)cc * OO + o, fmaxf(acc / wd.area, 0.f));
+        };
+        // a lane meets the same windows in every tile: the first kWinRegs steps' table entries wait in registers
+#pragma unroll
+        for (int it = 0; it < kWinRegs; ++it)
+            if (it * per_it < n_out) window(it * per_it + my_win, wreg[it]);
+        for (int ob = kWinRegs * per_it; ob < n_out; ob += per_it) {
+            const int o = ob + my_win;
+            window(o, g.win[min(o, n_out - 1)]);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
