@@ -53,9 +53,15 @@ template <typename Tag> __device__ __forceinline__ float vec_sum(const u32x4_t& 
 template <> __device__ __forceinline__ float vec_sum<F32Tag>(const u32x4_t& v) {
     return (__uint_as_float(v.x) + __uint_as_float(v.y)) + (__uint_as_float(v.z) + __uint_as_float(v.w));
 }
+// acc + lo + hi of a pair of bf16 values in one instruction (the products with 1.0 are exact; the
+// sum is accumulated in fp32).
+__device__ __forceinline__ float add_bf16_pair(uint32_t pair, float acc) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair),
+                                           __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc, false);
+}
 template <> __device__ __forceinline__ float vec_sum<BF16Tag>(const u32x4_t& v) {
-    return ((bf16_lo(v.x) + bf16_hi(v.x)) + (bf16_lo(v.y) + bf16_hi(v.y))) +
-           ((bf16_lo(v.z) + bf16_hi(v.z)) + (bf16_lo(v.w) + bf16_hi(v.w)));
+    return add_bf16_pair(v.y, add_bf16_pair(v.x, 0.f)) + add_bf16_pair(v.w, add_bf16_pair(v.z, 0.f));
 }
 
 // Elements of one 16-byte vector as floats, in memory order.

@@ -94,6 +94,41 @@ __global__ __launch_bounds__(256) void pool_ncs_wave_kernel(PoolArgs a, int vpc)
     }
 }
 
+// Split of one 16-byte vector at the channel boundary it may straddle: pa = sum of its first cnt
+// elements, pb = sum of the rest.  bf16: the boundary becomes a bit mask over the four element
+// pairs, built once per lane, and the pairs are added with the dot-product instruction.
+template <typename Tag> struct SplitMask;
+template <> struct SplitMask<F32Tag> {
+    __device__ __forceinline__ void set(int) {}
+    __device__ __forceinline__ void split(const u32x4_t& v, int cnt, float& pa, float& pb) const {
+        float e[4];
+        vec_unpack<F32Tag>(v, e);
+        pa = 0.f; pb = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            pa += (k < cnt) ? e[k] : 0.f;
+            pb += (k < cnt) ? 0.f : e[k];
+        }
+    }
+};
+template <> struct SplitMask<BF16Tag> {
+    uint32_t m[4];     // bits of the elements that belong to the first channel
+    __device__ __forceinline__ void set(int cnt) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            m[d] = (2 * d < cnt ? 0x0000ffffu : 0u) | (2 * d + 1 < cnt ? 0xffff0000u : 0u);
+    }
+    __device__ __forceinline__ void split(const u32x4_t& v, int, float& pa, float& pb) const {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        pa = 0.f; pb = 0.f;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            pa = add_bf16_pair(w[d] & m[d], pa);
+            pb = add_bf16_pair(w[d] & ~m[d], pb);
+        }
+    }
+};
+
 // ---------------------------------------------------------------------------------------
 // [n,C,S] with short or 16-byte-unaligned channels (S = 49, 196, 64, ...), wave-granular.
 // A sample's channels are one flat, contiguous stream, so a wave takes a tile of `gt` whole
@@ -140,6 +175,21 @@ __global__ __launch_bounds__(256) void pool_ncs_segw_kernel(PoolArgs a, int gt, 
                                                 ((r * a.C + c_first) * (long)a.S) * Tag::kBytes);
     };
 
+    // Where a lane's j-th vector lies relative to the channel boundaries is the same in every tile
+    // (tiles start on a channel): cnt[j] = elements of the vector that belong to the channel of its
+    // first element, found once.  (Recomputing it per tile, with the selects below on all 8 bf16
+    // elements, kept the vector ALUs 87 % busy and the kernel below HBM speed.)
+    int cnt[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const unsigned o = (unsigned)(lane + 64 * j) * V;    // first element, tile-local
+        const unsigned ch = __umulhi(o, magic_S);            // o / S
+        cnt[j] = a.S - (int)(o - ch * (unsigned)a.S);
+    }
+    SplitMask<Tag> mask[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) mask[j].set(cnt[j]);
+
     u32x4_t v[J];
     unsigned i = 0;
     int c_first = 0, nch = 0;
@@ -155,17 +205,8 @@ __global__ __launch_bounds__(256) void pool_ncs_segw_kernel(PoolArgs a, int gt, 
         for (int j = 0; j < J; ++j) {
             const int idx = lane + 64 * j;
             if (idx < tile_vecs) {
-                const unsigned o = (unsigned)idx * V;            // first element, tile-local
-                const unsigned ch = __umulhi(o, magic_S);        // o / S
-                const int cnt = a.S - (int)(o - ch * (unsigned)a.S);  // elements left in that channel
-                float e[V];
-                vec_unpack<Tag>(v[j], e);
-                float pa = 0.f, pb = 0.f;
-#pragma unroll
-                for (int k = 0; k < V; ++k) {
-                    pa += (k < cnt) ? e[k] : 0.f;
-                    pb += (k < cnt) ? 0.f : e[k];
-                }
+                float pa, pb;
+                mask[j].split(v[j], cnt[j], pa, pb);
                 A[idx] = pa;
                 B[idx] = pb;
             }
@@ -442,14 +483,6 @@ template <> __device__ __forceinline__ float lds_elem<F32Tag>(const u32x4_t* raw
 }
 template <> __device__ __forceinline__ float lds_elem<BF16Tag>(const u32x4_t* raw, int idx) {
     return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(raw)[idx] << 16);
-}
-
-// acc + lo + hi of a pair of bf16 values in one instruction (the products with 1.0 are exact; the
-// sum is accumulated in fp32).
-__device__ __forceinline__ float add_bf16_pair(uint32_t pair, float acc) {
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair),
-                                           __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc, false);
 }
 
 // WW > 0: every window is WW columns wide (known on the host), so a window row's LDS reads are
