@@ -326,6 +326,10 @@ class Trainer:
              n: Optional[int] = None):
         """pooled [n, >=C] fp32, labels [n] int32, teacher [n, >=K] fp32: device tensors."""
         n = pooled.shape[0] if n is None else n
+        import torch
+        assert pooled.dtype == torch.float32 and teacher.dtype == torch.float32 and labels.dtype == torch.int32
+        assert pooled.stride(1) == 1 and teacher.stride(1) == 1 and labels.stride(0) == 1
+        assert pooled.shape[1] >= self.C and teacher.shape[1] >= self.K and labels.shape[0] >= n
         _check(gati_trainer_step(self.handle, pooled, pooled.stride(0), n, labels, teacher, teacher.stride(0),
                                  TrainParams(lr, alpha, fp_weight), losses, stream), "gati_trainer_step")
 
