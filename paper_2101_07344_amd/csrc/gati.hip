@@ -397,7 +397,9 @@ int conv_reorder(const gati_cache_desc_t* d, const float* W1, int k_step, std::v
 
 template <typename Tag>
 hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, hipStream_t st) {
-    const int max_blocks = c->num_cu * c->pool_blocks_per_cu;
+    // grid cap per CU: the wave kernel streams fastest with a wave per channel group and no grid-stride
+    // loop (7.03 against 6.86 TB/s at 16 blocks per CU; no change beyond 64), the tiled kernels with 12-24
+    const int max_blocks = c->num_cu * (variant == POOL_NCS_WAVE ? 64 : c->pool_blocks_per_cu);
     switch (variant) {
     case POOL_NCS_WAVE: {
         static const int cpi_of[] = {8, 4, 2, 2, 1};
