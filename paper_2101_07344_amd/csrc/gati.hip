@@ -398,8 +398,13 @@ int conv_reorder(const gati_cache_desc_t* d, const float* W1, int k_step, std::v
 template <typename Tag>
 hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, hipStream_t st) {
     // grid cap per CU: the wave kernel streams fastest with a wave per channel group and no grid-stride
-    // loop (7.03 against 6.86 TB/s at 16 blocks per CU; no change beyond 64), the tiled kernels with 12-24
-    const int max_blocks = c->num_cu * (variant == POOL_NCS_WAVE ? 64 : c->pool_blocks_per_cu);
+    // loop (7.03 against 6.86 TB/s at 16 blocks per CU; no change beyond 64), the tiled kernels with 12-24;
+    // the adaptive-pool kernel with 48 for its large (J >= 8) tiles (6.8 against 6.4 TB/s inside a stack pass;
+    // 128 drops to 5.9) and 24 otherwise
+    int per_cu = c->pool_blocks_per_cu;
+    if (variant == POOL_NCS_WAVE) per_cu = 64;
+    else if (variant == POOL_NCS_ADAPTIVE) per_cu = c->ad_j >= 8 ? 48 : 24;
+    const int max_blocks = c->num_cu * per_cu;
     switch (variant) {
     case POOL_NCS_WAVE: {
         static const int cpi_of[] = {8, 4, 2, 2, 1};
