@@ -126,6 +126,35 @@ def test_five_steps_then_serve(name, layer, n):
     tr.close(); cache.close()
 
 
+@pytest.mark.parametrize("C,H,K,n", [(40, 24, 100, 19), (37, 50, 1100, 23), (130, 65, 7, 70), (64, 33, 257, 5)])
+def test_odd_shapes_cover_every_kernel_path(C, H, K, n):
+    """Sizes that are multiples of nothing: scalar operand loads (leading dimensions not multiples
+    of 4), ragged 64 x 64 tiles, and the row kernel's four class-count ranges (K <= 64, <= 256,
+    <= 1024, larger)."""
+    rng = np.random.default_rng(C * 1000 + K)
+    w = {"W1": (rng.standard_normal((H, C)) * np.sqrt(2.0 / C)).astype(np.float32),
+         "b1": (rng.standard_normal(H) * 0.1).astype(np.float32),
+         "W2": (rng.standard_normal((K, H)) * np.sqrt(2.0 / H)).astype(np.float32),
+         "b2": (rng.standard_normal(K) * 0.1).astype(np.float32),
+         "ws": (rng.standard_normal(C + K) * 0.3).astype(np.float32), "bs": 0.25}
+    pooled = rng.standard_normal((n, C)).astype(np.float32)
+    labels = rng.integers(0, K, n).astype(np.int32)
+    Y = W.teacher_distribution(labels, K, seed=K)
+    assert _margin_ok(w, pooled, Y)
+    lr, alpha, lam = 1.0, 0.6, 1.5
+    tr = g.Trainer(C, H, K, w, max_rows=n)
+    losses = torch.zeros(2, device="cuda")
+    tr.step(torch.from_numpy(pooled).cuda(), torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda(),
+            lr, alpha, lam, losses)
+    torch.cuda.synchronize()
+    want, lp, ls = train.sgd_step(w, pooled, labels, Y, lr, alpha, lam)
+    grads = train.gradients(w, pooled, labels, Y, alpha, lam)
+    _check_update(tr.get_weights(), want, w, grads, lr, where=f"C={C} H={H} K={K} n={n}")
+    lg = losses.cpu().numpy()
+    assert abs(lg[0] - lp) <= 1e-5 * max(1.0, abs(lp)) and abs(lg[1] - ls) <= 1e-5 * max(1.0, abs(ls))
+    tr.close()
+
+
 def test_minibatch_epochs():
     """Two epochs over 150 samples in batches of 64 (64 + 64 + 22): sliced inputs, ragged last batch."""
     lr, alpha, lam = 0.01, 0.4, 2.0
