@@ -31,7 +31,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X published dense mat
 
 # HBM traffic of the dominant pooling kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs (summaries under profiles/); keyed by workload.  None until measured.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 820_010_000}
+MEASURED_TRAFFIC_BYTES = {"resnet50": 819_310_000}
 
 
 def log(*a):
