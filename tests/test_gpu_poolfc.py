@@ -64,15 +64,17 @@ def test_adaptive_pool_matches_oracle(C, ih, iw, oh, ow, dtype, variant):
     cache.close()
 
 
-@pytest.mark.parametrize("C,ih,iw,oh,ow,K,dtype", [
-    (256, 14, 14, 4, 4, 1000, "bf16"),     # F = 4096, overlapping 14 -> 4 windows
-    (64, 16, 16, 8, 8, 10, "f32"),         # F = 4096: the paper's 16x16 -> 8x8 shape
-    (2048, 7, 7, 2, 2, 1000, "bf16"),      # F = 8192
-    (24, 5, 10, 3, 4, 33, "bf16"),
+@pytest.mark.parametrize("C,ih,iw,oh,ow,K,dtype,n", [
+    (256, 14, 14, 4, 4, 1000, "bf16", 45),     # F = 4096, overlapping 14 -> 4 windows
+    (64, 16, 16, 8, 8, 10, "f32", 45),         # F = 4096: the paper's 16x16 -> 8x8 shape
+    (2048, 7, 7, 2, 2, 1000, "bf16", 45),      # F = 8192
+    (24, 5, 10, 3, 4, 33, "bf16", 45),
+    # more rows than a few 32-row tiles, F = 2048 .. 4096, and a feature count that is a multiple of nothing
+    (256, 14, 14, 4, 4, 1000, "bf16", 150), (128, 8, 8, 4, 4, 200, "f32", 140), (530, 6, 6, 2, 2, 130, "bf16", 260),
 ])
-def test_pool_fc_lookup_matches_oracle(C, ih, iw, oh, ow, K, dtype):
+def test_pool_fc_lookup_matches_oracle(C, ih, iw, oh, ow, K, dtype, n):
     rng = np.random.default_rng(C + K)
-    n, S, F = 45, ih * iw, C * oh * ow
+    S, F = ih * iw, C * oh * ow
     x = torch.from_numpy((rng.standard_normal((n, C, S)) + 0.4).astype(np.float32))
     x = x.bfloat16() if dtype == "bf16" else x
     w = _weights(F, K, rng)
