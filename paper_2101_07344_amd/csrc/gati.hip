@@ -403,6 +403,7 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
     // 128 drops to 5.9) and 24 otherwise
     int per_cu = c->pool_blocks_per_cu;
     if (variant == POOL_NCS_WAVE) per_cu = 64;
+    else if (variant == POOL_NCS_SEGW) per_cu = 12;      // 5.70 / 4.22 TB/s at S = 196 / 49 against 5.61 / 4.11 at 16
     else if (variant == POOL_NCS_ADAPTIVE) per_cu = c->ad_j >= 8 ? 48 : 24;
     const int max_blocks = c->num_cu * per_cu;
     switch (variant) {
