@@ -19,6 +19,11 @@ ingredients, not the formulas; the reading taken here:
   update     plain SGD, theta <- theta - lr * grad, both networks in the same step, the selector
              on the predictor's outputs of BEFORE the update.
 
+  hidden-layer selector (Section 3, "Selector Network Design": the paper's selector has one hidden
+             layer): when the weights hold "Ws", "cs", "vs" the selector is
+                 g_i = relu(Ws [p_i ; q_i] + cs),  c_i = logistic(vs . g_i + bs)
+             with the same loss; its gradients flow through the ReLU into Ws and cs, never into q.
+
 Every function takes and returns fp64 arrays; `pooled` are the features the lookup oracle reports.
 """
 from __future__ import annotations
@@ -35,10 +40,18 @@ def forward(w: dict, pooled: np.ndarray):
     z = h @ W2.T + b2
     e = np.exp(z - z.max(axis=1, keepdims=True))
     q = e / e.sum(axis=1, keepdims=True)
-    ws = np.asarray(w["ws"], np.float64)
-    u = np.concatenate([p, q], axis=1) @ ws + float(w["bs"])
-    c = 1.0 / (1.0 + np.exp(-u))
-    return {"p": p, "a": a, "h": h, "z": z, "q": q, "u": u, "c": c}
+    x = np.concatenate([p, q], axis=1)
+    out = {"p": p, "a": a, "h": h, "z": z, "q": q, "x": x}
+    if "Ws" in w:
+        sa = x @ np.asarray(w["Ws"], np.float64).T + np.asarray(w["cs"], np.float64)
+        g = np.maximum(sa, 0.0)
+        u = g @ np.asarray(w["vs"], np.float64) + float(w["bs"])
+        out.update({"sa": sa, "g": g})
+    else:
+        u = x @ np.asarray(w["ws"], np.float64) + float(w["bs"])
+    out["u"] = u
+    out["c"] = 1.0 / (1.0 + np.exp(-u))
+    return out
 
 
 def targets(labels: np.ndarray, teacher: np.ndarray, alpha: float) -> np.ndarray:
@@ -76,8 +89,13 @@ def gradients(w: dict, pooled, labels, teacher, alpha: float, fp_weight: float) 
     db1 = dh.sum(axis=0)
     G = (f["z"].argmax(axis=1) == np.asarray(teacher).argmax(axis=1)).astype(np.float64)
     du = (G * (f["c"] - 1.0) + fp_weight * (1.0 - G) * f["c"]) / n
-    x = np.concatenate([f["p"], f["q"]], axis=1)
-    return {"W1": dW1, "b1": db1, "W2": dW2, "b2": db2, "ws": du @ x, "bs": float(du.sum())}
+    out = {"W1": dW1, "b1": db1, "W2": dW2, "b2": db2, "bs": float(du.sum())}
+    if "Ws" in w:
+        dg = np.outer(du, np.asarray(w["vs"], np.float64)) * (f["sa"] > 0.0)
+        out.update({"vs": du @ f["g"], "Ws": dg.T @ f["x"], "cs": dg.sum(axis=0)})
+    else:
+        out["ws"] = du @ f["x"]
+    return out
 
 
 def sgd_step(w: dict, pooled, labels, teacher, lr: float, alpha: float, fp_weight: float):
@@ -85,6 +103,6 @@ def sgd_step(w: dict, pooled, labels, teacher, lr: float, alpha: float, fp_weigh
     the losses evaluated before the update."""
     g = gradients(w, pooled, labels, teacher, alpha, fp_weight)
     Lp, Ls = losses(w, pooled, labels, teacher, alpha, fp_weight)
-    new = {k: np.asarray(w[k], np.float64) - lr * g[k] for k in ("W1", "b1", "W2", "b2", "ws")}
+    new = {k: np.asarray(w[k], np.float64) - lr * g[k] for k in g if k != "bs"}
     new["bs"] = float(w["bs"]) - lr * g["bs"]
     return new, Lp, Ls

@@ -98,3 +98,65 @@ def test_a_step_goes_downhill_and_zero_rate_is_the_identity():
         cur, lp1, ls1 = train.sgd_step(cur, pooled, labels, Y, 0.05, 0.3, 2.0)
     lp2 = train.losses(cur, pooled, labels, Y, 0.3, 2.0)[0]
     assert lp2 < lp and lp1 < lp
+
+
+def _case_hidden(seed=0, n=9, C=5, H=4, K=3, Hs=6):
+    w, pooled, labels, Y = _case(seed, n, C, H, K)
+    rng = np.random.default_rng(seed + 100)
+    del w["ws"]
+    w.update({"Ws": rng.standard_normal((Hs, C + K)) * 0.6, "cs": rng.standard_normal(Hs) * 0.3,
+              "vs": rng.standard_normal(Hs) * 0.8})
+    return w, pooled, labels, Y
+
+
+def test_hidden_layer_selector_gradients():
+    """Finite differences of the oracle's own loss, and autograd on an independently written one."""
+    w, pooled, labels, Y = _case_hidden(seed=2, n=11, C=6, H=5, K=4, Hs=7)
+    alpha, lam = 0.4, 2.0
+    g = train.gradients(w, pooled, labels, Y, alpha, lam)
+    assert set(g) == {"W1", "b1", "W2", "b2", "Ws", "cs", "vs", "bs"}
+    eps = 1e-6
+    for key in ("Ws", "cs", "vs"):
+        flat = np.asarray(w[key], np.float64)
+        for idx in list(np.ndindex(flat.shape))[:: max(1, flat.size // 9)]:
+            wp = {**w, key: flat.copy()}
+            wm = {**w, key: flat.copy()}
+            wp[key][idx] += eps
+            wm[key][idx] -= eps
+            num = (train.losses(wp, pooled, labels, Y, alpha, lam)[1] -
+                   train.losses(wm, pooled, labels, Y, alpha, lam)[1]) / (2 * eps)
+            assert abs(num - g[key][idx]) < 1e-7, (key, idx, num, g[key][idx])
+    tw = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in w.items() if k != "bs"}
+    bs = torch.tensor(float(w["bs"]), dtype=torch.float64, requires_grad=True)
+    p = torch.tensor(pooled)
+    z = torch.relu(p @ tw["W1"].T + tw["b1"]) @ tw["W2"].T + tw["b2"]
+    q = torch.softmax(z, dim=1).detach()
+    gh = torch.relu(torch.cat([p, q], dim=1) @ tw["Ws"].T + tw["cs"])
+    u = gh @ tw["vs"] + bs
+    G = torch.tensor((z.detach().numpy().argmax(1) == Y.argmax(1)).astype(np.float64))
+    Ls = -(G * torch.nn.functional.logsigmoid(u) + lam * (1 - G) * torch.nn.functional.logsigmoid(-u)).sum() / len(labels)
+    Ls.backward()
+    for k in ("Ws", "cs", "vs"):
+        assert np.max(np.abs(tw[k].grad.numpy() - g[k])) < 1e-12, k
+    assert abs(bs.grad.item() - g["bs"]) < 1e-12
+    assert tw["W1"].grad is None or float(tw["W1"].grad.abs().max()) == 0.0     # nothing reaches the predictor
+    assert abs(train.losses(w, pooled, labels, Y, alpha, lam)[1] - Ls.item()) < 1e-12
+
+
+def test_hidden_layer_selector_limits():
+    """One always-active unit with vs = 1 and cs = 0 is the linear selector; a unit that the ReLU clamps
+    for every sample gets no gradient."""
+    w, pooled, labels, Y = _case(seed=4)
+    lin = train.gradients(w, pooled, labels, Y, 0.3, 2.0)
+    f = train.forward(w, pooled)
+    shift = 1.0 - f["x"] @ w["ws"]                       # keep the single unit positive for every sample
+    big = float(shift.max()) + 1.0
+    wh = {k: v for k, v in w.items() if k != "ws"}
+    wh.update({"Ws": np.asarray(w["ws"])[None, :], "cs": np.array([big]), "vs": np.array([1.0]), "bs": w["bs"] - big})
+    fh = train.forward(wh, pooled)
+    assert np.allclose(fh["u"], f["u"], atol=1e-12)
+    gh = train.gradients(wh, pooled, labels, Y, 0.3, 2.0)
+    assert np.allclose(gh["Ws"][0], lin["ws"], atol=1e-12) and abs(gh["cs"][0] - lin["bs"]) < 1e-12
+    wd = {**wh, "Ws": np.vstack([wh["Ws"], -wh["Ws"]]), "cs": np.array([big, -big - 50.0]), "vs": np.array([1.0, 0.7])}
+    gd = train.gradients(wd, pooled, labels, Y, 0.3, 2.0)
+    assert np.all(gd["Ws"][1] == 0.0) and gd["cs"][1] == 0.0 and gd["vs"][1] == 0.0
