@@ -230,8 +230,11 @@ const char *gati_cache_pool_variant(const gati_cache_t *cache);
  *   every weight theta <- theta - lr dL/dtheta, with L_pred for W1, b1, W2, b2 and L_sel for ws, bs;
  *   the selector sees q as data (L_sel has no gradient into the predictor), and uses the q and
  *   the G of before the update.
- * Only GATI_PRED_GAP_MLP with GATI_SEL_LINEAR is supported (GATI_ERR_UNSUPPORTED otherwise);
- * act_dtype, layout, S and threshold of the descriptor are ignored.                               */
+ * With GATI_SEL_HIDDEN (Section 3, "Selector Network Design": the selector has one hidden layer) the
+ * selector is g_i = relu(Ws [p_i ; q_i] + cs), c_i = 1/(1 + exp(-(vs . g_i + bs))) with the same loss;
+ * its gradients reach Ws, cs, vs and bs through the ReLU, never q.
+ * Only GATI_PRED_GAP_MLP with GATI_SEL_LINEAR or GATI_SEL_HIDDEN is supported (GATI_ERR_UNSUPPORTED
+ * otherwise); act_dtype, layout, S and threshold of the descriptor are ignored.                    */
 typedef struct gati_trainer gati_trainer_t; /* opaque, owned by the library */
 
 typedef struct {
@@ -262,9 +265,14 @@ gati_status_t gati_trainer_step(gati_trainer_t *trainer, const float *pooled, in
                                 const gati_train_params_t *params, float *losses, void *stream);
 
 /* Copy the current weights to HOST arrays W1 [H, C], b1 [H], W2 [K, H], b2 [K], ws [C + K] and
- * *bs, after waiting for all work on the device. */
+ * *bs, after waiting for all work on the device.  A trainer with a hidden-layer selector has no ws
+ * (NULL is accepted there); its selector comes from gati_trainer_get_hidden_selector. */
 gati_status_t gati_trainer_get_weights(gati_trainer_t *trainer, float *W1, float *b1, float *W2, float *b2,
                                        float *ws, float *bs);
+
+/* The hidden-layer selector's weights to HOST arrays Ws [selector_hidden, C + K], cs and vs
+ * [selector_hidden]; GATI_ERR_UNSUPPORTED for a trainer with the linear selector. */
+gati_status_t gati_trainer_get_hidden_selector(gati_trainer_t *trainer, float *Ws, float *cs, float *vs);
 
 #ifdef __cplusplus
 }

@@ -21,6 +21,7 @@ exported_symbols = (
     "gati_cache_create", "gati_cache_destroy", "gati_cache_set_weights", "gati_cache_set_selector", "gati_cache_lookup",
     "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_status_string", "gati_cache_pool_variant",
     "gati_trainer_create", "gati_trainer_destroy", "gati_trainer_step", "gati_trainer_get_weights",
+    "gati_trainer_get_hidden_selector",
 )
 
 
@@ -98,6 +99,8 @@ def load_library():
     lib.gati_trainer_step.argtypes = [vp, vp, i32, i32, vp, vp, i32, C.POINTER(TrainParams), vp, vp]
     lib.gati_trainer_get_weights.restype = C.c_int
     lib.gati_trainer_get_weights.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.gati_trainer_get_hidden_selector.restype = C.c_int
+    lib.gati_trainer_get_hidden_selector.argtypes = [vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -307,20 +310,34 @@ def gati_trainer_get_weights(handle, W1, b1, W2, b2, ws, bs) -> int:
     return load_library().gati_trainer_get_weights(handle, a(W1), a(b1), a(W2), a(b2), a(ws), a(bs))
 
 
-class Trainer:
-    """SGD steps on one cache's predictor and selector (pooling predictor, linear selector)."""
+def gati_trainer_get_hidden_selector(handle, Ws, cs, vs) -> int:
+    a = lambda x: x.ctypes.data if x is not None else None
+    return load_library().gati_trainer_get_hidden_selector(handle, a(Ws), a(cs), a(vs))
 
-    def __init__(self, C_: int, H: int, K: int, weights: dict, max_rows: int):
-        keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in ("W1", "b1", "W2", "b2", "ws")}
+
+class Trainer:
+    """SGD steps on one cache's predictor and selector (pooling predictor; linear selector, or the
+    hidden-layer selector when sel_hidden > 0 and the weights hold Ws, cs, vs)."""
+
+    def __init__(self, C_: int, H: int, K: int, weights: dict, max_rows: int, sel_hidden: int = 0):
+        names = ("W1", "b1", "W2", "b2") + (("Ws", "cs", "vs") if sel_hidden else ("ws",))
+        keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
         assert keep["W1"].shape == (H, C_) and keep["b1"].shape == (H,) and keep["W2"].shape == (K, H)
-        assert keep["b2"].shape == (K,) and keep["ws"].shape == (C_ + K,)
-        desc = CacheDesc(C_, 1, H, K, GATI_F32, GATI_LAYOUT_NCS, 0.5, max_rows, GATI_SEL_LINEAR, GATI_PRED_GAP_MLP,
-                         0, 0, 0, 0, 0, 0, 0)
-        w = CacheWeights(*(keep[k].ctypes.data for k in ("W1", "b1", "W2", "b2", "ws")), float(weights["bs"]),
-                         None, None, None)
+        assert keep["b2"].shape == (K,)
+        if sel_hidden:
+            assert keep["Ws"].shape == (sel_hidden, C_ + K) and keep["cs"].shape == (sel_hidden,) \
+                and keep["vs"].shape == (sel_hidden,)
+        else:
+            assert keep["ws"].shape == (C_ + K,)
+        desc = CacheDesc(C_, 1, H, K, GATI_F32, GATI_LAYOUT_NCS, 0.5, max_rows,
+                         GATI_SEL_HIDDEN if sel_hidden else GATI_SEL_LINEAR, GATI_PRED_GAP_MLP, 0, 0, 0, 0,
+                         int(sel_hidden), 0, 0)
+        ptr = lambda k: keep[k].ctypes.data if k in keep else None
+        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]),
+                         ptr("Ws"), ptr("cs"), ptr("vs"))
         st, self.handle = gati_trainer_create(desc, w)
         _check(st, "gati_trainer_create")
-        self.C, self.H, self.K, self.max_rows = C_, H, K, max_rows
+        self.C, self.H, self.K, self.max_rows, self.sel_hidden = C_, H, K, max_rows, int(sel_hidden)
 
     def step(self, pooled, labels, teacher, lr: float, alpha: float, fp_weight: float, losses=None, stream=None,
              n: Optional[int] = None):
@@ -348,12 +365,18 @@ class Trainer:
 
     def get_weights(self) -> dict:
         out = {"W1": np.empty((self.H, self.C), np.float32), "b1": np.empty(self.H, np.float32),
-               "W2": np.empty((self.K, self.H), np.float32), "b2": np.empty(self.K, np.float32),
-               "ws": np.empty(self.C + self.K, np.float32)}
+               "W2": np.empty((self.K, self.H), np.float32), "b2": np.empty(self.K, np.float32)}
+        if not self.sel_hidden:
+            out["ws"] = np.empty(self.C + self.K, np.float32)
         bs = np.empty(1, np.float32)
-        _check(gati_trainer_get_weights(self.handle, out["W1"], out["b1"], out["W2"], out["b2"], out["ws"], bs),
+        _check(gati_trainer_get_weights(self.handle, out["W1"], out["b1"], out["W2"], out["b2"], out.get("ws"), bs),
                "gati_trainer_get_weights")
         out["bs"] = float(bs[0])
+        if self.sel_hidden:
+            out.update({"Ws": np.empty((self.sel_hidden, self.C + self.K), np.float32),
+                        "cs": np.empty(self.sel_hidden, np.float32), "vs": np.empty(self.sel_hidden, np.float32)})
+            _check(gati_trainer_get_hidden_selector(self.handle, out["Ws"], out["cs"], out["vs"]),
+                   "gati_trainer_get_hidden_selector")
         return out
 
     def close(self):

@@ -18,6 +18,10 @@ struct gati_trainer {
     float *h = nullptr, *z = nullptr, *q = nullptr, *dh = nullptr, *du = nullptr, *lp = nullptr, *ls = nullptr;
     float* part = nullptr;     // split-reduction slices of the largest product
     size_t part_floats = 0;
+    // selector with a hidden layer: Hs units over input rows X = [p ; q] of stride Sx (C + K rounded up to 4,
+    // zero padded, so that rows stay 16-byte aligned); Ws is held with the same stride
+    int Hs = 0, Sx = 0;
+    float *Ws = nullptr, *cs = nullptr, *vs = nullptr, *X = nullptr, *g = nullptr, *dg = nullptr, *G = nullptr;
 };
 
 namespace {
@@ -25,7 +29,8 @@ namespace {
 constexpr int kMaxSlices = 16;
 
 void free_all(gati_trainer* t) {
-    void* ptrs[] = {t->W1, t->b1, t->W2, t->b2, t->ws, t->bs, t->h, t->z, t->q, t->dh, t->du, t->lp, t->ls, t->part};
+    void* ptrs[] = {t->W1, t->b1, t->W2, t->b2, t->ws, t->bs, t->h, t->z, t->q, t->dh, t->du, t->lp, t->ls, t->part,
+                    t->Ws, t->cs, t->vs, t->X, t->g, t->dg, t->G};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -87,8 +92,12 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
                                   gati_trainer_t** out) {
     if (!desc || !w || !out) return GATI_ERR_INVALID_ARG;
     if (desc->C <= 0 || desc->H <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
-    if (!w->W1 || !w->b1 || !w->W2 || !w->b2 || !w->ws) return GATI_ERR_INVALID_ARG;
-    if (desc->predictor != GATI_PRED_GAP_MLP || desc->selector != GATI_SEL_LINEAR) return GATI_ERR_UNSUPPORTED;
+    if (!w->W1 || !w->b1 || !w->W2 || !w->b2) return GATI_ERR_INVALID_ARG;
+    if (desc->predictor != GATI_PRED_GAP_MLP) return GATI_ERR_UNSUPPORTED;
+    if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_HIDDEN) return GATI_ERR_UNSUPPORTED;
+    const bool hidden = desc->selector == GATI_SEL_HIDDEN;
+    if (hidden ? (!w->Ws || !w->cs || !w->vs || desc->selector_hidden <= 0 || desc->selector_hidden > 4096) : !w->ws)
+        return GATI_ERR_INVALID_ARG;
     gati_trainer* t = new (std::nothrow) gati_trainer;
     if (!t) return GATI_ERR_OOM;
     t->C = desc->C; t->H = desc->H; t->K = desc->K; t->max_rows = desc->max_rows;
@@ -98,7 +107,10 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
         t->num_cu = cus;
     const size_t C = t->C, H = t->H, K = t->K, n = t->max_rows;
     // the largest split product: slices x (M x N) over the five products of a step
-    const size_t mn[5] = {n * H, n * K, n * H, K * H, H * C};
+    t->Hs = hidden ? desc->selector_hidden : 0;
+    t->Sx = hidden ? (int)((C + K + 3) / 4 * 4) : 0;
+    const size_t Hs = t->Hs, Sx = t->Sx;
+    const size_t mn[7] = {n * H, n * K, n * H, K * H, H * C, n * Hs, Hs * Sx};
     t->part_floats = 0;
     for (size_t v : mn) t->part_floats = std::max(t->part_floats, v * kMaxSlices);
     t->part_floats = std::min<size_t>(t->part_floats, (size_t)64 << 20);   // 256 MB at most; fewer slices beyond
@@ -108,7 +120,7 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
     take(dev_alloc(&t->b1, H, w->b1));
     take(dev_alloc(&t->W2, K * H, w->W2));
     take(dev_alloc(&t->b2, K, w->b2));
-    take(dev_alloc(&t->ws, C + K, w->ws));
+    if (!hidden) take(dev_alloc(&t->ws, C + K, w->ws));
     take(dev_alloc(&t->bs, 1, &w->bs));
     take(dev_alloc(&t->h, n * H, nullptr));
     take(dev_alloc(&t->z, n * K, nullptr));
@@ -118,6 +130,22 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
     take(dev_alloc(&t->lp, n, nullptr));
     take(dev_alloc(&t->ls, n, nullptr));
     take(dev_alloc(&t->part, t->part_floats, nullptr));
+    if (hidden) {
+        take(dev_alloc(&t->Ws, Hs * Sx, nullptr));
+        take(dev_alloc(&t->cs, Hs, w->cs));
+        take(dev_alloc(&t->vs, Hs, w->vs));
+        take(dev_alloc(&t->X, n * Sx, nullptr));
+        take(dev_alloc(&t->g, n * Hs, nullptr));
+        take(dev_alloc(&t->dg, n * Hs, nullptr));
+        take(dev_alloc(&t->G, n, nullptr));
+        // the padding columns of X and Ws are zero and stay zero (their gradient is a product with zero)
+        if (st == GATI_OK && (hipMemset(t->X, 0, n * Sx * sizeof(float)) != hipSuccess ||
+                              hipMemset(t->Ws, 0, Hs * Sx * sizeof(float)) != hipSuccess ||
+                              hipMemcpy2D(t->Ws, Sx * sizeof(float), w->Ws, (C + K) * sizeof(float), (C + K) * sizeof(float), Hs,
+                                          hipMemcpyHostToDevice) != hipSuccess)) {
+            (void)hipGetLastError(); st = GATI_ERR_DEVICE;
+        }
+    }
     if (st != GATI_OK) { free_all(t); delete t; return st; }
     *out = t;
     return GATI_OK;
@@ -159,12 +187,28 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
         a.z = t->z; a.q = t->q; a.p = pooled; a.ldp = ld_pooled; a.labels = labels; a.Y = teacher; a.ldy = ld_teacher;
         a.ws = t->ws; a.bs = t->bs; a.n = n; a.C = C; a.K = K; a.alpha = params->alpha; a.fp_weight = params->fp_weight;
         a.du = t->du; a.lp = t->lp; a.ls = t->ls;
+        a.X = t->X; a.ldx = t->Sx; a.G = t->G;      // null for the linear selector
         const int blocks = (n + 3) / 4;
         if (K <= 64) train_row_kernel<1><<<blocks, 256, 0, st>>>(a);
         else if (K <= 256) train_row_kernel<4><<<blocks, 256, 0, st>>>(a);
         else if (K <= 1024) train_row_kernel<16><<<blocks, 256, 0, st>>>(a);
         else train_row_kernel<0><<<blocks, 256, 0, st>>>(a);
         if ((e = hipGetLastError()) != hipSuccess) goto fail;
+    }
+    if (t->Hs) {
+        // g = relu(X Ws^T + cs), then score, loss and gradients per sample
+        g = GemmArgs{}; g.A = t->X; g.lda = t->Sx; g.B = t->Ws; g.ldb = t->Sx; g.M = n; g.N = t->Hs; g.Kd = t->Sx;
+        g.out = t->g; g.ldo = t->Hs; g.bias = t->cs;
+        if ((e = launch_gemm<false, true, EPI_BIAS_RELU>(t, g, st)) != hipSuccess) goto fail;
+        TrainSelHiddenArgs sh;
+        sh.g = t->g; sh.dg = t->dg; sh.vs = t->vs; sh.bs = t->bs; sh.G = t->G; sh.n = n; sh.Hs = t->Hs;
+        sh.fp_weight = params->fp_weight; sh.du = t->du; sh.ls = t->ls;
+        train_selector_hidden_kernel<<<(n + 3) / 4, 256, 0, st>>>(sh);
+        if ((e = hipGetLastError()) != hipSuccess) goto fail;
+        // Ws -= lr dg^T X
+        g = GemmArgs{}; g.A = t->dg; g.lda = t->Hs; g.B = t->X; g.ldb = t->Sx; g.M = t->Hs; g.N = t->Sx; g.Kd = n;
+        g.out = t->Ws; g.ldo = t->Sx; g.lr = lr;
+        if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
     }
     // dh = (dz W2) where h > 0      (uses W2 before its update)
     g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = t->W2; g.ldb = H; g.M = n; g.N = H; g.Kd = K;
@@ -184,8 +228,13 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
         c.n = n; c.lr = lr;
         c.job[0] = ColsumJob{t->z, K, K, nullptr, t->b2, 0};
         c.job[1] = ColsumJob{t->dh, H, H, nullptr, t->b1, 0};
-        c.job[2] = ColsumJob{pooled, ld_pooled, C, t->du, t->ws, 0};
-        c.job[3] = ColsumJob{t->q, K, K, t->du, t->ws + C, 0};
+        if (t->Hs) {
+            c.job[2] = ColsumJob{t->dg, t->Hs, t->Hs, nullptr, t->cs, 0};
+            c.job[3] = ColsumJob{t->g, t->Hs, t->Hs, t->du, t->vs, 0};
+        } else {
+            c.job[2] = ColsumJob{pooled, ld_pooled, C, t->du, t->ws, 0};
+            c.job[3] = ColsumJob{t->q, K, K, t->du, t->ws + C, 0};
+        }
         int blocks = 0;
         for (int j = 0; j < 4; ++j) { c.job[j].first_block = blocks; blocks += (c.job[j].cols + 63) / 64; }
         train_colsums_kernel<<<blocks, 1024, 0, st>>>(c);
@@ -200,16 +249,30 @@ fail:
 
 gati_status_t gati_trainer_get_weights(gati_trainer_t* t, float* W1, float* b1, float* W2, float* b2,
                                        float* ws, float* bs) {
-    if (!t || !W1 || !b1 || !W2 || !b2 || !ws || !bs) return GATI_ERR_INVALID_ARG;
+    if (!t || !W1 || !b1 || !W2 || !b2 || !bs || (!t->Hs && !ws)) return GATI_ERR_INVALID_ARG;
     if (!on_trainer_device(t)) return GATI_ERR_DEVICE;
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
     const size_t C = t->C, H = t->H, K = t->K;
     struct { float* dst; const float* src; size_t n; } cp[] = {
-        {W1, t->W1, H * C}, {b1, t->b1, H}, {W2, t->W2, K * H}, {b2, t->b2, K}, {ws, t->ws, C + K}, {bs, t->bs, 1}};
+        {W1, t->W1, H * C}, {b1, t->b1, H}, {W2, t->W2, K * H}, {b2, t->b2, K}, {ws, t->ws, t->Hs ? 0 : C + K}, {bs, t->bs, 1}};
     for (auto& c : cp)
-        if (hipMemcpy(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
+        if (c.n && hipMemcpy(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
             (void)hipGetLastError(); return GATI_ERR_DEVICE;
         }
+    return GATI_OK;
+}
+
+gati_status_t gati_trainer_get_hidden_selector(gati_trainer_t* t, float* Ws, float* cs, float* vs) {
+    if (!t || !Ws || !cs || !vs) return GATI_ERR_INVALID_ARG;
+    if (!t->Hs) return GATI_ERR_UNSUPPORTED;
+    if (!on_trainer_device(t)) return GATI_ERR_DEVICE;
+    if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+    const size_t w = (size_t)(t->C + t->K) * sizeof(float);
+    if (hipMemcpy2D(Ws, w, t->Ws, (size_t)t->Sx * sizeof(float), w, t->Hs, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(cs, t->cs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(vs, t->vs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError(); return GATI_ERR_DEVICE;
+    }
     return GATI_OK;
 }
 

@@ -173,6 +173,10 @@ struct TrainRowArgs {
     const float* bs;       // device scalar
     int n, C, K;
     float alpha, fp_weight;
+    // selector with a hidden layer: this kernel only prepares its input rows X = [p ; q] and the ground
+    // truth, and train_selector_hidden_kernel does the rest (X null: the linear selector, finished here)
+    float* X; int ldx;     // [n][ldx]
+    float* G;              // [n] 1.0 where argmax z == argmax Y
     float* du;             // [n] d(selector loss)/d(score)
     float* lp;             // [n] predictor loss term (not yet divided by n)
     float* ls;             // [n] selector loss term
@@ -215,7 +219,10 @@ __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
     }
     // the selector's feature half does not depend on the softmax: issue its loads early
     float u = 0.0f;
-    for (int c = lane; c < a.C; c += 64) u += a.ws[c] * p[c];
+    const bool hidden = a.X != nullptr;                      // uniform
+    float* x = hidden ? a.X + (size_t)row * a.ldx : nullptr;
+    if (hidden) for (int c = lane; c < a.C; c += 64) x[c] = p[c];
+    else for (int c = lane; c < a.C; c += 64) u += a.ws[c] * p[c];
 
     float zm = -INFINITY, ym = -INFINITY;
     int zi = 0x7fffffff, yi = 0x7fffffff;
@@ -251,18 +258,58 @@ __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
             const float qk = expf(zc) * inv_se;
             const float tk = a.alpha * yv + (k == label ? 1.0f - a.alpha : 0.0f);
             lp -= tk * (zc - log_se);
-            u += a.ws[a.C + k] * qk;
+            if (hidden) x[a.C + k] = qk;
+            else u += a.ws[a.C + k] * qk;
             q[k] = qk;
             z[k] = (qk - tk) * inv_n;
         }
     }
     lp = wave_sum(lp);
+    if (hidden) {
+        if (lane == 0) { a.lp[row] = lp; a.G[row] = zi == yi ? 1.0f : 0.0f; }
+        return;
+    }
     u = wave_sum(u) + *a.bs;
     if (lane == 0) {
         const float conf = 1.0f / (1.0f + expf(-u));
         const float G = zi == yi ? 1.0f : 0.0f;
         a.du[row] = (G * (conf - 1.0f) + a.fp_weight * (1.0f - G) * conf) * inv_n;
         a.lp[row] = lp;
+        a.ls[row] = G * softplus(-u) + a.fp_weight * (1.0f - G) * softplus(u);
+    }
+}
+
+// Selector with a hidden layer (Section 3, "Selector Network Design"), one wave per sample: from the
+// hidden vector g = relu(Ws [p ; q] + cs) (a product kernel wrote it) the score u = vs . g + bs, the
+// confidence, the weighted cross-entropy term, its gradient du with respect to u, and the gradient
+// with respect to the hidden pre-activations, dg_j = du vs_j [g_j > 0].
+struct TrainSelHiddenArgs {
+    const float* g;        // [n][Hs]
+    float* dg;             // [n][Hs] out
+    const float* vs;       // [Hs]
+    const float* bs;       // device scalar
+    const float* G;        // [n]
+    int n, Hs;
+    float fp_weight;
+    float* du;             // [n]
+    float* ls;             // [n]
+};
+
+__global__ __launch_bounds__(256) void train_selector_hidden_kernel(TrainSelHiddenArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.n) return;
+    const float* g = a.g + (size_t)row * a.Hs;
+    float u = 0.0f;
+    for (int j = lane; j < a.Hs; j += 64) u += a.vs[j] * g[j];
+    u = wave_sum(u) + *a.bs;
+    const float conf = 1.0f / (1.0f + expf(-u));
+    const float G = a.G[row];
+    const float du = (G * (conf - 1.0f) + a.fp_weight * (1.0f - G) * conf) / (float)a.n;
+    float* dg = a.dg + (size_t)row * a.Hs;
+    for (int j = lane; j < a.Hs; j += 64) dg[j] = g[j] > 0.0f ? du * a.vs[j] : 0.0f;
+    if (lane == 0) {
+        a.du[row] = du;
         a.ls[row] = G * softplus(-u) + a.fp_weight * (1.0f - G) * softplus(u);
     }
 }

@@ -76,6 +76,10 @@ def test_trainer_calls_reject_bad_arguments_on_the_host():
     # only the pooling predictor with the linear selector can be trained
     for key, other in (("predictor", g.GATI_PRED_FC_MLP), ("selector", g.GATI_SEL_SOFTMAX)):
         assert g.gati_trainer_create(g.CacheDesc(**{**good, key: other}), w)[0] == g.GATI_ERR_UNSUPPORTED, key
+    # the hidden-layer selector needs its three arrays and a unit count
+    hid = {**good, "selector": g.GATI_SEL_HIDDEN, "selector_hidden": 8}
+    assert g.gati_trainer_create(g.CacheDesc(**hid), w)[0] == g.GATI_ERR_INVALID_ARG            # Ws, cs, vs missing
+    assert g.gati_trainer_get_hidden_selector(None, *(keep[:3])) == g.GATI_ERR_INVALID_ARG
     p = g.TrainParams(0.002, 0.5, 2.0)
     assert g.gati_trainer_step(None, 16, 4, 4, 16, 16, 4, p, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_trainer_get_weights(None, *(keep + [np.zeros(1, np.float32)])) == g.GATI_ERR_INVALID_ARG

@@ -49,7 +49,7 @@ def _margin_ok(w, pooled_ref, Y):
 
 
 def _check_update(got, want, old, grads, lr, steps=1, where=""):
-    for k in PARAMS:
+    for k in [k for k in want if k != "bs"]:
         tol = steps * (lr * G_RTOL * np.max(np.abs(grads[k])) + ULP * np.max(np.abs(old[k])))
         err = np.max(np.abs(got[k].astype(np.float64) - want[k]))
         assert err <= tol, f"{where}: {k} max abs err {err} > {tol}"
@@ -153,6 +153,94 @@ def test_odd_shapes_cover_every_kernel_path(C, H, K, n):
     lg = losses.cpu().numpy()
     assert abs(lg[0] - lp) <= 1e-5 * max(1.0, abs(lp)) and abs(lg[1] - ls) <= 1e-5 * max(1.0, abs(ls))
     tr.close()
+
+
+def _hidden_case(C, H, K, Hs, n, seed):
+    rng = np.random.default_rng(seed)
+    w = {"W1": (rng.standard_normal((H, C)) * np.sqrt(2.0 / C)).astype(np.float32),
+         "b1": (rng.standard_normal(H) * 0.1).astype(np.float32),
+         "W2": (rng.standard_normal((K, H)) * np.sqrt(2.0 / H)).astype(np.float32),
+         "b2": (rng.standard_normal(K) * 0.1).astype(np.float32),
+         "Ws": (rng.standard_normal((Hs, C + K)) * np.sqrt(2.0 / (C + K))).astype(np.float32),
+         "cs": (rng.standard_normal(Hs) * 0.2).astype(np.float32),
+         "vs": (rng.standard_normal(Hs) * 0.5).astype(np.float32), "bs": -0.1}
+    pooled = rng.standard_normal((n, C)).astype(np.float32)
+    labels = rng.integers(0, K, n).astype(np.int32)
+    return w, pooled, labels, W.teacher_distribution(labels, K, seed=seed)
+
+
+@pytest.mark.parametrize("C,H,K,Hs,n", [(64, 32, 10, 16, 40), (37, 20, 50, 33, 21), (256, 128, 1000, 64, 131),
+                                        (96, 48, 300, 70, 65)])
+def test_hidden_layer_selector_step(C, H, K, Hs, n):
+    """The paper's selector shape (Section 3, "Selector Network Design"): gradients with lr = 1, then
+    three more steps at a small rate."""
+    w, pooled, labels, Y = _hidden_case(C, H, K, Hs, n, seed=C + Hs)
+    assert _margin_ok(w, pooled, Y)
+    f = train.forward(w, pooled)
+    assert np.min(np.abs(f["sa"])) > 1e-6            # no hidden unit sits on the ReLU's kink
+    pd, ld, Yd = torch.from_numpy(pooled).cuda(), torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda()
+    tr = g.Trainer(C, H, K, w, max_rows=n, sel_hidden=Hs)
+    losses = torch.zeros(2, device="cuda")
+    tr.step(pd, ld, Yd, 1.0, 0.3, 2.0, losses)
+    torch.cuda.synchronize()
+    want, lp, ls = train.sgd_step(w, pooled, labels, Y, 1.0, 0.3, 2.0)
+    grads = train.gradients(w, pooled, labels, Y, 0.3, 2.0)
+    got = tr.get_weights()
+    assert set(got) == set(want)
+    _check_update(got, want, w, grads, 1.0, where=f"hidden selector C={C} Hs={Hs}")
+    lg = losses.cpu().numpy()
+    assert abs(lg[0] - lp) <= 1e-5 * max(1.0, abs(lp)) and abs(lg[1] - ls) <= 1e-5 * max(1.0, abs(ls)), (lg, lp, ls)
+    tr.close()
+    # a fresh trainer, four steps at a small rate
+    tr = g.Trainer(C, H, K, w, max_rows=n + 5, sel_hidden=Hs)
+    cur, gmax = w, None
+    for _ in range(4):
+        fc = train.forward(cur, pooled)
+        assert _margin_ok(cur, pooled, Y) and np.min(np.abs(fc["sa"])) > 1e-6
+        tr.step(pd, ld, Yd, 0.01, 0.5, 3.0)
+        gr = train.gradients(cur, pooled, labels, Y, 0.5, 3.0)
+        gmax = gr if gmax is None else {k: np.maximum(np.abs(gmax[k]), np.abs(gr[k])) for k in gr}
+        cur, _, _ = train.sgd_step(cur, pooled, labels, Y, 0.01, 0.5, 3.0)
+    torch.cuda.synchronize()
+    _check_update(tr.get_weights(), cur, w, gmax, 0.01, steps=4, where="hidden selector, 4 steps")
+    tr.close()
+
+
+def test_hidden_selector_retrain_then_serve():
+    """Retrain a resnet50_hsel cache's predictor and hidden-layer selector, swap the weights into the
+    serving cache, and look up."""
+    base = W.get_workload("resnet50_hsel")
+    n = 96
+    spec = W.WorkloadSpec(name="hsel@96", batch=n, zipf_s=base.zipf_s, seed=base.seed + 3, layers=base.layers[8:9],
+                          storage="gather")
+    L = spec.layers[0]
+    labels = W.zipf_labels(n, L.K, spec.zipf_s, spec.seed)
+    w = W.cache_weights(spec, 0)
+    act = W.activation_bulk(spec, 0, labels, np.arange(n), device="cpu")
+    Y = W.teacher_distribution(labels, L.K, spec.seed)
+    d = admit.cache_defs(spec, mirror=False)[0]
+    pooled_ref = oracle.pool(d, W.to_host_array(act))
+    cache, pooled = _gpu_pooled(L, w, act, n)
+    tr = g.Trainer(L.C, L.H, L.K, w, max_rows=n, sel_hidden=L.sel_hidden)
+    cur = {k: w[k] for k in ("W1", "b1", "W2", "b2", "Ws", "cs", "vs", "bs")}
+    for _ in range(3):
+        assert _margin_ok(cur, pooled_ref, Y)
+        tr.step(pooled, torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda(), 0.002, 0.5, 2.0)
+        cur, _, _ = train.sgd_step(cur, pooled_ref, labels, Y, 0.002, 0.5, 2.0)
+    torch.cuda.synchronize()
+    got = tr.get_weights()
+    cache.set_weights(got)
+    w32 = {k: (np.asarray(v, np.float32) if k != "bs" else float(np.float32(v))) for k, v in cur.items()}
+    want = oracle.lookup(d, w32, W.to_host_array(act))
+    pc = torch.empty(n, dtype=torch.int32, device="cuda")
+    conf = torch.empty(n, device="cuda")
+    hit = torch.empty(n, dtype=torch.uint8, device="cuda")
+    logits = torch.empty((n, L.K), device="cuda")
+    cache.lookup(act.cuda(), None, n, None, pc, conf, hit, logits)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(logits.cpu().numpy() - want["logits"])) <= 2e-2
+    assert np.max(np.abs(conf.cpu().numpy() - want["confidence"])) <= 2e-2
+    tr.close(); cache.close()
 
 
 def test_minibatch_epochs():
