@@ -19,6 +19,8 @@ ingredients, not the formulas; the reading taken here:
   update     plain SGD, theta <- theta - lr * grad, both networks in the same step, the selector
              on the predictor's outputs of BEFORE the update.
 
+  Pool(h) predictor (Section 3, table of predictor architectures: pooled windows -> one FC): weights
+             without "W1"/"b1"; `pooled` are then the ReLU'd window means and z = W2 pooled + b2.
   hidden-layer selector (Section 3, "Selector Network Design": the paper's selector has one hidden
              layer): when the weights hold "Ws", "cs", "vs" the selector is
                  g_i = relu(Ws [p_i ; q_i] + cs),  c_i = logistic(vs . g_i + bs)
@@ -33,10 +35,12 @@ import numpy as np
 
 def forward(w: dict, pooled: np.ndarray):
     p = np.asarray(pooled, np.float64)
-    W1, b1 = np.asarray(w["W1"], np.float64), np.asarray(w["b1"], np.float64)
     W2, b2 = np.asarray(w["W2"], np.float64), np.asarray(w["b2"], np.float64)
-    a = p @ W1.T + b1
-    h = np.maximum(a, 0.0)
+    if "W1" in w:
+        a = p @ np.asarray(w["W1"], np.float64).T + np.asarray(w["b1"], np.float64)
+        h = np.maximum(a, 0.0)
+    else:                         # Pool(h): the (already ReLU'd) pooled windows feed the output layer directly
+        a = h = p
     z = h @ W2.T + b2
     e = np.exp(z - z.max(axis=1, keepdims=True))
     q = e / e.sum(axis=1, keepdims=True)
@@ -84,12 +88,15 @@ def gradients(w: dict, pooled, labels, teacher, alpha: float, fp_weight: float) 
     W2 = np.asarray(w["W2"], np.float64)
     dW2 = dz.T @ f["h"]
     db2 = dz.sum(axis=0)
-    dh = (dz @ W2) * (f["a"] > 0.0)
-    dW1 = dh.T @ f["p"]
-    db1 = dh.sum(axis=0)
+    if "W1" in w:
+        dh = (dz @ W2) * (f["a"] > 0.0)
+        dW1 = dh.T @ f["p"]
+        db1 = dh.sum(axis=0)
     G = (f["z"].argmax(axis=1) == np.asarray(teacher).argmax(axis=1)).astype(np.float64)
     du = (G * (f["c"] - 1.0) + fp_weight * (1.0 - G) * f["c"]) / n
-    out = {"W1": dW1, "b1": db1, "W2": dW2, "b2": db2, "bs": float(du.sum())}
+    out = {"W2": dW2, "b2": db2, "bs": float(du.sum())}
+    if "W1" in w:
+        out.update({"W1": dW1, "b1": db1})
     if "Ws" in w:
         dg = np.outer(du, np.asarray(w["vs"], np.float64)) * (f["sa"] > 0.0)
         out.update({"vs": du @ f["g"], "Ws": dg.T @ f["x"], "cs": dg.sum(axis=0)})

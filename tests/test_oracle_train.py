@@ -160,3 +160,28 @@ def test_hidden_layer_selector_limits():
     wd = {**wh, "Ws": np.vstack([wh["Ws"], -wh["Ws"]]), "cs": np.array([big, -big - 50.0]), "vs": np.array([1.0, 0.7])}
     gd = train.gradients(wd, pooled, labels, Y, 0.3, 2.0)
     assert np.all(gd["Ws"][1] == 0.0) and gd["cs"][1] == 0.0 and gd["vs"][1] == 0.0
+
+
+def test_pool_fc_predictor_is_softmax_regression():
+    """Without a hidden layer the predictor is multinomial logistic regression on the features: the
+    gradient has the closed form (q - t)^T f / n, and it equals the two-layer network whose first layer is
+    the identity on non-negative features."""
+    w, pooled, labels, Y = _case(seed=6, n=10, C=5, H=5, K=4)
+    feats = np.abs(pooled)                                     # ReLU'd window means are non-negative
+    wp = {"W2": np.random.default_rng(1).standard_normal((4, 5)) * 0.5, "b2": w["b2"], "ws": w["ws"], "bs": w["bs"]}
+    g = train.gradients(wp, feats, labels, Y, 0.3, 2.0)
+    assert set(g) == {"W2", "b2", "ws", "bs"}
+    f = train.forward(wp, feats)
+    t = train.targets(labels, Y, 0.3)
+    assert np.allclose(g["W2"], (f["q"] - t).T @ feats / len(labels), atol=1e-15)
+    two = {**wp, "W1": np.eye(5), "b1": np.zeros(5)}
+    g2 = train.gradients(two, feats, labels, Y, 0.3, 2.0)
+    for k in ("W2", "b2", "ws"):
+        assert np.allclose(g[k], g2[k], atol=1e-15), k
+    assert train.losses(wp, feats, labels, Y, 0.3, 2.0) == train.losses(two, feats, labels, Y, 0.3, 2.0)
+    eps = 1e-6
+    bump = wp["W2"].copy(); bump[1, 2] += eps
+    low = wp["W2"].copy(); low[1, 2] -= eps
+    num = (train.losses({**wp, "W2": bump}, feats, labels, Y, 0.3, 2.0)[0] -
+           train.losses({**wp, "W2": low}, feats, labels, Y, 0.3, 2.0)[0]) / (2 * eps)
+    assert abs(num - g["W2"][1, 2]) < 1e-7
