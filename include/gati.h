@@ -233,8 +233,11 @@ const char *gati_cache_pool_variant(const gati_cache_t *cache);
  * With GATI_SEL_HIDDEN (Section 3, "Selector Network Design": the selector has one hidden layer) the
  * selector is g_i = relu(Ws [p_i ; q_i] + cs), c_i = 1/(1 + exp(-(vs . g_i + bs))) with the same loss;
  * its gradients reach Ws, cs, vs and bs through the ReLU, never q.
- * Only GATI_PRED_GAP_MLP with GATI_SEL_LINEAR or GATI_SEL_HIDDEN is supported (GATI_ERR_UNSUPPORTED
- * otherwise); act_dtype, layout, S and threshold of the descriptor are ignored.                    */
+ * With GATI_PRED_POOL_FC (the paper's Pool(h)) there is no hidden layer: p are the C*out_h*out_w ReLU'd
+ * window means gati_cache_pool writes for such a cache, z = W2 p + b2, and W1, b1 are not used (NULL).
+ * GATI_PRED_GAP_MLP and GATI_PRED_POOL_FC with GATI_SEL_LINEAR or GATI_SEL_HIDDEN are supported
+ * (GATI_ERR_UNSUPPORTED otherwise); act_dtype, layout, S, in_h, in_w and threshold of the descriptor
+ * are ignored.                                                                                     */
 typedef struct gati_trainer gati_trainer_t; /* opaque, owned by the library */
 
 typedef struct {
@@ -252,7 +255,8 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t *desc, const gati_cach
 gati_status_t gati_trainer_destroy(gati_trainer_t *trainer);
 
 /* Enqueue one SGD step on `stream`.
- *   pooled      device [n, ld_pooled] fp32, ld_pooled >= C: row i holds sample i's C pooled features
+ *   pooled      device [n, ld_pooled] fp32, ld_pooled >= F: row i holds sample i's F features (F = C, or
+ *               C*out_h*out_w for GATI_PRED_POOL_FC)
  *   n           host count, 0 <= n <= max_rows (0: nothing happens)
  *   labels      device [n] int32 true class, in [0, K)
  *   teacher     device [n, ld_teacher] fp32, ld_teacher >= K: the base DNN's class probabilities
@@ -266,7 +270,8 @@ gati_status_t gati_trainer_step(gati_trainer_t *trainer, const float *pooled, in
 
 /* Copy the current weights to HOST arrays W1 [H, C], b1 [H], W2 [K, H], b2 [K], ws [C + K] and
  * *bs, after waiting for all work on the device.  A trainer with a hidden-layer selector has no ws
- * (NULL is accepted there); its selector comes from gati_trainer_get_hidden_selector. */
+ * (NULL is accepted there); its selector comes from gati_trainer_get_hidden_selector.  A
+ * GATI_PRED_POOL_FC trainer has no W1, b1 (NULL accepted); its W2 is [K, F] and ws [F + K]. */
 gati_status_t gati_trainer_get_weights(gati_trainer_t *trainer, float *W1, float *b1, float *W2, float *b2,
                                        float *ws, float *bs);
 

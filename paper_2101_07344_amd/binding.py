@@ -319,25 +319,34 @@ class Trainer:
     """SGD steps on one cache's predictor and selector (pooling predictor; linear selector, or the
     hidden-layer selector when sel_hidden > 0 and the weights hold Ws, cs, vs)."""
 
-    def __init__(self, C_: int, H: int, K: int, weights: dict, max_rows: int, sel_hidden: int = 0):
-        names = ("W1", "b1", "W2", "b2") + (("Ws", "cs", "vs") if sel_hidden else ("ws",))
+    def __init__(self, C_: int, H: int, K: int, weights: dict, max_rows: int, sel_hidden: int = 0,
+                 predictor: str = "gap_mlp", out_hw=(0, 0)):
+        """predictor "pool_fc" (the paper's Pool(h)): no hidden layer, H is ignored, the features are the
+        C_*out_h*out_w window means and W2 is [K, F]."""
+        pool_fc = predictor == "pool_fc"
+        assert predictor in ("gap_mlp", "pool_fc")
+        F = C_ * out_hw[0] * out_hw[1] if pool_fc else C_
+        H = 0 if pool_fc else H
+        names = (("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")) + (("Ws", "cs", "vs") if sel_hidden else ("ws",))
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
-        assert keep["W1"].shape == (H, C_) and keep["b1"].shape == (H,) and keep["W2"].shape == (K, H)
-        assert keep["b2"].shape == (K,)
+        if not pool_fc:
+            assert keep["W1"].shape == (H, C_) and keep["b1"].shape == (H,)
+        assert keep["W2"].shape == (K, F if pool_fc else H) and keep["b2"].shape == (K,)
         if sel_hidden:
-            assert keep["Ws"].shape == (sel_hidden, C_ + K) and keep["cs"].shape == (sel_hidden,) \
+            assert keep["Ws"].shape == (sel_hidden, F + K) and keep["cs"].shape == (sel_hidden,) \
                 and keep["vs"].shape == (sel_hidden,)
         else:
-            assert keep["ws"].shape == (C_ + K,)
+            assert keep["ws"].shape == (F + K,)
         desc = CacheDesc(C_, 1, H, K, GATI_F32, GATI_LAYOUT_NCS, 0.5, max_rows,
-                         GATI_SEL_HIDDEN if sel_hidden else GATI_SEL_LINEAR, GATI_PRED_GAP_MLP, 0, 0, 0, 0,
+                         GATI_SEL_HIDDEN if sel_hidden else GATI_SEL_LINEAR,
+                         GATI_PRED_POOL_FC if pool_fc else GATI_PRED_GAP_MLP, 0, 0, int(out_hw[0]), int(out_hw[1]),
                          int(sel_hidden), 0, 0)
         ptr = lambda k: keep[k].ctypes.data if k in keep else None
         w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]),
                          ptr("Ws"), ptr("cs"), ptr("vs"))
         st, self.handle = gati_trainer_create(desc, w)
         _check(st, "gati_trainer_create")
-        self.C, self.H, self.K, self.max_rows, self.sel_hidden = C_, H, K, max_rows, int(sel_hidden)
+        self.C, self.H, self.K, self.max_rows, self.sel_hidden = F, H, K, max_rows, int(sel_hidden)
 
     def step(self, pooled, labels, teacher, lr: float, alpha: float, fp_weight: float, losses=None, stream=None,
              n: Optional[int] = None):
@@ -364,12 +373,13 @@ class Trainer:
                           None if losses is None else losses[e, b], stream)
 
     def get_weights(self) -> dict:
-        out = {"W1": np.empty((self.H, self.C), np.float32), "b1": np.empty(self.H, np.float32),
-               "W2": np.empty((self.K, self.H), np.float32), "b2": np.empty(self.K, np.float32)}
+        out = {"W2": np.empty((self.K, self.H if self.H else self.C), np.float32), "b2": np.empty(self.K, np.float32)}
+        if self.H:
+            out.update({"W1": np.empty((self.H, self.C), np.float32), "b1": np.empty(self.H, np.float32)})
         if not self.sel_hidden:
             out["ws"] = np.empty(self.C + self.K, np.float32)
         bs = np.empty(1, np.float32)
-        _check(gati_trainer_get_weights(self.handle, out["W1"], out["b1"], out["W2"], out["b2"], out.get("ws"), bs),
+        _check(gati_trainer_get_weights(self.handle, out.get("W1"), out.get("b1"), out["W2"], out["b2"], out.get("ws"), bs),
                "gati_trainer_get_weights")
         out["bs"] = float(bs[0])
         if self.sel_hidden:

@@ -91,16 +91,23 @@ extern "C" {
 gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cache_weights_t* w,
                                   gati_trainer_t** out) {
     if (!desc || !w || !out) return GATI_ERR_INVALID_ARG;
-    if (desc->C <= 0 || desc->H <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
-    if (!w->W1 || !w->b1 || !w->W2 || !w->b2) return GATI_ERR_INVALID_ARG;
-    if (desc->predictor != GATI_PRED_GAP_MLP) return GATI_ERR_UNSUPPORTED;
+    if (desc->C <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
+    if (desc->predictor != GATI_PRED_GAP_MLP && desc->predictor != GATI_PRED_POOL_FC) return GATI_ERR_UNSUPPORTED;
+    // Pool(h): no hidden layer; the features are the C * out_h * out_w pooled windows
+    const bool pool_fc = desc->predictor == GATI_PRED_POOL_FC;
+    if (pool_fc ? (desc->out_h <= 0 || desc->out_w <= 0 || (long)desc->C * desc->out_h * desc->out_w > (1L << 24))
+                : (desc->H <= 0 || !w->W1 || !w->b1))
+        return GATI_ERR_INVALID_ARG;
+    if (!w->W2 || !w->b2) return GATI_ERR_INVALID_ARG;
     if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_HIDDEN) return GATI_ERR_UNSUPPORTED;
     const bool hidden = desc->selector == GATI_SEL_HIDDEN;
     if (hidden ? (!w->Ws || !w->cs || !w->vs || desc->selector_hidden <= 0 || desc->selector_hidden > 4096) : !w->ws)
         return GATI_ERR_INVALID_ARG;
     gati_trainer* t = new (std::nothrow) gati_trainer;
     if (!t) return GATI_ERR_OOM;
-    t->C = desc->C; t->H = desc->H; t->K = desc->K; t->max_rows = desc->max_rows;
+    t->C = pool_fc ? desc->C * desc->out_h * desc->out_w : desc->C;      // features per sample
+    t->H = pool_fc ? 0 : desc->H;                                         // 0: no hidden layer
+    t->K = desc->K; t->max_rows = desc->max_rows;
     if (hipGetDevice(&t->device) != hipSuccess) { (void)hipGetLastError(); delete t; return GATI_ERR_DEVICE; }
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device) == hipSuccess && cus > 0)
@@ -110,15 +117,15 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
     t->Hs = hidden ? desc->selector_hidden : 0;
     t->Sx = hidden ? (int)((C + K + 3) / 4 * 4) : 0;
     const size_t Hs = t->Hs, Sx = t->Sx;
-    const size_t mn[7] = {n * H, n * K, n * H, K * H, H * C, n * Hs, Hs * Sx};
+    const size_t mn[7] = {n * H, n * K, n * H, K * (H ? H : C), H * C, n * Hs, Hs * Sx};
     t->part_floats = 0;
     for (size_t v : mn) t->part_floats = std::max(t->part_floats, v * kMaxSlices);
     t->part_floats = std::min<size_t>(t->part_floats, (size_t)64 << 20);   // 256 MB at most; fewer slices beyond
     gati_status_t st = GATI_OK;
     auto take = [&](gati_status_t s) { if (st == GATI_OK) st = s; };
-    take(dev_alloc(&t->W1, H * C, w->W1));
-    take(dev_alloc(&t->b1, H, w->b1));
-    take(dev_alloc(&t->W2, K * H, w->W2));
+    take(dev_alloc(&t->W1, H * C, H ? w->W1 : nullptr));
+    take(dev_alloc(&t->b1, H, H ? w->b1 : nullptr));
+    take(dev_alloc(&t->W2, K * (H ? H : C), w->W2));
     take(dev_alloc(&t->b2, K, w->b2));
     if (!hidden) take(dev_alloc(&t->ws, C + K, w->ws));
     take(dev_alloc(&t->bs, 1, &w->bs));
@@ -174,12 +181,16 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
     const float lr = params->lr;
     hipError_t e;
     GemmArgs g{};
-    // h = relu(p W1^T + b1)
-    g = GemmArgs{}; g.A = pooled; g.lda = ld_pooled; g.B = t->W1; g.ldb = C; g.M = n; g.N = H; g.Kd = C;
-    g.out = t->h; g.ldo = H; g.bias = t->b1;
-    if ((e = launch_gemm<false, true, EPI_BIAS_RELU>(t, g, st)) != hipSuccess) goto fail;
+    // the layer that feeds the output FC: h = relu(p W1^T + b1), or the features themselves (Pool(h))
+    const float* hin = H ? t->h : pooled;
+    const int ldh = H ? H : ld_pooled, Hin = H ? H : C;
+    if (H) {
+        g = GemmArgs{}; g.A = pooled; g.lda = ld_pooled; g.B = t->W1; g.ldb = C; g.M = n; g.N = H; g.Kd = C;
+        g.out = t->h; g.ldo = H; g.bias = t->b1;
+        if ((e = launch_gemm<false, true, EPI_BIAS_RELU>(t, g, st)) != hipSuccess) goto fail;
+    }
     // z = h W2^T + b2
-    g = GemmArgs{}; g.A = t->h; g.lda = H; g.B = t->W2; g.ldb = H; g.M = n; g.N = K; g.Kd = H;
+    g = GemmArgs{}; g.A = hin; g.lda = ldh; g.B = t->W2; g.ldb = Hin; g.M = n; g.N = K; g.Kd = Hin;
     g.out = t->z; g.ldo = K; g.bias = t->b2;
     if ((e = launch_gemm<false, true, EPI_BIAS>(t, g, st)) != hipSuccess) goto fail;
     {
@@ -210,18 +221,22 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
         g.out = t->Ws; g.ldo = t->Sx; g.lr = lr;
         if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
     }
-    // dh = (dz W2) where h > 0      (uses W2 before its update)
-    g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = t->W2; g.ldb = H; g.M = n; g.N = H; g.Kd = K;
-    g.out = t->dh; g.ldo = H; g.mask = t->h;
-    if ((e = launch_gemm<false, false, EPI_MASK>(t, g, st)) != hipSuccess) goto fail;
+    if (H) {
+        // dh = (dz W2) where h > 0      (uses W2 before its update)
+        g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = t->W2; g.ldb = H; g.M = n; g.N = H; g.Kd = K;
+        g.out = t->dh; g.ldo = H; g.mask = t->h;
+        if ((e = launch_gemm<false, false, EPI_MASK>(t, g, st)) != hipSuccess) goto fail;
+    }
     // W2 -= lr dz^T h
-    g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = t->h; g.ldb = H; g.M = K; g.N = H; g.Kd = n;
-    g.out = t->W2; g.ldo = H; g.lr = lr;
+    g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = hin; g.ldb = ldh; g.M = K; g.N = Hin; g.Kd = n;
+    g.out = t->W2; g.ldo = Hin; g.lr = lr;
     if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
-    // W1 -= lr dh^T p
-    g = GemmArgs{}; g.A = t->dh; g.lda = H; g.B = pooled; g.ldb = ld_pooled; g.M = H; g.N = C; g.Kd = n;
-    g.out = t->W1; g.ldo = C; g.lr = lr;
-    if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
+    if (H) {
+        // W1 -= lr dh^T p
+        g = GemmArgs{}; g.A = t->dh; g.lda = H; g.B = pooled; g.ldb = ld_pooled; g.M = H; g.N = C; g.Kd = n;
+        g.out = t->W1; g.ldo = C; g.lr = lr;
+        if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
+    }
     // biases and selector
     {
         ColsumArgs c;
@@ -249,12 +264,12 @@ fail:
 
 gati_status_t gati_trainer_get_weights(gati_trainer_t* t, float* W1, float* b1, float* W2, float* b2,
                                        float* ws, float* bs) {
-    if (!t || !W1 || !b1 || !W2 || !b2 || !bs || (!t->Hs && !ws)) return GATI_ERR_INVALID_ARG;
+    if (!t || !W2 || !b2 || !bs || (!t->Hs && !ws) || (t->H && (!W1 || !b1))) return GATI_ERR_INVALID_ARG;
     if (!on_trainer_device(t)) return GATI_ERR_DEVICE;
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
     const size_t C = t->C, H = t->H, K = t->K;
     struct { float* dst; const float* src; size_t n; } cp[] = {
-        {W1, t->W1, H * C}, {b1, t->b1, H}, {W2, t->W2, K * H}, {b2, t->b2, K}, {ws, t->ws, t->Hs ? 0 : C + K}, {bs, t->bs, 1}};
+        {W1, t->W1, H * C}, {b1, t->b1, H}, {W2, t->W2, K * (H ? H : C)}, {b2, t->b2, K}, {ws, t->ws, t->Hs ? 0 : C + K}, {bs, t->bs, 1}};
     for (auto& c : cp)
         if (c.n && hipMemcpy(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
             (void)hipGetLastError(); return GATI_ERR_DEVICE;

@@ -243,6 +243,47 @@ def test_hidden_selector_retrain_then_serve():
     tr.close(); cache.close()
 
 
+@pytest.mark.parametrize("layer,n,sel_hidden", [(3, 64, 0), (13, 50, 0), (8, 40, 24)])
+def test_pool_fc_predictor_step(layer, n, sel_hidden):
+    """The paper's Pool(h) predictor (no hidden layer): features from gati_cache_pool of a Pool(h)
+    cache, one step with lr = 1, then the retrained weights serve lookups."""
+    base = W.get_workload("resnet50_pool")
+    spec = W.WorkloadSpec(name=f"pool@{n}", batch=n, zipf_s=base.zipf_s, seed=base.seed + 5,
+                          layers=base.layers[layer:layer + 1], storage="gather")
+    L = spec.layers[0]
+    labels = W.zipf_labels(n, L.K, spec.zipf_s, spec.seed)
+    w = W.cache_weights(spec, 0)
+    act = W.activation_bulk(spec, 0, labels, np.arange(n), device="cpu")
+    Y = W.teacher_distribution(labels, L.K, spec.seed)
+    d = admit.cache_defs(spec, mirror=False)[0]
+    feats_ref = oracle.pool(d, W.to_host_array(act))
+    F = feats_ref.shape[1]
+    wt = {"W2": w["W2"], "b2": w["b2"], "bs": w["bs"]}
+    if sel_hidden:
+        rng = np.random.default_rng(layer)
+        wt.update({"Ws": (rng.standard_normal((sel_hidden, F + L.K)) * np.sqrt(2.0 / (F + L.K))).astype(np.float32),
+                   "cs": (rng.standard_normal(sel_hidden) * 0.2).astype(np.float32),
+                   "vs": (rng.standard_normal(sel_hidden) * 0.5).astype(np.float32)})
+    else:
+        wt["ws"] = w["ws"]
+    assert _margin_ok(wt, feats_ref, Y)
+    cache = g.Cache.from_layer(L, w, n)
+    feats = torch.empty((n, F), device="cuda")
+    cache.pool(act.cuda(), None, n, None, feats)
+    tr = g.Trainer(L.C, 0, L.K, wt, max_rows=n, sel_hidden=sel_hidden, predictor="pool_fc", out_hw=L.out_hw)
+    losses = torch.zeros(2, device="cuda")
+    tr.step(feats, torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda(), 1.0, 0.4, 2.0, losses)
+    torch.cuda.synchronize()
+    got = tr.get_weights()
+    want, lp, ls = train.sgd_step(wt, feats_ref, labels, Y, 1.0, 0.4, 2.0)
+    grads = train.gradients(wt, feats_ref, labels, Y, 0.4, 2.0)
+    assert set(got) == set(want)
+    _check_update(got, want, wt, grads, 1.0, where=f"pool_fc layer {layer}")
+    lg = losses.cpu().numpy()
+    assert abs(lg[0] - lp) <= 1e-5 * max(1.0, abs(lp)) and abs(lg[1] - ls) <= 1e-5 * max(1.0, abs(ls))
+    tr.close(); cache.close()
+
+
 def test_minibatch_epochs():
     """Two epochs over 150 samples in batches of 64 (64 + 64 + 22): sliced inputs, ragged last batch."""
     lr, alpha, lam = 0.01, 0.4, 2.0
