@@ -425,12 +425,15 @@ def time_training(spec, weights, caches, acts, torch, g, W, with_cpu, reps=10):
     lab_d, Y_d = torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda()
     out, seen = [], set()
     for l, L in enumerate(spec.layers):
-        if L.C in seen or L.predictor != "gap_mlp" or L.selector != "linear":
+        if (L.C, L.F) in seen or L.predictor not in ("gap_mlp", "pool_fc") or L.selector not in ("linear", "hidden"):
             continue
-        seen.add(L.C)
-        pooled = torch.empty((n, L.C), device="cuda")
+        seen.add((L.C, L.F))
+        pool_fc, hid = L.predictor == "pool_fc", (L.sel_hidden if L.selector == "hidden" else 0)
+        F, Hd = L.F, (0 if pool_fc else L.H)
+        pooled = torch.empty((n, F), device="cuda")
         caches[l].pool(acts[l], None, n, None, pooled)
-        tr = g.Trainer(L.C, L.H, L.K, weights[l], max_rows=n)
+        tr = g.Trainer(L.C, Hd, L.K, weights[l], max_rows=n, sel_hidden=hid,
+                       predictor=L.predictor, out_hw=getattr(L, "out_hw", (0, 0)))
         losses = torch.zeros(2, device="cuda")
         for _ in range(3):
             tr.step(pooled, lab_d, Y_d, 0.002, 0.5, 2.0, losses)
@@ -441,14 +444,18 @@ def time_training(spec, weights, caches, acts, torch, g, W, with_cpu, reps=10):
         ev[1].record()
         torch.cuda.synchronize()
         us = ev[0].elapsed_time(ev[1]) / reps * 1e3
-        flops = 2 * n * (L.C * L.H + L.H * L.K) + 2 * n * L.H * L.K + 2 * n * (L.K * L.H + L.H * L.C)
-        row = {"layer": l, "C": L.C, "H": L.H, "K": L.K, "n": n, "step_us": round(us, 1),
+        # forward + backward products: predictor (3x the forward of each layer, the first layer's input gradient
+        # is not needed), hidden-layer selector (forward + weight gradient)
+        flops = (6 * n * Hd * L.K + 4 * n * F * Hd) if Hd else 4 * n * F * L.K
+        flops += 4 * n * (F + L.K) * hid
+        row = {"layer": l, "F": F, "H": Hd, "K": L.K, "selector_hidden": hid, "n": n, "step_us": round(us, 1),
                "TFLOPs": round(flops / (us * 1e-6) / 1e12, 2), "frac_of_fp32_mfma_peak": round(flops / (us * 1e-6) / 1e12 / 157.3, 4)}
         if with_cpu and len(out) == 0:            # CPU baseline leg: the fp64 oracle's step on the same batch
             from oracle import train as otrain
             p_host = pooled.cpu().numpy()
             t0 = time.perf_counter()
-            otrain.sgd_step(weights[l], p_host, labels, Y, 0.002, 0.5, 2.0)
+            keys = (("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")) + (("Ws", "cs", "vs") if hid else ("ws",)) + ("bs",)
+            otrain.sgd_step({k: weights[l][k] for k in keys}, p_host, labels, Y, 0.002, 0.5, 2.0)
             row["oracle_cpu_ms"] = round((time.perf_counter() - t0) * 1e3, 1)
         out.append(row)
         tr.close()
