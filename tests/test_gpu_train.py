@@ -307,6 +307,30 @@ def test_minibatch_epochs():
     tr.close(); cache.close()
 
 
+def test_steps_are_bit_reproducible():
+    """No float atomics, every reduction in a fixed order: two trainers fed the same three steps end
+    with identical bits, for both selectors."""
+    for hid in (0, 16):
+        if hid:
+            w, pooled, labels, Y = _hidden_case(72, 40, 130, hid, 90, seed=9)
+        else:
+            spec, L, labels, w, act, Y, pooled = _inputs("resnet18", 6, 90)
+        C, H, K = w["W1"].shape[1], w["W1"].shape[0], w["W2"].shape[0]
+        pd, ld, Yd = torch.from_numpy(np.ascontiguousarray(pooled)).cuda(), torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda()
+        outs = []
+        for _ in range(2):
+            tr = g.Trainer(C, H, K, w, max_rows=90, sel_hidden=hid)
+            losses = torch.zeros((3, 2), device="cuda")
+            for s in range(3):
+                tr.step(pd, ld, Yd, 0.05, 0.5, 2.0, losses[s])
+            torch.cuda.synchronize()
+            outs.append((tr.get_weights(), losses.cpu().numpy()))
+            tr.close()
+        for k in outs[0][0]:
+            assert np.array_equal(np.asarray(outs[0][0][k]), np.asarray(outs[1][0][k])), k
+        assert np.array_equal(outs[0][1], outs[1][1])
+
+
 def test_step_argument_checks_and_empty_batch():
     spec, L, labels, w, act, Y, pooled_ref = _inputs("tiny", 0, 8)
     tr = g.Trainer(L.C, L.H, L.K, w, max_rows=8)
