@@ -187,7 +187,13 @@ gati_status_t gati_cache_pool(gati_cache_t *cache, const void *act, const int32_
  *   n_max,n_dev as above (cache->max_rows bounds n_max when cache is not NULL; cache may be
  *               NULL, the call needs no cache state)
  *   ids_out     device [n_max] int32; must not alias ids_in
- *   n_miss_dev  device int32 scalar; may alias n_dev (it is read before it is written) */
+ *   n_miss_dev  device int32 scalar; may alias n_dev (it is read before it is written)
+ *
+ * Lists of up to 4096 entries are compacted by one workgroup in one launch.  Longer lists take two
+ * launches over many workgroups that share a 4 KB table of per-span miss counts in device memory;
+ * the library allocates that table (hipMalloc) the first time a device sees n_max > 4096 and keeps
+ * it until the process ends, so such calls must not overlap in time on one device, and the first
+ * of them must not be issued under stream capture. */
 gati_status_t gati_compact_misses(gati_cache_t *cache, const uint8_t *hit, const int32_t *ids_in,
                                   int32_t n_max, const int32_t *n_dev,
                                   int32_t *ids_out, int32_t *n_miss_dev, void *stream);

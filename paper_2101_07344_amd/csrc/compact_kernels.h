@@ -71,4 +71,76 @@ __global__ __launch_bounds__(1024) void compact_misses_kernel(CompactArgs a) {
     if (tid == 0) *a.n_miss = st.carry;
 }
 
+// ---------------------------------------------------------------------------------------
+// Long lists: two launches over many workgroups instead of one workgroup walking the list.
+// The list is cut into `chunks` equal spans of `steps` x 1024 entries; workgroup b owns span b.
+//   compact_count_kernel    counts[b] = misses in span b; also records the clamped row count, so
+//                           that the second launch never reads n_dev (which n_miss may alias)
+//   compact_scatter_kernel  offset of span b = counts[0] + ... + counts[b-1] (every workgroup adds
+//                           them up itself: at most 1024 integers), then the same stable
+//                           workgroup-wide compaction as above, starting at that offset; the last
+//                           workgroup also writes the total.
+// No workgroup waits for another one: the launch boundary is the only dependence.
+// scratch: kCompactScratchWords int32 of device memory, word 0 = row count, words 1.. = counts.
+// ---------------------------------------------------------------------------------------
+constexpr int kCompactMaxChunks = 1024;
+constexpr int kCompactScratchWords = 1 + kCompactMaxChunks;
+
+struct CompactWideArgs {
+    CompactArgs c;
+    int32_t* scratch;   // [kCompactScratchWords]
+    int steps;          // 1024-entry steps per workgroup
+};
+
+__global__ __launch_bounds__(1024) void compact_count_kernel(CompactWideArgs a) {
+    __shared__ int wave_total[16];
+    const int n = active_rows(a.c.n_dev, a.c.n_max);
+    const int tid = threadIdx.x;
+    const long first = (long)blockIdx.x * a.steps * 1024;
+    int mine = 0;
+    for (int s = 0; s < a.steps; ++s) {
+        const long i = first + (long)s * 1024 + tid;
+        mine += (i < n && a.c.hit[i] == 0) ? 1 : 0;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) mine += __shfl_xor(mine, m, 64);
+    if ((tid & 63) == 0) wave_total[tid >> 6] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += wave_total[w];
+        a.scratch[1 + blockIdx.x] = t;
+        if (blockIdx.x == 0) a.scratch[0] = n;
+    }
+}
+
+__global__ __launch_bounds__(1024) void compact_scatter_kernel(CompactWideArgs a) {
+    __shared__ CompactState<16> st;
+    __shared__ int wave_total[16];
+    const int n = a.scratch[0];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    // misses in the spans before this one (gridDim.x <= 1024: one count per lane)
+    int before = (tid < b) ? a.scratch[1 + tid] : 0;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) before += __shfl_xor(before, m, 64);
+    if ((tid & 63) == 0) wave_total[tid >> 6] = before;
+    __syncthreads();
+    if (tid == 0) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += wave_total[w];
+        st.carry = t;
+    }
+    const long first = (long)b * a.steps * 1024;
+    for (int s = 0; s < a.steps; ++s) {
+        const long i = first + (long)s * 1024 + tid;
+        const bool miss = (i < n) && (a.c.hit[i] == 0);
+        const int slot = compact_step<16>(st, miss, tid);      // its first barrier publishes st.carry
+        if (slot >= 0) a.c.ids_out[slot] = a.c.ids_in ? a.c.ids_in[i] : (int32_t)i;
+    }
+    if (b == (int)gridDim.x - 1 && tid == 0) *a.c.n_miss = st.carry;
+}
+
 }  // namespace gati

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -716,6 +717,29 @@ bool on_cache_device(const gati_cache* c) {
     return hipGetDevice(&dev) == hipSuccess && dev == c->device;
 }
 
+// ---- compaction of long lists: two launches that share a small table of per-span counts ----
+constexpr int kCompactSingleMax = 4096;   // up to here one workgroup walks the list (one launch, no table)
+constexpr int kMaxDevices = 64;
+std::mutex g_compact_mu;
+int32_t* g_compact_ws[kMaxDevices];       // gati_compact_misses: allocated on a device's first long list
+
+hipError_t launch_compact(const CompactArgs& c, int32_t* table, hipStream_t st) {
+    if (c.n_max <= kCompactSingleMax) {
+        compact_misses_kernel<<<1, 1024, 0, st>>>(c);
+        return hipGetLastError();
+    }
+    CompactWideArgs a;
+    a.c = c; a.scratch = table;
+    const long steps_total = ((long)c.n_max + 1023) / 1024;
+    a.steps = (int)((steps_total + kCompactMaxChunks - 1) / kCompactMaxChunks);
+    const int chunks = (int)((steps_total + a.steps - 1) / a.steps);   // <= kCompactMaxChunks
+    compact_count_kernel<<<chunks, 1024, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    compact_scatter_kernel<<<chunks, 1024, 0, st>>>(a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 extern "C" {
@@ -971,8 +995,20 @@ gati_status_t gati_compact_misses(gati_cache_t* c, const uint8_t* hit, const int
     if (c && !on_cache_device(c)) return GATI_ERR_DEVICE;
     CompactArgs a;
     a.hit = hit; a.ids_in = ids_in; a.n_dev = n_dev; a.n_max = n_max; a.ids_out = ids_out; a.n_miss = n_miss_dev;
-    compact_misses_kernel<<<1, 1024, 0, (hipStream_t)stream>>>(a);
-    return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+    int32_t* table = nullptr;
+    if (n_max > kCompactSingleMax) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+        if (dev < 0 || dev >= kMaxDevices) return GATI_ERR_UNSUPPORTED;
+        std::lock_guard<std::mutex> lock(g_compact_mu);
+        if (!g_compact_ws[dev]) {
+            void* p = nullptr;
+            if (hipMalloc(&p, kCompactScratchWords * sizeof(int32_t)) != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_OOM; }
+            g_compact_ws[dev] = static_cast<int32_t*>(p);
+        }
+        table = g_compact_ws[dev];
+    }
+    return launch_compact(a, table, (hipStream_t)stream) == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
 }
 
 const char* gati_cache_pool_variant(const gati_cache_t* c) {

@@ -23,7 +23,7 @@ def _run(hit, ids, n_max=None, n_dev_val=None):
     return out.cpu().numpy(), int(cnt.item())
 
 
-@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 256, 1023, 1024, 1025, 2047, 4096, 5000, 70001])
+@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 256, 1023, 1024, 1025, 2047, 4096, 4097, 5000, 8193, 70001, 1048577, 4200000])
 @pytest.mark.parametrize("rate", [0.0, 0.3, 1.0])
 def test_compaction_matches_oracle(n, rate):
     rng = np.random.default_rng(n * 3 + int(rate * 10))
@@ -54,5 +54,27 @@ def test_device_count_and_aliasing():
     assert g.gati_compact_misses(None, hd, idd, 3000, cnt, outd, cnt) == g.GATI_OK
     torch.cuda.synchronize()
     want = oracle.compact_misses(hit[:2000], ids[:2000])
+    assert int(cnt.item()) == len(want)
+    assert np.array_equal(outd.cpu().numpy()[:len(want)], want)
+
+
+def test_long_list_device_count_and_aliasing():
+    """Lists beyond one workgroup's reach (two launches over many workgroups): a device-side count
+    that ends inside a span, and the count read and written through one device scalar."""
+    rng = np.random.default_rng(7)
+    n_max = 50000
+    hit = (rng.random(n_max) < 0.4).astype(np.uint8)
+    ids = rng.permutation(n_max).astype(np.int32)
+    for n_true in (0, 1, 4096, 4097, 33333, 50000, 60000):
+        out, m = _run(hit, ids, n_max=n_max, n_dev_val=n_true)
+        want = oracle.compact_misses(hit[:min(n_true, n_max)], ids[:min(n_true, n_max)])
+        assert m == len(want) and np.array_equal(out[:m], want), n_true
+        assert np.all(out[m:] == -1)
+    hd, idd = torch.from_numpy(hit).cuda(), torch.from_numpy(ids).cuda()
+    outd = torch.zeros(n_max, dtype=torch.int32, device="cuda")
+    cnt = torch.tensor([41234], dtype=torch.int32, device="cuda")
+    assert g.gati_compact_misses(None, hd, idd, n_max, cnt, outd, cnt) == g.GATI_OK
+    torch.cuda.synchronize()
+    want = oracle.compact_misses(hit[:41234], ids[:41234])
     assert int(cnt.item()) == len(want)
     assert np.array_equal(outd.cpu().numpy()[:len(want)], want)
