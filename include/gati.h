@@ -198,6 +198,19 @@ gati_status_t gati_compact_misses(gati_cache_t *cache, const uint8_t *hit, const
                                   int32_t n_max, const int32_t *n_dev,
                                   int32_t *ids_out, int32_t *n_miss_dev, void *stream);
 
+/* gati_compact_misses for callers that cannot allocate device memory at all: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results; the
+ * table of per-span miss counts lives in a fixed array inside the library's code object (4 KB per
+ * GPU, present from load until the process ends), so no call ever allocates or frees anything.
+ * n_max above GATI_COMPACT_STATIC_MAX_ROWS is GATI_ERR_UNSUPPORTED.  Every call on a GPU uses that
+ * GPU's one array: calls with n_max > 4096 that overlap in time on one GPU (two streams, two
+ * threads) race and give wrong lists; calls on one stream are safe.  Nothing needs clearing between
+ * calls: each call writes every table entry it later reads. */
+#define GATI_COMPACT_STATIC_MAX_ROWS (1 << 22)
+gati_status_t gati_compact_misses_static(gati_cache_t *cache, const uint8_t *hit, const int32_t *ids_in,
+                                         int32_t n_max, const int32_t *n_dev,
+                                         int32_t *ids_out, int32_t *n_miss_dev, void *stream);
+
 /* gati_cache_lookup followed by gati_compact_misses on its hit flags, as one call: the last
  * kernel of the lookup also compacts (Section 1 / Appendix A.1: only the misses of one
  * layer's cache reach the next layer's).  Arguments as in the two calls above; ids_out and

@@ -15,11 +15,12 @@ GATI_F32, GATI_BF16 = 0, 1
 GATI_LAYOUT_NCS, GATI_LAYOUT_NSC = 0, 1
 GATI_SEL_LINEAR, GATI_SEL_SOFTMAX, GATI_SEL_HIDDEN = 0, 1, 2
 GATI_PRED_GAP_MLP, GATI_PRED_POOL_FC, GATI_PRED_FC_MLP, GATI_PRED_CONV_FC = 0, 1, 2, 3
+GATI_COMPACT_STATIC_MAX_ROWS = 1 << 22
 
 # every extern "C" symbol include/gati.h declares
 exported_symbols = (
     "gati_cache_create", "gati_cache_destroy", "gati_cache_set_weights", "gati_cache_set_selector", "gati_cache_lookup",
-    "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_status_string", "gati_cache_pool_variant",
+    "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_compact_misses_static", "gati_status_string", "gati_cache_pool_variant",
     "gati_trainer_create", "gati_trainer_destroy", "gati_trainer_step", "gati_trainer_get_weights",
     "gati_trainer_get_hidden_selector",
 )
@@ -87,6 +88,8 @@ def load_library():
     lib.gati_cache_pool.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.gati_compact_misses.restype = C.c_int
     lib.gati_compact_misses.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.gati_compact_misses_static.restype = C.c_int
+    lib.gati_compact_misses_static.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
     lib.gati_status_string.restype = C.c_char_p
     lib.gati_status_string.argtypes = [C.c_int]
     lib.gati_cache_pool_variant.restype = C.c_char_p
@@ -174,6 +177,11 @@ def gati_cache_pool(handle, act, row_index, n_max: int, n_dev, pooled, stream=No
 def gati_compact_misses(handle, hit, ids_in, n_max: int, n_dev, ids_out, n_miss_dev, stream=None) -> int:
     return load_library().gati_compact_misses(handle, _dptr(hit), _dptr(ids_in), int(n_max), _dptr(n_dev),
                                               _dptr(ids_out), _dptr(n_miss_dev), _stream(stream))
+
+
+def gati_compact_misses_static(handle, hit, ids_in, n_max: int, n_dev, ids_out, n_miss_dev, stream=None) -> int:
+    return load_library().gati_compact_misses_static(handle, _dptr(hit), _dptr(ids_in), int(n_max), _dptr(n_dev),
+                                                     _dptr(ids_out), _dptr(n_miss_dev), _stream(stream))
 
 
 def gati_cache_pool_variant(handle) -> str:

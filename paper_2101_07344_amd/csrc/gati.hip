@@ -722,6 +722,7 @@ constexpr int kCompactSingleMax = 4096;   // up to here one workgroup walks the 
 constexpr int kMaxDevices = 64;
 std::mutex g_compact_mu;
 int32_t* g_compact_ws[kMaxDevices];       // gati_compact_misses: allocated on a device's first long list
+int32_t* g_compact_static[kMaxDevices];   // gati_compact_misses_static: this device's copy of `scratch`
 
 hipError_t launch_compact(const CompactArgs& c, int32_t* table, hipStream_t st) {
     if (c.n_max <= kCompactSingleMax) {
@@ -741,6 +742,11 @@ hipError_t launch_compact(const CompactArgs& c, int32_t* table, hipStream_t st) 
 }
 
 }  // namespace
+
+// The count table of gati_compact_misses_static: device memory that exists from the moment the
+// library is loaded, one copy per GPU.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) int32_t scratch[kCompactScratchWords];
 
 extern "C" {
 
@@ -1008,6 +1014,33 @@ gati_status_t gati_compact_misses(gati_cache_t* c, const uint8_t* hit, const int
         }
         table = g_compact_ws[dev];
     }
+    return launch_compact(a, table, (hipStream_t)stream) == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+
+gati_status_t gati_compact_misses_static(gati_cache_t* c, const uint8_t* hit, const int32_t* ids_in, int32_t n_max,
+                                         const int32_t* n_dev, int32_t* ids_out, int32_t* n_miss_dev, void* stream) {
+    if (n_max < 0 || !n_miss_dev) return GATI_ERR_INVALID_ARG;
+    if (c && n_max > c->desc.max_rows) return GATI_ERR_INVALID_ARG;
+    if (n_max > GATI_COMPACT_STATIC_MAX_ROWS) return GATI_ERR_UNSUPPORTED;
+    if (n_max > 0 && (!hit || !ids_out)) return GATI_ERR_INVALID_ARG;
+    if (ids_in && ids_in == ids_out) return GATI_ERR_INVALID_ARG;
+    if (c && !on_cache_device(c)) return GATI_ERR_DEVICE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+    if (dev < 0 || dev >= kMaxDevices) return GATI_ERR_UNSUPPORTED;
+    int32_t* table = nullptr;
+    {
+        // first call on this device: ask the runtime where this device's copy of the array lives
+        std::lock_guard<std::mutex> lock(g_compact_mu);
+        if (!g_compact_static[dev]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+            g_compact_static[dev] = static_cast<int32_t*>(p);
+        }
+        table = g_compact_static[dev];
+    }
+    CompactArgs a;
+    a.hit = hit; a.ids_in = ids_in; a.n_dev = n_dev; a.n_max = n_max; a.ids_out = ids_out; a.n_miss = n_miss_dev;
     return launch_compact(a, table, (hipStream_t)stream) == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
 }
 

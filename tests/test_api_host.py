@@ -13,8 +13,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_is_built_and_exports_the_declared_symbols():
     lib = g.load_library()
-    with open(os.path.join(ROOT, "include", "gati.h")) as f:
-        header = f.read()
+    header = ""
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):     # every header under include/
+        assert name.endswith(".h"), name
+        with open(os.path.join(ROOT, "include", name)) as f:
+            header += f.read()
     declared = set(re.findall(r"\b(gati_[a-z_]+)\s*\(", header))
     assert declared == set(g.exported_symbols)
     for name in declared:
@@ -63,6 +66,9 @@ def test_calls_reject_null_handles_and_bad_counts_on_the_host():
     assert g.gati_compact_misses(None, None, None, 4, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_compact_misses(None, 16, 32, 4, None, 32, 16, stream=0) == g.GATI_ERR_INVALID_ARG   # in/out alias
     assert g.gati_cache_pool_variant(None) == "none"
+    assert g.gati_compact_misses_static(None, 16, None, -1, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_compact_misses_static(None, 16, None, g.GATI_COMPACT_STATIC_MAX_ROWS + 1, None, 16, 16, stream=0) \
+        == g.GATI_ERR_UNSUPPORTED
 
 
 def test_trainer_calls_reject_bad_arguments_on_the_host():
