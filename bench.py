@@ -29,9 +29,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X published dense matrix peaks
 
-# HBM traffic of the dominant pooling kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (summaries under profiles/); keyed by workload.  None until measured.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 819_310_000}
+# HBM traffic per launch of a pooling kernel instance, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this file (not re-measured by a plain run: counters need the profiler).  Keyed by
+# (workload, kernel instance); each entry names the summary under profiles/ it was read from.  The
+# figure is attached only when that instance is the dominant one of the run.
+PROFILED_TRAFFIC = {
+    ("resnet50", "ncs_wave[C=256,S=3136,bf16]"): (819_310_000, "profiles/pool_ncs_wave_bf16_resnet50_hbm_traffic.md"),
+}
 
 
 def log(*a):
@@ -214,6 +218,66 @@ def cpu_baseline(spec, weights, acts, stack, counts, budget_requests, torch, W):
                       f"({lookups} lookups, {dt:.1f} s, single thread, gcc -O2, fp64 accumulation)"}
 
 
+def cpu_baseline_all_cores(spec, weights, acts, budget_requests, torch, W):
+    """The same oracle over the same requests, sharded by request over the host cores: each shard of
+    requests goes through the whole stack on its own (requests are independent), one single-threaded
+    oracle call chain per host thread (the C library runs outside the interpreter lock).  Gather
+    storage only.  A pool sized to the machine's CPU share for one GPU, at most 16."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import admit
+    defs = admit.cache_defs(spec, mirror=True)
+    m = min(budget_requests, spec.batch)
+    threads = max(1, min(16, os.cpu_count() or 1, m))
+    host = [W.to_host_array(a[:m]) for a in acts]
+    bounds = np.linspace(0, m, threads + 1).astype(int)
+
+    def shard(k):
+        lo, hi = int(bounds[k]), int(bounds[k + 1])
+        if hi <= lo:
+            return 0
+        res = oracle.stack(defs, weights, [h[lo:hi] for h in host], hi - lo, storage="gather")
+        return int(sum(len(r.ids_in) for r in res))
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        lookups = sum(ex.map(shard, range(threads)))
+    dt = time.perf_counter() - t0
+    return {"value": lookups / dt, "unit": "lookups/s", "cores": threads, "kind": "oracle x cores",
+            "host_cpu_count": os.cpu_count(),
+            "sample": f"first {m} of {spec.batch} requests through all {len(defs)} layers, request-sharded over "
+                      f"{threads} host threads ({lookups} lookups, {dt:.2f} s)"}
+
+
+def stream_read_ceiling(acts, torch, g, min_bytes=512 << 20, reps=10):
+    """What a plain streaming read reaches on this machine, this run: the library's read-only probe kernel
+    (non-temporal 16-byte loads, nothing written) over a tensor well beyond the last-level cache."""
+    buf = acts[0] if acts[0].numel() * acts[0].element_size() >= min_bytes else torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+    nbytes = buf.numel() * buf.element_size() // 16 * 16
+    sink = torch.zeros(256 * 32 * 1024, dtype=torch.float32, device="cuda")
+    best = None
+    for bpc in (1, 2, 4, 8, 16):        # which launch shape reads fastest differs from box to box
+        for _ in range(2):
+            assert g.gati_probe_stream_read(buf, nbytes, sink, bpc) == g.GATI_OK
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.gati_probe_stream_read(buf, nbytes, sink, bpc)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        t = ts[len(ts) // 2] * 1e-3
+        if best is None or t < best[0]:
+            best = (t, bpc)
+    t, bpc = best
+    return {"GBps": round(nbytes / t / 1e9, 1), "bytes": nbytes, "us": round(t * 1e6, 1),
+            "kernel": f"probe_stream_read_kernel (gati_probe_stream_read), {bpc} workgroups per CU (best of 1, 2, 4, 8, 16), "
+                      f"median of {reps} launches"}
+
+
 def pool_yardstick(spec, acts, torch):
     """The vendor reduction (torch mean over the pooled axis, fp32 result) on layer 0's full tensor."""
     L = spec.layers[0]
@@ -258,14 +322,15 @@ def time_compaction(cache, stack, batch, torch, reps=20):
 
 
 def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False,
-                 graph=False, overlap=False, yardstick=False, train=False):
+                 graph=False, overlap=False, yardstick=False, train=False, ceiling=False):
     t_build = time.perf_counter()
     spec, labels, weights, caches, stack, acts = build_workload(name, torch, g, W)
     if copy_probe:
         dst = torch.empty_like(acts[0])
-        dst.copy_(acts[0])
+        nbytes = acts[0].numel() * acts[0].element_size()
+        assert g.gati_probe_copy(dst, acts[0], nbytes) == g.GATI_OK
         torch.cuda.synchronize()
-        log(f"[{name}] copy probe: {acts[0].numel() * acts[0].element_size()} bytes read, same written")
+        log(f"[{name}] copy probe (probe_copy_kernel): {nbytes} bytes read, same written")
         del dst
     log(f"[{name}] inputs ready in {time.perf_counter() - t_build:.1f}s "
         f"({sum(a.numel() * a.element_size() for a in acts) / 1e9:.2f} GB of activations)")
@@ -306,7 +371,8 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
     achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 if dom["ms"] > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": dom_key, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "traffic": PROFILED_TRAFFIC.get((name, dom_key), (None, None))[0],
+                "traffic_source": PROFILED_TRAFFIC.get((name, dom_key), (None, None))[1],
                 "bytes_per_launch": int(dom["bytes"] / max(1, dom["launches"])),
                 "avg_launch_us": round(dom["ms"] / max(1, dom["launches"]) * 1e3, 2),
                 "launches_per_step": dom["launches"]}
@@ -317,7 +383,7 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
         peak = MFMA_PEAK_TFLOPS[spec.layers[0].dtype]
         roofline.update({"bound": "mfma", "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s",
                          "frac": round(tf / peak, 4), "flops_per_launch": int(dom["flops"] / max(1, dom["launches"])),
-                         "hbm_GBps": round(achieved, 1), "traffic": None})
+                         "hbm_GBps": round(achieved, 1), "traffic": None, "traffic_source": None})
     pool_total_bytes = sum(k["bytes"] for k in by_kernel.values())
     pool_total_ms = sum(k["ms"] for k in by_kernel.values())
     out = {
@@ -340,8 +406,15 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
         out["graph_ms_per_step"] = round(time_graph(stack, acts, steps, warmup, torch), 4)
     if overlap and spec.storage == "gather":
         out["overlap"] = time_overlap(stack, acts, steps, warmup, torch)
+    if ceiling:
+        sc = stream_read_ceiling(acts, torch, g)
+        out["stream_read_ceiling"] = sc
+        out["roofline"]["frac_of_stream_read_ceiling"] = round(achieved / sc["GBps"], 4) if out["roofline"]["bound"] == "hbm" else None
+        out["pool_all_layers"]["frac_of_stream_read_ceiling"] = round(out["pool_all_layers"]["GBps"] / sc["GBps"], 4)
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(spec, weights, acts, stack, counts, cpu_requests, torch, W)
+        if spec.storage == "gather":
+            out["cpu_baseline_all_cores"] = cpu_baseline_all_cores(spec, weights, acts, cpu_requests, torch, W)
     if yardstick and spec.layers[0].predictor == "gap_mlp" and spec.storage == "gather":
         out["library_pool"] = pool_yardstick(spec, acts, torch)
     if train:
@@ -469,7 +542,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50",
                     help="tiny | resnet18 | resnet50 | bert_base | resnet152")
-    ap.add_argument("--also", default="bert_base",
+    ap.add_argument("--also", default="bert_base,resnet18,resnet152,tiny",
                     help="comma-separated further workloads reported under 'others' ('' for none)")
     ap.add_argument("--cpu-requests", type=int, default=512,
                     help="requests of the batch the CPU oracle is timed on")
@@ -510,7 +583,7 @@ def main():
         spec, main_res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
                                       args.cpu_requests, torch, g, W, copy_probe=args.copy_probe,
                                       graph=args.graph, overlap=args.overlap, yardstick=args.gemm_yardstick,
-                                      train=args.train)
+                                      train=args.train, ceiling=True)
         others = {}
         for name in [n for n in args.also.split(",") if n and n != args.workload]:
             _, r = run_workload(name, args.steps, args.warmup, False, 0, torch, g, W)
@@ -532,6 +605,8 @@ def main():
                    "cumulative_hit_rate": main_res["cumulative_hit_rate"]},
         "roofline": main_res["roofline"],
         "cpu_baseline": main_res.get("cpu_baseline"),
+        "cpu_baseline_all_cores": main_res.get("cpu_baseline_all_cores"),
+        "stream_read_ceiling": main_res.get("stream_read_ceiling"),
         "request_layers_per_s": main_res["request_layers_per_s"],
         "pool_all_layers": main_res["pool_all_layers"],
         "pool_kernels": main_res["pool_kernels"],

@@ -23,6 +23,7 @@ exported_symbols = (
     "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_compact_misses_static", "gati_status_string", "gati_cache_pool_variant",
     "gati_trainer_create", "gati_trainer_destroy", "gati_trainer_step", "gati_trainer_get_weights",
     "gati_trainer_get_hidden_selector",
+    "gati_probe_stream_read", "gati_probe_copy",
 )
 
 
@@ -104,6 +105,10 @@ def load_library():
     lib.gati_trainer_get_weights.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.gati_trainer_get_hidden_selector.restype = C.c_int
     lib.gati_trainer_get_hidden_selector.argtypes = [vp, vp, vp, vp]
+    lib.gati_probe_stream_read.restype = C.c_int
+    lib.gati_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
+    lib.gati_probe_copy.restype = C.c_int
+    lib.gati_probe_copy.argtypes = [vp, vp, C.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -182,6 +187,14 @@ def gati_compact_misses(handle, hit, ids_in, n_max: int, n_dev, ids_out, n_miss_
 def gati_compact_misses_static(handle, hit, ids_in, n_max: int, n_dev, ids_out, n_miss_dev, stream=None) -> int:
     return load_library().gati_compact_misses_static(handle, _dptr(hit), _dptr(ids_in), int(n_max), _dptr(n_dev),
                                                      _dptr(ids_out), _dptr(n_miss_dev), _stream(stream))
+
+
+def gati_probe_stream_read(buf, nbytes: int, sink, blocks_per_cu: int = 1, stream=None) -> int:
+    return load_library().gati_probe_stream_read(_dptr(buf), int(nbytes), _dptr(sink), int(blocks_per_cu), _stream(stream))
+
+
+def gati_probe_copy(dst, src, nbytes: int, stream=None) -> int:
+    return load_library().gati_probe_copy(_dptr(dst), _dptr(src), int(nbytes), _stream(stream))
 
 
 def gati_cache_pool_variant(handle) -> str:

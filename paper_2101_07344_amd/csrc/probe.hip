@@ -1,0 +1,65 @@
+// Measurement probes (see include/gati_probe.h): a streaming read and a plain copy of known size.
+// No part of the lookup runs through them.
+#include <hip/hip_runtime.h>
+
+#include "../../include/gati_probe.h"
+#include "common.h"
+
+using namespace gati;
+
+namespace {
+
+constexpr int kLoadsInFlight = 8;
+
+// Grid-stride over 16-byte vectors, kLoadsInFlight independent loads per lane before the first use.
+__global__ __launch_bounds__(256) void probe_stream_read_kernel(const u32x4_t* __restrict__ p, long nvec, float* sink) {
+    const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long stride = (long)gridDim.x * blockDim.x;
+    float acc = 0.f;
+    long i = tid;
+    for (; i + (kLoadsInFlight - 1) * stride < nvec; i += kLoadsInFlight * stride) {
+        u32x4_t v[kLoadsInFlight];
+#pragma unroll
+        for (int u = 0; u < kLoadsInFlight; ++u) v[u] = load_stream(p + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < kLoadsInFlight; ++u) acc += vec_sum<F32Tag>(v[u]);
+    }
+    for (; i < nvec; i += stride) acc += vec_sum<F32Tag>(load_stream(p + i));
+    if (acc == 123.456f) sink[tid] = acc;      // keeps the loads alive; never true for real data
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(u32x4_t* __restrict__ dst, const u32x4_t* __restrict__ src, long nvec) {
+    const long stride = (long)gridDim.x * blockDim.x;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
+}
+
+int cu_count() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    return cus;
+}
+
+}  // namespace
+
+extern "C" {
+
+gati_status_t gati_probe_stream_read(const void* buf, size_t bytes, float* sink, int32_t blocks_per_cu, void* stream) {
+    if (!buf || !sink || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0) return GATI_ERR_INVALID_ARG;
+    if (blocks_per_cu < 1 || blocks_per_cu > 32) return GATI_ERR_INVALID_ARG;
+    if (bytes == 0) return GATI_OK;
+    probe_stream_read_kernel<<<cu_count() * blocks_per_cu, 256, 0, (hipStream_t)stream>>>(static_cast<const u32x4_t*>(buf), (long)(bytes / 16), sink);
+    return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+
+gati_status_t gati_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || bytes % 16 != 0 || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) != 0)
+        return GATI_ERR_INVALID_ARG;
+    if (bytes == 0) return GATI_OK;
+    probe_copy_kernel<<<cu_count() * 8, 256, 0, (hipStream_t)stream>>>(static_cast<u32x4_t*>(dst), static_cast<const u32x4_t*>(src), (long)(bytes / 16));
+    return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+
+}  // extern "C"

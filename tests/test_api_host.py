@@ -69,6 +69,10 @@ def test_calls_reject_null_handles_and_bad_counts_on_the_host():
     assert g.gati_compact_misses_static(None, 16, None, -1, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_compact_misses_static(None, 16, None, g.GATI_COMPACT_STATIC_MAX_ROWS + 1, None, 16, 16, stream=0) \
         == g.GATI_ERR_UNSUPPORTED
+    assert g.gati_probe_stream_read(None, 16, 16, 1, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_probe_stream_read(16, 24, 16, 1, stream=0) == g.GATI_ERR_INVALID_ARG      # not whole 16-byte vectors
+    assert g.gati_probe_stream_read(16, 32, 16, 0, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_probe_copy(16, 24, 16, stream=0) == g.GATI_ERR_INVALID_ARG             # misaligned source
 
 
 def test_trainer_calls_reject_bad_arguments_on_the_host():
