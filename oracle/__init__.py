@@ -128,14 +128,16 @@ def _weights_c(w: dict, keep: list) -> _Weights:
 
 
 def _check_act(d: CacheDef, act: np.ndarray):
+    # Both map predictors take either storage order: position s = y*in_w + x of channel c is element
+    # [c][s] of a channel-major row and [s][c] of a channels-last row; the features are the same.
     if d.predictor == "pool_fc":
-        if d.layout != "ncs" or d.in_hw[0] * d.in_hw[1] != d.S or min(d.out_hw) < 1 or \
+        if d.in_hw[0] * d.in_hw[1] != d.S or min(d.out_hw) < 1 or \
                 d.out_hw[0] > d.in_hw[0] or d.out_hw[1] > d.in_hw[1]:
-            raise ValueError("pool_fc needs layout ncs, S = in_h*in_w and 1 <= out <= in")
+            raise ValueError("pool_fc needs S = in_h*in_w and 1 <= out <= in")
     if d.predictor == "conv_fc":
         k, s = d.conv_ks
-        if d.layout != "ncs" or d.in_hw[0] * d.in_hw[1] != d.S or k < 1 or s < 1 or k > min(d.in_hw):
-            raise ValueError("conv_fc needs layout ncs, S = in_h*in_w and 1 <= k <= min(in_h, in_w), s >= 1")
+        if d.in_hw[0] * d.in_hw[1] != d.S or k < 1 or s < 1 or k > min(d.in_hw):
+            raise ValueError("conv_fc needs S = in_h*in_w and 1 <= k <= min(in_h, in_w), s >= 1")
     want = np.uint16 if d.dtype == "bf16" else np.float32
     if act.dtype != want:
         raise TypeError(f"activation dtype {act.dtype}, cache wants {want}")

@@ -111,3 +111,24 @@ def test_bf16_arithmetic_rounds_the_filter(oracle):
     d0 = CacheDef(C=1, S=4, H=1, K=1, predictor="conv_fc", in_hw=(2, 2), conv_ks=(2, 1), dtype="bf16")
     f0 = _features(oracle, d0, _w(1, 1, 2, 1, 1, W1=[[[[1 + e, 0], [0, 0]]]]), x)
     assert f0.tolist() == [[np.float32(3 * (1 + e))]]
+
+
+def test_channels_last_map_gives_the_same_features(oracle):
+    """The map stored [position][channel]: the index probe again (a wrong stride would pick another
+    element), and equality with the channel-major result on random data."""
+    C, ih, iw, Co, k, s = 3, 5, 6, 2, 3, 2
+    oh, ow = (ih - k) // s + 1, (iw - k) // s + 1
+    x = np.array([[[100 * c + 10 * y + xx for y in range(ih) for xx in range(iw)] for c in range(C)]], np.float32)
+    xt = np.ascontiguousarray(x.transpose(0, 2, 1))
+    d_ncs = CacheDef(C=C, S=ih * iw, H=Co, K=1, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s))
+    d_nsc = CacheDef(C=C, S=ih * iw, H=Co, K=1, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s), layout="nsc")
+    for (o, c, dy, dx) in ((0, 0, 0, 0), (1, 2, k - 1, 1), (0, 1, 1, k - 1)):
+        W1 = np.zeros((Co, C, k, k), np.float32)
+        W1[o, c, dy, dx] = 1.0
+        f = _features(oracle, d_nsc, _w(C, Co, k, 1, d_nsc.F, W1=W1), xt).reshape(Co, oh, ow)
+        want = np.array([[100 * c + 10 * (oy * s + dy) + ox * s + dx for ox in range(ow)] for oy in range(oh)])
+        assert np.array_equal(f[o], want) and not f[1 - o].any()
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((2, C, ih * iw)).astype(np.float32)
+    w = _w(C, Co, k, 1, d_ncs.F, W1=rng.standard_normal((Co, C, k, k)), b1=rng.standard_normal(Co))
+    assert np.array_equal(_features(oracle, d_ncs, w, x), _features(oracle, d_nsc, w, np.ascontiguousarray(x.transpose(0, 2, 1))))

@@ -99,3 +99,25 @@ def test_pool_fc_lookup_against_library_ops(oracle):
     fb = torch.relu(torch.nn.functional.adaptive_avg_pool2d(xb.double().reshape(n, C, ih, iw), (oh, ow))).reshape(n, F).float()
     zb = fb.bfloat16().double() @ torch.from_numpy(w["W2"]).bfloat16().double().T + torch.from_numpy(w["b2"]).double()
     assert np.allclose(ob["logits"], zb.numpy(), atol=1e-5)
+
+
+def test_adaptive_pool_channels_last(oracle):
+    """The same map stored [position][channel]: identical features, bit for bit; a hand case in
+    which a wrong stride would show; the library's channels-last pooling as a third opinion."""
+    # 2 channels, 2x2 map -> 1x2.  channel-major rows: c0 = (1,2,3,4), c1 = (10,20,30,40);
+    # channels-last the row reads (1,10, 2,20, 3,30, 4,40)
+    x_ncs = np.array([[[1, 2, 3, 4], [10, 20, 30, 40]]], np.float32)
+    x_nsc = np.array([[[1, 10], [2, 20], [3, 30], [4, 40]]], np.float32)
+    want = [[2.0, 3.0, 20.0, 30.0]]                          # columns: (1+3)/2, (2+4)/2, (10+30)/2, (20+40)/2
+    assert oracle.pool(_d(2, 2, 2, 1, 2), x_ncs).tolist() == want
+    assert oracle.pool(_d(2, 2, 2, 1, 2, layout="nsc"), x_nsc).tolist() == want
+    g = np.random.default_rng(5)
+    for (C, ih, iw, oh, ow) in [(3, 7, 7, 2, 2), (4, 5, 9, 3, 2), (6, 14, 14, 4, 4)]:
+        x = g.standard_normal((2, C, ih * iw)).astype(np.float32)
+        xt = np.ascontiguousarray(x.transpose(0, 2, 1))
+        a = oracle.pool(_d(C, ih, iw, oh, ow), x)
+        b = oracle.pool(_d(C, ih, iw, oh, ow, layout="nsc"), xt)
+        assert np.array_equal(a, b), (C, ih, iw)
+        t = torch.from_numpy(x).double().reshape(2, C, ih, iw).contiguous(memory_format=torch.channels_last)
+        ref = torch.relu(torch.nn.functional.adaptive_avg_pool2d(t, (oh, ow))).reshape(2, -1).numpy()
+        assert np.allclose(b, ref, rtol=0, atol=1e-6)
