@@ -120,7 +120,8 @@ typedef struct {
     const float *b1; /* [H]                                                       */
     const float *W2; /* [K, H]                                                    */
     const float *b2; /* [K]                                                       */
-    const float *ws; /* [C + K]: weights of the pooled features first, then of the class probabilities */
+    const float *ws; /* [C + K]: weights of the pooled features first, then of the class probabilities;
+                        may be NULL for GATI_SEL_SOFTMAX and GATI_SEL_HIDDEN, which do not read it */
     float bs;        /* selector bias (GATI_SEL_HIDDEN: bias of its second layer)  */
     /* GATI_SEL_HIDDEN only (may be NULL otherwise); F = number of features, as for ws: */
     const float *Ws; /* [selector_hidden, F + K]: features first, then class probabilities */
@@ -145,8 +146,10 @@ gati_status_t gati_cache_destroy(gati_cache_t *cache);
  * lookups issued afterwards the new ones; no allocation takes place.  The threshold is kept. */
 gati_status_t gati_cache_set_weights(gati_cache_t *cache, const gati_cache_weights_t *weights);
 
-/* Replace the selector bias and threshold of an existing cache (host scalars; takes effect
- * for calls issued afterwards). */
+/* Replace the selector bias and threshold of an existing cache (host scalars).  They travel to the
+ * device as kernel arguments, so the change holds for calls enqueued after this one; launches
+ * already recorded in a captured HIP graph keep the values they were captured with (re-capture
+ * to change them). */
 gati_status_t gati_cache_set_selector(gati_cache_t *cache, float bs, float threshold);
 
 /* One lookup per active row (Section 3: prediction operation, then selection operation).
@@ -225,7 +228,7 @@ gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, co
 const char *gati_status_string(gati_status_t status);
 
 /* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_segw",
- * "ncs_seg", "nsc_row", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat", "conv_mfma",
+ * "ncs_seg", "nsc_unit", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat", "conv_mfma",
  * "conv_generic"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
 
@@ -236,12 +239,16 @@ const char *gati_cache_pool_variant(const gati_cache_t *cache);
  * master weights on the device and runs SGD steps on them; gati_trainer_get_weights +
  * gati_cache_set_weights move the result into a serving cache.
  *
+ * The paper names the ingredients of the two losses (true labels and the base DNN's class distribution
+ * for the predictor; a heavier penalty on selector false positives) and prints no formula: the target
+ * t, L_pred and L_sel below are THIS LIBRARY'S READING of Section 3, "Training Learned Caches", with
+ * alpha and fp_weight as parameters because the paper gives no values.
+ *
  * One step on a batch of n samples, all arithmetic in fp32:
  *   p        pooled features of the sample (what gati_cache_pool writes)
  *   h        = relu(W1 p + b1),  z = W2 h + b2,  q = softmax(z)
  *   target   t = (1 - alpha) onehot(label) + alpha Y          Y: the base DNN's class distribution
- *   L_pred   = -(1/n) sum_i sum_k t_ik log q_ik               (the paper's distillation-inspired loss:
- *                                                               true labels and the class distribution)
+ *   L_pred   = -(1/n) sum_i sum_k t_ik log q_ik               (reading of the distillation-style loss)
  *   G_i      = [argmax_k z_ik == argmax_k Y_ik], lowest index on ties   (selector ground truth)
  *   c_i      = 1/(1 + exp(-(ws . [p_i ; q_i] + bs)))
  *   L_sel    = -(1/n) sum_i [ G_i log c_i + fp_weight (1 - G_i) log(1 - c_i) ]

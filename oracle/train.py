@@ -6,12 +6,13 @@ Learned Caches"; Section 7 parameters: learning rate 0.002, 5 epochs).  The pape
 ingredients, not the formulas; the reading taken here:
 
   predictor  global pool -> FC(C->H) -> ReLU -> FC(H->K) -> softmax q.
-             Loss "inspired by distillation ... takes into account the true labels and also the
-             distribution of class probabilities":
+             The section describes a distillation-style loss that uses both the true label and the
+             base DNN's class distribution, and prints no formula.  This oracle's reading:
                  t_i = (1 - alpha) * onehot(y_i) + alpha * Y_i        (Y = the base DNN's distribution)
                  L_p = -(1/n) sum_i sum_k t_ik log q_ik
-  selector   ground truth G_i = [argmax_k z_ik == argmax_k Y_ik] (the paper's G); a cross-entropy
-             that "levies a higher loss penalty" on false positives (fp_weight >= 1):
+  selector   ground truth G_i = [argmax_k z_ik == argmax_k Y_ik] (the paper's G); the section asks for
+             false positives to cost more than false negatives and gives no weight.  This oracle's
+             reading, a cross-entropy whose G = 0 term is scaled by fp_weight >= 1:
                  c_i = logistic(ws . [p_i ; q_i] + bs)
                  L_s = -(1/n) sum_i [ G_i log c_i + fp_weight (1 - G_i) log(1 - c_i) ]
              The selector is trained on the predictor's outputs as data: no gradient flows from L_s

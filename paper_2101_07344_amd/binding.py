@@ -231,6 +231,7 @@ class Cache:
                          int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]), int(sel_hidden),
                          int(conv_ks[0]), int(conv_ks[1]))
         self._shape = (C_, S, H, K, pool_fc, fc_mlp, conv_fc, selector == "hidden", sel_hidden, tuple(conv_ks))
+        self._softmax_sel = selector == "softmax"
         w, _keep = self._marshal(weights)
         st, self.handle = gati_cache_create(desc, w)
         _check(st, "gati_cache_create")
@@ -250,6 +251,8 @@ class Cache:
         C_, S, H, K, pool_fc, fc_mlp, conv_fc, hidden_sel, sel_hidden, conv_ks = self._shape
         names = ("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")
         names += ("Ws", "cs", "vs") if hidden_sel else ("ws",)
+        if "ws" in names and weights.get("ws") is None and self._softmax_sel:
+            names = tuple(k for k in names if k != "ws")     # the softmax-threshold mode reads no selector weights
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
         if conv_fc:
             assert keep["W1"].shape == (H, C_, conv_ks[0], conv_ks[0])
@@ -259,10 +262,10 @@ class Cache:
         if hidden_sel:
             assert keep["Ws"].shape == (sel_hidden, self.F + K) and keep["cs"].shape == (sel_hidden,) \
                 and keep["vs"].shape == (sel_hidden,)
-        else:
+        elif "ws" in keep:
             assert keep["ws"].shape == (self.F + K,)
         ptr = lambda k: keep[k].ctypes.data if k in keep else None
-        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]),
+        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights.get("bs", 0.0)),
                          ptr("Ws"), ptr("cs"), ptr("vs"))
         return w, keep
 

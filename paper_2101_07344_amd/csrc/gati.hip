@@ -23,7 +23,7 @@ using namespace gati;
 
 namespace {
 
-enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_ROW = 5,
+enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_UNIT = 5,
                    POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7, POOL_FC_FLAT = 8, POOL_CONV = 9, POOL_CONV_GENERIC = 10 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
@@ -74,7 +74,6 @@ struct gati_cache {
     int gt = 0, tiles_per_row = 0, tpc_log2 = 0;  // ncs_seg
     unsigned magic_S = 0;
     int gw = 64, cvb_per_row = 0;                 // nsc_vec
-    int nsc_lpt = 1, cb_per_row = 0;              // nsc_row (4 waves per workgroup; 16 measured no faster)
     AdaptiveWindow* ad_win = nullptr;   // ncs_adaptive: [gt * out_h * out_w] window table
     int ad_j = 4, ad_tpo_log2 = 0, ad_ww = 0, ad_pair = 0;   // ncs_adaptive (tile in gt / tiles_per_row; common window width or 0; LDS read mode)
     int pool_blocks_per_cu = 16;  // persistent grid = CUs x this (more blocks than fit: finer tail balance)
@@ -278,11 +277,11 @@ void plan_pool(gati_cache* c) {
             c->gw = best;
             c->cvb_per_row = (CV + best - 1) / best;
             c->variant = POOL_NSC_VEC;
-            // enough tokens for four slices of several tokens each: stream whole token rows
+            // many tokens: one wave per (row, block of channel vectors) walks all of them
             if (S >= 32) {
-                c->nsc_lpt = std::min(4, (CV + 63) / 64);
-                c->cb_per_row = (CV + 64 * c->nsc_lpt - 1) / (64 * c->nsc_lpt);
-                c->variant = POOL_NSC_ROW;
+                c->gw = (CV % 32 == 0 || CV > 48) ? 32 : 16;
+                c->cvb_per_row = (CV + c->gw - 1) / c->gw;
+                c->variant = POOL_NSC_UNIT;
             }
         }
         return;
@@ -441,15 +440,10 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
         else pool_nsc_kernel<Tag, 16><<<blocks, 256, 0, st>>>(a, c->cvb_per_row);
         break;
     }
-    case POOL_NSC_ROW: {
-        const long items = (long)a.n_max * c->cb_per_row;
-        const int blocks = (int)std::min<long>(items, max_blocks);
-        switch (c->nsc_lpt) {
-        case 1: pool_nsc_row_kernel<Tag, 1, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-        case 2: pool_nsc_row_kernel<Tag, 2, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-        case 3: pool_nsc_row_kernel<Tag, 3, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-        default: pool_nsc_row_kernel<Tag, 4, 4><<<blocks, 256, 0, st>>>(a, c->cb_per_row); break;
-        }
+    case POOL_NSC_UNIT: {
+        const long units = (long)a.n_max * c->cvb_per_row;       // < 2^31: checked at creation (max_rows x features)
+        if (c->gw == 32) pool_nsc_unit_kernel<Tag, 8, 32><<<(int)units, 64, 0, st>>>(a, c->cvb_per_row);
+        else pool_nsc_unit_kernel<Tag, 8, 16><<<(int)units, 64, 0, st>>>(a, c->cvb_per_row);
         break;
     }
     case POOL_NCS_ADAPTIVE:
@@ -562,6 +556,8 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
     const int row_tiles = (n_max + 31) / 32;
     hipError_t e = hipSuccess;
     const bool sel_hidden = c->desc.selector == GATI_SEL_HIDDEN;
+    // a wave's share of the reduction beyond 8 k-steps: the kernel instance with the deeper load pipeline
+    auto deep = [](const FcArgs& f) { return f.Kdim / (BF16 ? 16 : 8) / 4 > 8; };
     if (sel_hidden && !logits) logits = c->zbuf;     // the selector's first layer reads the class probabilities
     FcArgs f2 = {};
     if (!c->pool_fc) {
@@ -569,7 +565,8 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
         f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
         f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
         if (!sel_hidden) { f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp; }
-        fc_kernel<BF16, 1, true><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
+        if (deep(f1)) fc_kernel<BF16, 1, true, 8><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
+        else fc_kernel<BF16, 1, true, 4><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         f2.A = c->h; f2.Kdim = c->Hp;
@@ -584,8 +581,13 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
     f2.n_max = n_max; f2.n_dev = n_dev;
     f2.K = c->desc.K; f2.ws_prob = c->ws_prob; f2.logits = logits; f2.stats = c->stats;
     const int n_tiles = c->Kp / (32 * c->fc2_nt);
-    if (c->fc2_nt == 2) fc_kernel<BF16, 2, false><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
-    else fc_kernel<BF16, 1, false><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
+    if (c->fc2_nt == 2) {
+        if (deep(f2)) fc_kernel<BF16, 2, false, 8><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
+        else fc_kernel<BF16, 2, false, 4><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
+    } else {
+        if (deep(f2)) fc_kernel<BF16, 1, false, 8><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
+        else fc_kernel<BF16, 1, false, 4><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -602,7 +604,8 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
         FcArgs fs = {};
         fs.A = c->sel_in; fs.Wp = c->Ws; fs.bias = c->cs; fs.Kdim = c->Sin; fs.N = c->Hsp;
         fs.n_max = n_max; fs.n_dev = n_dev; fs.h = c->sel_g;
-        fc_kernel<BF16, 1, true><<<dim3(c->Hsp / 32, row_tiles), 256, 0, st>>>(fs);
+        if (deep(fs)) fc_kernel<BF16, 1, true, 8><<<dim3(c->Hsp / 32, row_tiles), 256, 0, st>>>(fs);
+        else fc_kernel<BF16, 1, true, 4><<<dim3(c->Hsp / 32, row_tiles), 256, 0, st>>>(fs);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         fa.sel_g = c->sel_g; fa.sel_vs = c->vs; fa.sel_hs = c->Hs; fa.ldg = c->Hsp; fa.g_bf16 = BF16 ? 1 : 0;
@@ -674,7 +677,7 @@ gati_status_t upload_weights(gati_cache* c, const gati_cache_weights_t* w) {
         std::vector<float> b1(c->Hp, 0.f), b2(c->Kp, 0.f), wp(c->Cp, 0.f), wq(c->Kp, 0.f);
         if (!pool_fc) std::memcpy(b1.data(), w->b1, (size_t)desc->H * 4);   // conv_fc: one bias per filter
         std::memcpy(b2.data(), w->b2, (size_t)K * 4);
-        if (!sel_hidden) {      // otherwise both halves stay zero: the per-tile selector sums are unused
+        if (desc->selector == GATI_SEL_LINEAR) {      // otherwise both halves stay zero: the per-tile selector sums are unused
             std::memcpy(wp.data(), w->ws, (size_t)C * 4);
             std::memcpy(wq.data(), w->ws + C, (size_t)K * 4);
         }
@@ -799,7 +802,8 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     const bool sel_hidden = desc->selector == GATI_SEL_HIDDEN;
     if (sel_hidden && (desc->selector_hidden < 1 || desc->selector_hidden > 1024 || !w->Ws || !w->cs || !w->vs))
         return GATI_ERR_INVALID_ARG;
-    if (!w->W2 || !w->b2 || (!sel_hidden && !w->ws)) return GATI_ERR_INVALID_ARG;
+    const bool needs_ws = desc->selector == GATI_SEL_LINEAR;
+    if (!w->W2 || !w->b2 || (needs_ws && !w->ws)) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
     if (flat_fc && ((long)desc->C * desc->S) % 64 != 0) return GATI_ERR_UNSUPPORTED;
     if (flat_fc && (long)desc->C * desc->S >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
@@ -915,7 +919,7 @@ gati_status_t gati_cache_set_weights(gati_cache_t* c, const gati_cache_weights_t
     const bool pool_fc = c->desc.predictor == GATI_PRED_POOL_FC;
     const bool sel_hidden = c->desc.selector == GATI_SEL_HIDDEN;
     if (sel_hidden && (!w->Ws || !w->cs || !w->vs)) return GATI_ERR_INVALID_ARG;
-    if (!w->W2 || !w->b2 || (!sel_hidden && !w->ws)) return GATI_ERR_INVALID_ARG;
+    if (!w->W2 || !w->b2 || (c->desc.selector == GATI_SEL_LINEAR && !w->ws)) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
     if (!(w->bs == w->bs)) return GATI_ERR_INVALID_ARG;
     if (!on_cache_device(c)) return GATI_ERR_DEVICE;
@@ -1051,7 +1055,7 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     case POOL_NCS_SEG: return "ncs_seg";
     case POOL_NCS_SEGW: return "ncs_segw";
     case POOL_NSC_VEC: return "nsc_vec";
-    case POOL_NSC_ROW: return "nsc_row";
+    case POOL_NSC_UNIT: return "nsc_unit";
     case POOL_NCS_ADAPTIVE: return "ncs_adaptive";
     case POOL_ADAPTIVE_GENERIC: return "adaptive_generic";
     case POOL_FC_FLAT: return "fc_flat";

@@ -87,12 +87,13 @@ __device__ __forceinline__ void merge_tile_stats(const TileStat* st, int n_tiles
                                                  float* wsum_out, int* arg_out) {
     float m = -INFINITY, sum = 0.f, wsum = 0.f;
     int arg = 0;
-    for (int t0 = 0; t0 < n_tiles; t0 += 8) {
-        TileStat s[8];
+    constexpr int B = 16;                      // summaries requested together (K = 1000: all of a row's)
+    for (int t0 = 0; t0 < n_tiles; t0 += B) {
+        TileStat s[B];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s[u] = st[min(t0 + u, n_tiles - 1)];   // 8 loads in flight together
+        for (int u = 0; u < B; ++u) s[u] = st[min(t0 + u, n_tiles - 1)];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < B; ++u) {
             if (t0 + u < n_tiles && s[u].max > -INFINITY) {
                 if (s[u].max > m) {
                     const float w = expf(m - s[u].max);   // m = -inf -> 0
@@ -127,31 +128,37 @@ __device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, floa
 }
 
 // Pooled-feature half of the selector, fp32: u_pool[row] = ws_pool . p32[row].  The 32 rows of a
-// row tile are shared out over the column blocks of the grid row; a block's 256 lanes stride
-// over one row at a time and add up in a fixed order (lane partials -> wave butterfly -> 4 wave
-// totals).  Called by all 256 lanes of every block of the grid row.
-__device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, int n, int n_tiles_x) {
-    __shared__ float upart[4];
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+// row tile are shared out over the column blocks of the grid row, and a block's rows over its 4
+// waves: a wave's 64 lanes stride over one row and add up in a fixed order (lane partials ->
+// wave butterfly).  Nothing is shared between waves, so there is no barrier; rows up to the
+// padded row count exist in p32, so the loads do not wait for the device-side row count.
+__device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, const int32_t* n_dev, int n_max, int n_tiles_x) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rpb = (32 + n_tiles_x - 1) / n_tiles_x;   // rows per block
     const f32x4_t* wv = reinterpret_cast<const f32x4_t*>(a.ws_pool);
     const int nvec = a.ldp / 4;
-    for (int q = 0; q < rpb; ++q) {
-        const int rr = blockIdx.x * rpb + q;            // block-uniform
-        if (rr >= 32 || row0 + rr >= n) break;
+    for (int q = wave; q < rpb; q += 4) {
+        const int rr = blockIdx.x * rpb + q;            // wave-uniform
+        if (rr >= 32) break;
         const f32x4_t* pr = reinterpret_cast<const f32x4_t*>(a.p32 + (long)(row0 + rr) * a.ldp);
         float s = 0.f;
-        for (int k = tid; k < nvec; k += 256) {
-            const f32x4_t x = pr[k], w = wv[k];
-            s = fmaf(x[0], w[0], s); s = fmaf(x[1], w[1], s);
-            s = fmaf(x[2], w[2], s); s = fmaf(x[3], w[3], s);
+        for (int k0 = 0; k0 < nvec; k0 += 64 * 4) {
+            f32x4_t x[4], w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = min(k0 + u * 64 + lane, nvec - 1);
+                x[u] = pr[k]; w[u] = wv[k];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (k0 + u * 64 + lane < nvec) {
+                    s = fmaf(x[u][0], w[u][0], s); s = fmaf(x[u][1], w[u][1], s);
+                    s = fmaf(x[u][2], w[u][2], s); s = fmaf(x[u][3], w[u][3], s);
+                }
+            }
         }
         s = wave_sum(s);
-        __syncthreads();                                // previous row's upart has been read
-        if (lane == 0) upart[wave] = s;
-        __syncthreads();
-        if (tid == 0) a.u_pool[row0 + rr] = (upart[0] + upart[1]) + (upart[2] + upart[3]);
+        if (lane == 0 && row0 + rr < active_rows(n_dev, n_max)) a.u_pool[row0 + rr] = s;
     }
 }
 
@@ -159,17 +166,17 @@ __device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, in
 // HIDDEN: epilogue bias + ReLU -> h, plus a share of the pooled-feature half of the selector's
 // dot product (fp32).
 // !HIDDEN: epilogue bias -> logits (optional store) and the tile's softmax/argmax summary.
-template <bool BF16, int NT, bool HIDDEN>
+// U: k-steps per pipeline stage (two stages in registers): 4 when a wave's share of the reduction is
+// at most 8 k-steps (everything is in flight at once with half the registers), else 8.
+template <bool BF16, int NT, bool HIDDEN, int U>
 __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     using M = Mma<BF16>;
     using frag_t = typename M::frag_t;
     constexpr int kStep = M::kStep, kLane = M::kLane;
     __shared__ float red[4][NT * 16][64];      // split-K partial tiles, [wave][tile*16 + j][lane]
 
-    const int n = active_rows(a.n_dev, a.n_max);
     const int row0 = blockIdx.y * 32;
     const int tid = threadIdx.x;
-    if (row0 >= n) return;
     const int wave = tid >> 6, lane = tid & 63;
     const int r = lane & 31, kb = lane >> 5;
     const int n_tiles_x = a.N / (32 * NT);
@@ -191,38 +198,59 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
 
-    // Software pipeline, U k-steps per stage: the loads of stage s+1 are issued before the
-    // MFMAs of stage s, so a wave always has a full stage of fragments in flight.  Slots past
-    // the end re-read the last k-step (in bounds) and are skipped by the MFMA loop.
-    constexpr int U = 4;
+    const int n = active_rows(a.n_dev, a.n_max);
+    if (row0 >= n) return;      // before any load: a stack's late layers launch many more row tiles than they fill
+
+    // Software pipeline, two stages of U k-steps in registers.  What this kernel costs is a chain of
+    // dependent memory round trips, so as much as fits is requested up front: both stages, the
+    // epilogue's bias / selector weights and the selector's pooled half before the first MFMA, and a
+    // stage is refilled as soon as its MFMAs are issued.  Reductions of up to 16 k-steps per wave
+    // (C <= 1024 in bf16) are one round trip.  Slots past the end re-read the last k-step (in
+    // bounds) and are skipped by the MFMA loop.
     frag_t af[2][U], bf[2][NT][U];
     const int last = ksw - 1;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int k = min(u, last);
-        af[0][u] = ap[k * 2];
+    for (int half = 0; half < 2; ++half) {
+        if (half == 0 || U < ksw) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) bf[0][t][u] = bp[t * b_tile + (long)k * 64];
+            for (int u = 0; u < U; ++u) {
+                const int k = min(half * U + u, last);
+                af[half][u] = ap[k * 2];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) bf[half][t][u] = bp[t * b_tile + (long)k * 64];
+            }
+        }
+    }
+    // epilogue operands of this thread's output slots (tj = q*4 + wave), requested now
+    float ep_bias[4 * NT], ep_ws[4 * NT];
+#pragma unroll
+    for (int q = 0; q < 4 * NT; ++q) {
+        const int col = (nt0 + ((q * 4 + wave) >> 4)) * 32 + r;     // < N: bias and ws_prob are padded to N
+        ep_bias[q] = a.bias[col];
+        ep_ws[q] = HIDDEN ? 0.f : a.ws_prob[col];
+    }
+    if constexpr (HIDDEN) {
+        if (a.p32) selector_pool_part(a, row0, a.n_dev, a.n_max, n_tiles_x);   // null: this launch has no selector half
     }
     for (int ks = 0; ks < ksw; ks += 2 * U) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int cur = ks + half * U;          // first k-step of the stage in buffer `half`
-            const int nxt = cur + U;
-            if (nxt < ksw) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int k = min(nxt + u, last);
-                    af[half ^ 1][u] = ap[k * 2];
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) bf[half ^ 1][t][u] = bp[t * b_tile + (long)k * 64];
-                }
-            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (cur + u < ksw) {
 #pragma unroll
                     for (int t = 0; t < NT; ++t) acc[t] = M::mma(af[half][u], bf[half][t][u], acc[t]);
+                }
+            }
+            const int nxt = cur + 2 * U;
+            if (nxt < ksw) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int k = min(nxt + u, last);
+                    af[half][u] = ap[k * 2];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) bf[half][t][u] = bp[t * b_tile + (long)k * 64];
                 }
             }
         }
@@ -248,16 +276,16 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             const int tj = q * 4 + wave;
             const int col = (nt0 + (tj >> 4)) * 32 + r;
             const int row = row0 + mfma_row(tj & 15, kb);
-            const float v = fmaxf(z[q] + a.bias[col], 0.f);
+            const float v = fmaxf(z[q] + ep_bias[q], 0.f);
             if constexpr (BF16)
                 static_cast<__bf16*>(a.h)[(long)row * a.N + col] = (__bf16)v;
             else
                 static_cast<float*>(a.h)[(long)row * a.N + col] = v;
         }
-        if (a.p32) selector_pool_part(a, row0, n, n_tiles_x);   // null: this launch has no selector half
     } else {
         constexpr int TW = 32 * NT;                 // tile width in classes
         __shared__ float zt[32][TW + 1];
+        __shared__ float wst[TW];
         const int col_base = nt0 * 32;
 #pragma unroll
         for (int q = 0; q < 4 * NT; ++q) {
@@ -266,9 +294,10 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             const int col = col_base + lc;
             const int lr = mfma_row(tj & 15, kb);
             const bool valid = col < a.K;
-            const float v = z[q] + (valid ? a.bias[col] : 0.f);
+            const float v = z[q] + (valid ? ep_bias[q] : 0.f);
             if (a.logits && valid && row0 + lr < n) a.logits[(long)(row0 + lr) * a.K + col] = v;
             zt[lr][lc] = valid ? v : -INFINITY;
+            if ((tj & 15) == 0 && kb == 0) wst[lc] = ep_ws[q];      // one holder per column: output row 0 of its tile
         }
         __syncthreads();
         // 8 lanes per row; lane `sub` takes classes sub, sub+8, ...
@@ -293,7 +322,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             if (v > -INFINITY) {
                 const float e = expf(v - bm);
                 ps += e;
-                pt = fmaf(e, a.ws_prob[col_base + c], pt);
+                pt = fmaf(e, wst[c], pt);
             }
         }
 #pragma unroll
@@ -306,7 +335,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             s.max = bm; s.sum = ps; s.wsum = pt; s.arg = bi;
             a.stats[(long)(row0 + lr) * n_tiles_x + blockIdx.x] = s;
         }
-        if (a.p32) selector_pool_part(a, row0, n, n_tiles_x);   // predictors without a hidden-layer kernel
+        if (a.p32) selector_pool_part(a, row0, a.n_dev, a.n_max, n_tiles_x);   // predictors without a hidden-layer kernel
     }
 }
 
@@ -380,8 +409,9 @@ __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
     if (tid == 0) st.carry = 0;
     for (int base = 0; base < n; base += 1024) {
         const int i = base + tid;
-        bool miss = false;
-        if (i < n) {
+        const bool live = i < n;
+        bool is_hit = false;
+        if (live) {
             float u_in;
             if (a.sel_g) {                                  // second layer of the selector, in unit order
                 u_in = 0.f;                                 // rows are padded to 32 units: whole 16-byte loads
@@ -409,11 +439,11 @@ __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
             } else {
                 u_in = a.u_pool[i];
             }
-            miss = !finish_row(a.stats + (long)i * a.n_tiles, a.n_tiles, u_in, a.bs, a.tau, a.softmax_only != 0,
-                               &a.pred_class[i], &a.confidence[i], &a.hit[i]);
+            is_hit = finish_row(a.stats + (long)i * a.n_tiles, a.n_tiles, u_in, a.bs, a.tau, a.softmax_only != 0,
+                                &a.pred_class[i], &a.confidence[i], &a.hit[i]);
         }
         if (compact) {
-            const int slot = compact_step<16>(st, miss, tid);
+            const int slot = compact_step<16>(st, live && !is_hit, tid);
             if (slot >= 0) a.ids_out[slot] = a.ids_in ? a.ids_in[i] : i;
         }
     }

@@ -381,76 +381,58 @@ __global__ __launch_bounds__(256) void pool_nsc_kernel(PoolArgs a, int cvb_per_r
 }
 
 // ---------------------------------------------------------------------------------------
-// [n,S,C] with enough tokens to split: one workgroup per (row, block of 64*LPT channel
-// vectors); its NW waves take NW contiguous token slices, and within a slice a wave streams
-// whole token rows one after another (LPT loads per lane per token, UT tokens in flight), so
-// each wave reads one long contiguous span of memory.  The slice sums meet in LDS and are
-// added in slice order.  Requires C % kVec == 0.
+// [n,S,C] with many tokens, wave-granular units: one wave owns (row, block of CVB channel
+// vectors) and nothing else -- no LDS, no barrier, no other wave to wait for.  Its 64 lanes are
+// 64/CVB token phases x CVB channel vectors, R loads per lane in flight; the token phases meet by
+// lane shuffles in a fixed order.  Units leave the chip as they finish and the dispatcher brings
+// in the next ones, so a launch with few rows still spreads over every CU and has no slow
+// workgroup-sized tail (timestamps of the row-per-workgroup kernel showed workgroup end times
+// spread over 40 % of the launch).  The row index is requested before the device-side row count
+// is known (both scalar loads fly together).  Requires C % kVec == 0.
 // ---------------------------------------------------------------------------------------
-template <typename Tag, int LPT, int NW>
-__global__ __launch_bounds__(NW * 64) void pool_nsc_row_kernel(PoolArgs a, int cb_per_row) {
+template <typename Tag, int R, int CVB>
+__global__ __launch_bounds__(64) void pool_nsc_unit_kernel(PoolArgs a, int cvb_per_row) {
     constexpr int V = Tag::kVec;
-    constexpr int UT = LPT == 1 ? 8 : (LPT == 2 ? 4 : 2);   // tokens in flight per lane
-    __shared__ float red[NW][LPT * V * 64];
-
-    const int n = active_rows(a.n_dev, a.n_max);
-    const unsigned total = (unsigned)n * (unsigned)cb_per_row;
-    const int lane = threadIdx.x & 63;
-    const int wib = threadIdx.x >> 6;
+    constexpr int TP = 64 / CVB;                       // token phases per load instruction
+    const int lane = threadIdx.x;
+    const int cvl = lane % CVB, tp = lane / CVB;
     const int CV = a.C / V;
-
-    for (unsigned w = blockIdx.x; w < total; w += gridDim.x) {
-        const unsigned i = w / (unsigned)cb_per_row;
-        const int cb = (int)(w - i * (unsigned)cb_per_row);
-        const long r = a.row_index ? (long)a.row_index[i] : (long)i;
-        const int cv0 = cb * 64 * LPT + lane;
-        const u32x4_t* base =
-            reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) +
-                                             (r * a.S * (long)a.C) * Tag::kBytes);
-        float acc[LPT][V];
+    const unsigned w = blockIdx.x;
+    const unsigned i = w / (unsigned)cvb_per_row;      // < n_max by the grid size
+    const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+    const int n = active_rows(a.n_dev, a.n_max);
+    if (i >= (unsigned)n) return;
+    const int cb = (int)(w - i * (unsigned)cvb_per_row);
+    const int cv = cb * CVB + cvl;
+    const u32x4_t* base =
+        reinterpret_cast<const u32x4_t*>(static_cast<const char*>(a.act) + (r * a.S * (long)a.C) * Tag::kBytes) +
+        min(cv, CV - 1);
+    float acc[V];
 #pragma unroll
-        for (int q = 0; q < LPT; ++q)
+    for (int k = 0; k < V; ++k) acc[k] = 0.f;
+    for (int t0 = tp; t0 < a.S; t0 += TP * R) {
+        u32x4_t v[R];
 #pragma unroll
-            for (int k = 0; k < V; ++k) acc[q][k] = 0.f;
-        // Tokens are dealt to the waves in interleaved groups of UT, so that at any moment the
-        // workgroup reads one contiguous stretch of the row (NW*UT token rows) rather than NW
-        // separate slow streams.
-        for (int t = wib * UT; t < a.S; t += NW * UT) {
-            u32x4_t v[UT][LPT];
+        for (int u = 0; u < R; ++u)        // unconditional, clamped to the last token
+            v[u] = load_stream(base + (long)min(t0 + u * TP, a.S - 1) * CV);
 #pragma unroll
-            for (int u = 0; u < UT; ++u) {
-                const long trow = (long)min(t + u, a.S - 1) * CV;
+        for (int u = 0; u < R; ++u) {
+            const u32x4_t x = keep_or_zero(v[u], t0 + u * TP < a.S);
+            float e[V];
+            vec_unpack<Tag>(x, e);
 #pragma unroll
-                for (int q = 0; q < LPT; ++q) v[u][q] = load_stream(base + trow + min(cv0 + q * 64, CV - 1));
-            }
-#pragma unroll
-            for (int u = 0; u < UT; ++u) {
-#pragma unroll
-                for (int q = 0; q < LPT; ++q) {
-                    const u32x4_t x = keep_or_zero(v[u][q], (t + u < a.S) && (cv0 + q * 64 < CV));
-                    float e[V];
-                    vec_unpack<Tag>(x, e);
-#pragma unroll
-                    for (int k = 0; k < V; ++k) acc[q][k] += e[k];
-                }
-            }
+            for (int k = 0; k < V; ++k) acc[k] += e[k];
         }
-        // slice sums to LDS in channel order, so that the final stores are coalesced
+    }
 #pragma unroll
-        for (int q = 0; q < LPT; ++q)
+    for (int m = 32; m >= CVB; m >>= 1) {
 #pragma unroll
-            for (int k = 0; k < V; ++k) red[wib][(q * 64 + lane) * V + k] = acc[q][k];
-        __syncthreads();
-        const int c_first = cb * 64 * LPT * V;
-        for (int e = threadIdx.x; e < LPT * V * 64; e += NW * 64) {
-            if (c_first + e < a.C) {
-                float s = 0.f;
+        for (int k = 0; k < V; ++k) acc[k] += __shfl_xor(acc[k], m, 64);
+    }
+    if (tp == 0 && cv < CV) {
+        const long o = (long)i * a.out_stride + (long)cv * V;
 #pragma unroll
-                for (int g = 0; g < NW; ++g) s += red[g][e];
-                store_pooled(a, (long)i * a.out_stride + c_first + e, s * a.inv_S);
-            }
-        }
-        __syncthreads();
+        for (int k = 0; k < V; ++k) store_pooled(a, o + k, acc[k] * a.inv_S);
     }
 }
 

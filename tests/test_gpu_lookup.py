@@ -228,6 +228,12 @@ def test_softmax_threshold_selector(dtype, K):
     want_ideal = oracle.lookup(ideal_def(d), w, host, row_index=ok) if dtype == "bf16" else None
     compare_lookup(got, want, want_ideal, dtype, f"softmax selector {dtype}")
     cache.close()
+    # the mode reads no selector weights: a cache built without them gives the same bits
+    bare = g.Cache(C, S, H, K, dtype, "ncs", tau, n, {k: v for k, v in w.items() if k not in ("ws", "bs")}, selector="softmax")
+    got2 = _lookup_gpu(bare, x.cuda(), torch.from_numpy(ok).cuda(), len(ok), None, K)
+    for key in ("pred_class", "confidence", "hit", "logits"):
+        assert np.array_equal(got[key][:len(ok)], got2[key][:len(ok)]), key
+    bare.close()
 
 
 @pytest.mark.parametrize("dtype,predictor,K,Hs,want_logits", [

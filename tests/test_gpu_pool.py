@@ -35,14 +35,14 @@ SHAPES = [
     (256, 196, "f32", "ncs", "ncs_wave"), (512, 49, "f32", "ncs", "ncs_segw"),
     (256, 3136, "bf16", "ncs", "ncs_wave"), (512, 784, "bf16", "ncs", "ncs_wave"),
     (1024, 196, "bf16", "ncs", "ncs_segw"), (2048, 49, "bf16", "ncs", "ncs_segw"),
-    (768, 128, "bf16", "nsc", "nsc_row"), (768, 128, "f32", "nsc", "nsc_row"),
-    (2056, 37, "bf16", "nsc", "nsc_row"), (8, 32, "f32", "nsc", "nsc_row"), (4104, 33, "f32", "nsc", "nsc_row"),
+    (768, 128, "bf16", "nsc", "nsc_unit"), (768, 128, "f32", "nsc", "nsc_unit"),
+    (2056, 37, "bf16", "nsc", "nsc_unit"), (8, 32, "f32", "nsc", "nsc_unit"), (4104, 33, "f32", "nsc", "nsc_unit"),
     # ragged / odd shapes
     (24, 50, "bf16", "ncs", "ncs_segw"), (40, 49, "bf16", "ncs", "ncs_segw"), (12, 9, "f32", "ncs", "ncs_segw"),
     (16, 1001, "bf16", "ncs", "ncs_seg"), (24, 333, "f32", "ncs", "ncs_seg"),
     (7, 33, "f32", "ncs", "generic"), (5, 3, "bf16", "ncs", "generic"), (3, 5000, "bf16", "ncs", "ncs_wave"),
     (10, 1024 + 8, "bf16", "ncs", "ncs_wave"), (100, 37, "bf16", "nsc", "generic"),
-    (104, 37, "bf16", "nsc", "nsc_row"), (104, 31, "bf16", "nsc", "nsc_vec"), (2056, 5, "f32", "nsc", "nsc_vec"), (8, 1, "bf16", "nsc", "nsc_vec"),
+    (104, 37, "bf16", "nsc", "nsc_unit"), (104, 31, "bf16", "nsc", "nsc_vec"), (2056, 5, "f32", "nsc", "nsc_vec"), (8, 1, "bf16", "nsc", "nsc_vec"),
     (130, 64, "f32", "ncs", "ncs_segw"),
 ]
 

@@ -46,7 +46,7 @@ def test_global_pool_random_shapes():
         seen.add(cache.pool_variant)
         _features_match(d, w, x, cache, n, 2e-6 * max(1.0, float(x.float().abs().max())))
         cache.close()
-    assert {"ncs_wave", "ncs_segw", "generic"} <= seen and ({"nsc_row", "nsc_vec"} & seen)
+    assert {"ncs_wave", "ncs_segw", "generic"} <= seen and ({"nsc_unit", "nsc_vec"} & seen)
 
 
 def test_adaptive_pool_random_shapes():
