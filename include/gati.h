@@ -74,17 +74,21 @@ typedef enum { GATI_SEL_LINEAR = 0, GATI_SEL_SOFTMAX = 1, GATI_SEL_HIDDEN = 2 } 
  *   GATI_PRED_POOL_FC  the paper's Pool(h): adaptive average pool of the in_h x in_w feature map to
  *                      out_h x out_w (window i of an axis covers [floor(i*in/out), ceil((i+1)*in/out)),
  *                      the PyTorch rule), ReLU, then one FC over the F = C*out_h*out_w features
- *                      (feature order [c][oy][ox]).  Needs GATI_LAYOUT_NCS and S = in_h*in_w.
- *                      H, W1 and b1 are unused; W2 is [K, F] and ws is [F + K].
+ *                      (feature order [c][oy][ox]).  Needs S = in_h*in_w; position y*in_w + x of the map
+ *                      is element s of the row in either layout (channels-last maps take a plain
+ *                      kernel, channel-major ones the tiled one).  H, W1 and b1 are unused; W2 is
+ *                      [K, F] and ws is [F + K].
  *   GATI_PRED_FC_MLP   the paper's FC(h): the activation row flattened in storage order (D = C*S
  *                      values) -> FC(D->H) -> ReLU -> FC(H->K).  W1 is [H, D]; the selector reads
  *                      [hidden ; prob], so ws is [H + K]; the "pooled" features reported by
- *                      gati_cache_pool are the H hidden activations.  D must be a multiple of 64
- *                      (GATI_ERR_UNSUPPORTED otherwise).
+ *                      gati_cache_pool are the H hidden activations.  Rows whose length D is a
+ *                      multiple of 64 run on the matrix cores (activation pointer 16-byte aligned);
+ *                      other lengths take a plain kernel.
  *   GATI_PRED_CONV_FC  the paper's Conv(k,s): convolution of the C x in_h x in_w map with H filters of
  *                      conv_k x conv_k, stride conv_s, no padding, ReLU, then one FC over the
  *                      F = H*oh*ow hidden values, oh = (in_h - conv_k)/conv_s + 1 (feature order
- *                      [filter][oy][ox]).  Needs GATI_LAYOUT_NCS and S = in_h*in_w.  W1 is
+ *                      [filter][oy][ox]).  Needs S = in_h*in_w (either layout; channels-last maps take a
+ *                      plain kernel).  W1 is
  *                      [H, C, conv_k, conv_k], b1 [H], W2 [K, F], ws [F + K].  H <= 64, conv_k <= 15
  *                      (GATI_ERR_UNSUPPORTED otherwise).                                            */
 typedef enum { GATI_PRED_GAP_MLP = 0, GATI_PRED_POOL_FC = 1, GATI_PRED_FC_MLP = 2, GATI_PRED_CONV_FC = 3 } gati_predictor_t;
@@ -228,7 +232,7 @@ gati_status_t gati_cache_lookup_compact(gati_cache_t *cache, const void *act, co
 const char *gati_status_string(gati_status_t status);
 
 /* Name of the pooling kernel variant the cache dispatches to ("ncs_wave", "ncs_segw",
- * "ncs_seg", "nsc_unit", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat", "conv_mfma",
+ * "ncs_seg", "nsc_unit", "nsc_vec", "generic", "ncs_adaptive", "adaptive_generic", "fc_flat", "fc_flat_generic", "conv_mfma",
  * "conv_generic"); static string, for reports and profiles. */
 const char *gati_cache_pool_variant(const gati_cache_t *cache);
 

@@ -29,7 +29,7 @@
 // untransposed form is bound by LDS and VALU instruction issue, several times over the MFMA
 // time.  Records of a group of 8 positions are stored XOR-swizzled by the group index so the
 // transposing stores of neighbouring lanes (256 bytes apart) do not fall on one bank.
-// conv_generic_kernel takes everything else (any shape or alignment; one lane per output).
+// conv_generic_kernel takes everything else (any shape, alignment or layout; one lane per output).
 #pragma once
 
 #include "head_kernels.h"
@@ -326,10 +326,10 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a) {
     }
 }
 
-// Any shape, layout NCS: one lane per hidden value, scalar loads, fp32 accumulation in
-// (channel, dy, dx) order.
+// Any shape, either layout: one lane per hidden value, scalar loads, fp32 accumulation in
+// (channel, dy, dx) order.  nsc_layout = 1: the map is stored [position][channel].
 template <bool BF16>
-__global__ __launch_bounds__(256) void conv_generic_kernel(ConvArgs a) {
+__global__ __launch_bounds__(256) void conv_generic_kernel(ConvArgs a, int nsc_layout) {
     const int n = active_rows(a.n_dev, a.n_max);
     const int OHW = a.oh * a.ow;
     const long F = (long)a.Co * OHW;
@@ -341,13 +341,14 @@ __global__ __launch_bounds__(256) void conv_generic_kernel(ConvArgs a) {
         const int co = f / OHW, q = f - co * OHW;
         const int oy = q / a.ow, ox = q - oy * a.ow;
         const long r = a.row_index ? (long)a.row_index[i] : i;
+        const long pos_step = nsc_layout ? a.C : 1;
         float acc = 0.f;
         for (int c = 0; c < a.C; ++c) {
-            const long plane = (r * a.C + c) * (long)a.S;
+            const long plane = nsc_layout ? r * a.S * (long)a.C + c : (r * a.C + c) * (long)a.S;
             const float* w = a.Wplain + ((long)co * a.C + c) * a.k * a.k;
             for (int dy = 0; dy < a.k; ++dy)
                 for (int dx = 0; dx < a.k; ++dx) {
-                    const long e = plane + (long)(oy * a.s + dy) * a.in_w + ox * a.s + dx;
+                    const long e = plane + ((long)(oy * a.s + dy) * a.in_w + ox * a.s + dx) * pos_step;
                     float x;
                     if constexpr (BF16) x = __uint_as_float((uint32_t)static_cast<const uint16_t*>(a.act)[e] << 16);
                     else x = static_cast<const float*>(a.act)[e];

@@ -382,4 +382,53 @@ __global__ __launch_bounds__(256) void fc_flat_reduce_kernel(FlatReduceArgs a) {
     }
 }
 
+// FC(h) for rows whose length is not a multiple of 64 elements (the MFMA kernels consume whole
+// 128-byte lines): one wave per (row, hidden unit), lanes stride over the row, fp32 products added
+// lane-wise and then by the wave butterfly -- a fixed order.  W1 is kept as stored, [H, D], in the
+// cache's element type.  Slow (no operand reuse); a correctness path for odd shapes.
+struct FlatGenericArgs {
+    const void* act;           // [rows, D]
+    const int32_t* row_index;
+    const int32_t* n_dev;
+    int n_max;
+    long D;
+    int H;
+    const void* W;             // [H, D] bf16 or f32
+    const float* bias;         // [H]
+    float* p;                  // [rows, ldp]
+    __bf16* p16;               // or null
+    int ldp;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void fc_flat_generic_kernel(FlatGenericArgs a) {
+    const int n = active_rows(a.n_dev, a.n_max);
+    const int lane = threadIdx.x & 63;
+    const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const long nwaves = (long)gridDim.x * (blockDim.x >> 6);
+    const long total = (long)n * a.H;
+    for (long w = wave; w < total; w += nwaves) {
+        const long i = w / a.H;
+        const int j = (int)(w - i * a.H);
+        const long r = a.row_index ? (long)a.row_index[i] : i;
+        float s = 0.f;
+        if constexpr (BF16) {
+            const uint16_t* x = static_cast<const uint16_t*>(a.act) + r * a.D;
+            const uint16_t* wt = static_cast<const uint16_t*>(a.W) + (long)j * a.D;
+            for (long e = lane; e < a.D; e += 64)
+                s = fmaf(__uint_as_float((uint32_t)x[e] << 16), __uint_as_float((uint32_t)wt[e] << 16), s);
+        } else {
+            const float* x = static_cast<const float*>(a.act) + r * a.D;
+            const float* wt = static_cast<const float*>(a.W) + (long)j * a.D;
+            for (long e = lane; e < a.D; e += 64) s = fmaf(x[e], wt[e], s);
+        }
+        s = wave_sum(s);
+        if (lane == 0) {
+            const float v = fmaxf(s + a.bias[j], 0.f);
+            a.p[i * a.ldp + j] = v;
+            if (a.p16) a.p16[i * a.ldp + j] = (__bf16)v;
+        }
+    }
+}
+
 }  // namespace gati

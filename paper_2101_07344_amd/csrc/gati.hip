@@ -24,7 +24,8 @@ using namespace gati;
 namespace {
 
 enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_UNIT = 5,
-                   POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7, POOL_FC_FLAT = 8, POOL_CONV = 9, POOL_CONV_GENERIC = 10 };
+                   POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7, POOL_FC_FLAT = 8, POOL_CONV = 9, POOL_CONV_GENERIC = 10,
+                   POOL_FC_FLAT_GENERIC = 11 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -49,6 +50,7 @@ struct gati_cache {
     // FC(h) plan: wave register tile MT=NT=flat_t, padded sizes, split-K
     int flat_t = 1, Hb = 0, rows_b = 0, flat_KS = 0, flat_splits = 1, flat_ks_per = 0, flat_tiles_m = 0, flat_tiles_n = 0;
     float* flat_partial = nullptr;   // [splits][rows_b][Hb]
+    bool flat_generic = false;       // FC(h) rows of a length the MFMA kernels cannot take: W1 kept as stored
     int F = 0;                // features the pooling step produces per row (C, or C*out_h*out_w)
     // padded sizes: Cp % 64 == 0 (Cp pads F) and Hp % 64 == 0 (reduction axes: 4 waves x whole
     // k-steps), Kp % (32*fc2_nt) == 0, rows_pad % 32 == 0
@@ -123,6 +125,7 @@ void plan_conv(gati_cache* c) {
     const int k_step = c->bf16 ? 16 : 8;
     const int oh = c->conv_oh, ow = c->conv_ow;
     c->variant = POOL_CONV_GENERIC;
+    if (d.layout == GATI_LAYOUT_NSC) return;      // channels-last maps: the generic kernel
     c->conv_ntc = d.H > 32 ? 2 : 1;
     const int max_pixels = c->conv_ntc == 2 ? 512 : 1024;   // 4 waves x TPW tiles x 32 pixels
     c->conv_tpw = c->conv_ntc == 2 ? 4 : 8;
@@ -182,7 +185,7 @@ hipError_t launch_conv_t(const gati_cache* c, const void* act, const int32_t* ro
     if (c->variant != POOL_CONV || (reinterpret_cast<uintptr_t>(act) & 15u) != 0) {
         const long items = (long)n_max * c->F;
         const int blocks = (int)std::min<long>((items + 255) / 256, (long)c->num_cu * 16);
-        conv_generic_kernel<BF16><<<blocks, 256, 0, st>>>(a);
+        conv_generic_kernel<BF16><<<blocks, 256, 0, st>>>(a, d.layout == GATI_LAYOUT_NSC ? 1 : 0);
     } else {
         // the split slabs are laid out for out_stride == Cp (the cache's own feature buffer and
         // gati_cache_pool's F-wide output both fit: out_stride <= Cp)
@@ -224,7 +227,7 @@ void plan_pool(gati_cache* c) {
     c->variant = POOL_GENERIC;
     if (c->pool_fc) {
         c->variant = POOL_ADAPTIVE_GENERIC;
-        if (S >= V && ((long)C * S) % V == 0) {
+        if (c->desc.layout == GATI_LAYOUT_NCS && S >= V && ((long)C * S) % V == 0) {
             int g0 = 1;
             while (((long)g0 * S) % V != 0) ++g0;
             const long vec0 = (long)g0 * S / V;            // vectors of the smallest aligned tile
@@ -454,7 +457,7 @@ hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, h
         if (variant == POOL_ADAPTIVE_GENERIC) {
             const long items = (long)a.n_max * c->F;
             const int blocks = (int)std::min<long>((items + 255) / 256, max_blocks);
-            pool_adaptive_generic_kernel<Tag><<<blocks, 256, 0, st>>>(a, g);
+            pool_adaptive_generic_kernel<Tag><<<blocks, 256, 0, st>>>(a, g, c->desc.layout == GATI_LAYOUT_NSC ? 1 : 0);
             break;
         }
         const long tiles = (long)a.n_max * c->tiles_per_row;
@@ -502,6 +505,15 @@ hipError_t raise_flat_lds_limit(bool bf16) {
 template <bool BF16>
 hipError_t launch_flat_t(const gati_cache* c, const void* act, const int32_t* row_index, int n_max,
                          const int32_t* n_dev, float* out, void* out16, int out_stride, hipStream_t st) {
+    if (c->flat_generic) {
+        FlatGenericArgs ga;
+        ga.act = act; ga.row_index = row_index; ga.n_dev = n_dev; ga.n_max = n_max;
+        ga.D = (long)c->desc.C * c->desc.S; ga.H = c->desc.H; ga.W = c->W1; ga.bias = c->b1;
+        ga.p = out; ga.p16 = static_cast<__bf16*>(out16); ga.ldp = out_stride;
+        const long waves = (long)n_max * ga.H;
+        fc_flat_generic_kernel<BF16><<<(int)std::min<long>((waves + 3) / 4, (long)c->num_cu * 16), 256, 0, st>>>(ga);
+        return hipGetLastError();
+    }
     FlatArgs f;
     f.act = act; f.row_index = row_index; f.n_dev = n_dev; f.n_max = n_max;
     f.D = (long)c->desc.C * c->desc.S; f.Wp = c->W1; f.KS = c->flat_KS; f.Hb = c->Hb; f.rows_b = c->rows_b;
@@ -632,7 +644,12 @@ gati_status_t upload_weights(gati_cache* c, const gati_cache_weights_t* w) {
         // weights in MFMA fragment order, zero padded
         if (c->bf16) {
             std::vector<uint16_t> t1, t2;
-            if (flat_fc) {
+            if (flat_fc && c->flat_generic) {
+                const size_t cnt = (size_t)desc->H * desc->C * desc->S;
+                t1.resize(cnt);
+                for (size_t q = 0; q < cnt; ++q) t1[q] = f32_to_bf16_rne(w->W1[q]);
+                st = upload(&c->W1, t1.data(), cnt * 2);
+            } else if (flat_fc) {
                 const int D = desc->C * desc->S;
                 pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 16, t1, f32_to_bf16_rne);
                 st = upload(&c->W1, t1.data(), t1.size() * 2);
@@ -656,7 +673,9 @@ gati_status_t upload_weights(gati_cache* c, const gati_cache_weights_t* w) {
         } else {
             std::vector<float> t1, t2;
             auto same = [](float x) { return x; };
-            if (flat_fc) {
+            if (flat_fc && c->flat_generic) {
+                st = upload(&c->W1, w->W1, (size_t)desc->H * desc->C * desc->S * 4);
+            } else if (flat_fc) {
                 const int D = desc->C * desc->S;
                 pack_weights_flat(w->W1, desc->H, (long)D, c->Hb, 8, t1, same);
                 st = upload(&c->W1, t1.data(), t1.size() * 4);
@@ -776,7 +795,6 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     const bool no_hidden_kernel = pool_fc || flat_fc || conv_fc;
     int conv_oh = 0, conv_ow = 0;
     if (conv_fc) {
-        if (desc->layout != GATI_LAYOUT_NCS) return GATI_ERR_INVALID_ARG;
         if (desc->in_h <= 0 || desc->in_w <= 0 || desc->conv_k <= 0 || desc->conv_s <= 0) return GATI_ERR_INVALID_ARG;
         if (desc->conv_k > desc->in_h || desc->conv_k > desc->in_w) return GATI_ERR_INVALID_ARG;
         if ((long)desc->in_h * desc->in_w != (long)desc->S) return GATI_ERR_INVALID_ARG;
@@ -789,7 +807,6 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     if (desc->C <= 0 || desc->S <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && desc->H <= 0) return GATI_ERR_INVALID_ARG;
     if (pool_fc) {
-        if (desc->layout != GATI_LAYOUT_NCS) return GATI_ERR_INVALID_ARG;
         if (desc->in_h <= 0 || desc->in_w <= 0 || desc->out_h <= 0 || desc->out_w <= 0) return GATI_ERR_INVALID_ARG;
         if (desc->out_h > desc->in_h || desc->out_w > desc->in_w) return GATI_ERR_INVALID_ARG;
         if ((long)desc->in_h * desc->in_w != (long)desc->S) return GATI_ERR_INVALID_ARG;
@@ -805,7 +822,6 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     const bool needs_ws = desc->selector == GATI_SEL_LINEAR;
     if (!w->W2 || !w->b2 || (needs_ws && !w->ws)) return GATI_ERR_INVALID_ARG;
     if (!pool_fc && (!w->W1 || !w->b1)) return GATI_ERR_INVALID_ARG;
-    if (flat_fc && ((long)desc->C * desc->S) % 64 != 0) return GATI_ERR_UNSUPPORTED;
     if (flat_fc && (long)desc->C * desc->S >= (1L << 31)) return GATI_ERR_UNSUPPORTED;
     if (!(desc->threshold == desc->threshold)) return GATI_ERR_INVALID_ARG;   // NaN
     // sizes whose padded products still fit the kernels' 32-bit tile arithmetic
@@ -841,7 +857,10 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         (void)hipGetLastError();
     c->pool_blocks_per_cu = 16;
 
-    if (flat_fc) {
+    if (flat_fc && ((long)desc->C * desc->S) % 64 != 0) {
+        c->flat_generic = true;
+        c->variant = POOL_FC_FLAT_GENERIC;
+    } else if (flat_fc) {
         const int k_step = c->bf16 ? 16 : 8;
         const long D = (long)desc->C * desc->S;
         c->flat_t = (desc->max_rows >= 256 && desc->H >= 256) ? 4 : (desc->max_rows >= 128 && desc->H >= 128) ? 2 : 1;
@@ -891,7 +910,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
     if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);
     if (st == GATI_OK && !no_hidden_kernel) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
-    if (st == GATI_OK && flat_fc)
+    if (st == GATI_OK && flat_fc && !c->flat_generic)
         st = upload((void**)&c->flat_partial, nullptr, (size_t)c->flat_splits * c->rows_b * c->Hb * 4);
     if (st == GATI_OK && conv_fc && c->conv_ksplit > 1)
         st = upload((void**)&c->conv_partial, nullptr, (size_t)c->conv_ksplit * desc->max_rows * c->Cp * 4);
@@ -945,9 +964,10 @@ gati_status_t gati_cache_pool(gati_cache_t* c, const void* act, const int32_t* r
     if (!c || n_max < 0 || n_max > c->desc.max_rows) return GATI_ERR_INVALID_ARG;
     if (n_max == 0) return GATI_OK;
     if (!act || !pooled) return GATI_ERR_INVALID_ARG;
-    if (c->flat_fc && ((reinterpret_cast<uintptr_t>(act) | reinterpret_cast<uintptr_t>(pooled)) & 15u) != 0)
+    const bool flat_mfma = c->flat_fc && !c->flat_generic;
+    if (flat_mfma && ((reinterpret_cast<uintptr_t>(act) | reinterpret_cast<uintptr_t>(pooled)) & 15u) != 0)
         return GATI_ERR_UNSUPPORTED;
-    if (c->flat_fc && c->F % 4 != 0) return GATI_ERR_UNSUPPORTED;
+    if (flat_mfma && c->F % 4 != 0) return GATI_ERR_UNSUPPORTED;
     if (!on_cache_device(c)) return GATI_ERR_DEVICE;
     const hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, pooled, nullptr, c->F, (hipStream_t)stream);
     return e == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
@@ -958,7 +978,7 @@ gati_status_t lookup_impl(gati_cache_t* c, const void* act, const int32_t* row_i
                           const int32_t* n_dev, int32_t* pred_class, float* confidence, uint8_t* hit,
                           float* logits, const int32_t* ids_in, int32_t* ids_out, int32_t* n_miss,
                           hipStream_t st) {
-    if (c->flat_fc && (reinterpret_cast<uintptr_t>(act) & 15u) != 0) return GATI_ERR_UNSUPPORTED;
+    if (c->flat_fc && !c->flat_generic && (reinterpret_cast<uintptr_t>(act) & 15u) != 0) return GATI_ERR_UNSUPPORTED;
     hipError_t e = launch_pool(c, act, row_index, n_max, n_dev, c->p, c->p16, c->Cp, st);
     if (e != hipSuccess) return GATI_ERR_DEVICE;
     e = c->bf16 ? launch_head_t<true>(c, n_max, n_dev, pred_class, confidence, hit, logits, ids_in, ids_out, n_miss, st)
@@ -1059,6 +1079,7 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     case POOL_NCS_ADAPTIVE: return "ncs_adaptive";
     case POOL_ADAPTIVE_GENERIC: return "adaptive_generic";
     case POOL_FC_FLAT: return "fc_flat";
+    case POOL_FC_FLAT_GENERIC: return "fc_flat_generic";
     case POOL_CONV: return "conv_mfma";
     case POOL_CONV_GENERIC: return "conv_generic";
     default: return "generic";

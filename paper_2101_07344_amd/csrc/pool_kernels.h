@@ -596,8 +596,11 @@ __global__ __launch_bounds__(WPB * 64) void pool_ncs_adaptive_kernel(PoolArgs a,
 }
 
 // Adaptive pool for shapes the tiled kernel cannot take: one lane per output window, scalar loads.
+// nsc_layout = 0: [n,C,S] rows, consecutive lanes take consecutive features (c*OO + window).
+// nsc_layout = 1: [n,S,C] rows (channels-last maps): consecutive lanes take consecutive channels of one
+// window, so a wave's loads fall on consecutive addresses; feature order stays [c][oy][ox].
 template <typename Tag>
-__global__ __launch_bounds__(256) void pool_adaptive_generic_kernel(PoolArgs a, AdaptiveArgs g) {
+__global__ __launch_bounds__(256) void pool_adaptive_generic_kernel(PoolArgs a, AdaptiveArgs g, int nsc_layout) {
     const int n = active_rows(a.n_dev, a.n_max);
     const int OO = g.out_h * g.out_w;
     const long F = (long)a.C * OO;
@@ -605,17 +608,20 @@ __global__ __launch_bounds__(256) void pool_adaptive_generic_kernel(PoolArgs a, 
     const long stride = (long)gridDim.x * blockDim.x;
     for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
         const long i = idx / F;
-        const int f = (int)(idx - i * F);
-        const int c = f / OO, wi = f - c * OO;
+        const int q = (int)(idx - i * F);
+        const int c = nsc_layout ? q % a.C : q / OO;
+        const int wi = nsc_layout ? q / a.C : q - c * OO;
+        const int f = c * OO + wi;
         const int oy = wi / g.out_w, ox = wi - oy * g.out_w;
         const int y0 = (oy * g.in_h) / g.out_h, y1 = ((oy + 1) * g.in_h + g.out_h - 1) / g.out_h;
         const int x0 = (ox * g.in_w) / g.out_w, x1 = ((ox + 1) * g.in_w + g.out_w - 1) / g.out_w;
         const long r = a.row_index ? (long)a.row_index[i] : i;
-        const long first = (r * a.C + c) * (long)a.S;
+        const long first = nsc_layout ? r * a.S * (long)a.C + c : (r * a.C + c) * (long)a.S;
+        const long step = nsc_layout ? a.C : 1;
         float s = 0.f;
         for (int y = y0; y < y1; ++y)
             for (int x = x0; x < x1; ++x) {
-                const long e = first + y * g.in_w + x;
+                const long e = first + (long)(y * g.in_w + x) * step;
                 if (Tag::kBytes == 4) s += static_cast<const float*>(a.act)[e];
                 else s += __uint_as_float((uint32_t)static_cast<const uint16_t*>(a.act)[e] << 16);
             }

@@ -49,9 +49,9 @@ def test_create_rejects_bad_arguments_on_the_host():
                             keep[4].ctypes.data, 0.0)
     assert g.gati_cache_create(g.CacheDesc(**good), w_null)[0] == g.GATI_ERR_INVALID_ARG
     assert g.gati_cache_create(g.CacheDesc(**{**good, "C": 1 << 21}), w)[0] == g.GATI_ERR_UNSUPPORTED
-    # Pool(h): the map sizes must multiply to S, the pooled map must fit in the input map, layout NCS
+    # Pool(h): the map sizes must multiply to S, the pooled map must fit in the input map
     pool = {**good, "predictor": g.GATI_PRED_POOL_FC, "H": 0, "S": 16, "in_h": 4, "in_w": 4, "out_h": 2, "out_w": 2}
-    for key, bad in (("in_h", 5), ("out_h", 0), ("out_w", 5), ("layout", g.GATI_LAYOUT_NSC)):
+    for key, bad in (("in_h", 5), ("out_h", 0), ("out_w", 5)):
         assert g.gati_cache_create(g.CacheDesc(**{**pool, key: bad}), w)[0] == g.GATI_ERR_INVALID_ARG, key
 
 

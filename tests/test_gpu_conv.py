@@ -27,6 +27,8 @@ SHAPES = [
     (32, 28, 28, 8, 5, 2, 10, 7, "bf16", "conv_mfma"),      # whole-plane staging with the transposing store
     (16, 16, 16, 40, 3, 1, 6, 9, "bf16", "conv_mfma"),      # the same with two filter tiles
     (16, 24, 24, 8, 3, 1, 5, 6, "f32", "conv_mfma"),        # fp32, several tiles per wave
+    (16, 12, 10, 6, 3, 2, 5, 14, "bf16", "conv_generic:nsc"),   # channels-last map
+    (7, 9, 9, 3, 2, 1, 4, 10, "f32", "conv_generic:nsc"),
 ]
 
 
@@ -42,10 +44,12 @@ def _weights(C, Co, k, K, F, rng):
 def test_conv_predictor_matches_oracle(C, ih, iw, Co, k, s, K, n, dtype, variant):
     rng = np.random.default_rng(C * ih + Co * k + s)
     S = ih * iw
-    x = torch.from_numpy((rng.standard_normal((n, C, S)) + 0.2).astype(np.float32))
+    variant, _, layout = variant.partition(":")
+    layout = layout or "ncs"
+    x = torch.from_numpy((rng.standard_normal((n, C, S) if layout == "ncs" else (n, S, C)) + 0.2).astype(np.float32))
     x = x.bfloat16() if dtype == "bf16" else x
     d = CacheDef(C=C, S=S, H=Co, K=K, dtype=dtype, threshold=0.5, round_operands=(dtype == "bf16"),
-                 predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s))
+                 predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s), layout=layout)
     F = d.F
     w = _weights(C, Co, k, K, F, rng)
     host = W.to_host_array(x)
@@ -54,7 +58,7 @@ def test_conv_predictor_matches_oracle(C, ih, iw, Co, k, s, K, n, dtype, variant
     ok = np.setdiff1d(np.arange(n), admit.inadmissible_rows(d, w, host)).astype(np.int32)
     assert len(ok) > n // 2
     want = oracle.lookup(d, w, host, row_index=ok)
-    cache = g.Cache(C, S, Co, K, dtype, "ncs", 0.5, n, w, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s))
+    cache = g.Cache(C, S, Co, K, dtype, layout, 0.5, n, w, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s))
     assert cache.pool_variant == variant and cache.F == F
     m = len(ok)
     okd = torch.from_numpy(ok).cuda()
@@ -97,8 +101,6 @@ def test_conv_rejects_bad_shapes():
         return g.Cache(C, S or ih * iw, Co, 3, "f32", layout, 0.5, 4, w, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s))
     with pytest.raises(g.GatiError):       # filter larger than the map
         make(8, 3, 3, 4, 4, 1)
-    with pytest.raises(g.GatiError):       # token-major storage has no 2-D map
-        make(8, 4, 4, 4, 3, 1, layout="nsc")
     with pytest.raises(g.GatiError):       # more filters than the kernels hold
         make(8, 4, 4, 65, 3, 1)
     make(8, 4, 4, 64, 3, 1).close()

@@ -36,18 +36,23 @@ SHAPES = [
     (3, 80, 80, 5, 5, "f32", "adaptive_generic"), (8, 13, 3, 13, 1, "bf16", "ncs_adaptive"),
     # 14-wide windows on an odd-width map (rows start on odd elements) and on a 14-wide map
     (16, 6, 27, 2, 2, "bf16", "ncs_adaptive"), (32, 4, 14, 2, 1, "bf16", "ncs_adaptive"),
+    # channels-last maps
+    (64, 14, 14, 4, 4, "bf16", "adaptive_generic:nsc"), (24, 5, 10, 3, 4, "f32", "adaptive_generic:nsc"),
+    (7, 3, 11, 2, 5, "bf16", "adaptive_generic:nsc"),
 ]
 
 
 @pytest.mark.parametrize("C,ih,iw,oh,ow,dtype,variant", SHAPES)
 def test_adaptive_pool_matches_oracle(C, ih, iw, oh, ow, dtype, variant):
     n, S, F = 9, ih * iw, C * oh * ow
+    variant, _, layout = variant.partition(":")
+    layout = layout or "ncs"
     gen = torch.Generator().manual_seed(C + ih + oh)
-    x = torch.randn((n, C, S), generator=gen) + 0.3
+    x = torch.randn((n, C, S) if layout == "ncs" else (n, S, C), generator=gen) + 0.3
     x = x.bfloat16() if dtype == "bf16" else x
-    cache = g.Cache(C, S, 0, 4, dtype, "ncs", 0.5, 32, _weights(F, 4), predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+    cache = g.Cache(C, S, 0, 4, dtype, layout, 0.5, 32, _weights(F, 4), predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
     assert cache.pool_variant == variant
-    d = CacheDef(C=C, S=S, H=0, K=4, dtype=dtype, predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+    d = CacheDef(C=C, S=S, H=0, K=4, dtype=dtype, predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow), layout=layout)
     want = oracle.pool(d, W.to_host_array(x))
     xd = x.cuda()
     idx = torch.tensor([8, 0, 3, 3, 5, 1, 7], dtype=torch.int32, device="cuda")
@@ -71,15 +76,18 @@ def test_adaptive_pool_matches_oracle(C, ih, iw, oh, ow, dtype, variant):
     (24, 5, 10, 3, 4, 33, "bf16", 45),
     # more rows than a few 32-row tiles, F = 2048 .. 4096, and a feature count that is a multiple of nothing
     (256, 14, 14, 4, 4, 1000, "bf16", 150), (128, 8, 8, 4, 4, 200, "f32", 140), (530, 6, 6, 2, 2, 130, "bf16", 260),
+    (96, 7, 7, 2, 2, 50, "bf16:nsc", 70),      # channels-last map through the whole lookup
 ])
 def test_pool_fc_lookup_matches_oracle(C, ih, iw, oh, ow, K, dtype, n):
     rng = np.random.default_rng(C + K)
     S, F = ih * iw, C * oh * ow
-    x = torch.from_numpy((rng.standard_normal((n, C, S)) + 0.4).astype(np.float32))
+    dtype, _, layout = dtype.partition(":")
+    layout = layout or "ncs"
+    x = torch.from_numpy((rng.standard_normal((n, C, S) if layout == "ncs" else (n, S, C)) + 0.4).astype(np.float32))
     x = x.bfloat16() if dtype == "bf16" else x
     w = _weights(F, K, rng)
     d = CacheDef(C=C, S=S, H=0, K=K, dtype=dtype, threshold=0.5, round_operands=(dtype == "bf16"),
-                 predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+                 predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow), layout=layout)
     host = W.to_host_array(x)
     s0 = oracle.lookup(d, {**w, "bs": 0.0}, host)["score"]
     w["bs"] = float(np.float32(-np.median(s0)))                 # about half the rows hit
@@ -87,7 +95,7 @@ def test_pool_fc_lookup_matches_oracle(C, ih, iw, oh, ow, K, dtype, n):
     assert len(ok) > n // 2
     want = oracle.lookup(d, w, host, row_index=ok)
     assert 0 < want["hit"].sum() < len(ok)
-    cache = g.Cache(C, S, 0, K, dtype, "ncs", 0.5, n, w, predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
+    cache = g.Cache(C, S, 0, K, dtype, layout, 0.5, n, w, predictor="pool_fc", in_hw=(ih, iw), out_hw=(oh, ow))
     m = len(ok)
     out = {"pred_class": torch.zeros(m, dtype=torch.int32, device="cuda"), "confidence": torch.zeros(m, device="cuda"),
            "hit": torch.zeros(m, dtype=torch.uint8, device="cuda"), "logits": torch.zeros(m, K, device="cuda")}
