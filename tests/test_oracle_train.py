@@ -185,3 +185,114 @@ def test_pool_fc_predictor_is_softmax_regression():
     num = (train.losses({**wp, "W2": bump}, feats, labels, Y, 0.3, 2.0)[0] -
            train.losses({**wp, "W2": low}, feats, labels, Y, 0.3, 2.0)[0]) / (2 * eps)
     assert abs(num - g["W2"][1, 2]) < 1e-7
+
+
+def _fd_check(w, x, labels, Y, alpha, lam, arch, keys, which):
+    g = train.gradients(w, x, labels, Y, alpha, lam, arch)
+    eps = 1e-6
+    for key in keys:
+        flat = np.asarray(w[key], np.float64)
+        for idx in list(np.ndindex(flat.shape))[:: max(1, flat.size // 9)]:
+            wp = {**w, key: flat.copy()}
+            wm = {**w, key: flat.copy()}
+            wp[key][idx] += eps
+            wm[key][idx] -= eps
+            num = (train.losses(wp, x, labels, Y, alpha, lam, arch)[which] -
+                   train.losses(wm, x, labels, Y, alpha, lam, arch)[which]) / (2 * eps)
+            assert abs(num - g[key][idx]) < 1e-7, (key, idx, num, g[key][idx])
+    return g
+
+
+def test_fc_predictor_whose_selector_reads_the_hidden_layer():
+    """FC(h): the same two-layer network on the flattened row; the selector reads [h ; q] and treats both as
+    data.  Finite differences, autograd on an independently written loss, and the predictor's gradients must
+    not depend on which features the selector reads."""
+    rng = np.random.default_rng(21)
+    n, D, H, K = 10, 12, 5, 4
+    w = {"W1": rng.standard_normal((H, D)) * 0.5, "b1": rng.standard_normal(H) * 0.2, "W2": rng.standard_normal((K, H)) * 0.7,
+         "b2": rng.standard_normal(K) * 0.2, "ws": rng.standard_normal(H + K) * 0.5, "bs": -0.2}
+    x = np.maximum(rng.standard_normal((n, D)), 0)
+    labels = rng.integers(0, K, n)
+    Y = rng.random((n, K)) + 0.05
+    Y /= Y.sum(axis=1, keepdims=True)
+    arch = {"sel_input": "hidden"}
+    g = _fd_check(w, x, labels, Y, 0.4, 2.0, arch, ("W1", "b1", "W2", "b2"), 0)
+    _fd_check(w, x, labels, Y, 0.4, 2.0, arch, ("ws",), 1)
+    tw = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in w.items() if k != "bs"}
+    bs = torch.tensor(float(w["bs"]), dtype=torch.float64, requires_grad=True)
+    h = torch.relu(torch.tensor(x) @ tw["W1"].T + tw["b1"])
+    z = h @ tw["W2"].T + tw["b2"]
+    Lp = -(torch.tensor(train.targets(labels, Y, 0.4)) * torch.log_softmax(z, dim=1)).sum() / n
+    u = torch.cat([h.detach(), torch.softmax(z, dim=1).detach()], dim=1) @ tw["ws"] + bs
+    G = torch.tensor((z.detach().numpy().argmax(1) == Y.argmax(1)).astype(np.float64))
+    Ls = -(G * torch.nn.functional.logsigmoid(u) + 2.0 * (1 - G) * torch.nn.functional.logsigmoid(-u)).sum() / n
+    (Lp + Ls).backward()
+    for k in ("W1", "b1", "W2", "b2", "ws"):
+        assert np.max(np.abs(tw[k].grad.numpy() - g[k])) < 1e-12, k
+    assert abs(bs.grad.item() - g["bs"]) < 1e-12
+    # the predictor's part equals that of a network whose selector reads the input instead
+    wi = {**w, "ws": rng.standard_normal(D + K)}
+    gi = train.gradients(wi, x, labels, Y, 0.4, 2.0, {"sel_input": "input"})
+    for k in ("W1", "b1", "W2", "b2"):
+        assert np.array_equal(g[k], gi[k]), k
+    assert g["ws"].shape == (H + K,) and gi["ws"].shape == (D + K,)
+
+
+def test_conv_predictor_gradients():
+    """Conv(k,s): finite differences, autograd through the library's convolution, and the full-size filter,
+    which must give the FC(h) gradients on the flattened map."""
+    rng = np.random.default_rng(22)
+    n, C, ih, iw, Co, k, s, K = 6, 3, 7, 6, 4, 3, 2, 5
+    oh, ow = (ih - k) // s + 1, (iw - k) // s + 1
+    F = Co * oh * ow
+    w = {"W1": rng.standard_normal((Co, C, k, k)) * 0.4, "b1": rng.standard_normal(Co) * 0.2,
+         "W2": rng.standard_normal((K, F)) * 0.4, "b2": rng.standard_normal(K) * 0.2,
+         "ws": rng.standard_normal(F + K) * 0.4, "bs": 0.1}
+    x = rng.standard_normal((n, C, ih, iw))
+    labels = rng.integers(0, K, n)
+    Y = rng.random((n, K)) + 0.05
+    Y /= Y.sum(axis=1, keepdims=True)
+    arch = {"stride": s}
+    f = train.forward(w, x, arch)
+    assert f["h"].shape == (n, F)
+    ref = torch.relu(torch.nn.functional.conv2d(torch.tensor(x), torch.tensor(w["W1"]), torch.tensor(w["b1"]), stride=s))
+    assert np.allclose(f["h"], ref.reshape(n, -1).numpy(), atol=1e-12)          # [filter][oy][ox] order
+    g = _fd_check(w, x, labels, Y, 0.3, 2.5, arch, ("W1", "b1", "W2", "b2"), 0)
+    _fd_check(w, x, labels, Y, 0.3, 2.5, arch, ("ws",), 1)
+    tw = {kk: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for kk, v in w.items() if kk != "bs"}
+    bs = torch.tensor(float(w["bs"]), dtype=torch.float64, requires_grad=True)
+    h = torch.relu(torch.nn.functional.conv2d(torch.tensor(x), tw["W1"], tw["b1"], stride=s)).reshape(n, -1)
+    z = h @ tw["W2"].T + tw["b2"]
+    Lp = -(torch.tensor(train.targets(labels, Y, 0.3)) * torch.log_softmax(z, dim=1)).sum() / n
+    u = torch.cat([h.detach(), torch.softmax(z, dim=1).detach()], dim=1) @ tw["ws"] + bs
+    G = torch.tensor((z.detach().numpy().argmax(1) == Y.argmax(1)).astype(np.float64))
+    Ls = -(G * torch.nn.functional.logsigmoid(u) + 2.5 * (1 - G) * torch.nn.functional.logsigmoid(-u)).sum() / n
+    (Lp + Ls).backward()
+    for kk in ("W1", "b1", "W2", "b2", "ws"):
+        assert np.max(np.abs(tw[kk].grad.numpy() - g[kk])) < 1e-12, kk
+    lp, ls = train.losses(w, x, labels, Y, 0.3, 2.5, arch)
+    assert abs(lp - Lp.item()) < 1e-12 and abs(ls - Ls.item()) < 1e-12
+    # a filter as large as the (square) map: one output position per filter = FC over the flattened map
+    xs = rng.standard_normal((n, C, 4, 4))
+    wf = {"W1": rng.standard_normal((Co, C, 4, 4)) * 0.3, "b1": w["b1"], "W2": rng.standard_normal((K, Co)) * 0.5,
+          "b2": w["b2"], "ws": rng.standard_normal(Co + K) * 0.4, "bs": 0.1}
+    gc = train.gradients(wf, xs, labels, Y, 0.3, 2.5, {"stride": 1})
+    gf = train.gradients({**wf, "W1": wf["W1"].reshape(Co, -1)}, xs.reshape(n, -1), labels, Y, 0.3, 2.5, {"sel_input": "hidden"})
+    assert np.allclose(gc["W1"].reshape(Co, -1), gf["W1"], atol=1e-14)
+    for kk in ("b1", "W2", "b2", "ws"):
+        assert np.allclose(gc[kk], gf[kk], atol=1e-14), kk
+
+
+def test_softmax_threshold_mode_trains_the_predictor_alone():
+    """No selector network: the predictor's gradients equal those of the same network with a selector, the
+    selector loss is zero and no selector gradient exists."""
+    w, pooled, labels, Y = _case(seed=9)
+    g = train.gradients(w, pooled, labels, Y, 0.3, 2.0)
+    bare = {k: v for k, v in w.items() if k not in ("ws", "bs")}
+    gb = train.gradients(bare, pooled, labels, Y, 0.3, 2.0)
+    assert set(gb) == {"W1", "b1", "W2", "b2"}
+    for k in gb:
+        assert np.array_equal(gb[k], g[k]), k
+    assert train.losses(bare, pooled, labels, Y, 0.3, 2.0) == (train.losses(w, pooled, labels, Y, 0.3, 2.0)[0], 0.0)
+    new, lp, ls = train.sgd_step(bare, pooled, labels, Y, 0.1, 0.3, 2.0)
+    assert set(new) == {"W1", "b1", "W2", "b2"} and ls == 0.0
