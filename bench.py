@@ -498,15 +498,21 @@ def time_training(spec, weights, caches, acts, torch, g, W, with_cpu, reps=10):
     lab_d, Y_d = torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda()
     out, seen = [], set()
     for l, L in enumerate(spec.layers):
-        if (L.C, L.F) in seen or L.predictor not in ("gap_mlp", "pool_fc") or L.selector not in ("linear", "hidden"):
+        if (L.C, L.F) in seen:
             continue
         seen.add((L.C, L.F))
-        pool_fc, hid = L.predictor == "pool_fc", (L.sel_hidden if L.selector == "hidden" else 0)
+        pool_fc, fc_mlp, conv_fc = L.predictor == "pool_fc", L.predictor == "fc_mlp", L.predictor == "conv_fc"
+        hid = L.sel_hidden if L.selector == "hidden" else 0
         F, Hd = L.F, (0 if pool_fc else L.H)
-        pooled = torch.empty((n, F), device="cuda")
-        caches[l].pool(acts[l], None, n, None, pooled)
-        tr = g.Trainer(L.C, Hd, L.K, weights[l], max_rows=n, sel_hidden=hid,
-                       predictor=L.predictor, out_hw=getattr(L, "out_hw", (0, 0)))
+        if fc_mlp or conv_fc:
+            # these predictors train on the activation itself: the rows as fp32 (the trainer's arithmetic)
+            pooled = acts[l].reshape(n, -1).float()
+        else:
+            pooled = torch.empty((n, F), device="cuda")
+            caches[l].pool(acts[l], None, n, None, pooled)
+        tr = g.Trainer(L.C, Hd, L.K, weights[l], max_rows=n, sel_hidden=hid, predictor=L.predictor,
+                       out_hw=getattr(L, "out_hw", (0, 0)), S=L.S, in_hw=getattr(L, "in_hw", (0, 0)),
+                       conv_ks=getattr(L, "conv_ks", (0, 0)), selector=L.selector)
         losses = torch.zeros(2, device="cuda")
         for _ in range(3):
             tr.step(pooled, lab_d, Y_d, 0.002, 0.5, 2.0, losses)
@@ -519,10 +525,32 @@ def time_training(spec, weights, caches, acts, torch, g, W, with_cpu, reps=10):
         us = ev[0].elapsed_time(ev[1]) / reps * 1e3
         # forward + backward products: predictor (3x the forward of each layer, the first layer's input gradient
         # is not needed), hidden-layer selector (forward + weight gradient)
-        flops = (6 * n * Hd * L.K + 4 * n * F * Hd) if Hd else 4 * n * F * L.K
-        flops += 4 * n * (F + L.K) * hid
-        row = {"layer": l, "F": F, "H": Hd, "K": L.K, "selector_hidden": hid, "n": n, "step_us": round(us, 1),
-               "TFLOPs": round(flops / (us * 1e-6) / 1e12, 2), "frac_of_fp32_mfma_peak": round(flops / (us * 1e-6) / 1e12 / 157.3, 4)}
+        if fc_mlp:
+            D = L.C * L.S
+            flops = 4 * n * D * Hd + 6 * n * Hd * L.K
+            Fs = Hd
+        elif conv_fc:
+            k = L.conv_ks[0]
+            flops = 4 * n * F * L.C * k * k + 6 * n * F * L.K          # F = filters x positions
+            Fs = F
+        else:
+            flops = (6 * n * Hd * L.K + 4 * n * F * Hd) if Hd else 4 * n * F * L.K
+            Fs = F
+        flops += 4 * n * (Fs + L.K) * hid
+        row = {"layer": l, "predictor": L.predictor, "F": F, "H": Hd, "K": L.K, "selector_hidden": hid, "n": n,
+               "step_us": round(us, 1), "TFLOPs": round(flops / (us * 1e-6) / 1e12, 2),
+               "frac_of_fp32_mfma_peak": round(flops / (us * 1e-6) / 1e12 / 157.3, 4)}
+        if fc_mlp:
+            # the update streams the fp32 master copy of W1 once (read + write): the HBM floor of a step
+            wb = 2 * Hd * L.C * L.S * 4
+            row["W1_update_bytes"] = wb
+            row["hbm_floor_us"] = round(wb / (HBM_PEAK_GBS * 1e9) * 1e6, 1)
+        if fc_mlp or conv_fc:
+            out.append(row)
+            tr.close()
+            del pooled
+            torch.cuda.empty_cache()
+            continue
         if with_cpu and len(out) == 0:            # CPU baseline leg: the fp64 oracle's step on the same batch
             from oracle import train as otrain
             p_host = pooled.cpu().numpy()

@@ -265,9 +265,16 @@ const char *gati_cache_pool_variant(const gati_cache_t *cache);
  * its gradients reach Ws, cs, vs and bs through the ReLU, never q.
  * With GATI_PRED_POOL_FC (the paper's Pool(h)) there is no hidden layer: p are the C*out_h*out_w ReLU'd
  * window means gati_cache_pool writes for such a cache, z = W2 p + b2, and W1, b1 are not used (NULL).
- * GATI_PRED_GAP_MLP and GATI_PRED_POOL_FC with GATI_SEL_LINEAR or GATI_SEL_HIDDEN are supported
- * (GATI_ERR_UNSUPPORTED otherwise); act_dtype, layout, S, in_h, in_w and threshold of the descriptor
- * are ignored.                                                                                     */
+ * With GATI_PRED_FC_MLP (the paper's FC(h)) the input rows are the flattened activation (D = C*S values,
+ * as fp32), W1 is [H, D], and the selector reads [h ; q] -- the hidden layer and the class distribution,
+ * as the lookup does -- both as data: L_sel sends no gradient into the predictor.
+ * With GATI_PRED_CONV_FC (the paper's Conv(k,s)) the input rows are the channel-major map (C*in_h*in_w
+ * values, as fp32), W1 is [H, C, conv_k, conv_k] (H filters), h = relu(conv(x, W1, stride conv_s) + b1)
+ * flattened [filter][oy][ox], W2 is [K, F] and the selector reads [h ; q] (F + K inputs).
+ * With GATI_SEL_SOFTMAX (no selector network) only the predictor is trained: L_sel = 0, ws and bs are not
+ * used and gati_trainer_get_weights leaves them alone (ws may be NULL).
+ * act_dtype, layout and threshold of the descriptor are ignored; S, in_h, in_w, conv_k, conv_s matter for
+ * the predictors that name them above.                                                             */
 typedef struct gati_trainer gati_trainer_t; /* opaque, owned by the library */
 
 typedef struct {
@@ -285,8 +292,8 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t *desc, const gati_cach
 gati_status_t gati_trainer_destroy(gati_trainer_t *trainer);
 
 /* Enqueue one SGD step on `stream`.
- *   pooled      device [n, ld_pooled] fp32, ld_pooled >= F: row i holds sample i's F features (F = C, or
- *               C*out_h*out_w for GATI_PRED_POOL_FC)
+ *   pooled      device [n, ld_pooled] fp32, ld_pooled >= F: row i holds sample i's F input values (F = C;
+ *               C*out_h*out_w for GATI_PRED_POOL_FC; C*S for GATI_PRED_FC_MLP and GATI_PRED_CONV_FC)
  *   n           host count, 0 <= n <= max_rows (0: nothing happens)
  *   labels      device [n] int32 true class, in [0, K)
  *   teacher     device [n, ld_teacher] fp32, ld_teacher >= K: the base DNN's class probabilities
@@ -299,9 +306,11 @@ gati_status_t gati_trainer_step(gati_trainer_t *trainer, const float *pooled, in
                                 const gati_train_params_t *params, float *losses, void *stream);
 
 /* Copy the current weights to HOST arrays W1 [H, C], b1 [H], W2 [K, H], b2 [K], ws [C + K] and
- * *bs, after waiting for all work on the device.  A trainer with a hidden-layer selector has no ws
- * (NULL is accepted there); its selector comes from gati_trainer_get_hidden_selector.  A
- * GATI_PRED_POOL_FC trainer has no W1, b1 (NULL accepted); its W2 is [K, F] and ws [F + K]. */
+ * *bs, after waiting for all work on the device; shapes as gati_cache_create takes them for the
+ * trainer's predictor (FC(h): W1 [H, C*S], ws [H + K]; Conv(k,s): W1 [H, C, k, k], W2 [K, F],
+ * ws [F + K]).  A trainer with a hidden-layer selector or without a selector network has no ws
+ * (NULL is accepted there); the hidden-layer selector comes from gati_trainer_get_hidden_selector.
+ * A GATI_PRED_POOL_FC trainer has no W1, b1 (NULL accepted); its W2 is [K, F] and ws [F + K]. */
 gati_status_t gati_trainer_get_weights(gati_trainer_t *trainer, float *W1, float *b1, float *W2, float *b2,
                                        float *ws, float *bs);
 

@@ -340,37 +340,55 @@ def gati_trainer_get_hidden_selector(handle, Ws, cs, vs) -> int:
 
 
 class Trainer:
-    """SGD steps on one cache's predictor and selector (pooling predictor; linear selector, or the
-    hidden-layer selector when sel_hidden > 0 and the weights hold Ws, cs, vs)."""
+    """SGD steps on one cache's predictor and selector.  predictor: "gap_mlp" (input rows = pooled features
+    [n, C]), "pool_fc" (the paper's Pool(h): input rows = the C*out_h*out_w window means, no hidden layer, H
+    ignored), "fc_mlp" (the paper's FC(h): input rows = the flattened activation [n, C*S] as fp32) or "conv_fc"
+    (the paper's Conv(k,s): input rows = the channel-major map [n, C*in_h*in_w] as fp32, H filters).
+    selector: "linear", "hidden" (sel_hidden > 0 units; weights hold Ws, cs, vs) or "softmax" (no selector
+    network: the predictor alone is trained)."""
 
     def __init__(self, C_: int, H: int, K: int, weights: dict, max_rows: int, sel_hidden: int = 0,
-                 predictor: str = "gap_mlp", out_hw=(0, 0)):
-        """predictor "pool_fc" (the paper's Pool(h)): no hidden layer, H is ignored, the features are the
-        C_*out_h*out_w window means and W2 is [K, F]."""
-        pool_fc = predictor == "pool_fc"
-        assert predictor in ("gap_mlp", "pool_fc")
-        F = C_ * out_hw[0] * out_hw[1] if pool_fc else C_
+                 predictor: str = "gap_mlp", out_hw=(0, 0), S: int = 1, in_hw=(0, 0), conv_ks=(0, 0), selector: str = None):
+        pool_fc, fc_mlp, conv_fc = predictor == "pool_fc", predictor == "fc_mlp", predictor == "conv_fc"
+        assert predictor in ("gap_mlp", "pool_fc", "fc_mlp", "conv_fc")
+        selector = selector or ("hidden" if sel_hidden else "linear")
+        sel_hidden = int(sel_hidden) if selector == "hidden" else 0
         H = 0 if pool_fc else H
-        names = (("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")) + (("Ws", "cs", "vs") if sel_hidden else ("ws",))
+        if conv_fc:
+            S = in_hw[0] * in_hw[1]
+            k, s = conv_ks
+            P = ((in_hw[0] - k) // s + 1) * ((in_hw[1] - k) // s + 1)
+        # width of the input rows, inputs of the output layer, features the selector reads
+        Cin = C_ * out_hw[0] * out_hw[1] if pool_fc else (C_ * S if (fc_mlp or conv_fc) else C_)
+        Hin = Cin if pool_fc else (H * P if conv_fc else H)
+        Fsel = Hin if (fc_mlp or conv_fc) else Cin
+        names = ("W2", "b2") if pool_fc else ("W1", "b1", "W2", "b2")
+        names += {"hidden": ("Ws", "cs", "vs"), "linear": ("ws",), "softmax": ()}[selector]
         keep = {k: np.ascontiguousarray(weights[k], dtype=np.float32) for k in names}
-        if not pool_fc:
-            assert keep["W1"].shape == (H, C_) and keep["b1"].shape == (H,)
-        assert keep["W2"].shape == (K, F if pool_fc else H) and keep["b2"].shape == (K,)
-        if sel_hidden:
-            assert keep["Ws"].shape == (sel_hidden, F + K) and keep["cs"].shape == (sel_hidden,) \
+        if conv_fc:
+            assert keep["W1"].shape == (H, C_, conv_ks[0], conv_ks[0]) and keep["b1"].shape == (H,)
+        elif not pool_fc:
+            assert keep["W1"].shape == (H, Cin) and keep["b1"].shape == (H,)
+        assert keep["W2"].shape == (K, Hin) and keep["b2"].shape == (K,)
+        if selector == "hidden":
+            assert keep["Ws"].shape == (sel_hidden, Fsel + K) and keep["cs"].shape == (sel_hidden,) \
                 and keep["vs"].shape == (sel_hidden,)
-        else:
-            assert keep["ws"].shape == (F + K,)
-        desc = CacheDesc(C_, 1, H, K, GATI_F32, GATI_LAYOUT_NCS, 0.5, max_rows,
-                         GATI_SEL_HIDDEN if sel_hidden else GATI_SEL_LINEAR,
-                         GATI_PRED_POOL_FC if pool_fc else GATI_PRED_GAP_MLP, 0, 0, int(out_hw[0]), int(out_hw[1]),
-                         int(sel_hidden), 0, 0)
+        elif selector == "linear":
+            assert keep["ws"].shape == (Fsel + K,)
+        desc = CacheDesc(C_, S, H, K, GATI_F32, GATI_LAYOUT_NCS, 0.5, max_rows,
+                         {"linear": GATI_SEL_LINEAR, "hidden": GATI_SEL_HIDDEN, "softmax": GATI_SEL_SOFTMAX}[selector],
+                         {"gap_mlp": GATI_PRED_GAP_MLP, "pool_fc": GATI_PRED_POOL_FC, "fc_mlp": GATI_PRED_FC_MLP,
+                          "conv_fc": GATI_PRED_CONV_FC}[predictor],
+                         int(in_hw[0]), int(in_hw[1]), int(out_hw[0]), int(out_hw[1]), sel_hidden,
+                         int(conv_ks[0]), int(conv_ks[1]))
         ptr = lambda k: keep[k].ctypes.data if k in keep else None
-        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights["bs"]),
+        w = CacheWeights(ptr("W1"), ptr("b1"), ptr("W2"), ptr("b2"), ptr("ws"), float(weights.get("bs", 0.0)),
                          ptr("Ws"), ptr("cs"), ptr("vs"))
         st, self.handle = gati_trainer_create(desc, w)
         _check(st, "gati_trainer_create")
-        self.C, self.H, self.K, self.max_rows, self.sel_hidden = F, H, K, max_rows, int(sel_hidden)
+        self.C, self.H, self.K, self.max_rows, self.sel_hidden = Cin, H, K, max_rows, sel_hidden
+        self.Hin, self.Fsel, self.selector = Hin, Fsel, selector
+        self._w1_shape = (H, C_, conv_ks[0], conv_ks[0]) if conv_fc else (H, Cin)
 
     def step(self, pooled, labels, teacher, lr: float, alpha: float, fp_weight: float, losses=None, stream=None,
              n: Optional[int] = None):
@@ -397,17 +415,18 @@ class Trainer:
                           None if losses is None else losses[e, b], stream)
 
     def get_weights(self) -> dict:
-        out = {"W2": np.empty((self.K, self.H if self.H else self.C), np.float32), "b2": np.empty(self.K, np.float32)}
+        out = {"W2": np.empty((self.K, self.Hin), np.float32), "b2": np.empty(self.K, np.float32)}
         if self.H:
-            out.update({"W1": np.empty((self.H, self.C), np.float32), "b1": np.empty(self.H, np.float32)})
-        if not self.sel_hidden:
-            out["ws"] = np.empty(self.C + self.K, np.float32)
+            out.update({"W1": np.empty(self._w1_shape, np.float32), "b1": np.empty(self.H, np.float32)})
+        if self.selector == "linear":
+            out["ws"] = np.empty(self.Fsel + self.K, np.float32)
         bs = np.empty(1, np.float32)
         _check(gati_trainer_get_weights(self.handle, out.get("W1"), out.get("b1"), out["W2"], out["b2"], out.get("ws"), bs),
                "gati_trainer_get_weights")
-        out["bs"] = float(bs[0])
-        if self.sel_hidden:
-            out.update({"Ws": np.empty((self.sel_hidden, self.C + self.K), np.float32),
+        if self.selector != "softmax":
+            out["bs"] = float(bs[0])
+        if self.selector == "hidden":
+            out.update({"Ws": np.empty((self.sel_hidden, self.Fsel + self.K), np.float32),
                         "cs": np.empty(self.sel_hidden, np.float32), "vs": np.empty(self.sel_hidden, np.float32)})
             _check(gati_trainer_get_hidden_selector(self.handle, out["Ws"], out["cs"], out["vs"]),
                    "gati_trainer_get_hidden_selector")

@@ -5,21 +5,39 @@
 
 #include <algorithm>
 #include <new>
+#include <vector>
 
 #include "../../include/gati.h"
 #include "train_kernels.h"
 
 using namespace gati;
 
+// What the trainer holds, by predictor (Section 3, table of predictor architectures):
+//   pooling (global)   input p [n, C]           -> W1 [H, C]       -> h [n, H]      -> W2 [K, H];   selector reads [p ; q]
+//   Pool(h)            input f [n, F]                                               -> W2 [K, F];   selector reads [f ; q]
+//   FC(h)              input x [n, D]           -> W1 [H, D]       -> h [n, H]      -> W2 [K, H];   selector reads [h ; q]
+//   Conv(k,s)          input x [n, C*ih*iw] -> windows Xc [n*P, C*k*k] -> W1 [Co, C*k*k] -> h [n*P, Co] = [n, P*Co]
+//                                                                                   -> W2 [K, P*Co]; selector reads [h ; q]
+// Conv(k,s) keeps its hidden values in [position][filter] order, which is what the product over windows
+// writes; the caller's order is [filter][position], so the columns of W2, ws and Ws that belong to hidden
+// values are permuted on the way in and out (every formula of the step is indifferent to that order).
 struct gati_trainer {
-    int C = 0, H = 0, K = 0, max_rows = 0;
+    int C = 0, H = 0, K = 0, max_rows = 0;    // C: width of the caller's input rows; H: first layer's outputs (0: none)
+    int Cin = 0;                              // reduction length of the first layer (C; C*k*k for Conv(k,s))
+    int P = 1;                                // first-layer output rows per sample (Conv(k,s): oh*ow)
+    int Hin = 0;                              // inputs of the output layer: P*H, or C without a first layer
+    int Fsel = 0;                             // features the selector reads beside q: C (pooling predictors) or Hin
+    bool sel_hidden_feat = false;             // the selector reads the hidden layer (FC(h), Conv(k,s))
+    bool no_selector = false;                 // softmax-threshold mode: the predictor alone is trained
+    int conv_k = 0, conv_s = 0, conv_c = 0, conv_ih = 0, conv_iw = 0, conv_oh = 0, conv_ow = 0;   // Conv(k,s) only
     int device = 0, num_cu = 256;
     float *W1 = nullptr, *b1 = nullptr, *W2 = nullptr, *b2 = nullptr, *ws = nullptr, *bs = nullptr;
     float *h = nullptr, *z = nullptr, *q = nullptr, *dh = nullptr, *du = nullptr, *lp = nullptr, *ls = nullptr;
+    float* Xc = nullptr;       // Conv(k,s): gathered windows [max_rows*P][Cin]
     float* part = nullptr;     // split-reduction slices of the largest product
     size_t part_floats = 0;
-    // selector with a hidden layer: Hs units over input rows X = [p ; q] of stride Sx (C + K rounded up to 4,
-    // zero padded, so that rows stay 16-byte aligned); Ws is held with the same stride
+    // selector with a hidden layer: Hs units over input rows X = [features ; q] of stride Sx (Fsel + K rounded up
+    // to 4, zero padded, so that rows stay 16-byte aligned); Ws is held with the same stride
     int Hs = 0, Sx = 0;
     float *Ws = nullptr, *cs = nullptr, *vs = nullptr, *X = nullptr, *g = nullptr, *dg = nullptr, *G = nullptr;
 };
@@ -30,7 +48,7 @@ constexpr int kMaxSlices = 16;
 
 void free_all(gati_trainer* t) {
     void* ptrs[] = {t->W1, t->b1, t->W2, t->b2, t->ws, t->bs, t->h, t->z, t->q, t->dh, t->du, t->lp, t->ls, t->part,
-                    t->Ws, t->cs, t->vs, t->X, t->g, t->dg, t->G};
+                    t->Ws, t->cs, t->vs, t->X, t->g, t->dg, t->G, t->Xc};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -79,6 +97,26 @@ hipError_t launch_gemm(const gati_trainer* t, GemmArgs g, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Conv(k,s): column of hidden value (filter o, position p) in the caller's order and in the trainer's.
+inline size_t col_caller(const gati_trainer* t, int o, int p) { return (size_t)o * t->P + p; }
+inline size_t col_inner(const gati_trainer* t, int o, int p) { return (size_t)p * t->H + o; }
+
+// Copy a [rows][Hin (+ tail)] matrix between the caller's column order and the trainer's (to_inner or
+// back); columns past the hidden values (the class-probability part of selector weights) keep their place.
+void permute_hidden_cols(const gati_trainer* t, const float* src, size_t lds, float* dst, size_t ldd, int rows, int tail,
+                         bool to_inner) {
+    for (int r = 0; r < rows; ++r) {
+        const float* s = src + (size_t)r * lds;
+        float* d = dst + (size_t)r * ldd;
+        for (int o = 0; o < t->H; ++o)
+            for (int p = 0; p < t->P; ++p) {
+                if (to_inner) d[col_inner(t, o, p)] = s[col_caller(t, o, p)];
+                else d[col_caller(t, o, p)] = s[col_inner(t, o, p)];
+            }
+        for (int k = 0; k < tail; ++k) d[t->Hin + k] = s[t->Hin + k];
+    }
+}
+
 bool on_trainer_device(const gati_trainer* t) {
     int dev = -1;
     return hipGetDevice(&dev) == hipSuccess && dev == t->device;
@@ -92,67 +130,110 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
                                   gati_trainer_t** out) {
     if (!desc || !w || !out) return GATI_ERR_INVALID_ARG;
     if (desc->C <= 0 || desc->K <= 0 || desc->max_rows <= 0) return GATI_ERR_INVALID_ARG;
-    if (desc->predictor != GATI_PRED_GAP_MLP && desc->predictor != GATI_PRED_POOL_FC) return GATI_ERR_UNSUPPORTED;
+    if (desc->predictor != GATI_PRED_GAP_MLP && desc->predictor != GATI_PRED_POOL_FC &&
+        desc->predictor != GATI_PRED_FC_MLP && desc->predictor != GATI_PRED_CONV_FC)
+        return GATI_ERR_INVALID_ARG;
     // Pool(h): no hidden layer; the features are the C * out_h * out_w pooled windows
     const bool pool_fc = desc->predictor == GATI_PRED_POOL_FC;
+    const bool flat_fc = desc->predictor == GATI_PRED_FC_MLP;
+    const bool conv_fc = desc->predictor == GATI_PRED_CONV_FC;
     if (pool_fc ? (desc->out_h <= 0 || desc->out_w <= 0 || (long)desc->C * desc->out_h * desc->out_w > (1L << 24))
                 : (desc->H <= 0 || !w->W1 || !w->b1))
         return GATI_ERR_INVALID_ARG;
+    if (flat_fc && (desc->S <= 0 || (long)desc->C * desc->S >= (1L << 30))) return GATI_ERR_INVALID_ARG;
+    int oh = 0, ow = 0;
+    if (conv_fc) {
+        if (desc->in_h <= 0 || desc->in_w <= 0 || desc->conv_k <= 0 || desc->conv_s <= 0 ||
+            desc->conv_k > desc->in_h || desc->conv_k > desc->in_w || (long)desc->in_h * desc->in_w != (long)desc->S)
+            return GATI_ERR_INVALID_ARG;
+        oh = (desc->in_h - desc->conv_k) / desc->conv_s + 1;
+        ow = (desc->in_w - desc->conv_k) / desc->conv_s + 1;
+        if ((long)desc->C * desc->S >= (1L << 30) || (long)desc->H * oh * ow > (1L << 24) ||
+            (long)desc->max_rows * oh * ow >= (1L << 31) / 64 * 64 || (long)desc->C * desc->conv_k * desc->conv_k >= (1L << 24))
+            return GATI_ERR_UNSUPPORTED;
+    }
     if (!w->W2 || !w->b2) return GATI_ERR_INVALID_ARG;
-    if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_HIDDEN) return GATI_ERR_UNSUPPORTED;
+    if (desc->selector != GATI_SEL_LINEAR && desc->selector != GATI_SEL_HIDDEN && desc->selector != GATI_SEL_SOFTMAX)
+        return GATI_ERR_INVALID_ARG;
     const bool hidden = desc->selector == GATI_SEL_HIDDEN;
-    if (hidden ? (!w->Ws || !w->cs || !w->vs || desc->selector_hidden <= 0 || desc->selector_hidden > 4096) : !w->ws)
+    const bool no_selector = desc->selector == GATI_SEL_SOFTMAX;
+    if (hidden ? (!w->Ws || !w->cs || !w->vs || desc->selector_hidden <= 0 || desc->selector_hidden > 4096)
+               : (!no_selector && !w->ws))
         return GATI_ERR_INVALID_ARG;
     gati_trainer* t = new (std::nothrow) gati_trainer;
     if (!t) return GATI_ERR_OOM;
-    t->C = pool_fc ? desc->C * desc->out_h * desc->out_w : desc->C;      // features per sample
+    t->C = pool_fc ? desc->C * desc->out_h * desc->out_w : (flat_fc || conv_fc) ? desc->C * desc->S : desc->C;
     t->H = pool_fc ? 0 : desc->H;                                         // 0: no hidden layer
     t->K = desc->K; t->max_rows = desc->max_rows;
+    t->P = conv_fc ? oh * ow : 1;
+    t->Cin = conv_fc ? desc->C * desc->conv_k * desc->conv_k : t->C;
+    t->Hin = t->H ? t->P * t->H : t->C;
+    t->sel_hidden_feat = flat_fc || conv_fc;
+    t->Fsel = t->sel_hidden_feat ? t->Hin : t->C;
+    t->no_selector = no_selector;
+    if (conv_fc) {
+        t->conv_k = desc->conv_k; t->conv_s = desc->conv_s; t->conv_c = desc->C;
+        t->conv_ih = desc->in_h; t->conv_iw = desc->in_w; t->conv_oh = oh; t->conv_ow = ow;
+    }
     if (hipGetDevice(&t->device) != hipSuccess) { (void)hipGetLastError(); delete t; return GATI_ERR_DEVICE; }
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, t->device) == hipSuccess && cus > 0)
         t->num_cu = cus;
-    const size_t C = t->C, H = t->H, K = t->K, n = t->max_rows;
-    // the largest split product: slices x (M x N) over the five products of a step
+    const size_t H = t->H, K = t->K, n = t->max_rows, Cin = t->Cin, Hin = t->Hin, P = t->P, F = t->Fsel;
+    // the largest split product: slices x (M x N) over the products of a step
     t->Hs = hidden ? desc->selector_hidden : 0;
-    t->Sx = hidden ? (int)((C + K + 3) / 4 * 4) : 0;
+    t->Sx = hidden ? (int)((F + K + 3) / 4 * 4) : 0;
     const size_t Hs = t->Hs, Sx = t->Sx;
-    const size_t mn[7] = {n * H, n * K, n * H, K * (H ? H : C), H * C, n * Hs, Hs * Sx};
+    const size_t mn[7] = {n * P * H, n * K, n * Hin, K * Hin, H * Cin, n * Hs, Hs * Sx};
     t->part_floats = 0;
     for (size_t v : mn) t->part_floats = std::max(t->part_floats, v * kMaxSlices);
     t->part_floats = std::min<size_t>(t->part_floats, (size_t)64 << 20);   // 256 MB at most; fewer slices beyond
     gati_status_t st = GATI_OK;
     auto take = [&](gati_status_t s) { if (st == GATI_OK) st = s; };
-    take(dev_alloc(&t->W1, H * C, H ? w->W1 : nullptr));
+    take(dev_alloc(&t->W1, H * Cin, H ? w->W1 : nullptr));     // Conv(k,s): [Co][C][k][k] is [Co][C*k*k] as stored
     take(dev_alloc(&t->b1, H, H ? w->b1 : nullptr));
-    take(dev_alloc(&t->W2, K * (H ? H : C), w->W2));
     take(dev_alloc(&t->b2, K, w->b2));
-    if (!hidden) take(dev_alloc(&t->ws, C + K, w->ws));
     take(dev_alloc(&t->bs, 1, &w->bs));
-    take(dev_alloc(&t->h, n * H, nullptr));
+    take(dev_alloc(&t->h, n * Hin * (H ? 1 : 0), nullptr));
     take(dev_alloc(&t->z, n * K, nullptr));
     take(dev_alloc(&t->q, n * K, nullptr));
-    take(dev_alloc(&t->dh, n * H, nullptr));
+    take(dev_alloc(&t->dh, n * Hin * (H ? 1 : 0), nullptr));
     take(dev_alloc(&t->du, n, nullptr));
     take(dev_alloc(&t->lp, n, nullptr));
     take(dev_alloc(&t->ls, n, nullptr));
     take(dev_alloc(&t->part, t->part_floats, nullptr));
-    if (hidden) {
-        take(dev_alloc(&t->Ws, Hs * Sx, nullptr));
-        take(dev_alloc(&t->cs, Hs, w->cs));
-        take(dev_alloc(&t->vs, Hs, w->vs));
-        take(dev_alloc(&t->X, n * Sx, nullptr));
-        take(dev_alloc(&t->g, n * Hs, nullptr));
-        take(dev_alloc(&t->dg, n * Hs, nullptr));
-        take(dev_alloc(&t->G, n, nullptr));
-        // the padding columns of X and Ws are zero and stay zero (their gradient is a product with zero)
-        if (st == GATI_OK && (hipMemset(t->X, 0, n * Sx * sizeof(float)) != hipSuccess ||
-                              hipMemset(t->Ws, 0, Hs * Sx * sizeof(float)) != hipSuccess ||
-                              hipMemcpy2D(t->Ws, Sx * sizeof(float), w->Ws, (C + K) * sizeof(float), (C + K) * sizeof(float), Hs,
-                                          hipMemcpyHostToDevice) != hipSuccess)) {
-            (void)hipGetLastError(); st = GATI_ERR_DEVICE;
+    if (conv_fc) take(dev_alloc(&t->Xc, n * P * Cin, nullptr));
+    try {
+        if (conv_fc) {
+            std::vector<float> tmp(K * Hin);
+            permute_hidden_cols(t, w->W2, Hin, tmp.data(), Hin, (int)K, 0, true);
+            take(dev_alloc(&t->W2, K * Hin, tmp.data()));
+            if (!hidden && !no_selector) {
+                tmp.assign(F + K, 0.f);
+                permute_hidden_cols(t, w->ws, F + K, tmp.data(), F + K, 1, (int)K, true);
+                take(dev_alloc(&t->ws, F + K, tmp.data()));
+            }
+        } else {
+            take(dev_alloc(&t->W2, K * Hin, w->W2));
+            if (!hidden && !no_selector) take(dev_alloc(&t->ws, F + K, w->ws));
         }
-    }
+        if (hidden) {
+            // zero padded to the row stride Sx; the padding columns stay zero (their gradient is a product with zero)
+            std::vector<float> wide(Hs * Sx, 0.f);
+            if (conv_fc) permute_hidden_cols(t, w->Ws, F + K, wide.data(), Sx, (int)Hs, (int)K, true);
+            else for (size_t j = 0; j < Hs; ++j) std::copy(w->Ws + j * (F + K), w->Ws + (j + 1) * (F + K), wide.begin() + j * Sx);
+            take(dev_alloc(&t->Ws, Hs * Sx, wide.data()));
+            take(dev_alloc(&t->cs, Hs, w->cs));
+            take(dev_alloc(&t->vs, Hs, w->vs));
+            take(dev_alloc(&t->X, n * Sx, nullptr));
+            take(dev_alloc(&t->g, n * Hs, nullptr));
+            take(dev_alloc(&t->dg, n * Hs, nullptr));
+            take(dev_alloc(&t->G, n, nullptr));
+            if (st == GATI_OK && hipMemset(t->X, 0, n * Sx * sizeof(float)) != hipSuccess) {
+                (void)hipGetLastError(); st = GATI_ERR_DEVICE;
+            }
+        }
+    } catch (const std::bad_alloc&) { take(GATI_ERR_OOM); }
     if (st != GATI_OK) { free_all(t); delete t; return st; }
     *out = t;
     return GATI_OK;
@@ -177,15 +258,30 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
         return GATI_ERR_INVALID_ARG;
     if (!on_trainer_device(t)) return GATI_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int C = t->C, H = t->H, K = t->K;
+    const int H = t->H, K = t->K, Cin = t->Cin, P = t->P, Hin = t->Hin;
     const float lr = params->lr;
     hipError_t e;
     GemmArgs g{};
-    // the layer that feeds the output FC: h = relu(p W1^T + b1), or the features themselves (Pool(h))
+    // first layer's operand rows: the caller's input, or the gathered windows of Conv(k,s)
+    const float* a1 = pooled;
+    int lda1 = ld_pooled;
+    // the layer that feeds the output FC: h = relu(a1 W1^T + b1), or the features themselves (Pool(h))
     const float* hin = H ? t->h : pooled;
-    const int ldh = H ? H : ld_pooled, Hin = H ? H : C;
+    const int ldh = H ? Hin : ld_pooled;
+    // what the selector reads beside the class probabilities
+    const float* sfeat = t->sel_hidden_feat ? t->h : pooled;
+    const int ldsf = t->sel_hidden_feat ? Hin : ld_pooled, Fsel = t->Fsel;
+    if (t->Xc) {
+        Im2colArgs ia;
+        ia.x = pooled; ia.ldx = ld_pooled; ia.Xc = t->Xc; ia.n = n; ia.C = t->conv_c; ia.ih = t->conv_ih; ia.iw = t->conv_iw;
+        ia.k = t->conv_k; ia.s = t->conv_s; ia.oh = t->conv_oh; ia.ow = t->conv_ow;
+        const long total = (long)n * P * Cin;
+        train_im2col_kernel<<<(int)std::min<long>((total + 255) / 256, (long)t->num_cu * 32), 256, 0, st>>>(ia);
+        if ((e = hipGetLastError()) != hipSuccess) goto fail;
+        a1 = t->Xc; lda1 = Cin;
+    }
     if (H) {
-        g = GemmArgs{}; g.A = pooled; g.lda = ld_pooled; g.B = t->W1; g.ldb = C; g.M = n; g.N = H; g.Kd = C;
+        g = GemmArgs{}; g.A = a1; g.lda = lda1; g.B = t->W1; g.ldb = Cin; g.M = n * P; g.N = H; g.Kd = Cin;
         g.out = t->h; g.ldo = H; g.bias = t->b1;
         if ((e = launch_gemm<false, true, EPI_BIAS_RELU>(t, g, st)) != hipSuccess) goto fail;
     }
@@ -195,8 +291,8 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
     if ((e = launch_gemm<false, true, EPI_BIAS>(t, g, st)) != hipSuccess) goto fail;
     {
         TrainRowArgs a;
-        a.z = t->z; a.q = t->q; a.p = pooled; a.ldp = ld_pooled; a.labels = labels; a.Y = teacher; a.ldy = ld_teacher;
-        a.ws = t->ws; a.bs = t->bs; a.n = n; a.C = C; a.K = K; a.alpha = params->alpha; a.fp_weight = params->fp_weight;
+        a.z = t->z; a.q = t->q; a.p = sfeat; a.ldp = ldsf; a.labels = labels; a.Y = teacher; a.ldy = ld_teacher;
+        a.ws = t->ws; a.bs = t->bs; a.n = n; a.C = Fsel; a.K = K; a.alpha = params->alpha; a.fp_weight = params->fp_weight;
         a.du = t->du; a.lp = t->lp; a.ls = t->ls;
         a.X = t->X; a.ldx = t->Sx; a.G = t->G;      // null for the linear selector
         const int blocks = (n + 3) / 4;
@@ -223,8 +319,8 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
     }
     if (H) {
         // dh = (dz W2) where h > 0      (uses W2 before its update)
-        g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = t->W2; g.ldb = H; g.M = n; g.N = H; g.Kd = K;
-        g.out = t->dh; g.ldo = H; g.mask = t->h;
+        g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = t->W2; g.ldb = Hin; g.M = n; g.N = Hin; g.Kd = K;
+        g.out = t->dh; g.ldo = Hin; g.mask = t->h;
         if ((e = launch_gemm<false, false, EPI_MASK>(t, g, st)) != hipSuccess) goto fail;
     }
     // W2 -= lr dz^T h
@@ -232,23 +328,26 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
     g.out = t->W2; g.ldo = Hin; g.lr = lr;
     if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
     if (H) {
-        // W1 -= lr dh^T p
-        g = GemmArgs{}; g.A = t->dh; g.lda = H; g.B = pooled; g.ldb = ld_pooled; g.M = H; g.N = C; g.Kd = n;
-        g.out = t->W1; g.ldo = C; g.lr = lr;
+        // W1 -= lr dh^T a1      (dh as [n*P][H])
+        g = GemmArgs{}; g.A = t->dh; g.lda = H; g.B = a1; g.ldb = lda1; g.M = H; g.N = Cin; g.Kd = n * P;
+        g.out = t->W1; g.ldo = Cin; g.lr = lr;
         if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
     }
     // biases and selector
     {
         ColsumArgs c;
-        c.n = n; c.lr = lr;
-        c.job[0] = ColsumJob{t->z, K, K, nullptr, t->b2, 0};
-        c.job[1] = ColsumJob{t->dh, H, H, nullptr, t->b1, 0};
+        c.lr = lr;
+        const ColsumJob none{t->z, K, 0, nullptr, t->b2, 0, 0};
+        c.job[0] = ColsumJob{t->z, K, K, nullptr, t->b2, 0, n};
+        c.job[1] = ColsumJob{t->dh, H, H, nullptr, t->b1, 0, n * P};     // dh as [n*P][H]
         if (t->Hs) {
-            c.job[2] = ColsumJob{t->dg, t->Hs, t->Hs, nullptr, t->cs, 0};
-            c.job[3] = ColsumJob{t->g, t->Hs, t->Hs, t->du, t->vs, 0};
+            c.job[2] = ColsumJob{t->dg, t->Hs, t->Hs, nullptr, t->cs, 0, n};
+            c.job[3] = ColsumJob{t->g, t->Hs, t->Hs, t->du, t->vs, 0, n};
+        } else if (!t->no_selector) {
+            c.job[2] = ColsumJob{sfeat, ldsf, Fsel, t->du, t->ws, 0, n};
+            c.job[3] = ColsumJob{t->q, K, K, t->du, t->ws + Fsel, 0, n};
         } else {
-            c.job[2] = ColsumJob{pooled, ld_pooled, C, t->du, t->ws, 0};
-            c.job[3] = ColsumJob{t->q, K, K, t->du, t->ws + C, 0};
+            c.job[2] = c.job[3] = none;
         }
         int blocks = 0;
         for (int j = 0; j < 4; ++j) { c.job[j].first_block = blocks; blocks += (c.job[j].cols + 63) / 64; }
@@ -264,16 +363,26 @@ fail:
 
 gati_status_t gati_trainer_get_weights(gati_trainer_t* t, float* W1, float* b1, float* W2, float* b2,
                                        float* ws, float* bs) {
-    if (!t || !W2 || !b2 || !bs || (!t->Hs && !ws) || (t->H && (!W1 || !b1))) return GATI_ERR_INVALID_ARG;
+    const bool has_ws = t && !t->Hs && !t->no_selector;
+    if (!t || !W2 || !b2 || !bs || (has_ws && !ws) || (t->H && (!W1 || !b1))) return GATI_ERR_INVALID_ARG;
     if (!on_trainer_device(t)) return GATI_ERR_DEVICE;
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
-    const size_t C = t->C, H = t->H, K = t->K;
-    struct { float* dst; const float* src; size_t n; } cp[] = {
-        {W1, t->W1, H * C}, {b1, t->b1, H}, {W2, t->W2, K * (H ? H : C)}, {b2, t->b2, K}, {ws, t->ws, t->Hs ? 0 : C + K}, {bs, t->bs, 1}};
-    for (auto& c : cp)
-        if (c.n && hipMemcpy(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
-            (void)hipGetLastError(); return GATI_ERR_DEVICE;
+    const size_t H = t->H, K = t->K, Cin = t->Cin, Hin = t->Hin, F = t->Fsel;
+    const bool permute = t->Xc != nullptr;                  // Conv(k,s): hidden-value columns back to [filter][position]
+    try {
+        std::vector<float> w2(permute ? K * Hin : 0), wsel(permute && has_ws ? F + K : 0);
+        struct { float* dst; const float* src; size_t n; } cp[] = {
+            {W1, t->W1, H * Cin}, {b1, t->b1, H}, {permute ? w2.data() : W2, t->W2, K * Hin}, {b2, t->b2, K},
+            {permute && has_ws ? wsel.data() : ws, t->ws, has_ws ? F + K : 0}, {bs, t->bs, 1}};
+        for (auto& c : cp)
+            if (c.n && hipMemcpy(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
+                (void)hipGetLastError(); return GATI_ERR_DEVICE;
+            }
+        if (permute) {
+            permute_hidden_cols(t, w2.data(), Hin, W2, Hin, (int)K, 0, false);
+            if (has_ws) permute_hidden_cols(t, wsel.data(), F + K, ws, F + K, 1, (int)K, false);
         }
+    } catch (const std::bad_alloc&) { return GATI_ERR_OOM; }
     return GATI_OK;
 }
 
@@ -282,12 +391,17 @@ gati_status_t gati_trainer_get_hidden_selector(gati_trainer_t* t, float* Ws, flo
     if (!t->Hs) return GATI_ERR_UNSUPPORTED;
     if (!on_trainer_device(t)) return GATI_ERR_DEVICE;
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
-    const size_t w = (size_t)(t->C + t->K) * sizeof(float);
-    if (hipMemcpy2D(Ws, w, t->Ws, (size_t)t->Sx * sizeof(float), w, t->Hs, hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(cs, t->cs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(vs, t->vs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
-        (void)hipGetLastError(); return GATI_ERR_DEVICE;
-    }
+    const size_t cols = (size_t)t->Fsel + t->K, w = cols * sizeof(float);
+    try {
+        std::vector<float> tmp(t->Xc ? (size_t)t->Hs * cols : 0);
+        float* dst = t->Xc ? tmp.data() : Ws;
+        if (hipMemcpy2D(dst, w, t->Ws, (size_t)t->Sx * sizeof(float), w, t->Hs, hipMemcpyDeviceToHost) != hipSuccess ||
+            hipMemcpy(cs, t->cs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess ||
+            hipMemcpy(vs, t->vs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError(); return GATI_ERR_DEVICE;
+        }
+        if (t->Xc) permute_hidden_cols(t, tmp.data(), cols, Ws, cols, t->Hs, t->K, false);
+    } catch (const std::bad_alloc&) { return GATI_ERR_OOM; }
     return GATI_OK;
 }
 

@@ -1,6 +1,7 @@
 // Kernels of one retraining step of a learned cache (Section 3, "Training Learned Caches";
-// Section 5, "Retraining Learned Caches"): forward and backward pass of the pooling predictor
-// (FC -> ReLU -> FC -> softmax) and of the linear selector, with the SGD update fused into the
+// Section 5, "Retraining Learned Caches"): forward and backward pass of the predictors of the
+// paper's table of architectures (pooling, FC(h), Conv(k,s) as a product over gathered windows;
+// all end in FC -> softmax) and of the selector, with the SGD update fused into the
 // weight-gradient products.  All arithmetic is fp32; the products run on the fp32 MFMA
 // (32x32x2), whose accumulation is an fp32 FMA chain.  gfx950, 64-wide waves.
 #pragma once
@@ -220,9 +221,10 @@ __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
     // the selector's feature half does not depend on the softmax: issue its loads early
     float u = 0.0f;
     const bool hidden = a.X != nullptr;                      // uniform
+    const bool nosel = !hidden && a.ws == nullptr;           // uniform: no selector network to train
     float* x = hidden ? a.X + (size_t)row * a.ldx : nullptr;
     if (hidden) for (int c = lane; c < a.C; c += 64) x[c] = p[c];
-    else for (int c = lane; c < a.C; c += 64) u += a.ws[c] * p[c];
+    else if (!nosel) for (int c = lane; c < a.C; c += 64) u += a.ws[c] * p[c];
 
     float zm = -INFINITY, ym = -INFINITY;
     int zi = 0x7fffffff, yi = 0x7fffffff;
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
             const float tk = a.alpha * yv + (k == label ? 1.0f - a.alpha : 0.0f);
             lp -= tk * (zc - log_se);
             if (hidden) x[a.C + k] = qk;
-            else u += a.ws[a.C + k] * qk;
+            else if (!nosel) u += a.ws[a.C + k] * qk;
             q[k] = qk;
             z[k] = (qk - tk) * inv_n;
         }
@@ -267,6 +269,10 @@ __global__ __launch_bounds__(256) void train_row_kernel(TrainRowArgs a) {
     lp = wave_sum(lp);
     if (hidden) {
         if (lane == 0) { a.lp[row] = lp; a.G[row] = zi == yi ? 1.0f : 0.0f; }
+        return;
+    }
+    if (nosel) {
+        if (lane == 0) { a.du[row] = 0.0f; a.lp[row] = lp; a.ls[row] = 0.0f; }
         return;
     }
     u = wave_sum(u) + *a.bs;
@@ -323,8 +329,9 @@ struct ColsumJob {
     const float* scale;
     float* out;
     int first_block;     // this job's first workgroup in the launch
+    int rows;            // rows of X to add up
 };
-struct ColsumArgs { ColsumJob job[4]; int n; float lr; };
+struct ColsumArgs { ColsumJob job[4]; float lr; };
 
 __global__ __launch_bounds__(1024) void train_colsums_kernel(ColsumArgs a) {
     __shared__ float part[16][64];
@@ -337,11 +344,11 @@ __global__ __launch_bounds__(1024) void train_colsums_kernel(ColsumArgs a) {
     const int c = (blockIdx.x - job.first_block) * 64 + lane;
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (c < job.cols) {
-        for (int i0 = w; i0 < a.n; i0 += 64) {
+        for (int i0 = w; i0 < job.rows; i0 += 64) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int i = i0 + 16 * r;
-                if (i < a.n) acc[r] += (job.scale ? job.scale[i] : 1.0f) * job.X[(size_t)i * job.ld + c];
+                if (i < job.rows) acc[r] += (job.scale ? job.scale[i] : 1.0f) * job.X[(size_t)i * job.ld + c];
             }
         }
     }
@@ -352,6 +359,30 @@ __global__ __launch_bounds__(1024) void train_colsums_kernel(ColsumArgs a) {
 #pragma unroll
         for (int t = 0; t < 16; ++t) s += part[t][lane];
         job.out[c] -= a.lr * s;
+    }
+}
+
+// Conv(k,s) predictor as a matrix product: row (i, oy, ox) of Xc holds the C*k*k input values under
+// that output position, in (channel, dy, dx) order -- the order of a filter's weights -- so the
+// convolution is Xc W1^T and its weight gradient dh^T Xc.  One lane per element, consecutive lanes
+// along a row of Xc.
+struct Im2colArgs {
+    const float* x; int ldx;     // [n][ldx] maps, channel-major: x[i][c*ih*iw + y*iw + xx]
+    float* Xc;                   // [n*oh*ow][C*k*k]
+    int n, C, ih, iw, k, s, oh, ow;
+};
+
+__global__ __launch_bounds__(256) void train_im2col_kernel(Im2colArgs a) {
+    const int kk = a.k * a.k, Cin = a.C * kk, P = a.oh * a.ow;
+    const long total = (long)a.n * P * Cin;
+    for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
+        const long rowp = idx / Cin;
+        const int col = (int)(idx - rowp * Cin);
+        const int i = (int)(rowp / P), pix = (int)(rowp - (long)i * P);
+        const int c = col / kk, tap = col - c * kk;
+        const int dy = tap / a.k, dx = tap - dy * a.k;
+        const int oy = pix / a.ow, ox = pix - oy * a.ow;
+        a.Xc[idx] = a.x[(size_t)i * a.ldx + (size_t)c * a.ih * a.iw + (size_t)(oy * a.s + dy) * a.iw + ox * a.s + dx];
     }
 }
 

@@ -83,9 +83,12 @@ def test_trainer_calls_reject_bad_arguments_on_the_host():
     for key, bad in (("C", 0), ("H", 0), ("K", -2), ("max_rows", 0)):
         st, h = g.gati_trainer_create(g.CacheDesc(**{**good, key: bad}), w)
         assert st == g.GATI_ERR_INVALID_ARG and h is None, key
-    # only the pooling predictor with the linear selector can be trained
-    for key, other in (("predictor", g.GATI_PRED_FC_MLP), ("selector", g.GATI_SEL_SOFTMAX)):
-        assert g.gati_trainer_create(g.CacheDesc(**{**good, key: other}), w)[0] == g.GATI_ERR_UNSUPPORTED, key
+    # every predictor of the table can be trained; shapes that make no sense are refused on the host
+    conv = {**good, "predictor": g.GATI_PRED_CONV_FC, "S": 16, "in_h": 4, "in_w": 4, "conv_k": 3, "conv_s": 1}
+    for key, bad in (("conv_k", 5), ("conv_s", 0), ("in_h", 3), ("conv_k", 0)):
+        assert g.gati_trainer_create(g.CacheDesc(**{**conv, key: bad}), w)[0] == g.GATI_ERR_INVALID_ARG, key
+    assert g.gati_trainer_create(g.CacheDesc(**{**good, "predictor": 9}), w)[0] == g.GATI_ERR_INVALID_ARG
+    assert g.gati_trainer_create(g.CacheDesc(**{**good, "selector": 9}), w)[0] == g.GATI_ERR_INVALID_ARG
     # the hidden-layer selector needs its three arrays and a unit count
     hid = {**good, "selector": g.GATI_SEL_HIDDEN, "selector_hidden": 8}
     assert g.gati_trainer_create(g.CacheDesc(**hid), w)[0] == g.GATI_ERR_INVALID_ARG            # Ws, cs, vs missing

@@ -376,3 +376,151 @@ def test_step_argument_checks_and_empty_batch():
     got = tr.get_weights()
     assert all(np.array_equal(got[k], w[k]) for k in PARAMS) and got["bs"] == float(np.float32(w["bs"]))
     tr.close()
+
+
+def _simplex(rng, n, K):
+    Y = rng.random((n, K)).astype(np.float32) + 0.05
+    return Y / Y.sum(axis=1, keepdims=True, dtype=np.float32)
+
+
+def _w32(w):
+    return {k: (np.asarray(v, np.float32) if k != "bs" else float(v)) for k, v in w.items()}
+
+
+@pytest.mark.parametrize("C,S,H,K,n,selector", [
+    (8, 16, 40, 7, 45, "linear"), (3, 50, 33, 12, 30, "linear"), (16, 49, 64, 100, 70, "hidden"), (6, 20, 24, 9, 33, "softmax"),
+])
+def test_fc_predictor_step(C, S, H, K, n, selector):
+    """FC(h): the first layer reads the flattened row; the selector reads [h ; q] as data."""
+    rng = np.random.default_rng(C * S + H)
+    D = C * S
+    w = {"W1": rng.standard_normal((H, D)) * np.sqrt(2.0 / D), "b1": rng.standard_normal(H) * 0.1,
+         "W2": rng.standard_normal((K, H)) * np.sqrt(2.0 / H), "b2": rng.standard_normal(K) * 0.1}
+    if selector == "linear":
+        w.update({"ws": rng.standard_normal(H + K) * 0.3, "bs": 0.2})
+    elif selector == "hidden":
+        w.update({"Ws": rng.standard_normal((10, H + K)) * 0.3, "cs": rng.standard_normal(10) * 0.1,
+                  "vs": rng.standard_normal(10) * 0.5, "bs": 0.2})
+    w = _w32(w)
+    x = np.maximum(rng.standard_normal((n, D)), 0).astype(np.float32)
+    labels = rng.integers(0, K, n).astype(np.int32)
+    Y = _simplex(rng, n, K)
+    arch = {"sel_input": "hidden"}
+    z = np.sort(train.forward(w, x, arch)["z"], axis=1)
+    assert (z[:, -1] - z[:, -2]).min() > 1e-5
+    tr = g.Trainer(C, H, K, w, max_rows=n, predictor="fc_mlp", S=S, selector=selector, sel_hidden=10 if selector == "hidden" else 0)
+    losses = torch.full((2,), -1.0, device="cuda")
+    tr.step(torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda(), 1.0, 0.3, 2.0, losses)
+    torch.cuda.synchronize()
+    got = tr.get_weights()
+    want, lp, ls = train.sgd_step(w, x, labels, Y, 1.0, 0.3, 2.0, arch)
+    grads = train.gradients(w, x, labels, Y, 0.3, 2.0, arch)
+    assert set(got) == set(want)
+    if selector == "softmax":
+        for k in want:
+            tol = G_RTOL * np.max(np.abs(grads[k])) + ULP * np.max(np.abs(w[k]))
+            assert np.max(np.abs(got[k].astype(np.float64) - want[k])) <= tol, k
+    else:
+        _check_update(got, want, w, grads, 1.0, where=f"fc_mlp {C}x{S}->{H}->{K} {selector}")
+    lg = losses.cpu().numpy()
+    assert abs(lg[0] - lp) <= 1e-5 * max(1.0, abs(lp)) and abs(lg[1] - ls) <= 1e-5 * max(1.0, abs(ls)), (lg, lp, ls)
+    tr.close()
+
+
+@pytest.mark.parametrize("C,ih,iw,Co,k,s,K,n,selector", [
+    (4, 9, 8, 5, 3, 2, 6, 20, "linear"), (16, 14, 14, 8, 3, 1, 10, 24, "linear"), (8, 12, 12, 8, 5, 2, 33, 40, "hidden"),
+    (3, 6, 6, 2, 6, 1, 4, 9, "softmax"),
+])
+def test_conv_predictor_step(C, ih, iw, Co, k, s, K, n, selector):
+    """Conv(k,s): weight gradients of the filters through the product over gathered windows; the caller's
+    [filter][position] order of the hidden values survives the trainer's internal order."""
+    rng = np.random.default_rng(C * ih + Co * k + s)
+    oh, ow = (ih - k) // s + 1, (iw - k) // s + 1
+    F = Co * oh * ow
+    w = {"W1": rng.standard_normal((Co, C, k, k)) * np.sqrt(2.0 / (C * k * k)), "b1": rng.standard_normal(Co) * 0.1,
+         "W2": rng.standard_normal((K, F)) * np.sqrt(2.0 / F), "b2": rng.standard_normal(K) * 0.1}
+    if selector == "linear":
+        w.update({"ws": rng.standard_normal(F + K) * 0.3, "bs": -0.1})
+    elif selector == "hidden":
+        w.update({"Ws": rng.standard_normal((6, F + K)) * 0.3, "cs": rng.standard_normal(6) * 0.1,
+                  "vs": rng.standard_normal(6) * 0.5, "bs": -0.1})
+    w = _w32(w)
+    x = (rng.standard_normal((n, C, ih, iw)) + 0.2).astype(np.float32)
+    labels = rng.integers(0, K, n).astype(np.int32)
+    Y = _simplex(rng, n, K)
+    arch = {"stride": s}
+    f = train.forward(w, x, arch)
+    z = np.sort(f["z"], axis=1)
+    assert (z[:, -1] - z[:, -2]).min() > 1e-5 and np.abs(f["a"][np.abs(f["a"]) > 0]).min() > 1e-6
+    tr = g.Trainer(C, Co, K, w, max_rows=n + 2, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s), selector=selector,
+                   sel_hidden=6 if selector == "hidden" else 0)
+    losses = torch.full((2,), -1.0, device="cuda")
+    tr.step(torch.from_numpy(x.reshape(n, -1)).cuda(), torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda(),
+            1.0, 0.4, 3.0, losses)
+    torch.cuda.synchronize()
+    got = tr.get_weights()
+    want, lp, ls = train.sgd_step(w, x, labels, Y, 1.0, 0.4, 3.0, arch)
+    grads = train.gradients(w, x, labels, Y, 0.4, 3.0, arch)
+    assert set(got) == set(want) and got["W1"].shape == (Co, C, k, k)
+    if selector == "softmax":
+        for kk in want:
+            tol = G_RTOL * np.max(np.abs(grads[kk])) + ULP * np.max(np.abs(w[kk]))
+            assert np.max(np.abs(got[kk].astype(np.float64) - want[kk])) <= tol, kk
+    else:
+        _check_update(got, want, w, grads, 1.0, where=f"conv {C}x{ih}x{iw} k{k}s{s} {selector}")
+    lg = losses.cpu().numpy()
+    assert abs(lg[0] - lp) <= 1e-5 * max(1.0, abs(lp)) and abs(lg[1] - ls) <= 1e-5 * max(1.0, abs(ls)), (lg, lp, ls)
+    tr.close()
+
+
+@pytest.mark.parametrize("predictor", ["fc_mlp", "conv_fc"])
+def test_retrain_then_serve_the_papers_gpu_predictors(predictor):
+    """Five steps at the paper's learning rate on an fp32 cache of each kind, then the weights go into the
+    serving cache and its lookups match the oracle's under the oracle-trained weights."""
+    rng = np.random.default_rng(5 if predictor == "fc_mlp" else 6)
+    n, C, ih, iw, K = 60, 8, 10, 10, 12
+    S = ih * iw
+    if predictor == "fc_mlp":
+        H, kw, arch = 48, {}, {"sel_input": "hidden"}
+        w = {"W1": rng.standard_normal((H, C * S)) * np.sqrt(2.0 / (C * S)), "b1": np.zeros(H),
+             "W2": rng.standard_normal((K, H)) * np.sqrt(2.0 / H), "b2": np.zeros(K), "ws": rng.standard_normal(H + K) * 0.3, "bs": 0.0}
+        d = oracle.CacheDef(C=C, S=S, H=H, K=K, predictor="fc_mlp", threshold=0.5)
+    else:
+        H, kw, arch = 8, dict(in_hw=(ih, iw), conv_ks=(3, 1)), {"stride": 1}
+        F = H * 8 * 8
+        w = {"W1": rng.standard_normal((H, C, 3, 3)) * np.sqrt(2.0 / (C * 9)), "b1": np.zeros(H),
+             "W2": rng.standard_normal((K, F)) * np.sqrt(2.0 / F), "b2": np.zeros(K), "ws": rng.standard_normal(F + K) * 0.1, "bs": 0.0}
+        d = oracle.CacheDef(C=C, S=S, H=H, K=K, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(3, 1), threshold=0.5)
+    w = _w32(w)
+    x = np.maximum(rng.standard_normal((n, C, ih, iw)) + 0.3, 0).astype(np.float32)
+    labels = rng.integers(0, K, n).astype(np.int32)
+    Y = _simplex(rng, n, K)
+    x_or = x if predictor == "conv_fc" else x.reshape(n, -1)
+    tr = g.Trainer(C, H, K, w, max_rows=n, predictor=predictor, S=S, **kw)
+    xd, lab_d, Y_d = torch.from_numpy(x.reshape(n, -1)).cuda(), torch.from_numpy(labels).cuda(), torch.from_numpy(Y).cuda()
+    cur = w
+    lp0 = None
+    for e in range(5):
+        tr.step(xd, lab_d, Y_d, 0.002, 0.5, 3.0)
+        cur, lp, ls = train.sgd_step(cur, x_or, labels, Y, 0.002, 0.5, 3.0, arch)
+        lp0 = lp if lp0 is None else lp0
+    torch.cuda.synchronize()
+    got = tr.get_weights()
+    assert lp < lp0
+    for k in ("W1", "b1", "W2", "b2", "ws"):
+        assert np.max(np.abs(got[k].astype(np.float64) - cur[k])) <= 1e-5 * max(1.0, np.max(np.abs(cur[k]))), k
+    cache = g.Cache(C, S, H, K, "f32", "ncs", 0.5, n, got, predictor=predictor, **kw)
+    w_or = {k: (np.asarray(v, np.float32) if k != "bs" else float(np.float32(v))) for k, v in cur.items()}
+    want = oracle.lookup(d, w_or, x.reshape(n, C, S))
+    pc = torch.empty(n, dtype=torch.int32, device="cuda")
+    conf = torch.empty(n, device="cuda")
+    hit = torch.empty(n, dtype=torch.uint8, device="cuda")
+    logits = torch.empty((n, K), device="cuda")
+    cache.lookup(torch.from_numpy(x.reshape(n, C, S)).cuda(), None, n, None, pc, conf, hit, logits)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(logits.cpu().numpy() - want["logits"])) <= 1e-4
+    assert np.max(np.abs(conf.cpu().numpy() - want["confidence"])) <= 1e-4
+    zs = np.sort(want["logits"].astype(np.float64), axis=1)
+    clear = (zs[:, -1] - zs[:, -2]) > 1e-3
+    assert np.array_equal(pc.cpu().numpy()[clear], want["pred_class"][clear])
+    tr.close(); cache.close()
