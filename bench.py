@@ -35,6 +35,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X published dense mat
 # figure is attached only when that instance is the dominant one of the run.
 PROFILED_TRAFFIC = {
     ("resnet50", "ncs_wave[C=256,S=3136,bf16]"): (819_310_000, "profiles/pool_ncs_wave_bf16_resnet50_hbm_traffic.md"),
+    ("bert_base", "nsc_unit[C=768,S=128,bf16]"): (142_730_000, "profiles/pool_nsc_unit_bf16_bert_base_hbm_traffic.md"),
 }
 
 
@@ -256,7 +257,7 @@ def stream_read_ceiling(acts, torch, g, min_bytes=512 << 20, reps=10):
     nbytes = buf.numel() * buf.element_size() // 16 * 16
     sink = torch.zeros(256 * 32 * 1024, dtype=torch.float32, device="cuda")
     best = None
-    for bpc in (1, 2, 4, 8, 16):        # which launch shape reads fastest differs from box to box
+    for bpc in (0, 1, 2, 4, 8, 16):     # which launch shape reads fastest differs from box to box (0: a wave per 8 KB chunk)
         for _ in range(2):
             assert g.gati_probe_stream_read(buf, nbytes, sink, bpc) == g.GATI_OK
         torch.cuda.synchronize()
@@ -274,8 +275,37 @@ def stream_read_ceiling(acts, torch, g, min_bytes=512 << 20, reps=10):
             best = (t, bpc)
     t, bpc = best
     return {"GBps": round(nbytes / t / 1e9, 1), "bytes": nbytes, "us": round(t * 1e6, 1),
-            "kernel": f"probe_stream_read_kernel (gati_probe_stream_read), {bpc} workgroups per CU (best of 1, 2, 4, 8, 16), "
+            "kernel": f"gati_probe_stream_read, " + (f"{bpc} workgroups per CU" if bpc else "one wave per 8 KB chunk") + " (best of 6 launch shapes), "
                       f"median of {reps} launches"}
+
+
+def plain_read_same_sizes(spec, acts, counts, torch, g, reps=5):
+    """A plain read of as many bytes as each layer's pooling launch reads, launched back to back in
+    layer order between one event pair (the way the pooling launches are timed): what a kernel that
+    does nothing but read gets out of launches of these sizes, ramp and drain included."""
+    sink = torch.zeros(256 * 32 * 1024, dtype=torch.float32, device="cuda")
+    nbytes = [int(counts[l]) * L.row_bytes // 16 * 16 for l, L in enumerate(spec.layers)]
+    total = sum(nbytes)
+    if total == 0:
+        return None
+    best = None
+    for bpc in (0, 1, 32):
+        ts = []
+        for r in range(-1, reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for a, nb in zip(acts, nbytes):
+                if nb:
+                    g.gati_probe_stream_read(a, nb, sink, bpc)
+            e1.record()
+            torch.cuda.synchronize()
+            if r >= 0:
+                ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        t = ts[len(ts) // 2] * 1e-3
+        if best is None or t < best:
+            best = t
+    return round(total / best / 1e9, 1)
 
 
 def pool_yardstick(spec, acts, torch):
@@ -400,6 +430,10 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
                              "launches": v["launches"]} for k, v in by_kernel.items()},
         "layers": per_layer,
     }
+    if spec.layers[0].predictor == "gap_mlp":
+        pr = plain_read_same_sizes(spec, acts, counts, torch, g)
+        out["pool_all_layers"]["plain_read_same_sizes_GBps"] = pr
+        out["pool_all_layers"]["frac_of_plain_read_same_sizes"] = round(out["pool_all_layers"]["GBps"] / pr, 4) if pr else None
     out["head_us_per_step"] = round((ms_step - pool_total_ms) * 1e3, 1)     # FC layers, softmax, selector, finish + compaction
     out["compact_alone_us"] = time_compaction(caches[0], stack, spec.batch, torch)
     if graph:

@@ -21,8 +21,9 @@ extern "C" {
 /* Read `bytes` bytes (a multiple of 16, 16-byte aligned) of device memory once, with the same
  * non-temporal 16-byte loads the pooling kernels use, and fold them into one float per lane that is
  * stored only under a condition that never holds.  blocks_per_cu (1..32) workgroups of 256 lanes per
- * compute unit stride over the buffer, 8 loads in flight per lane; which value reads fastest depends
- * on the box, so a caller after the ceiling tries a few.  sink: device, at least
+ * compute unit stride over the buffer, 8 loads in flight per lane; blocks_per_cu = 0 launches one wave
+ * per contiguous 8 KB chunk instead, with no loop.  Which shape reads fastest depends on the box, so a
+ * caller after the ceiling tries a few.  sink: device, at least
  * 256 * 4 * blocks_per_cu * CUs bytes.  Algorithmic traffic: `bytes` read, nothing written. */
 gati_status_t gati_probe_stream_read(const void *buf, size_t bytes, float *sink, int32_t blocks_per_cu, void *stream);
 

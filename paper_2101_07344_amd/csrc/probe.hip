@@ -28,6 +28,26 @@ __global__ __launch_bounds__(256) void probe_stream_read_kernel(const u32x4_t* _
     if (acc == 123.456f) sink[tid] = acc;      // keeps the loads alive; never true for real data
 }
 
+// The other launch shape: one wave per contiguous 8 KB chunk and no loop, so waves arrive and leave all
+// the time (the shape of the fastest pooling kernel).  A tail shorter than a chunk is read by the last wave.
+__global__ __launch_bounds__(256) void probe_stream_read_chunks_kernel(const u32x4_t* __restrict__ p, long nvec, float* sink) {
+    constexpr long kChunk = 64L * kLoadsInFlight;
+    const int lane = threadIdx.x & 63;
+    const long wave = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long first = wave * kChunk;
+    if (first >= nvec) return;
+    u32x4_t v[kLoadsInFlight];
+#pragma unroll
+    for (int u = 0; u < kLoadsInFlight; ++u) {
+        const long i = first + u * 64 + lane;
+        v[u] = load_stream(p + (i < nvec ? i : nvec - 1));
+    }
+    float acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < kLoadsInFlight; ++u) acc += vec_sum<F32Tag>(v[u]);
+    if (acc == 123.456f) sink[threadIdx.x] = acc;
+}
+
 __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4_t* __restrict__ dst, const u32x4_t* __restrict__ src, long nvec) {
     const long stride = (long)gridDim.x * blockDim.x;
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
@@ -48,8 +68,14 @@ extern "C" {
 
 gati_status_t gati_probe_stream_read(const void* buf, size_t bytes, float* sink, int32_t blocks_per_cu, void* stream) {
     if (!buf || !sink || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0) return GATI_ERR_INVALID_ARG;
-    if (blocks_per_cu < 1 || blocks_per_cu > 32) return GATI_ERR_INVALID_ARG;
+    if (blocks_per_cu < 0 || blocks_per_cu > 32) return GATI_ERR_INVALID_ARG;
     if (bytes == 0) return GATI_OK;
+    if (blocks_per_cu == 0) {
+        const long nvec = (long)(bytes / 16), waves = (nvec + 64 * kLoadsInFlight - 1) / (64 * kLoadsInFlight);
+        if ((waves + 3) / 4 > 0x7fffffffL) return GATI_ERR_UNSUPPORTED;
+        probe_stream_read_chunks_kernel<<<(int)((waves + 3) / 4), 256, 0, (hipStream_t)stream>>>(static_cast<const u32x4_t*>(buf), nvec, sink);
+        return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+    }
     probe_stream_read_kernel<<<cu_count() * blocks_per_cu, 256, 0, (hipStream_t)stream>>>(static_cast<const u32x4_t*>(buf), (long)(bytes / 16), sink);
     return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
 }

@@ -71,7 +71,7 @@ def test_calls_reject_null_handles_and_bad_counts_on_the_host():
         == g.GATI_ERR_UNSUPPORTED
     assert g.gati_probe_stream_read(None, 16, 16, 1, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_probe_stream_read(16, 24, 16, 1, stream=0) == g.GATI_ERR_INVALID_ARG      # not whole 16-byte vectors
-    assert g.gati_probe_stream_read(16, 32, 16, 0, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_probe_stream_read(16, 32, 16, 33, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_probe_copy(16, 24, 16, stream=0) == g.GATI_ERR_INVALID_ARG             # misaligned source
 
 
