@@ -318,6 +318,19 @@ gati_status_t gati_trainer_get_weights(gati_trainer_t *trainer, float *W1, float
  * [selector_hidden]; GATI_ERR_UNSUPPORTED for a trainer with the linear selector. */
 gati_status_t gati_trainer_get_hidden_selector(gati_trainer_t *trainer, float *Ws, float *cs, float *vs);
 
+/* Put a trainer's current weights into a serving cache without leaving the device (Section 5: the
+ * retrained predictor and selector replace the old ones while serving goes on).  Kernels on `stream`
+ * repack the trainer's fp32 master weights into the cache's own layouts (bf16 caches round to nearest
+ * even, as gati_cache_create does), so the swap is ordered with whatever else is enqueued on that
+ * stream: retraining steps enqueued before it are included, lookups enqueued before it on the same
+ * stream see the old weights and lookups enqueued after it the new ones.  Nothing is allocated and
+ * other streams are not waited for.  With a selector network the call then waits for `stream` itself
+ * (not for the device) to read back one scalar, the selector bias, which reaches the lookup kernels as
+ * an argument.  Cache and trainer must have been created on the same device for the same predictor,
+ * selector mode and shapes (GATI_ERR_INVALID_ARG otherwise).  The caller keeps lookups on OTHER streams
+ * away from the cache until the stream has passed the swap. */
+gati_status_t gati_cache_load_trainer(gati_cache_t *cache, gati_trainer_t *trainer, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,9 @@
 #include "conv_kernels.h"
 #include "flat_kernels.h"
 #include "head_kernels.h"
+#include "pack_kernels.h"
 #include "pool_kernels.h"
+#include "trainer_view.h"
 
 using namespace gati;
 
@@ -401,19 +403,21 @@ int conv_reorder(const gati_cache_desc_t* d, const float* W1, int k_step, std::v
 template <typename Tag>
 hipError_t launch_pool_t(const gati_cache* c, PoolArgs a, PoolVariant variant, hipStream_t st) {
     // grid cap per CU: the wave kernel streams fastest with a wave per channel group and no grid-stride
-    // loop (7.03 against 6.86 TB/s at 16 blocks per CU; no change beyond 64), the tiled kernels with 12-24;
+    // loop (7.03 against 6.86 TB/s at 16 blocks per CU), so it has no cap; the tiled kernels do best with 12-24;
     // the adaptive-pool kernel with 48 for its large (J >= 8) tiles (6.8 against 6.4 TB/s inside a stack pass;
     // 128 drops to 5.9) and 24 otherwise
     int per_cu = c->pool_blocks_per_cu;
-    if (variant == POOL_NCS_WAVE) per_cu = 64;
-    else if (variant == POOL_NCS_SEGW) per_cu = 12;      // 5.70 / 4.22 TB/s at S = 196 / 49 against 5.61 / 4.11 at 16
+    if (variant == POOL_NCS_SEGW) per_cu = 12;      // 5.70 / 4.22 TB/s at S = 196 / 49 against 5.61 / 4.11 at 16
     else if (variant == POOL_NCS_ADAPTIVE) per_cu = c->ad_j >= 8 ? 48 : 24;
     const int max_blocks = c->num_cu * per_cu;
     switch (variant) {
     case POOL_NCS_WAVE: {
         static const int cpi_of[] = {8, 4, 2, 2, 1};
         const long groups = (long)a.n_max * ((a.C + cpi_of[c->wave_cfg] - 1) / cpi_of[c->wave_cfg]);
-        const int blocks = (int)std::min<long>((groups + 3) / 4, max_blocks);
+        // a wave per channel group and no loop, however many groups (the kernel's wave-stride loop only
+        // serves launches beyond 2^24 workgroups): at 4096 rows of [256, 3136] the 64-blocks-per-CU grid
+        // that earlier builds looped over read 6.72 TB/s, one workgroup per four groups 6.92
+        const int blocks = (int)std::min<long>((groups + 3) / 4, 1L << 24);
         switch (c->wave_cfg) {
         case 0: pool_ncs_wave_kernel<Tag, 1, 8><<<blocks, 256, 0, st>>>(a, c->vpc); break;
         case 1: pool_ncs_wave_kernel<Tag, 2, 4><<<blocks, 256, 0, st>>>(a, c->vpc); break;
@@ -948,6 +952,103 @@ gati_status_t gati_cache_set_weights(gati_cache_t* c, const gati_cache_weights_t
     if (st != GATI_OK) return st;
     c->bs = w->bs;
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+    return GATI_OK;
+}
+
+}  // extern "C"
+
+namespace {
+template <bool BF16>
+hipError_t load_trainer_t(gati_cache* c, const TrainerView& v, hipStream_t st) {
+    using elem_t = typename PackElem<BF16>::type;
+    const gati_cache_desc_t& d = c->desc;
+    const int K = d.K, F = c->F;
+    const bool pool_fc = d.predictor == GATI_PRED_POOL_FC;
+    auto blocks = [&](long total) { return (int)std::max<long>(1, std::min<long>((total + 255) / 256, (long)c->num_cu * 32)); };
+    // first layer
+    if (c->flat_fc && c->flat_generic) {
+        const long cnt = (long)d.H * d.C * d.S;
+        pack_plain_kernel<BF16><<<blocks(cnt), 256, 0, st>>>(v.W1, cnt, static_cast<elem_t*>(c->W1));
+    } else if (c->flat_fc) {
+        const long D = (long)d.C * d.S;
+        pack_flat_kernel<BF16><<<blocks((long)c->Hb * D), 256, 0, st>>>(v.W1, D, d.H, c->Hb, static_cast<elem_t*>(c->W1));
+    } else if (c->conv_fc) {
+        const int rows_p = round_up(d.H, 32);
+        const int k_step = BF16 ? 16 : 8;
+        const long kd = (long)((d.C + k_step - 1) / k_step) * conv_taps_padded(d.conv_k) * k_step;
+        pack_conv_kernel<BF16><<<blocks(rows_p * kd), 256, 0, st>>>(v.W1, d.H, d.C, d.conv_k, rows_p, static_cast<elem_t*>(c->W1));
+        const long cnt = (long)d.H * d.C * d.conv_k * d.conv_k;
+        const ColMap all{(int)cnt, 0, (int)cnt, 0, 0};
+        pack_vector_kernel<BF16><<<blocks(cnt), 256, 0, st>>>(v.W1, cnt, all, c->W1plain);
+    } else if (!pool_fc) {
+        const ColMap m{d.C, 0, d.C, 0, 0};
+        pack_fc_kernel<BF16><<<blocks((long)c->Hp * c->Cp), 256, 0, st>>>(v.W1, d.C, d.H, c->Hp, c->Cp, m, static_cast<elem_t*>(c->W1));
+    }
+    if (!pool_fc) {
+        const ColMap m{d.H, 0, d.H, 0, 0};
+        // one bias per hidden unit (Conv(k,s): per filter), zero up to the padded length
+        pack_vector_kernel<false><<<blocks(c->Hp), 256, 0, st>>>(v.b1, c->Hp, m, c->b1);
+    }
+    // output layer: its inputs are the hidden layer or the features; Conv(k,s) hidden values change order
+    const int Hcols = c->pool_fc ? F : d.H;
+    const ColMap feat{Hcols, 0, Hcols, v.conv ? v.P : 0, v.conv ? v.H : 0};
+    pack_fc_kernel<BF16><<<blocks((long)c->Kp * c->Hp), 256, 0, st>>>(v.W2, v.Hin, K, c->Kp, c->Hp, feat, static_cast<elem_t*>(c->W2));
+    const ColMap km{K, 0, K, 0, 0};
+    pack_vector_kernel<false><<<blocks(c->Kp), 256, 0, st>>>(v.b2, c->Kp, km, c->b2);
+    if (d.selector == GATI_SEL_LINEAR) {
+        const ColMap fm{F, 0, F, v.conv ? v.P : 0, v.conv ? v.H : 0};
+        pack_vector_kernel<false><<<blocks(c->Cp), 256, 0, st>>>(v.ws, c->Cp, fm, c->ws_pool);
+        pack_vector_kernel<false><<<blocks(c->Kp), 256, 0, st>>>(v.ws + F, c->Kp, km, c->ws_prob);
+    } else if (d.selector == GATI_SEL_HIDDEN) {
+        const ColMap wide{F, c->Cp - F, F + K, v.conv ? v.P : 0, v.conv ? v.H : 0};
+        pack_fc_kernel<BF16><<<blocks((long)c->Hsp * c->Sin), 256, 0, st>>>(v.Ws, v.Sx, c->Hs, c->Hsp, c->Sin, wide,
+                                                                              static_cast<elem_t*>(c->Ws));
+        const ColMap hm{c->Hs, 0, c->Hs, 0, 0};
+        pack_vector_kernel<false><<<blocks(c->Hsp), 256, 0, st>>>(v.cs, c->Hsp, hm, c->cs);
+        pack_vector_kernel<false><<<blocks(c->Hsp), 256, 0, st>>>(v.vs, c->Hsp, hm, c->vs);
+    }
+    return hipGetLastError();
+}
+}  // namespace
+
+extern "C" {
+
+gati_status_t gati_cache_load_trainer(gati_cache_t* c, gati_trainer_t* t, void* stream) {
+    if (!c || !t) return GATI_ERR_INVALID_ARG;
+    TrainerView v;
+    trainer_view(t, &v);
+    const gati_cache_desc_t& d = c->desc;
+    if (!on_cache_device(c) || v.device != c->device) return GATI_ERR_DEVICE;
+    // the trainer must hold the same networks as the cache
+    bool same = v.K == d.K && v.Fsel == c->F;
+    switch (d.predictor) {
+    case GATI_PRED_GAP_MLP: same = same && !v.conv && !v.sel_hidden_feat && v.H == d.H && v.C == d.C; break;
+    case GATI_PRED_POOL_FC: same = same && v.H == 0 && v.C == c->F; break;
+    case GATI_PRED_FC_MLP: same = same && !v.conv && v.sel_hidden_feat && v.H == d.H && (long)v.C == (long)d.C * d.S; break;
+    case GATI_PRED_CONV_FC:
+        same = same && v.conv && v.H == d.H && v.Cin == d.C * d.conv_k * d.conv_k && v.P == c->conv_oh * c->conv_ow &&
+               (long)v.C == (long)d.C * d.S;
+        break;
+    }
+    switch (d.selector) {
+    case GATI_SEL_LINEAR: same = same && !v.no_selector && v.Hs == 0; break;
+    case GATI_SEL_HIDDEN: same = same && v.Hs == d.selector_hidden; break;
+    case GATI_SEL_SOFTMAX: same = same && v.no_selector; break;
+    }
+    if (!same) return GATI_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const hipError_t e = c->bf16 ? load_trainer_t<true>(c, v, st) : load_trainer_t<false>(c, v, st);
+    if (e != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
+    if (d.selector != GATI_SEL_SOFTMAX) {
+        // the selector bias travels to the kernels as an argument: fetch the scalar once the stream has caught up
+        float bs = 0.f;
+        if (hipMemcpyAsync(&bs, v.bs, sizeof(float), hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess) {
+            (void)hipGetLastError(); return GATI_ERR_DEVICE;
+        }
+        if (!(bs == bs)) return GATI_ERR_INVALID_ARG;
+        c->bs = bs;
+    }
     return GATI_OK;
 }
 

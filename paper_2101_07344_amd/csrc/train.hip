@@ -9,6 +9,7 @@
 
 #include "../../include/gati.h"
 #include "train_kernels.h"
+#include "trainer_view.h"
 
 using namespace gati;
 
@@ -123,6 +124,14 @@ bool on_trainer_device(const gati_trainer* t) {
 }
 
 }  // namespace
+
+void gati::trainer_view(const gati_trainer* t, gati::TrainerView* v) {
+    v->device = t->device; v->C = t->C; v->H = t->H; v->K = t->K; v->Cin = t->Cin; v->P = t->P; v->Hin = t->Hin;
+    v->Fsel = t->Fsel; v->conv = t->Xc != nullptr; v->sel_hidden_feat = t->sel_hidden_feat; v->no_selector = t->no_selector;
+    v->Hs = t->Hs; v->Sx = t->Sx;
+    v->W1 = t->W1; v->b1 = t->b1; v->W2 = t->W2; v->b2 = t->b2; v->ws = t->ws; v->bs = t->bs;
+    v->Ws = t->Ws; v->cs = t->cs; v->vs = t->vs;
+}
 
 extern "C" {
 
