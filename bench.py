@@ -389,6 +389,9 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
             per_layer.append({"layer": l, "n": n, "kernel": keys[l], "pool_us": round(share * 1e3, 2),
                               "pool_GBps": round(algo[l] / (share * 1e-3) / 1e9, 1) if share else 0.0,
                               "hit_rate": None if hits[l] is None else round(hits[l], 4)})
+            if flops[l] and share:
+                # FC(h): flops of the live rows only (rows a partly filled tile pads do not count)
+                per_layer[-1]["useful_TFLOPs"] = round(flops[l] / (share * 1e-3) / 1e12, 1)
             if n:
                 k["bytes"] += algo[l]
                 k["flops"] += flops[l]

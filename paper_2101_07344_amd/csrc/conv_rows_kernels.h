@@ -1,0 +1,227 @@
+// Conv(k,s) with few filters (Section 3, table of predictor architectures; the paper's convolution
+// predictors have a handful of filters) on channel-major bf16 maps, formulated over INPUT rows so that
+// the map is used exactly as it lies in memory -- no transposition on the way into LDS:
+//
+//   for an input row iy of channel c, P[t][o][x] = sum_dx W[o][c][dy_t][dx] * X[c][iy][s*x + dx]
+//   is what that row adds to output row y = (iy - dy_t) / s, where dy_t = (iy mod s) + s*t are the
+//   k/s taps (rounded up) whose row offset has the parity of iy.
+//
+// As one MFMA (32 x 32 x 16, bf16): the 32 rows of D are (t, o) -- up to 4 tap rows x 8 filters --
+// its 32 columns are output pixels x of one or several input rows (a "tile"), and the reduction
+// index is (channel, dx): SLOT = 8 horizontal taps of 2 channels, or SLOT = 4 taps of 4 channels.
+// A lane's B fragment is then SLOT consecutive elements of an input row starting at s*x: one
+// LDS read of bytes that were copied from global memory unchanged.  Taps past k meet zero weights.
+// The filters are repacked at cache creation into A fragments per (channel group, row parity).
+// A tile's accumulators stay in registers over all channels; since D's row index lives in the
+// register number (t = j / 4), a tap row's share is a group of four registers, and the shares
+// are added into the output rows through LDS at the end, in the fixed order of dy.
+//
+// One workgroup = one request (x one share of the channels when few requests would leave
+// CUs idle: the shares are summed in order by conv_reduce_kernel).  Its 4 waves split into row
+// parities (s = 2), then into tile sets, then -- small maps, fewer tiles than waves -- into channel
+// parts.  LDS holds one fill: CC channels of the map followed by their filter fragments; the next
+// fill waits in registers while this one is multiplied.
+#pragma once
+
+#include "conv_kernels.h"
+
+namespace gati {
+
+constexpr int kRowsMaxVec = 3840;        // 60 KB per fill (16-byte vectors): 8 channels of a 56 x 56 map and their fragments
+constexpr int kRowsFilters = 8;          // filters per MFMA row block
+
+struct ConvRowsArgs {
+    const void* act;           // [rows, C, in_h*in_w] bf16
+    const int32_t* row_index;  // [n] or null
+    const int32_t* n_dev;
+    int n_max;
+    int C, S, in_h, in_w, k, s, oh, ow, Co;
+    const void* Wr;            // [C / KC][s][64 lanes] x 16 bytes: A fragments, see pack_conv_rows
+    const float* bias;
+    int CC;                    // channels per fill: CC*S*2 bytes are a multiple of 16
+    int xw_log2;               // a tile gives every input row it holds 2^xw_log2 >= ow pixel lanes
+    int nwt_log2, ws;          // waves of one parity: 2^nwt_log2 tile sets x ws channel parts
+    float* out;                // [n, out_stride] fp32 features, order [filter][oy][ox]
+    __bf16* out16;             // bf16 copy or null
+    int out_stride;
+    int ksplit, fills_per_split;
+    float* partial;            // [ksplit][n_max][out_stride] raw sums when ksplit > 1
+};
+
+// 16 bytes of LDS at a 4-byte aligned address.
+struct __attribute__((packed, aligned(4))) lds_u32x4 { uint32_t w[4]; };
+
+// SLOT: horizontal taps per channel in the reduction index (8: stride 2, even row length; 4: k <= 3).
+// TPW: tiles per wave.
+template <int SLOT, int TPW>
+__global__ __launch_bounds__(256, (TPW <= 4 ? 2 : 1)) void conv_rows_kernel(ConvRowsArgs a) {
+    using frag_t = Mma<true>::frag_t;
+    constexpr int KC = 16 / SLOT;                            // channels per MFMA
+    constexpr int UG = TPW >= 4 ? 1 : (TPW == 2 ? 2 : 4);    // channel groups in flight per wave
+    constexpr int LPT = kRowsMaxVec / 256;
+    __shared__ u32x4_t lds[kRowsMaxVec];
+    unsigned char* const ldsb = reinterpret_cast<unsigned char*>(lds);
+
+    const int n = active_rows(a.n_dev, a.n_max);
+    const int split = blockIdx.x % a.ksplit;
+    const int i = blockIdx.x / a.ksplit;
+    if (i >= n) return;                                      // whole workgroup
+    const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int nn = lane & 31, kb = lane >> 5;
+
+    // wave -> (row parity, tile set, channel part)
+    const int pi = wave % a.s;
+    const int wc = wave / a.s;
+    const int wt = wc & ((1 << a.nwt_log2) - 1);
+    const int wp = wc >> a.nwt_log2;
+    // lane -> (input row within the tile, output column)
+    const int xs = nn & ((1 << a.xw_log2) - 1), jrow = nn >> a.xw_log2;
+    const int x = min(xs, a.ow - 1);
+    const int rpt_log2 = 5 - a.xw_log2;
+
+    int iy[TPW];                                             // the lane's input row per tile; past the map: unused
+    int boff[TPW][SLOT == 8 ? 1 : 2];                        // LDS byte offset of the lane's fragment in channel group 0
+    int bsh[TPW][SLOT == 8 ? 1 : 2];                         // SLOT 4: 16 when the fragment starts on an odd element
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        const int rho = ((wt + (t << a.nwt_log2)) << rpt_log2) + jrow;
+        iy[t] = pi + a.s * rho;
+        const int e0 = min(iy[t], a.in_h - 1) * a.in_w + a.s * x;
+        if constexpr (SLOT == 8) {
+            boff[t][0] = (kb * a.S + e0) * 2;                // even element by plan: 4-byte aligned
+            bsh[t][0] = 0;
+        } else {
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int e = (2 * kb + g) * a.S + e0;
+                boff[t][g] = (e >> 1) * 4;
+                bsh[t][g] = (e & 1) * 16;
+            }
+        }
+    }
+    const int gbytes = KC * a.S * 2;                         // one channel group further on
+    auto bfrag = [&](int t, int cg) -> frag_t {
+        const unsigned char* p = ldsb + cg * gbytes;
+        u32x4_t w;
+        if constexpr (SLOT == 8) {
+            const lds_u32x4 v = *reinterpret_cast<const lds_u32x4*>(p + boff[t][0]);
+            w[0] = v.w[0]; w[1] = v.w[1]; w[2] = v.w[2]; w[3] = v.w[3];
+        } else {
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const uint32_t* q = reinterpret_cast<const uint32_t*>(p + boff[t][g]);
+                const uint32_t d0 = q[0], d1 = q[1];
+                w[2 * g] = __builtin_amdgcn_alignbit(d1, d0, bsh[t][g]);
+                w[2 * g + 1] = d1 >> bsh[t][g];
+            }
+        }
+        return __builtin_bit_cast(frag_t, w);
+    };
+
+    // one fill: CC channels of the request's map, then their A fragments, both contiguous in memory
+    const int nva = a.CC * a.S * 2 / 16;
+    const int G = a.CC / KC;
+    const int nvw = G * a.s * 64;
+    const int nv = nva + nvw;
+    const int fill0 = split * a.fills_per_split;
+    const int fill1 = min(a.C / a.CC, fill0 + a.fills_per_split);
+    const unsigned char* abase = static_cast<const unsigned char*>(a.act) + r * (long)a.C * a.S * 2;
+    const unsigned char* wbase = static_cast<const unsigned char*>(a.Wr);
+    u32x4_t stage[LPT];
+    auto issue = [&](int f) {
+        const unsigned char* fa = abase + (long)f * nva * 16;
+        const unsigned char* fw = wbase + (long)f * nvw * 16;
+#pragma unroll
+        for (int q = 0; q < LPT; ++q) {
+            const int v = min(tid + 256 * q, nv - 1);        // surplus lanes repeat the last vector
+            stage[q] = *reinterpret_cast<const u32x4_t*>(v >= nva ? fw + (v - nva) * 16 : fa + v * 16);
+        }
+    };
+    auto park = [&]() {
+#pragma unroll
+        for (int q = 0; q < LPT; ++q)
+            if (tid + 256 * q < nv) lds[tid + 256 * q] = stage[q];
+    };
+    const unsigned char* const alds = ldsb + nva * 16 + (pi * 64 + lane) * 16;
+    auto afrag = [&](int cg) -> frag_t { return *reinterpret_cast<const frag_t*>(alds + cg * a.s * 1024); };
+
+    f32x16_t acc[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
+
+    const int gsteps = G / a.ws;                             // groups per wave and fill: a multiple of UG by plan
+    if (fill0 < fill1) issue(fill0);
+    for (int f = fill0; f < fill1; ++f) {
+        park();
+        __syncthreads();
+        if (f + 1 < fill1) issue(f + 1);                     // in flight while this fill is multiplied
+        // every fragment is read one round (UG groups x TPW tiles) ahead of its MFMA; nothing below is conditional
+        frag_t bf[UG][TPW], af[UG];
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+            const int cg = wp + u * a.ws;
+            af[u] = afrag(cg);
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) bf[u][t] = bfrag(t, cg);
+        }
+        for (int gs = 0; gs < gsteps; gs += UG) {
+#pragma unroll
+            for (int u = 0; u < UG; ++u) {
+                const int cgn = min(wp + (gs + u + UG) * a.ws, G - 1);   // past the fill: any valid group, never multiplied
+                const frag_t an = afrag(cgn);
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) {
+                    acc[t] = Mma<true>::mma(af[u], bf[u][t], acc[t]);
+                    bf[u][t] = bfrag(t, cgn);
+                }
+                af[u] = an;
+            }
+        }
+        __syncthreads();                                     // every wave is done with the fill
+    }
+
+    // shares of the tap rows -> output rows, through LDS (the fill buffer is free now), in the order
+    // (channel part, dy): within one round no two lanes meet in an output element
+    const int OHW = a.oh * a.ow;
+    const int F = a.Co * OHW;
+    float* const obuf = reinterpret_cast<float*>(lds);
+    for (int idx = tid; idx < F; idx += 256) obuf[idx] = 0.f;
+    for (int wpp = 0; wpp < a.ws; ++wpp) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            for (int pp = 0; pp < a.s; ++pp) {
+                __syncthreads();
+                const int dy = pp + a.s * t;
+                if (wp != wpp || pi != pp || dy >= a.k) continue;        // wave-uniform
+#pragma unroll
+                for (int tl = 0; tl < TPW; ++tl) {
+                    const int y = (iy[tl] - dy) / a.s;                   // exact: iy and dy have the same parity
+                    if (xs < a.ow && iy[tl] < a.in_h && iy[tl] >= dy && y < a.oh) {
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            const int o = 4 * kb + jj;
+                            if (o < a.Co) obuf[o * OHW + y * a.ow + x] += acc[tl][4 * t + jj];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // one split: bias and ReLU here; several: raw sums to this split's slab
+    const bool last = a.ksplit == 1;
+    float* orow = (last ? a.out : a.partial + (long)split * a.n_max * a.out_stride) + (long)i * a.out_stride;
+    __bf16* orow16 = (last && a.out16) ? a.out16 + (long)i * a.out_stride : nullptr;
+    for (int idx = tid; idx < F; idx += 256) {
+        float v = obuf[idx];
+        if (last) v = fmaxf(v + a.bias[idx / OHW], 0.f);
+        orow[idx] = v;
+        if (orow16) orow16[idx] = (__bf16)v;
+    }
+}
+
+}  // namespace gati

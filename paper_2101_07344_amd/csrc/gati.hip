@@ -15,6 +15,7 @@
 #include "common.h"
 #include "compact_kernels.h"
 #include "conv_kernels.h"
+#include "conv_rows_kernels.h"
 #include "flat_kernels.h"
 #include "head_kernels.h"
 #include "pack_kernels.h"
@@ -27,7 +28,7 @@ namespace {
 
 enum PoolVariant { POOL_NCS_WAVE = 0, POOL_NCS_SEG = 1, POOL_NSC_VEC = 2, POOL_GENERIC = 3, POOL_NCS_SEGW = 4, POOL_NSC_UNIT = 5,
                    POOL_NCS_ADAPTIVE = 6, POOL_ADAPTIVE_GENERIC = 7, POOL_FC_FLAT = 8, POOL_CONV = 9, POOL_CONV_GENERIC = 10,
-                   POOL_FC_FLAT_GENERIC = 11 };
+                   POOL_FC_FLAT_GENERIC = 11, POOL_CONV_ROWS = 12 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -95,6 +96,9 @@ struct gati_cache {
     bool conv_fc = false;
     int conv_oh = 0, conv_ow = 0, conv_R = 0, conv_nbands = 1, conv_rows_in = 0, conv_whole = 0, conv_tpw = 8, conv_ntc = 1, conv_tr = 0, conv_ksplit = 1, conv_cb_per = 0, conv_bps = 1;
     float* conv_partial = nullptr;   // [ksplit][max_rows][Cp] when ksplit > 1
+    // plan of conv_rows_kernel (few filters, bf16, channel-major): taps per channel in the reduction index,
+    // tiles per wave, channels per LDS fill, pixel lanes per input row, waves per tile set / channel part
+    int rows_slot = 0, rows_tpw = 0, rows_cc = 0, rows_xw_log2 = 0, rows_nwt_log2 = 0, rows_ws = 1, rows_fills_per = 0;
     float* W1plain = nullptr; // [Co, C, k, k] fp32 (rounded to bf16 values in bf16 caches)
 };
 
@@ -121,6 +125,58 @@ gati_status_t upload(void** dst, const void* src, size_t bytes) {
     return GATI_OK;
 }
 
+// Conv(k,s) with at most 8 filters on channel-major bf16 maps: the plan of conv_rows_kernel, or false.
+bool plan_conv_rows(gati_cache* c) {
+    const gati_cache_desc_t& d = c->desc;
+    const int k = d.conv_k, s = d.conv_s, oh = c->conv_oh, ow = c->conv_ow;
+    if (!c->bf16 || d.layout != GATI_LAYOUT_NCS || d.H > kRowsFilters) return false;
+    if (s != 1 && s != 2) return false;
+    int slot;
+    if (k <= 3) slot = 4;                                    // a fragment may start on an odd element
+    else if (s == 2 && k <= 8 && d.in_w % 2 == 0) slot = 8;  // fragments start on even elements only
+    else return false;
+    if ((k + s - 1) / s > 4) return false;                   // tap rows of one parity: D has room for 4
+    const int KC = 16 / slot;
+    if (ow > 32 || (long)d.H * oh * ow * 4 > (long)kRowsMaxVec * 16) return false;
+    if (d.C % KC != 0 || ((long)d.C * d.S * 2) % 16 != 0 || (long)d.C * d.S >= (1L << 30)) return false;
+    int xw = 0;
+    while ((1 << xw) < ow) ++xw;
+    const int rpt = 32 >> xw;                                // input rows per tile
+    const int nwc = 4 / s;                                   // waves per row parity
+    const int rows_c = (d.in_h + s - 1) / s;                 // rows of parity 0, the larger class
+    const int ntc = (rows_c + rpt - 1) / rpt;                // tiles per parity
+    int nwt_log2 = 0;
+    while ((2 << nwt_log2) <= std::min(nwc, ntc)) ++nwt_log2;
+    const int nwt = 1 << nwt_log2, ws = nwc / nwt;
+    const int need = (ntc + nwt - 1) / nwt;
+    int tpw = 0;
+    for (int cand : {1, 2, 4, 8, 14})
+        if (cand >= need) { tpw = cand; break; }
+    if (!tpw) return false;
+    const int ug = tpw >= 4 ? 1 : (tpw == 2 ? 2 : 4);
+    // channels per fill: whole 16-byte vectors, whole rounds of every wave, a divisor of C, at most 56 KB
+    // together with the fill's filter fragments
+    int unit = KC * ws * ug;
+    while (((long)unit * d.S * 2) % 16 != 0) unit *= 2;
+    int cc = 0;
+    for (int cand = unit; cand <= d.C; cand += unit) {
+        if (d.C % cand != 0) continue;
+        if ((long)cand * d.S * 2 + (long)(cand / KC) * s * 1024 > (long)kRowsMaxVec * 16) break;
+        cc = cand;
+    }
+    if (!cc) return false;
+    const int fills = d.C / cc;
+    // few requests: share the channels of a request among workgroups (fixed at creation, so results do not
+    // depend on how many rows a call has)
+    int ks = (int)((4L * c->num_cu + d.max_rows - 1) / d.max_rows);
+    ks = std::max(1, std::min(std::min(ks, fills), 16));
+    c->rows_fills_per = (fills + ks - 1) / ks;
+    c->conv_ksplit = (fills + c->rows_fills_per - 1) / c->rows_fills_per;
+    c->rows_slot = slot; c->rows_tpw = tpw; c->rows_cc = cc; c->rows_xw_log2 = xw;
+    c->rows_nwt_log2 = nwt_log2; c->rows_ws = ws;
+    return true;
+}
+
 // Conv(k,s): staging mode and band height of conv_relu_kernel, or the generic kernel.
 void plan_conv(gati_cache* c) {
     const gati_cache_desc_t& d = c->desc;
@@ -128,6 +184,7 @@ void plan_conv(gati_cache* c) {
     const int oh = c->conv_oh, ow = c->conv_ow;
     c->variant = POOL_CONV_GENERIC;
     if (d.layout == GATI_LAYOUT_NSC) return;      // channels-last maps: the generic kernel
+    if (plan_conv_rows(c)) { c->variant = POOL_CONV_ROWS; return; }
     c->conv_ntc = d.H > 32 ? 2 : 1;
     const int max_pixels = c->conv_ntc == 2 ? 512 : 1024;   // 4 waves x TPW tiles x 32 pixels
     c->conv_tpw = c->conv_ntc == 2 ? 4 : 8;
@@ -184,7 +241,42 @@ hipError_t launch_conv_t(const gati_cache* c, const void* act, const int32_t* ro
     a.out = out; a.out16 = static_cast<__bf16*>(out16); a.out_stride = out_stride;
     a.ksplit = 1; a.cb_per_split = a.CB; a.partial = nullptr; a.bps = c->conv_bps;
     if (n_max == 0) return hipSuccess;
-    if (c->variant != POOL_CONV || (reinterpret_cast<uintptr_t>(act) & 15u) != 0) {
+    if (c->variant == POOL_CONV_ROWS && (reinterpret_cast<uintptr_t>(act) & 15u) == 0) {
+        if constexpr (BF16) {
+            ConvRowsArgs ra;
+            ra.act = act; ra.row_index = row_index; ra.n_dev = n_dev; ra.n_max = n_max;
+            ra.C = d.C; ra.S = d.S; ra.in_h = d.in_h; ra.in_w = d.in_w; ra.k = d.conv_k; ra.s = d.conv_s;
+            ra.oh = c->conv_oh; ra.ow = c->conv_ow; ra.Co = d.H;
+            ra.Wr = c->W1; ra.bias = c->b1; ra.CC = c->rows_cc; ra.xw_log2 = c->rows_xw_log2;
+            ra.nwt_log2 = c->rows_nwt_log2; ra.ws = c->rows_ws;
+            ra.out = out; ra.out16 = static_cast<__bf16*>(out16); ra.out_stride = out_stride;
+            ra.ksplit = 1; ra.fills_per_split = d.C / c->rows_cc; ra.partial = nullptr;
+            if (c->conv_ksplit > 1 && out_stride <= c->Cp) {
+                ra.ksplit = c->conv_ksplit; ra.fills_per_split = c->rows_fills_per; ra.partial = c->conv_partial;
+            }
+            const int grid = n_max * ra.ksplit;
+            const int key = c->rows_slot * 16 + c->rows_tpw;
+            switch (key) {
+            case 8 * 16 + 1: conv_rows_kernel<8, 1><<<grid, 256, 0, st>>>(ra); break;
+            case 8 * 16 + 2: conv_rows_kernel<8, 2><<<grid, 256, 0, st>>>(ra); break;
+            case 8 * 16 + 4: conv_rows_kernel<8, 4><<<grid, 256, 0, st>>>(ra); break;
+            case 8 * 16 + 8: conv_rows_kernel<8, 8><<<grid, 256, 0, st>>>(ra); break;
+            case 8 * 16 + 14: conv_rows_kernel<8, 14><<<grid, 256, 0, st>>>(ra); break;
+            case 4 * 16 + 1: conv_rows_kernel<4, 1><<<grid, 256, 0, st>>>(ra); break;
+            case 4 * 16 + 2: conv_rows_kernel<4, 2><<<grid, 256, 0, st>>>(ra); break;
+            case 4 * 16 + 4: conv_rows_kernel<4, 4><<<grid, 256, 0, st>>>(ra); break;
+            case 4 * 16 + 8: conv_rows_kernel<4, 8><<<grid, 256, 0, st>>>(ra); break;
+            default: conv_rows_kernel<4, 14><<<grid, 256, 0, st>>>(ra); break;
+            }
+            if (ra.ksplit > 1) {
+                hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return e;
+                a.ksplit = ra.ksplit; a.partial = ra.partial;
+                const long items = (long)n_max * c->F;
+                conv_reduce_kernel<<<(int)std::min<long>((items + 255) / 256, (long)c->num_cu * 8), 256, 0, st>>>(a);
+            }
+        }
+    } else if (c->variant != POOL_CONV || (reinterpret_cast<uintptr_t>(act) & 15u) != 0) {
         const long items = (long)n_max * c->F;
         const int blocks = (int)std::min<long>((items + 255) / 256, (long)c->num_cu * 16);
         conv_generic_kernel<BF16><<<blocks, 256, 0, st>>>(a, d.layout == GATI_LAYOUT_NSC ? 1 : 0);
@@ -398,6 +490,27 @@ int conv_reorder(const gati_cache_desc_t* d, const float* W1, int k_step, std::v
                 out[(size_t)o * Kd + ((size_t)(c / k_step) * IT + t) * k_step + c % k_step] =
                     W1[((size_t)o * d->C + c) * k2 + t];
     return Kd;
+}
+
+// Filters of conv_rows_kernel as MFMA A fragments: [channel group][row parity][lane][8 bf16].  Lane
+// (m, kb): row m = tap row t (m / 8) x filter o (m % 8); its element e is horizontal tap e of channel
+// 2*group + kb (slot 8), or tap e % 4 of channel 4*group + 2*kb + e / 4 (slot 4); the tap row's offset
+// is dy = parity + s*t.  Everything outside the filter is zero.
+void pack_conv_rows(const gati_cache* c, const float* W1, std::vector<uint16_t>& out) {
+    const gati_cache_desc_t& d = c->desc;
+    const int k = d.conv_k, s = d.conv_s, slot = c->rows_slot, KC = 16 / slot;
+    out.assign((size_t)(d.C / KC) * s * 64 * 8, 0);
+    for (int cg = 0; cg < d.C / KC; ++cg)
+        for (int pi = 0; pi < s; ++pi)
+            for (int l = 0; l < 64; ++l)
+                for (int e = 0; e < 8; ++e) {
+                    const int m = l & 31, kb = l >> 5, t = m >> 3, o = m & 7;
+                    const int ch = slot == 8 ? 2 * cg + kb : 4 * cg + 2 * kb + (e >> 2);
+                    const int dx = slot == 8 ? e : (e & 3), dy = pi + s * t;
+                    if (o < d.H && dy < k && dx < k)
+                        out[(((size_t)cg * s + pi) * 64 + l) * 8 + e] =
+                            f32_to_bf16_rne(W1[(((size_t)o * d.C + ch) * k + dy) * k + dx]);
+                }
 }
 
 template <typename Tag>
@@ -659,8 +772,12 @@ gati_status_t upload_weights(gati_cache* c, const gati_cache_weights_t* w) {
                 st = upload(&c->W1, t1.data(), t1.size() * 2);
             } else if (conv_fc) {
                 std::vector<float> wr, plain;
-                const int kd = conv_reorder(desc, w->W1, 16, wr);
-                pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 16, t1, f32_to_bf16_rne);
+                if (c->variant == POOL_CONV_ROWS) {
+                    pack_conv_rows(c, w->W1, t1);
+                } else {
+                    const int kd = conv_reorder(desc, w->W1, 16, wr);
+                    pack_weights(wr.data(), desc->H, kd, round_up(desc->H, 32), kd, 16, t1, f32_to_bf16_rne);
+                }
                 st = upload(&c->W1, t1.data(), t1.size() * 2);
                 plain.resize((size_t)desc->H * desc->C * desc->conv_k * desc->conv_k);
                 for (size_t q = 0; q < plain.size(); ++q) {
@@ -973,10 +1090,16 @@ hipError_t load_trainer_t(gati_cache* c, const TrainerView& v, hipStream_t st) {
         const long D = (long)d.C * d.S;
         pack_flat_kernel<BF16><<<blocks((long)c->Hb * D), 256, 0, st>>>(v.W1, D, d.H, c->Hb, static_cast<elem_t*>(c->W1));
     } else if (c->conv_fc) {
-        const int rows_p = round_up(d.H, 32);
-        const int k_step = BF16 ? 16 : 8;
-        const long kd = (long)((d.C + k_step - 1) / k_step) * conv_taps_padded(d.conv_k) * k_step;
-        pack_conv_kernel<BF16><<<blocks(rows_p * kd), 256, 0, st>>>(v.W1, d.H, d.C, d.conv_k, rows_p, static_cast<elem_t*>(c->W1));
+        if (c->variant == POOL_CONV_ROWS) {
+            const long cnt = (long)(d.C / (16 / c->rows_slot)) * d.conv_s * 64 * 8;
+            pack_conv_rows_kernel<<<blocks(cnt), 256, 0, st>>>(v.W1, d.H, d.C, d.conv_k, d.conv_s, c->rows_slot, cnt,
+                                                              static_cast<__bf16*>(c->W1));
+        } else {
+            const int rows_p = round_up(d.H, 32);
+            const int k_step = BF16 ? 16 : 8;
+            const long kd = (long)((d.C + k_step - 1) / k_step) * conv_taps_padded(d.conv_k) * k_step;
+            pack_conv_kernel<BF16><<<blocks(rows_p * kd), 256, 0, st>>>(v.W1, d.H, d.C, d.conv_k, rows_p, static_cast<elem_t*>(c->W1));
+        }
         const long cnt = (long)d.H * d.C * d.conv_k * d.conv_k;
         const ColMap all{(int)cnt, 0, (int)cnt, 0, 0};
         pack_vector_kernel<BF16><<<blocks(cnt), 256, 0, st>>>(v.W1, cnt, all, c->W1plain);
@@ -1183,6 +1306,7 @@ const char* gati_cache_pool_variant(const gati_cache_t* c) {
     case POOL_FC_FLAT_GENERIC: return "fc_flat_generic";
     case POOL_CONV: return "conv_mfma";
     case POOL_CONV_GENERIC: return "conv_generic";
+    case POOL_CONV_ROWS: return "conv_rows";
     default: return "generic";
     }
 }

@@ -97,6 +97,22 @@ __global__ __launch_bounds__(256) void pack_conv_kernel(const float* __restrict_
     }
 }
 
+// Filters of conv_rows_kernel (conv_rows_kernels.h): A fragments [channel group][row parity][lane][8 bf16];
+// lane (m, kb) holds tap row t = m / 8 of filter o = m % 8, element e = horizontal tap e of channel
+// 2*group + kb (slot 8) or tap e % 4 of channel 4*group + 2*kb + e / 4 (slot 4), row offset dy = parity + s*t.
+__global__ __launch_bounds__(256) void pack_conv_rows_kernel(const float* __restrict__ W, int Co, int C, int k, int s, int slot,
+                                                             long total, __bf16* __restrict__ out) {
+    for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
+        const int e = (int)(idx & 7), l = (int)((idx >> 3) & 63);
+        const long g = idx >> 9;
+        const int pi = (int)(g % s), cg = (int)(g / s);
+        const int m = l & 31, kb = l >> 5, t = m >> 3, o = m & 7;
+        const int ch = slot == 8 ? 2 * cg + kb : 4 * cg + 2 * kb + (e >> 2);
+        const int dx = slot == 8 ? e : (e & 3), dy = pi + s * t;
+        out[idx] = (__bf16)(o < Co && dy < k && dx < k ? W[(((long)o * C + ch) * k + dy) * k + dx] : 0.f);
+    }
+}
+
 // dst[i] = src[map(i)] (fp32), zero where the map says so; BF16VAL rounds the value to bf16 and keeps it
 // as fp32 (the plain copies that the generic kernels read).
 template <bool BF16VAL>

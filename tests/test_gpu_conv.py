@@ -14,19 +14,28 @@ pytestmark = pytest.mark.gpu
 
 SHAPES = [
     # C, ih, iw, Co, k, s, K, n, dtype, variant
-    (32, 14, 14, 8, 3, 1, 10, 40, "bf16", "conv_mfma"),     # whole-plane staging, one band
+    (32, 14, 14, 8, 3, 1, 10, 40, "bf16", "conv_rows"),     # few filters: input-row formulation, 4-tap slots
     (16, 40, 40, 16, 3, 1, 7, 9, "bf16", "conv_mfma"),      # banded staging (S > 1024), ragged last band
-    (16, 56, 56, 8, 5, 2, 12, 6, "bf16", "conv_mfma"),      # Conv(5,2) on a ResNet stage-1 sized map
+    (16, 56, 56, 8, 5, 2, 12, 6, "bf16", "conv_rows"),      # Conv(5,2) on a ResNet stage-1 sized map: 14 tiles per wave
     (32, 9, 11, 40, 2, 1, 5, 21, "bf16", "conv_mfma"),      # 40 filters: two filter tiles, odd map
     (16, 12, 12, 5, 3, 2, 6, 33, "f32", "conv_mfma"),       # fp32 MFMA, 8-channel blocks
     (16, 6, 6, 4, 6, 1, 4, 17, "bf16", "conv_mfma"),        # filter as large as the map: one output pixel
-    (64, 7, 7, 8, 1, 1, 9, 12, "bf16", "conv_mfma"),        # 1x1 filter
+    (64, 7, 7, 8, 1, 1, 9, 12, "bf16", "conv_rows"),        # 1x1 filter, odd plane size
     (12, 10, 10, 3, 3, 1, 4, 11, "bf16", "conv_generic"),   # channels not a whole block
     (5, 9, 7, 2, 4, 3, 3, 8, "f32", "conv_generic"),
     (32, 32, 40, 4, 3, 1, 6, 5, "bf16", "conv_mfma"),       # wide rows: 38 output columns, several bands
-    (32, 28, 28, 8, 5, 2, 10, 7, "bf16", "conv_mfma"),      # whole-plane staging with the transposing store
+    (32, 28, 28, 8, 5, 2, 10, 7, "bf16", "conv_rows"),      # two input rows per tile
+    (32, 28, 28, 16, 5, 2, 10, 7, "bf16", "conv_mfma"),     # 16 filters: whole-plane staging with the transposing store
     (16, 16, 16, 40, 3, 1, 6, 9, "bf16", "conv_mfma"),      # the same with two filter tiles
     (16, 24, 24, 8, 3, 1, 5, 6, "f32", "conv_mfma"),        # fp32, several tiles per wave
+    # the input-row kernel: every slot width, parity, wave split and fill shape
+    (2048, 7, 7, 8, 3, 1, 10, 30, "bf16", "conv_rows"),     # 7x7 planes of 98 bytes: odd fragment starts, channel parts, 16 fills
+    (1024, 14, 14, 8, 3, 1, 10, 9, "bf16", "conv_rows"),    # few rows: the channels of a request shared among workgroups
+    (64, 30, 30, 7, 7, 2, 6, 5, "bf16", "conv_rows"),       # Conv(7,2): four tap rows per parity, 7 filters
+    (32, 18, 16, 8, 4, 2, 6, 5, "bf16", "conv_rows"),       # even filter, non-square map
+    (16, 13, 11, 5, 3, 2, 6, 12, "bf16", "conv_rows"),      # odd row length with stride 2: 4-tap slots, odd starts
+    (24, 9, 33, 2, 2, 1, 4, 7, "bf16", "conv_rows"),        # 32 output columns: every pixel lane of a tile in use
+    (8, 20, 21, 1, 3, 1, 3, 6, "bf16", "conv_rows"),        # one filter, 19 columns in 32 lanes
     (16, 12, 10, 6, 3, 2, 5, 14, "bf16", "conv_generic:nsc"),   # channels-last map
     (7, 9, 9, 3, 2, 1, 4, 10, "f32", "conv_generic:nsc"),
 ]

@@ -75,7 +75,7 @@ def test_adaptive_pool_random_shapes():
 def test_conv_random_shapes():
     rng = np.random.default_rng(99)
     seen = set()
-    for _ in range(24):
+    for _ in range(40):
         dtype = "bf16" if rng.random() < 0.7 else "f32"
         C = int(rng.choice([8, 16, 32, 48, 12]))
         ih, iw = int(rng.integers(3, 41)), int(rng.integers(3, 41))
@@ -98,7 +98,7 @@ def test_conv_random_shapes():
         seen.add(cache.pool_variant)
         _features_match(d, w, x, cache, n, 4e-3 if dtype == "bf16" else 2e-4)
         cache.close()
-    assert seen == {"conv_mfma", "conv_generic"}
+    assert seen == {"conv_mfma", "conv_generic", "conv_rows"}
 
 
 def test_lookup_random_head_shapes():
