@@ -17,18 +17,27 @@
 // are added into the output rows through LDS at the end, in the fixed order of dy.
 //
 // One workgroup = one request (x one share of the channels when few requests would leave
-// CUs idle: the shares are summed in order by conv_reduce_kernel).  Its 4 waves split into row
+// CUs idle: the shares are summed in order by conv_reduce_kernel).  Its 8 waves split into row
 // parities (s = 2), then into tile sets, then -- small maps, fewer tiles than waves -- into channel
-// parts.  LDS holds one fill: CC channels of the map followed by their filter fragments; the next
-// fill waits in registers while this one is multiplied.
+// parts.  A fill is CC channels of the map followed by their filter fragments; fills go from global
+// memory straight into a ring of LDS slots (global_load_lds: lane l of a wave-wide load lands at
+// base + 16*l, counted by vmcnt), three fills ahead of the one being multiplied, so no register
+// holds data in transit and ~90 KB per CU are in flight.
 #pragma once
 
 #include "conv_kernels.h"
 
 namespace gati {
 
-constexpr int kRowsMaxVec = 3840;        // 60 KB per fill (16-byte vectors): 8 channels of a 56 x 56 map and their fragments
+constexpr int kRowsSlotVec = 2048;       // 32 KB per fill (16-byte vectors)
+constexpr int kRowsDepth = 4;            // LDS slots: one being multiplied, three in flight
+constexpr int kRowsWaves = 8;            // waves per workgroup: two per SIMD, so one multiplies while the other waits
+constexpr int kRowsThreads = kRowsWaves * 64;
+constexpr int kRowsLoads = kRowsSlotVec / kRowsThreads;   // wave-wide loads per wave and fill: always this many (surplus
+                                                          // ones land in a spare KB), so the wait below can name a count
+constexpr int kRowsLdsBytes = kRowsDepth * kRowsSlotVec * 16 + 1024;
 constexpr int kRowsFilters = 8;          // filters per MFMA row block
+constexpr int kRowsMaxTiles = 7;         // tiles per wave: 7 x 16 accumulators
 
 struct ConvRowsArgs {
     const void* act;           // [rows, C, in_h*in_w] bf16
@@ -40,7 +49,7 @@ struct ConvRowsArgs {
     const float* bias;
     int CC;                    // channels per fill: CC*S*2 bytes are a multiple of 16
     int xw_log2;               // a tile gives every input row it holds 2^xw_log2 >= ow pixel lanes
-    int nwt_log2, ws;          // waves of one parity: 2^nwt_log2 tile sets x ws channel parts
+    int nwt_log2, ws;          // waves of one parity: 2^nwt_log2 tile sets x ws channel parts (waves past that only load)
     float* out;                // [n, out_stride] fp32 features, order [filter][oy][ox]
     __bf16* out16;             // bf16 copy or null
     int out_stride;
@@ -51,23 +60,40 @@ struct ConvRowsArgs {
 // 16 bytes of LDS at a 4-byte aligned address.
 struct __attribute__((packed, aligned(4))) lds_u32x4 { uint32_t w[4]; };
 
+// One wave-wide load of 64 x 16 bytes from global memory (base + the lane's byte offset) straight into LDS:
+// lane l lands at dst + 16*l; dst is wave-uniform and travels in M0.  Written as assembly so that the compiler
+// does not order every later LDS read behind it (it would wait for ALL outstanding loads before the first
+// fragment read of a fill); the kernel waits by count instead (wait_loads), and barriers separate a slot's
+// writers and readers.
+__device__ __forceinline__ void lds_direct_load(const void* base, uint32_t lane_off, void* dst) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst);
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    // (the builtin returns a signed int: without the casts the low half would sign-extend into the high one)
+    const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32) |
+                        (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(lane_off), "s"(sb) : "memory");
+}
+// Wait until at most N of this wave's vector-memory loads are outstanding (they complete in order).
+template <int N>
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
+
 // SLOT: horizontal taps per channel in the reduction index (8: stride 2, even row length; 4: k <= 3).
 // TPW: tiles per wave.
 template <int SLOT, int TPW>
-__global__ __launch_bounds__(256, (TPW <= 4 ? 2 : 1)) void conv_rows_kernel(ConvRowsArgs a) {
+__global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a) {
     using frag_t = Mma<true>::frag_t;
     constexpr int KC = 16 / SLOT;                            // channels per MFMA
-    constexpr int UG = TPW >= 4 ? 1 : (TPW == 2 ? 2 : 4);    // channel groups in flight per wave
-    constexpr int LPT = kRowsMaxVec / 256;
-    __shared__ u32x4_t lds[kRowsMaxVec];
-    unsigned char* const ldsb = reinterpret_cast<unsigned char*>(lds);
+    constexpr int UG = TPW >= 4 ? 1 : (TPW == 2 ? 2 : 4);    // channel groups whose fragments are in flight per wave
+    constexpr int D = kRowsDepth, QF = kRowsLoads, NW = kRowsWaves, NT = kRowsThreads;
+    extern __shared__ __align__(16) unsigned char rows_lds[];    // D slots, then the spare KB
 
     const int n = active_rows(a.n_dev, a.n_max);
     const int split = blockIdx.x % a.ksplit;
     const int i = blockIdx.x / a.ksplit;
     if (i >= n) return;                                      // whole workgroup
     const long r = a.row_index ? (long)a.row_index[i] : (long)i;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what follows from it stays in scalar registers
     const int nn = lane & 31, kb = lane >> 5;
 
     // wave -> (row parity, tile set, channel part)
@@ -101,8 +127,8 @@ __global__ __launch_bounds__(256, (TPW <= 4 ? 2 : 1)) void conv_rows_kernel(Conv
         }
     }
     const int gbytes = KC * a.S * 2;                         // one channel group further on
-    auto bfrag = [&](int t, int cg) -> frag_t {
-        const unsigned char* p = ldsb + cg * gbytes;
+    auto bfrag = [&](const unsigned char* slot, int t, int cg) -> frag_t {
+        const unsigned char* p = slot + cg * gbytes;
         u32x4_t w;
         if constexpr (SLOT == 8) {
             const lds_u32x4 v = *reinterpret_cast<const lds_u32x4*>(p + boff[t][0]);
@@ -119,32 +145,39 @@ __global__ __launch_bounds__(256, (TPW <= 4 ? 2 : 1)) void conv_rows_kernel(Conv
         return __builtin_bit_cast(frag_t, w);
     };
 
-    // one fill: CC channels of the request's map, then their A fragments, both contiguous in memory
+    // One fill: CC channels of the request's map (nva vectors, contiguous in memory), padded to whole KB, then
+    // their A fragments (whole KB).  A wave-wide load moves one KB, so every load has one source: the map or
+    // the fragments; only the map's last KB may be partial -- its surplus lanes repeat the last vector (the pad
+    // they fill is read by the last rows' fragments past the window, against zero weights).
     const int nva = a.CC * a.S * 2 / 16;
+    const int ca = (nva + 63) >> 6;                          // KB of map
     const int G = a.CC / KC;
-    const int nvw = G * a.s * 64;
-    const int nv = nva + nvw;
+    const int cw = G * a.s;                                  // KB of fragments
+    const int chunks = ca + cw;                              // <= kRowsSlotVec / 64 by plan
     const int fill0 = split * a.fills_per_split;
     const int fill1 = min(a.C / a.CC, fill0 + a.fills_per_split);
     const unsigned char* abase = static_cast<const unsigned char*>(a.act) + r * (long)a.C * a.S * 2;
     const unsigned char* wbase = static_cast<const unsigned char*>(a.Wr);
-    u32x4_t stage[LPT];
-    auto issue = [&](int f) {
-        const unsigned char* fa = abase + (long)f * nva * 16;
-        const unsigned char* fw = wbase + (long)f * nvw * 16;
+    unsigned char* const spare = rows_lds + D * kRowsSlotVec * 16;
+    const uint32_t off_full = lane * 16;
+    const uint32_t off_tail = min(lane, nva - 1 - (ca - 1) * 64) * 16;
+    // Fill `f` into slot `slot`.  Always QF loads per wave: KBs past the fill, and whole fills past the last
+    // one, re-read valid vectors into the spare KB.
+    auto issue = [&](int f, int slot) {
+        const bool live = f < fill1;
+        const int fc = min(f, fill1 - 1);
+        const unsigned char* fa = abase + (long)fc * nva * 16;
+        const unsigned char* fw = wbase + (long)fc * cw * 1024;
+        unsigned char* sb = rows_lds + slot * (kRowsSlotVec * 16);
 #pragma unroll
-        for (int q = 0; q < LPT; ++q) {
-            const int v = min(tid + 256 * q, nv - 1);        // surplus lanes repeat the last vector
-            stage[q] = *reinterpret_cast<const u32x4_t*>(v >= nva ? fw + (v - nva) * 16 : fa + v * 16);
+        for (int q = 0; q < QF; ++q) {
+            const int c = min(wave + NW * q, chunks - 1);    // wave-uniform
+            const bool is_w = c >= ca;
+            const unsigned char* src = is_w ? fw + (c - ca) * 1024 : fa + c * 1024;
+            unsigned char* dst = (live && wave + NW * q < chunks) ? sb + c * 1024 : spare;
+            lds_direct_load(src, (!is_w && c == ca - 1) ? off_tail : off_full, dst);
         }
     };
-    auto park = [&]() {
-#pragma unroll
-        for (int q = 0; q < LPT; ++q)
-            if (tid + 256 * q < nv) lds[tid + 256 * q] = stage[q];
-    };
-    const unsigned char* const alds = ldsb + nva * 16 + (pi * 64 + lane) * 16;
-    auto afrag = [&](int cg) -> frag_t { return *reinterpret_cast<const frag_t*>(alds + cg * a.s * 1024); };
 
     f32x16_t acc[TPW];
 #pragma unroll
@@ -152,43 +185,55 @@ __global__ __launch_bounds__(256, (TPW <= 4 ? 2 : 1)) void conv_rows_kernel(Conv
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
 
-    const int gsteps = G / a.ws;                             // groups per wave and fill: a multiple of UG by plan
-    if (fill0 < fill1) issue(fill0);
-    for (int f = fill0; f < fill1; ++f) {
-        park();
+    const int rounds = G / a.ws / UG;                        // rounds of UG groups per wave and fill: whole by plan
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d) issue(fill0 + d, d);
+    for (int f = fill0, it = 0; f < fill1; ++f, ++it) {
+        // this wave's loads of fill f have landed once at most the (D-2)*QF younger ones are outstanding; after
+        // the barrier so have everyone's, and everyone is done with the slot that the next fill goes to
+        wait_loads<(D - 2) * QF>();
         __syncthreads();
-        if (f + 1 < fill1) issue(f + 1);                     // in flight while this fill is multiplied
-        // every fragment is read one round (UG groups x TPW tiles) ahead of its MFMA; nothing below is conditional
+        issue(f + D - 1, (it + D - 1) % D);
+        if (wp >= a.ws) continue;                            // a wave without a channel part (few channels): loads only
+        const unsigned char* slot = rows_lds + (it % D) * (kRowsSlotVec * 16);
+        const unsigned char* const alds = slot + ca * 1024 + (pi * 64 + lane) * 16;
+        // every fragment is read one round (UG groups x TPW tiles) ahead of its MFMA; the last round only multiplies
         frag_t bf[UG][TPW], af[UG];
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             const int cg = wp + u * a.ws;
-            af[u] = afrag(cg);
+            af[u] = *reinterpret_cast<const frag_t*>(alds + cg * a.s * 1024);
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) bf[u][t] = bfrag(t, cg);
+            for (int t = 0; t < TPW; ++t) bf[u][t] = bfrag(slot, t, cg);
         }
-        for (int gs = 0; gs < gsteps; gs += UG) {
+        for (int rd = 1; rd < rounds; ++rd) {
 #pragma unroll
             for (int u = 0; u < UG; ++u) {
-                const int cgn = min(wp + (gs + u + UG) * a.ws, G - 1);   // past the fill: any valid group, never multiplied
-                const frag_t an = afrag(cgn);
+                const int cgn = wp + (rd * UG + u) * a.ws;
+                const frag_t an = *reinterpret_cast<const frag_t*>(alds + cgn * a.s * 1024);
+                __builtin_amdgcn_sched_barrier(0);           // keep this read ahead of the MFMAs that hide it
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     acc[t] = Mma<true>::mma(af[u], bf[u][t], acc[t]);
-                    bf[u][t] = bfrag(t, cgn);
+                    bf[u][t] = bfrag(slot, t, cgn);
                 }
                 af[u] = an;
             }
         }
-        __syncthreads();                                     // every wave is done with the fill
+#pragma unroll
+        for (int u = 0; u < UG; ++u)
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) acc[t] = Mma<true>::mma(af[u], bf[u][t], acc[t]);
     }
+    wait_loads<0>();                                         // the surplus loads of the last rounds
+    __syncthreads();
 
-    // shares of the tap rows -> output rows, through LDS (the fill buffer is free now), in the order
+    // shares of the tap rows -> output rows, through LDS (the slots are free now), in the order
     // (channel part, dy): within one round no two lanes meet in an output element
     const int OHW = a.oh * a.ow;
     const int F = a.Co * OHW;
-    float* const obuf = reinterpret_cast<float*>(lds);
-    for (int idx = tid; idx < F; idx += 256) obuf[idx] = 0.f;
+    float* const obuf = reinterpret_cast<float*>(rows_lds);
+    for (int idx = tid; idx < F; idx += NT) obuf[idx] = 0.f;
     for (int wpp = 0; wpp < a.ws; ++wpp) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -216,7 +261,7 @@ __global__ __launch_bounds__(256, (TPW <= 4 ? 2 : 1)) void conv_rows_kernel(Conv
     const bool last = a.ksplit == 1;
     float* orow = (last ? a.out : a.partial + (long)split * a.n_max * a.out_stride) + (long)i * a.out_stride;
     __bf16* orow16 = (last && a.out16) ? a.out16 + (long)i * a.out_stride : nullptr;
-    for (int idx = tid; idx < F; idx += 256) {
+    for (int idx = tid; idx < F; idx += NT) {
         float v = obuf[idx];
         if (last) v = fmaxf(v + a.bias[idx / OHW], 0.f);
         orow[idx] = v;

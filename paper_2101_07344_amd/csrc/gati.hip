@@ -137,44 +137,61 @@ bool plan_conv_rows(gati_cache* c) {
     else return false;
     if ((k + s - 1) / s > 4) return false;                   // tap rows of one parity: D has room for 4
     const int KC = 16 / slot;
-    if (ow > 32 || (long)d.H * oh * ow * 4 > (long)kRowsMaxVec * 16) return false;
+    if (ow > 32 || (long)d.H * oh * ow * 4 > (long)kRowsSlotVec * 16) return false;
     if (d.C % KC != 0 || ((long)d.C * d.S * 2) % 16 != 0 || (long)d.C * d.S >= (1L << 30)) return false;
     int xw = 0;
     while ((1 << xw) < ow) ++xw;
     const int rpt = 32 >> xw;                                // input rows per tile
-    const int nwc = 4 / s;                                   // waves per row parity
+    const int nwc = kRowsWaves / s;                          // waves per row parity
     const int rows_c = (d.in_h + s - 1) / s;                 // rows of parity 0, the larger class
     const int ntc = (rows_c + rpt - 1) / rpt;                // tiles per parity
     int nwt_log2 = 0;
     while ((2 << nwt_log2) <= std::min(nwc, ntc)) ++nwt_log2;
-    const int nwt = 1 << nwt_log2, ws = nwc / nwt;
+    const int nwt = 1 << nwt_log2;
     const int need = (ntc + nwt - 1) / nwt;
     int tpw = 0;
-    for (int cand : {1, 2, 4, 8, 14})
+    for (int cand : {1, 2, 4, kRowsMaxTiles})
         if (cand >= need) { tpw = cand; break; }
-    if (!tpw) return false;
+    if (!tpw || (slot == 4 && tpw > 4)) return false;       // 7 tiles of two-part fragments do not fit the registers
     const int ug = tpw >= 4 ? 1 : (tpw == 2 ? 2 : 4);
-    // channels per fill: whole 16-byte vectors, whole rounds of every wave, a divisor of C, at most 56 KB
-    // together with the fill's filter fragments
-    int unit = KC * ws * ug;
-    while (((long)unit * d.S * 2) % 16 != 0) unit *= 2;
-    int cc = 0;
-    for (int cand = unit; cand <= d.C; cand += unit) {
-        if (d.C % cand != 0) continue;
-        if ((long)cand * d.S * 2 + (long)(cand / KC) * s * 1024 > (long)kRowsMaxVec * 16) break;
-        cc = cand;
+    // channels per fill: whole 16-byte vectors, whole rounds of every wave, a divisor of C; the map part
+    // (rounded up to whole KB) and the fill's filter fragments share one LDS slot.  Waves left over once
+    // the tiles are dealt out split the channels of a fill, as far as C has channels for them.
+    int ws = nwc / nwt, cc = 0;
+    for (; ws >= 1 && !cc; ws /= 2) {
+        int unit = KC * ws * ug;
+        while (((long)unit * d.S * 2) % 16 != 0) unit *= 2;
+        for (int cand = unit; cand <= d.C; cand += unit) {
+            if (d.C % cand != 0) continue;
+            if (round_up((int)((long)cand * d.S * 2), 1024) + (long)(cand / KC) * s * 1024 > (long)kRowsSlotVec * 16) break;
+            cc = cand;
+        }
+        if (cc) break;
     }
     if (!cc) return false;
     const int fills = d.C / cc;
     // few requests: share the channels of a request among workgroups (fixed at creation, so results do not
     // depend on how many rows a call has)
-    int ks = (int)((4L * c->num_cu + d.max_rows - 1) / d.max_rows);
+    int ks = (int)((2L * c->num_cu + d.max_rows - 1) / d.max_rows);
     ks = std::max(1, std::min(std::min(ks, fills), 16));
     c->rows_fills_per = (fills + ks - 1) / ks;
     c->conv_ksplit = (fills + c->rows_fills_per - 1) / c->rows_fills_per;
     c->rows_slot = slot; c->rows_tpw = tpw; c->rows_cc = cc; c->rows_xw_log2 = xw;
     c->rows_nwt_log2 = nwt_log2; c->rows_ws = ws;
     return true;
+}
+
+typedef void (*conv_rows_fn)(ConvRowsArgs);
+conv_rows_fn conv_rows_instance(int slot, int tpw) {
+    switch (slot * 16 + tpw) {
+    case 8 * 16 + 1: return conv_rows_kernel<8, 1>;
+    case 8 * 16 + 2: return conv_rows_kernel<8, 2>;
+    case 8 * 16 + 4: return conv_rows_kernel<8, 4>;
+    case 8 * 16 + 7: return conv_rows_kernel<8, 7>;
+    case 4 * 16 + 1: return conv_rows_kernel<4, 1>;
+    case 4 * 16 + 2: return conv_rows_kernel<4, 2>;
+    default: return conv_rows_kernel<4, 4>;
+    }
 }
 
 // Conv(k,s): staging mode and band height of conv_relu_kernel, or the generic kernel.
@@ -255,19 +272,7 @@ hipError_t launch_conv_t(const gati_cache* c, const void* act, const int32_t* ro
                 ra.ksplit = c->conv_ksplit; ra.fills_per_split = c->rows_fills_per; ra.partial = c->conv_partial;
             }
             const int grid = n_max * ra.ksplit;
-            const int key = c->rows_slot * 16 + c->rows_tpw;
-            switch (key) {
-            case 8 * 16 + 1: conv_rows_kernel<8, 1><<<grid, 256, 0, st>>>(ra); break;
-            case 8 * 16 + 2: conv_rows_kernel<8, 2><<<grid, 256, 0, st>>>(ra); break;
-            case 8 * 16 + 4: conv_rows_kernel<8, 4><<<grid, 256, 0, st>>>(ra); break;
-            case 8 * 16 + 8: conv_rows_kernel<8, 8><<<grid, 256, 0, st>>>(ra); break;
-            case 8 * 16 + 14: conv_rows_kernel<8, 14><<<grid, 256, 0, st>>>(ra); break;
-            case 4 * 16 + 1: conv_rows_kernel<4, 1><<<grid, 256, 0, st>>>(ra); break;
-            case 4 * 16 + 2: conv_rows_kernel<4, 2><<<grid, 256, 0, st>>>(ra); break;
-            case 4 * 16 + 4: conv_rows_kernel<4, 4><<<grid, 256, 0, st>>>(ra); break;
-            case 4 * 16 + 8: conv_rows_kernel<4, 8><<<grid, 256, 0, st>>>(ra); break;
-            default: conv_rows_kernel<4, 14><<<grid, 256, 0, st>>>(ra); break;
-            }
+            conv_rows_instance(c->rows_slot, c->rows_tpw)<<<grid, kRowsThreads, kRowsLdsBytes, st>>>(ra);
             if (ra.ksplit > 1) {
                 hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return e;
@@ -1003,6 +1008,12 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         c->variant = POOL_FC_FLAT;
     } else if (conv_fc) {
         plan_conv(c);
+        // the LDS ring of conv_rows_kernel is above the 64 KB a kernel gets by default
+        if (c->variant == POOL_CONV_ROWS &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(conv_rows_instance(c->rows_slot, c->rows_tpw)),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kRowsLdsBytes) != hipSuccess) {
+            (void)hipGetLastError(); delete c; return GATI_ERR_DEVICE;
+        }
     } else {
         plan_pool(c);
     }
