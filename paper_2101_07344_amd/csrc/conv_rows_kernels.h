@@ -49,6 +49,7 @@ struct ConvRowsArgs {
     const float* bias;
     int CC;                    // channels per fill: CC*S*2 bytes are a multiple of 16
     int xw_log2;               // a tile gives every input row it holds 2^xw_log2 >= ow pixel lanes
+    int rs_log2;               // the rows of one tile are 2^rs_log2 apart (among the rows of their parity)
     int nwt_log2, ws;          // waves of one parity: 2^nwt_log2 tile sets x ws channel parts (waves past that only load)
     float* out;                // [n, out_stride] fp32 features, order [filter][oy][ox]
     __bf16* out16;             // bf16 copy or null
@@ -111,7 +112,10 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
     int bsh[TPW][SLOT == 8 ? 1 : 2];                         // SLOT 4: 16 when the fragment starts on an odd element
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-        const int rho = ((wt + (t << a.nwt_log2)) << rpt_log2) + jrow;
+        // tile tau holds the rows rho = block*RS*rpt + i + RS*j (block = tau / RS, i = tau % RS, j < rpt): the
+        // rows of a tile are RS apart, which the plan picks so that they fall on different LDS banks
+        const int tau = wt + (t << a.nwt_log2);
+        const int rho = ((tau >> a.rs_log2) << (a.rs_log2 + rpt_log2)) + (tau & ((1 << a.rs_log2) - 1)) + (jrow << a.rs_log2);
         iy[t] = pi + a.s * rho;
         const int e0 = min(iy[t], a.in_h - 1) * a.in_w + a.s * x;
         if constexpr (SLOT == 8) {

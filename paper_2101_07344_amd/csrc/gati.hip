@@ -98,7 +98,7 @@ struct gati_cache {
     float* conv_partial = nullptr;   // [ksplit][max_rows][Cp] when ksplit > 1
     // plan of conv_rows_kernel (few filters, bf16, channel-major): taps per channel in the reduction index,
     // tiles per wave, channels per LDS fill, pixel lanes per input row, waves per tile set / channel part
-    int rows_slot = 0, rows_tpw = 0, rows_cc = 0, rows_xw_log2 = 0, rows_nwt_log2 = 0, rows_ws = 1, rows_fills_per = 0;
+    int rows_slot = 0, rows_tpw = 0, rows_cc = 0, rows_xw_log2 = 0, rows_rs_log2 = 0, rows_nwt_log2 = 0, rows_ws = 1, rows_fills_per = 0;
     float* W1plain = nullptr; // [Co, C, k, k] fp32 (rounded to bf16 values in bf16 caches)
 };
 
@@ -144,7 +144,23 @@ bool plan_conv_rows(gati_cache* c) {
     const int rpt = 32 >> xw;                                // input rows per tile
     const int nwc = kRowsWaves / s;                          // waves per row parity
     const int rows_c = (d.in_h + s - 1) / s;                 // rows of parity 0, the larger class
-    const int ntc = (rows_c + rpt - 1) / rpt;                // tiles per parity
+    // several rows per tile: how far apart (1, 2 or 4 rows of the parity) they should be so that the first
+    // dwords of the 32 pixel lanes' fragments fall on as many different LDS banks as possible
+    int rs_log2 = 0;
+    if (rpt > 1) {
+        int best = 1 << 30;
+        for (int cand = 0; cand <= 2; ++cand) {
+            int per_bank[32] = {0}, worst = 0;
+            for (int j = 0; j < rpt; ++j)
+                for (int xx = 0; xx < std::min(ow, 32 / rpt); ++xx) {
+                    const int dword = ((j << cand) * s * d.in_w + s * xx) / 2;
+                    worst = std::max(worst, ++per_bank[dword & 31]);
+                }
+            if (worst < best) { best = worst; rs_log2 = cand; }
+        }
+    }
+    const int rs = 1 << rs_log2;
+    const int ntc = (rows_c + rs * rpt - 1) / (rs * rpt) * rs;   // tiles per parity
     int nwt_log2 = 0;
     while ((2 << nwt_log2) <= std::min(nwc, ntc)) ++nwt_log2;
     const int nwt = 1 << nwt_log2;
@@ -176,7 +192,7 @@ bool plan_conv_rows(gati_cache* c) {
     ks = std::max(1, std::min(std::min(ks, fills), 16));
     c->rows_fills_per = (fills + ks - 1) / ks;
     c->conv_ksplit = (fills + c->rows_fills_per - 1) / c->rows_fills_per;
-    c->rows_slot = slot; c->rows_tpw = tpw; c->rows_cc = cc; c->rows_xw_log2 = xw;
+    c->rows_slot = slot; c->rows_tpw = tpw; c->rows_cc = cc; c->rows_xw_log2 = xw; c->rows_rs_log2 = rs_log2;
     c->rows_nwt_log2 = nwt_log2; c->rows_ws = ws;
     return true;
 }
@@ -264,7 +280,7 @@ hipError_t launch_conv_t(const gati_cache* c, const void* act, const int32_t* ro
             ra.act = act; ra.row_index = row_index; ra.n_dev = n_dev; ra.n_max = n_max;
             ra.C = d.C; ra.S = d.S; ra.in_h = d.in_h; ra.in_w = d.in_w; ra.k = d.conv_k; ra.s = d.conv_s;
             ra.oh = c->conv_oh; ra.ow = c->conv_ow; ra.Co = d.H;
-            ra.Wr = c->W1; ra.bias = c->b1; ra.CC = c->rows_cc; ra.xw_log2 = c->rows_xw_log2;
+            ra.Wr = c->W1; ra.bias = c->b1; ra.CC = c->rows_cc; ra.xw_log2 = c->rows_xw_log2; ra.rs_log2 = c->rows_rs_log2;
             ra.nwt_log2 = c->rows_nwt_log2; ra.ws = c->rows_ws;
             ra.out = out; ra.out16 = static_cast<__bf16*>(out16); ra.out_stride = out_stride;
             ra.ksplit = 1; ra.fills_per_split = d.C / c->rows_cc; ra.partial = nullptr;
