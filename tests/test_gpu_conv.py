@@ -101,6 +101,28 @@ def test_conv_predictor_matches_oracle(C, ih, iw, Co, k, s, K, n, dtype, variant
     cache.close()
 
 
+@pytest.mark.parametrize("C,ih,iw,k,s", [(64, 56, 56, 5, 2), (128, 28, 28, 5, 2), (256, 14, 14, 3, 1), (512, 7, 7, 3, 1)])
+def test_conv_rows_many_fills_per_workgroup(C, ih, iw, k, s):
+    """A cache sized for a large batch keeps all channels of a request in one workgroup: 16 and more
+    fills run through every slot of the LDS ring, as in the full-size stacks, here against the oracle
+    on every hidden value."""
+    rng = np.random.default_rng(C + ih)
+    n, Co, K, S = 6, 8, 5, ih * iw
+    x = torch.from_numpy((rng.standard_normal((n, C, S)) + 0.2).astype(np.float32)).bfloat16()
+    d = CacheDef(C=C, S=S, H=Co, K=K, dtype="bf16", threshold=0.5, round_operands=True,
+                 predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s))
+    w = _weights(C, Co, k, K, d.F, rng)
+    want = oracle.lookup(d, w, W.to_host_array(x))["pooled"]
+    cache = g.Cache(C, S, Co, K, "bf16", "ncs", 0.5, 512, w, predictor="conv_fc", in_hw=(ih, iw), conv_ks=(k, s))
+    assert cache.pool_variant == "conv_rows"
+    feat = torch.full((n, d.F), -1.0, device="cuda")
+    cache.pool(x.cuda(), None, n, None, feat)
+    torch.cuda.synchronize()
+    err = np.max(np.abs(feat.cpu().numpy() - want))
+    assert err <= 2e-3, err
+    cache.close()
+
+
 def test_conv_rejects_bad_shapes():
     def make(C, ih, iw, Co, k, s, layout="ncs", S=None):
         oh, ow = max(0, (ih - k) // s + 1), max(0, (iw - k) // s + 1)
