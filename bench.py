@@ -279,6 +279,32 @@ def stream_read_ceiling(acts, torch, g, min_bytes=512 << 20, reps=10):
                       f"median of {reps} launches"}
 
 
+def dependent_launch_floor(torch, g, links=200, reps=5):
+    """What a launch costs that waits for its predecessor's output and computes nothing: chains of the
+    library's probe kernel (`gati_probe_launch_chain`), per link, at the grid sizes of the predictor /
+    selector kernels and with 0, 1 and 2 dependent loads per lane.  The head of a layer is three such
+    launches plus their arithmetic."""
+    cell = torch.zeros(2, dtype=torch.int32, device="cuda")
+    out = {}
+    for wgs in (16, 128, 512):
+        for loads in (0, 1, 2):
+            assert g.gati_probe_launch_chain(cell, 20, wgs, loads) == g.GATI_OK
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                g.gati_probe_launch_chain(cell, links, wgs, loads)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e3 / links)
+            ts.sort()
+            out[f"{wgs}wg_{loads}loads_us"] = round(ts[len(ts) // 2], 2)
+    out["what"] = (f"median of {reps} chains of {links} launches of gati_probe_launch_chain, microseconds per launch; "
+                   "workgroups of 256 lanes, every lane follows the given number of dependent 4-byte loads from a cell the previous launch wrote")
+    return out
+
+
 def plain_read_same_sizes(spec, acts, counts, torch, g, reps=5):
     """A plain read of as many bytes as each layer's pooling launch reads, launched back to back in
     layer order between one event pair (the way the pooling launches are timed): what a kernel that
@@ -448,6 +474,7 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
         out["stream_read_ceiling"] = sc
         out["roofline"]["frac_of_stream_read_ceiling"] = round(achieved / sc["GBps"], 4) if out["roofline"]["bound"] == "hbm" else None
         out["pool_all_layers"]["frac_of_stream_read_ceiling"] = round(out["pool_all_layers"]["GBps"] / sc["GBps"], 4)
+        out["dependent_launch_floor"] = dependent_launch_floor(torch, g)
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(spec, weights, acts, stack, counts, cpu_requests, torch, W)
         if spec.storage == "gather":
@@ -677,7 +704,7 @@ def main():
         "pool_kernels": main_res["pool_kernels"],
         "others": others,
     }
-    for key in ("head_us_per_step", "compact_alone_us", "graph_ms_per_step", "overlap", "library_pool", "train_step"):
+    for key in ("head_us_per_step", "dependent_launch_floor", "compact_alone_us", "graph_ms_per_step", "overlap", "library_pool", "train_step"):
         if key in main_res:
             line[key] = main_res[key]
     if args.gemm_yardstick and L0.predictor == "fc_mlp":

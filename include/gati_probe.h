@@ -2,7 +2,9 @@
  * gati_probe.h - measurement probes shipped with the learned-cache library.  They compute nothing of
  * the method: they exist so that a benchmark run can state, on the box it runs on, what a plain
  * streaming read reaches (the ceiling the pooling kernels are compared with, beside the published
- * HBM peak) and so that hardware byte counters can be scaled by a dispatch of exactly known traffic.
+ * HBM peak), so that hardware byte counters can be scaled by a dispatch of exactly known traffic, and
+ * what a launch costs that consumes its predecessor's output and does nothing else (the floor under
+ * the predictor / selector kernels, which are chains of such launches).
  * Same conventions as gati.h: device pointers, caller-owned buffers, enqueue on the caller's stream,
  * status return, nothing allocated.
  */
@@ -31,6 +33,13 @@ gati_status_t gati_probe_stream_read(const void *buf, size_t bytes, float *sink,
  * and stores.  Algorithmic traffic: `bytes` read and `bytes` written - the known quantity against
  * which FETCH_SIZE / WRITE_SIZE counter readings are scaled. */
 gati_status_t gati_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/* Enqueue `links` (0..4096) launches of `workgroups` (1..65536) workgroups of 256 lanes, one after the
+ * other on `stream`; every lane of a link follows `loads` (0..8) dependent 4-byte loads starting at a
+ * cell that the previous link wrote, and one lane writes that cell for the next link.  cell: device,
+ * two int32, zero before the first call and zero afterwards.  Time per link = the cost of a launch
+ * that waits for its predecessor's result and has nothing to compute. */
+gati_status_t gati_probe_launch_chain(int32_t *cell, int32_t links, int32_t workgroups, int32_t loads, void *stream);
 
 #ifdef __cplusplus
 }

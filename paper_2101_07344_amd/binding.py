@@ -23,7 +23,7 @@ exported_symbols = (
     "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_compact_misses_static", "gati_status_string", "gati_cache_pool_variant",
     "gati_trainer_create", "gati_trainer_destroy", "gati_trainer_step", "gati_trainer_get_weights",
     "gati_trainer_get_hidden_selector", "gati_cache_load_trainer",
-    "gati_probe_stream_read", "gati_probe_copy",
+    "gati_probe_launch_chain", "gati_probe_stream_read", "gati_probe_copy",
 )
 
 
@@ -107,6 +107,8 @@ def load_library():
     lib.gati_trainer_get_hidden_selector.argtypes = [vp, vp, vp, vp]
     lib.gati_cache_load_trainer.restype = C.c_int
     lib.gati_cache_load_trainer.argtypes = [vp, vp, vp]
+    lib.gati_probe_launch_chain.restype = C.c_int
+    lib.gati_probe_launch_chain.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp]
     lib.gati_probe_stream_read.restype = C.c_int
     lib.gati_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
     lib.gati_probe_copy.restype = C.c_int
@@ -193,6 +195,10 @@ def gati_compact_misses_static(handle, hit, ids_in, n_max: int, n_dev, ids_out, 
 
 def gati_probe_stream_read(buf, nbytes: int, sink, blocks_per_cu: int = 1, stream=None) -> int:
     return load_library().gati_probe_stream_read(_dptr(buf), int(nbytes), _dptr(sink), int(blocks_per_cu), _stream(stream))
+
+
+def gati_probe_launch_chain(cell, links: int, workgroups: int, loads: int, stream=None) -> int:
+    return load_library().gati_probe_launch_chain(_dptr(cell), int(links), int(workgroups), int(loads), _stream(stream))
 
 
 def gati_probe_copy(dst, src, nbytes: int, stream=None) -> int:

@@ -1,4 +1,5 @@
-// Measurement probes (see include/gati_probe.h): a streaming read and a plain copy of known size.
+// Measurement probes (see include/gati_probe.h): a streaming read, a plain copy of known size and a chain of
+// dependent near-empty launches.
 // No part of the lookup runs through them.
 #include <hip/hip_runtime.h>
 
@@ -53,6 +54,17 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4_t* __restrict__ d
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
 }
 
+// One link of a chain of launches: every lane follows `loads` dependent loads that start at a cell the
+// previous link wrote (the values are always 0, so the walk stays inside the two cells), then one lane
+// writes the cell for the next link.  What it costs is what any kernel pays that consumes its
+// predecessor's output: dispatch, argument fetch, the dependent round trips, the end-of-kernel write-back.
+__global__ __launch_bounds__(256) void probe_chain_kernel(int32_t* cell, int loads) {
+    const volatile int32_t* p = cell;
+    int v = 0;
+    for (int d = 0; d < loads; ++d) v = p[v & 1];
+    if (blockIdx.x == 0 && threadIdx.x == 0) cell[0] = v & 1;
+}
+
 int cu_count() {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
@@ -85,6 +97,14 @@ gati_status_t gati_probe_copy(void* dst, const void* src, size_t bytes, void* st
         return GATI_ERR_INVALID_ARG;
     if (bytes == 0) return GATI_OK;
     probe_copy_kernel<<<cu_count() * 8, 256, 0, (hipStream_t)stream>>>(static_cast<u32x4_t*>(dst), static_cast<const u32x4_t*>(src), (long)(bytes / 16));
+    return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
+}
+
+gati_status_t gati_probe_launch_chain(int32_t* cell, int32_t links, int32_t workgroups, int32_t loads, void* stream) {
+    if (!cell || links < 0 || links > 4096 || workgroups < 1 || workgroups > 65536 || loads < 0 || loads > 8)
+        return GATI_ERR_INVALID_ARG;
+    if (links == 0) return GATI_OK;
+    for (int l = 0; l < links; ++l) probe_chain_kernel<<<workgroups, 256, 0, (hipStream_t)stream>>>(cell, loads);
     return hipGetLastError() == hipSuccess ? GATI_OK : GATI_ERR_DEVICE;
 }
 

@@ -73,6 +73,10 @@ def test_calls_reject_null_handles_and_bad_counts_on_the_host():
     assert g.gati_probe_stream_read(16, 24, 16, 1, stream=0) == g.GATI_ERR_INVALID_ARG      # not whole 16-byte vectors
     assert g.gati_probe_stream_read(16, 32, 16, 33, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_probe_copy(16, 24, 16, stream=0) == g.GATI_ERR_INVALID_ARG             # misaligned source
+    assert g.gati_probe_launch_chain(None, 1, 1, 0, stream=0) == g.GATI_ERR_INVALID_ARG
+    assert g.gati_probe_launch_chain(16, 1, 0, 0, stream=0) == g.GATI_ERR_INVALID_ARG      # no workgroups
+    assert g.gati_probe_launch_chain(16, 1, 1, 9, stream=0) == g.GATI_ERR_INVALID_ARG      # more dependent loads than offered
+    assert g.gati_probe_launch_chain(16, 0, 1, 0, stream=0) == g.GATI_OK                   # an empty chain launches nothing
 
 
 def test_trainer_calls_reject_bad_arguments_on_the_host():
