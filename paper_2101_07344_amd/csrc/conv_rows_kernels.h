@@ -165,6 +165,19 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
     unsigned char* const spare = rows_lds + D * kRowsSlotVec * 16;
     const uint32_t off_full = lane * 16;
     const uint32_t off_tail = min(lane, nva - 1 - (ca - 1) * 64) * 16;
+    // This wave's QF loads of a fill, the same for every fill: which KB, from the map or the fragments
+    int l_src[QF], l_dst[QF];
+    uint32_t l_off[QF];
+    bool l_w[QF], l_live[QF];
+#pragma unroll
+    for (int q = 0; q < QF; ++q) {
+        const int c = min(wave + NW * q, chunks - 1);        // wave-uniform
+        l_w[q] = c >= ca;
+        l_src[q] = (l_w[q] ? c - ca : c) * 1024;
+        l_dst[q] = c * 1024;
+        l_live[q] = wave + NW * q < chunks;
+        l_off[q] = (!l_w[q] && c == ca - 1) ? off_tail : off_full;
+    }
     // Fill `f` into slot `slot`.  Always QF loads per wave: KBs past the fill, and whole fills past the last
     // one, re-read valid vectors into the spare KB.
     auto issue = [&](int f, int slot) {
@@ -174,13 +187,8 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
         const unsigned char* fw = wbase + (long)fc * cw * 1024;
         unsigned char* sb = rows_lds + slot * (kRowsSlotVec * 16);
 #pragma unroll
-        for (int q = 0; q < QF; ++q) {
-            const int c = min(wave + NW * q, chunks - 1);    // wave-uniform
-            const bool is_w = c >= ca;
-            const unsigned char* src = is_w ? fw + (c - ca) * 1024 : fa + c * 1024;
-            unsigned char* dst = (live && wave + NW * q < chunks) ? sb + c * 1024 : spare;
-            lds_direct_load(src, (!is_w && c == ca - 1) ? off_tail : off_full, dst);
-        }
+        for (int q = 0; q < QF; ++q)
+            lds_direct_load((l_w[q] ? fw : fa) + l_src[q], l_off[q], (live && l_live[q]) ? sb + l_dst[q] : spare);
     };
 
     f32x16_t acc[TPW];
@@ -189,20 +197,15 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
 
-    const int rounds = G / a.ws / UG;                        // rounds of UG groups per wave and fill: whole by plan
-#pragma unroll
-    for (int d = 0; d < D - 1; ++d) issue(fill0 + d, d);
-    for (int f = fill0, it = 0; f < fill1; ++f, ++it) {
-        // this wave's loads of fill f have landed once at most the (D-2)*QF younger ones are outstanding; after
-        // the barrier so have everyone's, and everyone is done with the slot that the next fill goes to
-        wait_loads<(D - 2) * QF>();
-        __syncthreads();
-        issue(f + D - 1, (it + D - 1) % D);
-        if (wp >= a.ws) continue;                            // a wave without a channel part (few channels): loads only
-        const unsigned char* slot = rows_lds + (it % D) * (kRowsSlotVec * 16);
+    // The multiplication is one stream of rounds (UG channel groups x TPW tiles) over all fills: every fragment is
+    // read one round ahead of its MFMA, the last round of a fill reads the first groups of the NEXT fill.  Before
+    // that round the wave makes sure the next fill has landed (its own loads by count, everyone's by the
+    // barrier); past the barrier nobody reads the current slot any more, so the fill D ahead goes there.
+    const int rounds = G / a.ws / UG;                        // rounds per wave and fill: whole by plan
+    const bool active = wp < a.ws;                           // a wave without a channel part (few channels) only loads
+    frag_t bf[UG][TPW], af[UG];
+    auto preload = [&](const unsigned char* slot) {
         const unsigned char* const alds = slot + ca * 1024 + (pi * 64 + lane) * 16;
-        // every fragment is read one round (UG groups x TPW tiles) ahead of its MFMA; the last round only multiplies
-        frag_t bf[UG][TPW], af[UG];
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             const int cg = wp + u * a.ws;
@@ -210,24 +213,39 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
 #pragma unroll
             for (int t = 0; t < TPW; ++t) bf[u][t] = bfrag(slot, t, cg);
         }
-        for (int rd = 1; rd < rounds; ++rd) {
+    };
+    // multiply what the ring holds, refill it with round `rd` of the fill in `slot`
+    auto round = [&](const unsigned char* slot, int rd) {
+        const unsigned char* const alds = slot + ca * 1024 + (pi * 64 + lane) * 16;
 #pragma unroll
-            for (int u = 0; u < UG; ++u) {
-                const int cgn = wp + (rd * UG + u) * a.ws;
-                const frag_t an = *reinterpret_cast<const frag_t*>(alds + cgn * a.s * 1024);
-                __builtin_amdgcn_sched_barrier(0);           // keep this read ahead of the MFMAs that hide it
+        for (int u = 0; u < UG; ++u) {
+            const int cgn = wp + (rd * UG + u) * a.ws;
+            const frag_t an = *reinterpret_cast<const frag_t*>(alds + cgn * a.s * 1024);
+            __builtin_amdgcn_sched_barrier(0);               // keep this read ahead of the MFMAs that hide it
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    acc[t] = Mma<true>::mma(af[u], bf[u][t], acc[t]);
-                    bf[u][t] = bfrag(slot, t, cgn);
-                }
-                af[u] = an;
+            for (int t = 0; t < TPW; ++t) {
+                acc[t] = Mma<true>::mma(af[u], bf[u][t], acc[t]);
+                bf[u][t] = bfrag(slot, t, cgn);
             }
+            af[u] = an;
         }
+    };
 #pragma unroll
-        for (int u = 0; u < UG; ++u)
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) acc[t] = Mma<true>::mma(af[u], bf[u][t], acc[t]);
+    for (int d = 0; d < D; ++d) issue(fill0 + d, d);
+    wait_loads<(D - 1) * QF>();                              // the first fill
+    __syncthreads();
+    if (active) preload(rows_lds);
+    int cur = 0;
+    for (int f = fill0; f < fill1; ++f) {
+        const unsigned char* slot = rows_lds + cur * (kRowsSlotVec * 16);
+        if (active)
+            for (int rd = 1; rd < rounds; ++rd) round(slot, rd);
+        wait_loads<(D - 2) * QF>();                          // fill f+1: D-2 younger fills are in flight behind it
+        __syncthreads();
+        issue(f + D, cur);
+        cur = cur + 1 == D ? 0 : cur + 1;
+        // past the last fill this reads a slot that holds an older fill: finite data, multiplied by nobody
+        if (active) round(rows_lds + cur * (kRowsSlotVec * 16), 0);
     }
     wait_loads<0>();                                         // the surplus loads of the last rounds
     __syncthreads();
