@@ -168,8 +168,18 @@ __device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, co
 // !HIDDEN: epilogue bias -> logits (optional store) and the tile's softmax/argmax summary.
 // U: k-steps per pipeline stage (two stages in registers): 4 when a wave's share of the reduction is
 // at most 8 k-steps (everything is in flight at once with half the registers), else 8.
-template <bool BF16, int NT, bool HIDDEN, int U>
+// ASTAGE (bf16, NT = 2, Kdim a multiple of 256): long reductions -- the output layer over thousands of
+// features.  A lane's A fragment is 16 bytes of ITS row, so a wave-wide fragment load touches 32
+// different 128-byte lines and uses 32 bytes of each: the texture path, which takes a line per clock,
+// is then busy 4x longer on A than the bytes need and the kernel is bound by it (counters at
+// F = 4096: waves stalled on issue 70 % of the time, 7.5 M line accesses per launch).  Here every wave
+// loads its A block of 32 rows x 128 bytes (4 k-steps) with whole lines -- 8 lanes per row, 4 loads --
+// parks it in its own 4 KB of LDS (16-byte chunks of a row rotated by the row number, so neither the
+// stores nor the fragment reads conflict) and reads the fragments back.  The region is the wave's
+// slice of `red`, which it writes only after its last fragment read: no barrier is involved.
+template <bool BF16, int NT, bool HIDDEN, int U, bool ASTAGE = false>
 __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
+    static_assert(!ASTAGE || (BF16 && NT == 2 && !HIDDEN), "staged A: bf16 output layer with 64-column tiles");
     using M = Mma<BF16>;
     using frag_t = typename M::frag_t;
     constexpr int kStep = M::kStep, kLane = M::kLane;
@@ -211,7 +221,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     const int last = ksw - 1;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-        if (half == 0 || U < ksw) {
+        if (!ASTAGE && (half == 0 || U < ksw)) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int k = min(half * U + u, last);
@@ -232,6 +242,59 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     if constexpr (HIDDEN) {
         if (a.p32) selector_pool_part(a, row0, a.n_dev, a.n_max, n_tiles_x);   // null: this launch has no selector half
     }
+    if constexpr (ASTAGE) {
+        constexpr int PD = 3;                               // blocks in flight in registers (A and W)
+        const int NB = ksw >> 2;                            // blocks of 4 k-steps = one 128-byte line per row
+        unsigned char* const my = reinterpret_cast<unsigned char*>(&red[wave][0][0]);   // 8 KB: two blocks
+        const char* const abase = static_cast<const char*>(a.A) + ((long)row0 * a.Kdim + (long)ks0 * kStep) * 2;
+        int aoff[4], rd[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 8 * i + (lane >> 3);
+            aoff[i] = row * a.Kdim * 2 + (((lane & 7) - row) & 7) * 16;     // load i, lane -> (row, chunk): slot 64 i + lane
+            rd[i] = (r * 8 + ((2 * i + kb + r) & 7)) * 16;                  // k-step i of the block, this lane's fragment
+        }
+        auto gload_a = [&](u32x4_t (&g)[4], int b) {
+            const long o = (long)min(b, NB - 1) * 128;      // past the end: the last block again, never multiplied
+#pragma unroll
+            for (int i = 0; i < 4; ++i) g[i] = *reinterpret_cast<const u32x4_t*>(abase + aoff[i] + o);
+        };
+        auto gload_w = [&](frag_t (&w)[NT][4], int b) {
+            const long k0 = (long)min(b, NB - 1) * 4;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[t][j] = bp[t * b_tile + (k0 + j) * 64];
+        };
+        auto lstore = [&](int buf, const u32x4_t (&g)[4]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4_t*>(my + buf * 4096 + (64 * i + lane) * 16) = g[i];
+        };
+        u32x4_t ga[PD][4];
+        frag_t bw[PD][NT][4];
+#pragma unroll
+        for (int p = 0; p < PD; ++p) { gload_a(ga[p], p); gload_w(bw[p], p); }
+        lstore(0, ga[0]);
+        gload_a(ga[0], PD);
+        for (int b0 = 0; b0 < NB; b0 += PD) {
+#pragma unroll
+            for (int p = 0; p < PD; ++p) {
+                const int b = b0 + p;
+                if (b < NB) {                               // uniform
+                    frag_t fa[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) fa[j] = *reinterpret_cast<const frag_t*>(my + (b & 1) * 4096 + rd[j]);
+                    lstore((b + 1) & 1, ga[(p + 1) % PD]);  // block b+1, multiplied in the next iteration
+                    gload_a(ga[(p + 1) % PD], b + 1 + PD);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) acc[t] = M::mma(fa[j], bw[p][t][j], acc[t]);
+                    gload_w(bw[p], b + PD);
+                }
+            }
+        }
+    } else
     for (int ks = 0; ks < ksw; ks += 2 * U) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
