@@ -132,13 +132,13 @@ __device__ __forceinline__ bool finish_row(const TileStat* st, int n_tiles, floa
 // waves: a wave's 64 lanes stride over one row and add up in a fixed order (lane partials ->
 // wave butterfly).  Nothing is shared between waves, so there is no barrier; rows up to the
 // padded row count exist in p32, so the loads do not wait for the device-side row count.
-__device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, const int32_t* n_dev, int n_max, int n_tiles_x) {
+__device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, int tile_x, const int32_t* n_dev, int n_max, int n_tiles_x) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rpb = (32 + n_tiles_x - 1) / n_tiles_x;   // rows per block
     const f32x4_t* wv = reinterpret_cast<const f32x4_t*>(a.ws_pool);
     const int nvec = a.ldp / 4;
     for (int q = wave; q < rpb; q += 4) {
-        const int rr = blockIdx.x * rpb + q;            // wave-uniform
+        const int rr = tile_x * rpb + q;                // wave-uniform
         if (rr >= 32) break;
         const f32x4_t* pr = reinterpret_cast<const f32x4_t*>(a.p32 + (long)(row0 + rr) * a.ldp);
         float s = 0.f;
@@ -185,7 +185,22 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     constexpr int kStep = M::kStep, kLane = M::kLane;
     __shared__ float red[4][NT * 16][64];      // split-K partial tiles, [wave][tile*16 + j][lane]
 
-    const int row0 = blockIdx.y * 32;
+    // tile of this workgroup.  The long-reduction instance deals the tiles out so that one XCD (consecutive
+    // workgroup ids go round the 8 XCDs) owns a block of 8 row tiles x (column tiles / 4): its L2 then holds
+    // 8 activation tiles and a quarter of the weights instead of all activation tiles and an eighth of the weights
+    int bx = blockIdx.x, by = blockIdx.y;
+    if constexpr (ASTAGE) {
+        if ((gridDim.x & 3) == 0 && (gridDim.y & 15) == 0) {
+            const int lin = blockIdx.y * gridDim.x + blockIdx.x;
+            const int xcd = lin & 7, j = lin >> 3;                       // j: 0 .. gx*gy/8 - 1 within the XCD
+            const int cpx = gridDim.x >> 2;                              // column tiles per XCD
+            const int per = 8 * cpx;                                     // tiles of one XCD per block of 16 row tiles
+            const int blk = j / per, jj = j - blk * per;
+            by = blk * 16 + (xcd & 1) * 8 + (jj & 7);
+            bx = (xcd >> 1) * cpx + (jj >> 3);
+        }
+    }
+    const int row0 = by * 32;
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int r = lane & 31, kb = lane >> 5;
@@ -195,7 +210,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     const int KS = a.Kdim / kStep;
     const int ksw = KS >> 2;                    // k-steps per wave
     const int ks0 = wave * ksw;
-    const int nt0 = blockIdx.x * NT;
+    const int nt0 = bx * NT;
     // A advances kStep elements = 2 fragments of 16 bytes per k-step
     const frag_t* ap = reinterpret_cast<const frag_t*>(
         static_cast<const char*>(a.A) + ((long)(row0 + r) * a.Kdim + (long)ks0 * kStep + kb * kLane) * (BF16 ? 2 : 4));
@@ -240,7 +255,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
         ep_ws[q] = HIDDEN ? 0.f : a.ws_prob[col];
     }
     if constexpr (HIDDEN) {
-        if (a.p32) selector_pool_part(a, row0, a.n_dev, a.n_max, n_tiles_x);   // null: this launch has no selector half
+        if (a.p32) selector_pool_part(a, row0, bx, a.n_dev, a.n_max, n_tiles_x);   // null: this launch has no selector half
     }
     if constexpr (ASTAGE) {
         constexpr int PD = 3;                               // blocks in flight in registers (A and W)
@@ -396,9 +411,9 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
         if (sub == 0) {
             TileStat s;
             s.max = bm; s.sum = ps; s.wsum = pt; s.arg = bi;
-            a.stats[(long)(row0 + lr) * n_tiles_x + blockIdx.x] = s;
+            a.stats[(long)(row0 + lr) * n_tiles_x + bx] = s;
         }
-        if (a.p32) selector_pool_part(a, row0, a.n_dev, a.n_max, n_tiles_x);   // predictors without a hidden-layer kernel
+        if (a.p32) selector_pool_part(a, row0, bx, a.n_dev, a.n_max, n_tiles_x);   // predictors without a hidden-layer kernel
     }
 }
 
