@@ -318,6 +318,19 @@ gati_status_t gati_trainer_get_weights(gati_trainer_t *trainer, float *W1, float
  * [selector_hidden]; GATI_ERR_UNSUPPORTED for a trainer with the linear selector. */
 gati_status_t gati_trainer_get_hidden_selector(gati_trainer_t *trainer, float *Ws, float *cs, float *vs);
 
+/* A second handle on the same cache for concurrent use: the fork shares the weights, tables and selector
+ * scalars of `cache` (Section 5: one deployed predictor / selector per layer) and has a workspace of its
+ * own, so lookups through the fork may overlap in time with lookups through `cache` or through other
+ * forks, e.g. on another stream - calls through ONE handle still may not overlap, since they share that
+ * handle's workspace.  Weights and the selector change only through the cache that was created
+ * (gati_cache_set_weights, gati_cache_set_selector and gati_cache_load_trainer return
+ * GATI_ERR_INVALID_ARG for a fork) and are then seen by every fork, under the ordering rules of those
+ * calls.  Allocates the workspace (GATI_ERR_OOM if that fails) and waits for the device once; must be
+ * called with the cache's device current.  A fork is destroyed with gati_cache_destroy; destroying a cache
+ * that still has forks returns GATI_ERR_INVALID_ARG and destroys nothing.  Forking and destroying handles of
+ * one cache from several host threads at once is not supported. */
+gati_status_t gati_cache_fork(gati_cache_t *cache, gati_cache_t **fork);
+
 /* Put a trainer's current weights into a serving cache without leaving the device (Section 5: the
  * retrained predictor and selector replace the old ones while serving goes on).  Kernels on `stream`
  * repack the trainer's fp32 master weights into the cache's own layouts (bf16 caches round to nearest

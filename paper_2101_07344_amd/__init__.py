@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     gati_cache_create, gati_cache_destroy, gati_cache_lookup, gati_cache_lookup_compact, gati_cache_pool,
     gati_compact_misses, gati_compact_misses_static, gati_cache_set_selector, gati_cache_set_weights, gati_status_string, gati_cache_pool_variant,
     gati_trainer_create, gati_trainer_destroy, gati_trainer_step, gati_trainer_get_weights,
-    gati_trainer_get_hidden_selector, gati_cache_load_trainer, gati_probe_stream_read, gati_probe_copy, gati_probe_launch_chain,
+    gati_trainer_get_hidden_selector, gati_cache_load_trainer, gati_cache_fork, gati_probe_stream_read, gati_probe_copy, gati_probe_launch_chain,
 )

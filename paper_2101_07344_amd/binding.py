@@ -22,7 +22,7 @@ exported_symbols = (
     "gati_cache_create", "gati_cache_destroy", "gati_cache_set_weights", "gati_cache_set_selector", "gati_cache_lookup",
     "gati_cache_lookup_compact", "gati_cache_pool", "gati_compact_misses", "gati_compact_misses_static", "gati_status_string", "gati_cache_pool_variant",
     "gati_trainer_create", "gati_trainer_destroy", "gati_trainer_step", "gati_trainer_get_weights",
-    "gati_trainer_get_hidden_selector", "gati_cache_load_trainer",
+    "gati_trainer_get_hidden_selector", "gati_cache_load_trainer", "gati_cache_fork",
     "gati_probe_launch_chain", "gati_probe_stream_read", "gati_probe_copy",
 )
 
@@ -105,6 +105,8 @@ def load_library():
     lib.gati_trainer_get_weights.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.gati_trainer_get_hidden_selector.restype = C.c_int
     lib.gati_trainer_get_hidden_selector.argtypes = [vp, vp, vp, vp]
+    lib.gati_cache_fork.restype = C.c_int
+    lib.gati_cache_fork.argtypes = [vp, C.POINTER(vp)]
     lib.gati_cache_load_trainer.restype = C.c_int
     lib.gati_cache_load_trainer.argtypes = [vp, vp, vp]
     lib.gati_probe_launch_chain.restype = C.c_int
@@ -281,6 +283,15 @@ class Cache:
         w, _keep = self._marshal(weights)
         _check(gati_cache_set_weights(self.handle, w), "gati_cache_set_weights")
 
+    def fork(self) -> "Cache":
+        """A handle with its own workspace on the same weights, for lookups that overlap in time with this one's."""
+        import copy
+        st, handle = gati_cache_fork(self.handle)
+        _check(st, "gati_cache_fork")
+        other = copy.copy(self)
+        other.handle = handle
+        return other
+
     def load_trainer(self, trainer: "Trainer", stream=None):
         _check(gati_cache_load_trainer(self.handle, trainer.handle, stream), "gati_cache_load_trainer")
 
@@ -343,6 +354,12 @@ def gati_trainer_get_weights(handle, W1, b1, W2, b2, ws, bs) -> int:
     """Host numpy fp32 arrays (bs: a 1-element array) filled in place."""
     a = lambda x: x.ctypes.data if x is not None else None
     return load_library().gati_trainer_get_weights(handle, a(W1), a(b1), a(W2), a(b2), a(ws), a(bs))
+
+
+def gati_cache_fork(cache_handle):
+    out = C.c_void_p()
+    st = load_library().gati_cache_fork(cache_handle, C.byref(out))
+    return st, out.value
 
 
 def gati_cache_load_trainer(cache_handle, trainer_handle, stream=None) -> int:

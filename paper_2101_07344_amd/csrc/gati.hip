@@ -100,17 +100,26 @@ struct gati_cache {
     // tiles per wave, channels per LDS fill, pixel lanes per input row, waves per tile set / channel part
     int rows_slot = 0, rows_tpw = 0, rows_cc = 0, rows_xw_log2 = 0, rows_rs_log2 = 0, rows_nwt_log2 = 0, rows_ws = 1, rows_fills_per = 0;
     float* W1plain = nullptr; // [Co, C, k, k] fp32 (rounded to bf16 values in bf16 caches)
+    // gati_cache_fork: a fork shares its owner's weights, tables and selector scalars and has a workspace of its own
+    gati_cache* owner = nullptr;
+    int forks = 0;            // live forks of an owner
 };
 
 namespace {
 
 void free_all(gati_cache* c) {
-    void* ptrs[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->p, c->p16, c->h, c->u_pool, c->stats,
-                    c->flat_partial, c->Ws, c->cs, c->vs, c->sel_in, c->sel_g, c->zbuf, c->W1plain, c->conv_partial,
-                    c->ad_win};
-    for (void* q : ptrs)
+    void* workspace[] = {c->p, c->p16, c->h, c->u_pool, c->stats, c->flat_partial, c->sel_in, c->sel_g, c->zbuf,
+                         c->conv_partial};
+    for (void* q : workspace)
+        if (q) (void)hipFree(q);
+    if (c->owner) return;      // weights and tables belong to the owner
+    void* weights[] = {c->W1, c->W2, c->b1, c->b2, c->ws_pool, c->ws_prob, c->Ws, c->cs, c->vs, c->W1plain, c->ad_win};
+    for (void* q : weights)
         if (q) (void)hipFree(q);
 }
+
+// where the selector scalars of a cache live: in the cache that owns the weights
+inline const gati_cache* weights_of(const gati_cache* c) { return c->owner ? c->owner : c; }
 
 // Device copy of a host array (src == NULL: zeros).  *dst == NULL allocates; otherwise the existing
 // allocation of the same size is overwritten (weight replacement).
@@ -768,7 +777,7 @@ output_layer_launched:
         if (e != hipSuccess) return e;
         fa.sel_g = c->sel_g; fa.sel_vs = c->vs; fa.sel_hs = c->Hs; fa.ldg = c->Hsp; fa.g_bf16 = BF16 ? 1 : 0;
     }
-    fa.stats = c->stats; fa.n_tiles = n_tiles; fa.u_pool = c->u_pool; fa.bs = c->bs; fa.tau = c->tau;
+    fa.stats = c->stats; fa.n_tiles = n_tiles; fa.u_pool = c->u_pool; fa.bs = weights_of(c)->bs; fa.tau = weights_of(c)->tau;
     fa.softmax_only = c->desc.selector == GATI_SEL_SOFTMAX ? 1 : 0;
     fa.n_max = n_max; fa.n_dev = n_dev; fa.pred_class = pred_class; fa.confidence = confidence; fa.hit = hit;
     fa.ids_in = ids_in; fa.ids_out = ids_out; fa.n_miss = n_miss;
@@ -881,6 +890,26 @@ gati_status_t upload_weights(gati_cache* c, const gati_cache_weights_t* w) {
     } catch (const std::bad_alloc&) {
         st = GATI_ERR_OOM;
     }
+    return st;
+}
+
+// Workspace of a cache (or of a fork), zeroed once: the padding columns of p are never written and must read as 0.
+gati_status_t alloc_workspace(gati_cache* c) {
+    const gati_cache_desc_t* desc = &c->desc;
+    const bool sel_hidden = desc->selector == GATI_SEL_HIDDEN;
+    gati_status_t st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
+    if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);
+    if (st == GATI_OK && !c->pool_fc) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
+    if (st == GATI_OK && c->flat_fc && !c->flat_generic)
+        st = upload((void**)&c->flat_partial, nullptr, (size_t)c->flat_splits * c->rows_b * c->Hb * 4);
+    if (st == GATI_OK && c->conv_fc && c->conv_ksplit > 1)
+        st = upload((void**)&c->conv_partial, nullptr, (size_t)c->conv_ksplit * desc->max_rows * c->Cp * 4);
+    if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
+    if (st == GATI_OK && sel_hidden) st = upload(&c->sel_in, nullptr, (size_t)c->rows_pad * c->Sin * c->elem);
+    if (st == GATI_OK && sel_hidden) st = upload(&c->sel_g, nullptr, (size_t)c->rows_pad * c->Hsp * c->elem);
+    if (st == GATI_OK && sel_hidden) st = upload((void**)&c->zbuf, nullptr, (size_t)desc->max_rows * desc->K * 4);
+    if (st == GATI_OK)
+        st = upload((void**)&c->stats, nullptr, (size_t)c->rows_pad * (c->Kp / (32 * c->fc2_nt)) * sizeof(TileStat));
     return st;
 }
 
@@ -1064,20 +1093,7 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
             st = upload((void**)&c->ad_win, win.data(), win.size() * sizeof(AdaptiveWindow));
         } catch (const std::bad_alloc&) { st = GATI_ERR_OOM; }
     }
-    // workspace, zeroed once: the padding columns of p are never written and must read as 0
-    if (st == GATI_OK) st = upload((void**)&c->p, nullptr, (size_t)c->rows_pad * c->Cp * 4);
-    if (st == GATI_OK && c->bf16) st = upload(&c->p16, nullptr, (size_t)c->rows_pad * c->Cp * 2);
-    if (st == GATI_OK && !no_hidden_kernel) st = upload(&c->h, nullptr, (size_t)c->rows_pad * c->Hp * (c->bf16 ? 2 : 4));
-    if (st == GATI_OK && flat_fc && !c->flat_generic)
-        st = upload((void**)&c->flat_partial, nullptr, (size_t)c->flat_splits * c->rows_b * c->Hb * 4);
-    if (st == GATI_OK && conv_fc && c->conv_ksplit > 1)
-        st = upload((void**)&c->conv_partial, nullptr, (size_t)c->conv_ksplit * desc->max_rows * c->Cp * 4);
-    if (st == GATI_OK) st = upload((void**)&c->u_pool, nullptr, (size_t)c->rows_pad * 4);
-    if (st == GATI_OK && sel_hidden) st = upload(&c->sel_in, nullptr, (size_t)c->rows_pad * c->Sin * c->elem);
-    if (st == GATI_OK && sel_hidden) st = upload(&c->sel_g, nullptr, (size_t)c->rows_pad * c->Hsp * c->elem);
-    if (st == GATI_OK && sel_hidden) st = upload((void**)&c->zbuf, nullptr, (size_t)desc->max_rows * K * 4);
-    if (st == GATI_OK)
-        st = upload((void**)&c->stats, nullptr, (size_t)c->rows_pad * (c->Kp / (32 * c->fc2_nt)) * sizeof(TileStat));
+    if (st == GATI_OK) st = alloc_workspace(c);
     if (st == GATI_OK && hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); st = GATI_ERR_DEVICE; }
     if (st != GATI_OK) { free_all(c); delete c; return st; }
     *out = c;
@@ -1086,13 +1102,32 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
 
 gati_status_t gati_cache_destroy(gati_cache_t* c) {
     if (!c) return GATI_OK;
+    if (c->forks > 0) return GATI_ERR_INVALID_ARG;      // its forks still use the weights
+    if (c->owner) --c->owner->forks;
     free_all(c);
     delete c;
     return GATI_OK;
 }
 
+gati_status_t gati_cache_fork(gati_cache_t* src, gati_cache_t** out) {
+    if (!src || !out) return GATI_ERR_INVALID_ARG;
+    gati_cache* root = src->owner ? src->owner : src;
+    if (!on_cache_device(root)) return GATI_ERR_DEVICE;
+    gati_cache* c = new (std::nothrow) gati_cache(*root);   // plan, padded sizes and the owner's device pointers
+    if (!c) return GATI_ERR_OOM;
+    c->owner = root; c->forks = 0;
+    c->p = nullptr; c->p16 = nullptr; c->h = nullptr; c->u_pool = nullptr; c->stats = nullptr;
+    c->flat_partial = nullptr; c->sel_in = nullptr; c->sel_g = nullptr; c->zbuf = nullptr; c->conv_partial = nullptr;
+    gati_status_t st = alloc_workspace(c);
+    if (st == GATI_OK && hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); st = GATI_ERR_DEVICE; }
+    if (st != GATI_OK) { free_all(c); delete c; return st; }
+    ++root->forks;
+    *out = c;
+    return GATI_OK;
+}
+
 gati_status_t gati_cache_set_weights(gati_cache_t* c, const gati_cache_weights_t* w) {
-    if (!c || !w) return GATI_ERR_INVALID_ARG;
+    if (!c || !w || c->owner) return GATI_ERR_INVALID_ARG;       // weights change through the cache that owns them
     const bool pool_fc = c->desc.predictor == GATI_PRED_POOL_FC;
     const bool sel_hidden = c->desc.selector == GATI_SEL_HIDDEN;
     if (sel_hidden && (!w->Ws || !w->cs || !w->vs)) return GATI_ERR_INVALID_ARG;
@@ -1174,7 +1209,7 @@ hipError_t load_trainer_t(gati_cache* c, const TrainerView& v, hipStream_t st) {
 extern "C" {
 
 gati_status_t gati_cache_load_trainer(gati_cache_t* c, gati_trainer_t* t, void* stream) {
-    if (!c || !t) return GATI_ERR_INVALID_ARG;
+    if (!c || !t || c->owner) return GATI_ERR_INVALID_ARG;
     TrainerView v;
     trainer_view(t, &v);
     const gati_cache_desc_t& d = c->desc;
@@ -1213,7 +1248,7 @@ gati_status_t gati_cache_load_trainer(gati_cache_t* c, gati_trainer_t* t, void* 
 }
 
 gati_status_t gati_cache_set_selector(gati_cache_t* c, float bs, float threshold) {
-    if (!c || !(bs == bs) || !(threshold == threshold)) return GATI_ERR_INVALID_ARG;
+    if (!c || c->owner || !(bs == bs) || !(threshold == threshold)) return GATI_ERR_INVALID_ARG;
     c->bs = bs;
     c->tau = threshold;
     c->desc.threshold = threshold;

@@ -66,6 +66,7 @@ def test_calls_reject_null_handles_and_bad_counts_on_the_host():
     assert g.gati_compact_misses(None, None, None, 4, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_compact_misses(None, 16, 32, 4, None, 32, 16, stream=0) == g.GATI_ERR_INVALID_ARG   # in/out alias
     assert g.gati_cache_pool_variant(None) == "none"
+    assert g.gati_cache_fork(None)[0] == g.GATI_ERR_INVALID_ARG
     assert g.gati_compact_misses_static(None, 16, None, -1, None, 16, 16, stream=0) == g.GATI_ERR_INVALID_ARG
     assert g.gati_compact_misses_static(None, 16, None, g.GATI_COMPACT_STATIC_MAX_ROWS + 1, None, 16, 16, stream=0) \
         == g.GATI_ERR_UNSUPPORTED
