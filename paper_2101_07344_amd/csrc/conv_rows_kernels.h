@@ -16,8 +16,9 @@
 // register number (t = j / 4), a tap row's share is a group of four registers, and the shares
 // are added into the output rows through LDS at the end, in the fixed order of dy.
 //
-// One workgroup = one request (x one share of the channels when few requests would leave
-// CUs idle: the shares are summed in order by conv_reduce_kernel).  Its 8 waves split into row
+// One workgroup = one request -- or 2 on small maps, whose tiles then share every filter
+// fragment that is fetched -- (x one share of the channels when few requests would leave CUs
+// idle: the shares are summed in order by conv_reduce_kernel).  Its 8 waves split into row
 // parities (s = 2), then into tile sets, then -- small maps, fewer tiles than waves -- into channel
 // parts.  A fill is CC channels of the map followed by their filter fragments; fills go from global
 // memory straight into a ring of LDS slots (global_load_lds: lane l of a wave-wide load lands at
@@ -47,6 +48,7 @@ struct ConvRowsArgs {
     int C, S, in_h, in_w, k, s, oh, ow, Co;
     const void* Wr;            // [C / KC][s][64 lanes] x 16 bytes: A fragments, see pack_conv_rows
     const float* bias;
+    int rb, ntq;               // requests per workgroup (1 or 2); tiles per row parity of one request
     int CC;                    // channels per fill: CC*S*2 bytes are a multiple of 16
     int xw_log2;               // a tile gives every input row it holds 2^xw_log2 >= ow pixel lanes
     int rs_log2;               // the rows of one tile are 2^rs_log2 apart (among the rows of their parity)
@@ -90,9 +92,8 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
 
     const int n = active_rows(a.n_dev, a.n_max);
     const int split = blockIdx.x % a.ksplit;
-    const int i = blockIdx.x / a.ksplit;
-    if (i >= n) return;                                      // whole workgroup
-    const long r = a.row_index ? (long)a.row_index[i] : (long)i;
+    const int i0 = (blockIdx.x / a.ksplit) * a.rb;           // first of this workgroup's requests
+    if (i0 >= n) return;                                     // whole workgroup
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what follows from it stays in scalar registers
     const int nn = lane & 31, kb = lane >> 5;
@@ -107,25 +108,32 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
     const int x = min(xs, a.ow - 1);
     const int rpt_log2 = 5 - a.xw_log2;
 
+    const int nva = a.CC * a.S * 2 / 16;                     // vectors of one request's part of a fill
+    const int ca = (nva + 63) >> 6;                          // ... in whole KB
     int iy[TPW];                                             // the lane's input row per tile; past the map: unused
+    int tq[TPW];                                             // the tile's request among the workgroup's
     int boff[TPW][SLOT == 8 ? 1 : 2];                        // LDS byte offset of the lane's fragment in channel group 0
     int bsh[TPW][SLOT == 8 ? 1 : 2];                         // SLOT 4: 16 when the fragment starts on an odd element
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
         // tile tau holds the rows rho = block*RS*rpt + i + RS*j (block = tau / RS, i = tau % RS, j < rpt): the
         // rows of a tile are RS apart, which the plan picks so that they fall on different LDS banks
-        const int tau = wt + (t << a.nwt_log2);
+        const int tall = wt + (t << a.nwt_log2);             // tile among those of all the workgroup's requests
+        const int q = min(tall / a.ntq, a.rb - 1);
+        const int tau = tall - q * a.ntq;                    // a surplus tile (past the last request's) lands past the map
         const int rho = ((tau >> a.rs_log2) << (a.rs_log2 + rpt_log2)) + (tau & ((1 << a.rs_log2) - 1)) + (jrow << a.rs_log2);
-        iy[t] = pi + a.s * rho;
-        const int e0 = min(iy[t], a.in_h - 1) * a.in_w + a.s * x;
+        tq[t] = q;
+        iy[t] = i0 + q < n ? pi + a.s * rho : a.in_h;        // a request past n: every row "past the map"
+        const int e0 = min(pi + a.s * rho, a.in_h - 1) * a.in_w + a.s * x;
+        const int part = q * ca * 1024;                      // the request's part of the fill
         if constexpr (SLOT == 8) {
-            boff[t][0] = (kb * a.S + e0) * 2;                // even element by plan: 4-byte aligned
+            boff[t][0] = part + (kb * a.S + e0) * 2;         // even element by plan: 4-byte aligned
             bsh[t][0] = 0;
         } else {
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
                 const int e = (2 * kb + g) * a.S + e0;
-                boff[t][g] = (e >> 1) * 4;
+                boff[t][g] = part + (e >> 1) * 4;
                 bsh[t][g] = (e & 1) * 16;
             }
         }
@@ -149,46 +157,48 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
         return __builtin_bit_cast(frag_t, w);
     };
 
-    // One fill: CC channels of the request's map (nva vectors, contiguous in memory), padded to whole KB, then
-    // their A fragments (whole KB).  A wave-wide load moves one KB, so every load has one source: the map or
-    // the fragments; only the map's last KB may be partial -- its surplus lanes repeat the last vector (the pad
-    // they fill is read by the last rows' fragments past the window, against zero weights).
-    const int nva = a.CC * a.S * 2 / 16;
-    const int ca = (nva + 63) >> 6;                          // KB of map
+    // One fill: per request CC channels of its map (nva vectors, contiguous in memory, padded to whole KB), then
+    // the channels' A fragments (whole KB).  A wave-wide load moves one KB, so every load has one source: one
+    // request's map or the fragments; only a map part's last KB may be partial -- its surplus lanes repeat the
+    // last vector (the pad they fill is read by the last rows' fragments past the window, against zero weights).
     const int G = a.CC / KC;
     const int cw = G * a.s;                                  // KB of fragments
-    const int chunks = ca + cw;                              // <= kRowsSlotVec / 64 by plan
+    const int cm = a.rb * ca;                                // KB of map
+    const int chunks = cm + cw;                              // <= kRowsSlotVec / 64 by plan
     const int fill0 = split * a.fills_per_split;
     const int fill1 = min(a.C / a.CC, fill0 + a.fills_per_split);
-    const unsigned char* abase = static_cast<const unsigned char*>(a.act) + r * (long)a.C * a.S * 2;
-    const unsigned char* wbase = static_cast<const unsigned char*>(a.Wr);
     unsigned char* const spare = rows_lds + D * kRowsSlotVec * 16;
     const uint32_t off_full = lane * 16;
     const uint32_t off_tail = min(lane, nva - 1 - (ca - 1) * 64) * 16;
-    // This wave's QF loads of a fill, the same for every fill: which KB, from the map or the fragments
-    int l_src[QF], l_dst[QF];
+    // This wave's QF loads of a fill, the same for every fill: which KB, of which request's map or of the
+    // fragments, as a base address and a step from one fill to the next
+    const unsigned char* l_base[QF];
+    int l_step[QF], l_dst[QF];
     uint32_t l_off[QF];
-    bool l_w[QF], l_live[QF];
+    bool l_live[QF];
 #pragma unroll
     for (int q = 0; q < QF; ++q) {
         const int c = min(wave + NW * q, chunks - 1);        // wave-uniform
-        l_w[q] = c >= ca;
-        l_src[q] = (l_w[q] ? c - ca : c) * 1024;
+        const bool is_w = c >= cm;
+        const int part = min(c / ca, a.rb - 1), cq = c - part * ca;
+        const int iq = min(i0 + part, n - 1);                // a request past n: the last one again, computed and dropped
+        const long row = a.row_index ? (long)a.row_index[iq] : (long)iq;
+        l_base[q] = is_w ? static_cast<const unsigned char*>(a.Wr) + (long)(c - cm) * 1024
+                         : static_cast<const unsigned char*>(a.act) + row * a.C * a.S * 2 + (long)cq * 1024;
+        l_step[q] = is_w ? cw * 1024 : nva * 16;
         l_dst[q] = c * 1024;
         l_live[q] = wave + NW * q < chunks;
-        l_off[q] = (!l_w[q] && c == ca - 1) ? off_tail : off_full;
+        l_off[q] = (!is_w && cq == ca - 1) ? off_tail : off_full;
     }
     // Fill `f` into slot `slot`.  Always QF loads per wave: KBs past the fill, and whole fills past the last
     // one, re-read valid vectors into the spare KB.
     auto issue = [&](int f, int slot) {
         const bool live = f < fill1;
         const int fc = min(f, fill1 - 1);
-        const unsigned char* fa = abase + (long)fc * nva * 16;
-        const unsigned char* fw = wbase + (long)fc * cw * 1024;
         unsigned char* sb = rows_lds + slot * (kRowsSlotVec * 16);
 #pragma unroll
         for (int q = 0; q < QF; ++q)
-            lds_direct_load((l_w[q] ? fw : fa) + l_src[q], l_off[q], (live && l_live[q]) ? sb + l_dst[q] : spare);
+            lds_direct_load(l_base[q] + (long)fc * l_step[q], l_off[q], (live && l_live[q]) ? sb + l_dst[q] : spare);
     };
 
     f32x16_t acc[TPW];
@@ -205,7 +215,7 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
     const bool active = wp < a.ws;                           // a wave without a channel part (few channels) only loads
     frag_t bf[UG][TPW], af[UG];
     auto preload = [&](const unsigned char* slot) {
-        const unsigned char* const alds = slot + ca * 1024 + (pi * 64 + lane) * 16;
+        const unsigned char* const alds = slot + cm * 1024 + (pi * 64 + lane) * 16;
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             const int cg = wp + u * a.ws;
@@ -216,7 +226,7 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
     };
     // multiply what the ring holds, refill it with round `rd` of the fill in `slot`
     auto round = [&](const unsigned char* slot, int rd) {
-        const unsigned char* const alds = slot + ca * 1024 + (pi * 64 + lane) * 16;
+        const unsigned char* const alds = slot + cm * 1024 + (pi * 64 + lane) * 16;
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             const int cgn = wp + (rd * UG + u) * a.ws;
@@ -254,8 +264,8 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
     // (channel part, dy): within one round no two lanes meet in an output element
     const int OHW = a.oh * a.ow;
     const int F = a.Co * OHW;
-    float* const obuf = reinterpret_cast<float*>(rows_lds);
-    for (int idx = tid; idx < F; idx += NT) obuf[idx] = 0.f;
+    float* const obuf = reinterpret_cast<float*>(rows_lds);  // [request][filter][oy][ox]
+    for (int idx = tid; idx < a.rb * F; idx += NT) obuf[idx] = 0.f;
     for (int wpp = 0; wpp < a.ws; ++wpp) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -270,7 +280,7 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
 #pragma unroll
                         for (int jj = 0; jj < 4; ++jj) {
                             const int o = 4 * kb + jj;
-                            if (o < a.Co) obuf[o * OHW + y * a.ow + x] += acc[tl][4 * t + jj];
+                            if (o < a.Co) obuf[tq[tl] * F + o * OHW + y * a.ow + x] += acc[tl][4 * t + jj];
                         }
                     }
                 }
@@ -281,13 +291,15 @@ __global__ __launch_bounds__(kRowsThreads) void conv_rows_kernel(ConvRowsArgs a)
 
     // one split: bias and ReLU here; several: raw sums to this split's slab
     const bool last = a.ksplit == 1;
-    float* orow = (last ? a.out : a.partial + (long)split * a.n_max * a.out_stride) + (long)i * a.out_stride;
-    __bf16* orow16 = (last && a.out16) ? a.out16 + (long)i * a.out_stride : nullptr;
-    for (int idx = tid; idx < F; idx += NT) {
-        float v = obuf[idx];
-        if (last) v = fmaxf(v + a.bias[idx / OHW], 0.f);
-        orow[idx] = v;
-        if (orow16) orow16[idx] = (__bf16)v;
+    for (int q = 0; q < a.rb && i0 + q < n; ++q) {
+        float* orow = (last ? a.out : a.partial + (long)split * a.n_max * a.out_stride) + (long)(i0 + q) * a.out_stride;
+        __bf16* orow16 = (last && a.out16) ? a.out16 + (long)(i0 + q) * a.out_stride : nullptr;
+        for (int idx = tid; idx < F; idx += NT) {
+            float v = obuf[q * F + idx];
+            if (last) v = fmaxf(v + a.bias[idx / OHW], 0.f);
+            orow[idx] = v;
+            if (orow16) orow16[idx] = (__bf16)v;
+        }
     }
 }
 

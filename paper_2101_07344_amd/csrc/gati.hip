@@ -98,7 +98,7 @@ struct gati_cache {
     float* conv_partial = nullptr;   // [ksplit][max_rows][Cp] when ksplit > 1
     // plan of conv_rows_kernel (few filters, bf16, channel-major): taps per channel in the reduction index,
     // tiles per wave, channels per LDS fill, pixel lanes per input row, waves per tile set / channel part
-    int rows_slot = 0, rows_tpw = 0, rows_cc = 0, rows_xw_log2 = 0, rows_rs_log2 = 0, rows_nwt_log2 = 0, rows_ws = 1, rows_fills_per = 0;
+    int rows_slot = 0, rows_tpw = 0, rows_cc = 0, rows_xw_log2 = 0, rows_rs_log2 = 0, rows_nwt_log2 = 0, rows_ws = 1, rows_fills_per = 0, rows_rb = 1, rows_ntq = 1;
     float* W1plain = nullptr; // [Co, C, k, k] fp32 (rounded to bf16 values in bf16 caches)
     // gati_cache_fork: a fork shares its owner's weights, tables and selector scalars and has a workspace of its own
     gati_cache* owner = nullptr;
@@ -170,40 +170,53 @@ bool plan_conv_rows(gati_cache* c) {
     }
     const int rs = 1 << rs_log2;
     const int ntc = (rows_c + rs * rpt - 1) / (rs * rpt) * rs;   // tiles per parity
-    int nwt_log2 = 0;
-    while ((2 << nwt_log2) <= std::min(nwc, ntc)) ++nwt_log2;
-    const int nwt = 1 << nwt_log2;
-    const int need = (ntc + nwt - 1) / nwt;
-    int tpw = 0;
-    for (int cand : {1, 2, 4, kRowsMaxTiles})
-        if (cand >= need) { tpw = cand; break; }
-    if (!tpw || (slot == 4 && tpw > 4)) return false;       // 7 tiles of two-part fragments do not fit the registers
-    const int ug = tpw >= 4 ? 1 : (tpw == 2 ? 2 : 4);
-    // channels per fill: whole 16-byte vectors, whole rounds of every wave, a divisor of C; the map part
-    // (rounded up to whole KB) and the fill's filter fragments share one LDS slot.  Waves left over once
-    // the tiles are dealt out split the channels of a fill, as far as C has channels for them.
-    int ws = nwc / nwt, cc = 0;
-    for (; ws >= 1 && !cc; ws /= 2) {
-        int unit = KC * ws * ug;
-        while (((long)unit * d.S * 2) % 16 != 0) unit *= 2;
-        for (int cand = unit; cand <= d.C; cand += unit) {
-            if (d.C % cand != 0) continue;
-            if (round_up((int)((long)cand * d.S * 2), 1024) + (long)(cand / KC) * s * 1024 > (long)kRowsSlotVec * 16) break;
-            cc = cand;
+    // Requests per workgroup: the filter fragments of a fill are fetched once per workgroup (from L2, but through
+    // the same path as the map, which takes ~24 GB/s per CU whatever it carries), so on small maps, where they
+    // are a sizeable share of a fill, 2 requests share them (4 were measured too: slower on the 7 x 7 maps, where
+    // the gain should have been largest, 1475 -> 866 GB/s: the fills get too small).
+    const long map_bytes = (long)d.S * 2 * KC, frag_bytes = (long)s * 1024;      // per channel group and request
+    for (int rb : {2, 1}) {
+        if (rb == 2 && 4 * frag_bytes < map_bytes) continue;
+        if (rb > 1 && d.max_rows < 2 * rb) continue;
+        const int tiles = rb * ntc;                              // tiles per parity of one workgroup
+        int nwt_log2 = 0;
+        while ((2 << nwt_log2) <= std::min(nwc, tiles)) ++nwt_log2;
+        const int nwt = 1 << nwt_log2;
+        const int need = (tiles + nwt - 1) / nwt;
+        int tpw = 0;
+        for (int cand : {1, 2, 4, kRowsMaxTiles})
+            if (cand >= need) { tpw = cand; break; }
+        if (!tpw || (slot == 4 && tpw > 4)) continue;           // 7 tiles of two-part fragments do not fit the registers
+        const int ug = tpw >= 4 ? 1 : (tpw == 2 ? 2 : 4);
+        // channels per fill: whole 16-byte vectors, whole rounds of every wave, a divisor of C; the requests' map
+        // parts (each rounded up to whole KB) and the fill's filter fragments share one LDS slot.  Waves left over
+        // once the tiles are dealt out split the channels of a fill, as far as C has channels for them.
+        int ws = nwc / nwt, cc = 0;
+        for (; ws >= 1 && !cc; ws /= 2) {
+            int unit = KC * ws * ug;
+            while (((long)unit * d.S * 2) % 16 != 0) unit *= 2;
+            for (int cand = unit; cand <= d.C; cand += unit) {
+                if (d.C % cand != 0) continue;
+                if ((long)rb * round_up((int)((long)cand * d.S * 2), 1024) + (long)(cand / KC) * s * 1024 > (long)kRowsSlotVec * 16) break;
+                cc = cand;
+            }
+            if (cc) break;
         }
-        if (cc) break;
+        if (!cc || (long)rb * d.H * oh * ow * 4 > (long)kRowsDepth * kRowsSlotVec * 16) continue;
+        const int fills = d.C / cc;
+        // few workgroups: share the channels of a request among several (fixed at creation, so results do not
+        // depend on how many rows a call has)
+        const long groups = (d.max_rows + rb - 1) / rb;
+        int ks = (int)((2L * c->num_cu + groups - 1) / groups);
+        if (rb > 1) ks = 1;
+        ks = std::max(1, std::min(std::min(ks, fills), 16));
+        c->rows_fills_per = (fills + ks - 1) / ks;
+        c->conv_ksplit = (fills + c->rows_fills_per - 1) / c->rows_fills_per;
+        c->rows_slot = slot; c->rows_tpw = tpw; c->rows_cc = cc; c->rows_xw_log2 = xw; c->rows_rs_log2 = rs_log2;
+        c->rows_nwt_log2 = nwt_log2; c->rows_ws = ws; c->rows_rb = rb; c->rows_ntq = ntc;
+        return true;
     }
-    if (!cc) return false;
-    const int fills = d.C / cc;
-    // few requests: share the channels of a request among workgroups (fixed at creation, so results do not
-    // depend on how many rows a call has)
-    int ks = (int)((2L * c->num_cu + d.max_rows - 1) / d.max_rows);
-    ks = std::max(1, std::min(std::min(ks, fills), 16));
-    c->rows_fills_per = (fills + ks - 1) / ks;
-    c->conv_ksplit = (fills + c->rows_fills_per - 1) / c->rows_fills_per;
-    c->rows_slot = slot; c->rows_tpw = tpw; c->rows_cc = cc; c->rows_xw_log2 = xw; c->rows_rs_log2 = rs_log2;
-    c->rows_nwt_log2 = nwt_log2; c->rows_ws = ws;
-    return true;
+    return false;
 }
 
 typedef void (*conv_rows_fn)(ConvRowsArgs);
@@ -290,13 +303,14 @@ hipError_t launch_conv_t(const gati_cache* c, const void* act, const int32_t* ro
             ra.C = d.C; ra.S = d.S; ra.in_h = d.in_h; ra.in_w = d.in_w; ra.k = d.conv_k; ra.s = d.conv_s;
             ra.oh = c->conv_oh; ra.ow = c->conv_ow; ra.Co = d.H;
             ra.Wr = c->W1; ra.bias = c->b1; ra.CC = c->rows_cc; ra.xw_log2 = c->rows_xw_log2; ra.rs_log2 = c->rows_rs_log2;
+            ra.rb = c->rows_rb; ra.ntq = c->rows_ntq;
             ra.nwt_log2 = c->rows_nwt_log2; ra.ws = c->rows_ws;
             ra.out = out; ra.out16 = static_cast<__bf16*>(out16); ra.out_stride = out_stride;
             ra.ksplit = 1; ra.fills_per_split = d.C / c->rows_cc; ra.partial = nullptr;
             if (c->conv_ksplit > 1 && out_stride <= c->Cp) {
                 ra.ksplit = c->conv_ksplit; ra.fills_per_split = c->rows_fills_per; ra.partial = c->conv_partial;
             }
-            const int grid = n_max * ra.ksplit;
+            const int grid = (n_max + ra.rb - 1) / ra.rb * ra.ksplit;
             conv_rows_instance(c->rows_slot, c->rows_tpw)<<<grid, kRowsThreads, kRowsLdsBytes, st>>>(ra);
             if (ra.ksplit > 1) {
                 hipError_t e = hipGetLastError();
