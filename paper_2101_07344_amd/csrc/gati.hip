@@ -720,6 +720,8 @@ hipError_t launch_pool(const gati_cache* c, const void* act, const int32_t* row_
     return c->bf16 ? launch_pool_t<BF16Tag>(c, a, v, st) : launch_pool_t<F32Tag>(c, a, v, st);
 }
 
+constexpr int kCompactSingleMax = 4096;   // up to here one workgroup walks the list (one launch, no table)
+
 // FC1 (+ pooled half of the selector), FC2 (+ per-tile softmax summaries), then the per-row
 // finish; with ids_out the finish also compacts the misses.
 template <bool BF16>
@@ -795,6 +797,18 @@ output_layer_launched:
     fa.softmax_only = c->desc.selector == GATI_SEL_SOFTMAX ? 1 : 0;
     fa.n_max = n_max; fa.n_dev = n_dev; fa.pred_class = pred_class; fa.confidence = confidence; fa.hit = hit;
     fa.ids_in = ids_in; fa.ids_out = ids_out; fa.n_miss = n_miss;
+    if (n_max > 1024 && (!ids_out || n_max <= kCompactSingleMax)) {
+        // many rows: the per-row finish over several workgroups, then (with ids_out) the compaction by itself
+        fa.ids_out = nullptr;
+        finalize_kernel<<<(n_max + 255) / 256, 256, 0, st>>>(fa);
+        if (!ids_out) return hipGetLastError();
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        CompactArgs ca;
+        ca.hit = hit; ca.ids_in = ids_in; ca.n_dev = n_dev; ca.n_max = n_max; ca.ids_out = ids_out; ca.n_miss = n_miss;
+        compact_misses_kernel<<<1, 1024, 0, st>>>(ca);
+        return hipGetLastError();
+    }
     finalize_kernel<<<1, 1024, 0, st>>>(fa);
     return hipGetLastError();
 }
@@ -933,7 +947,6 @@ bool on_cache_device(const gati_cache* c) {
 }
 
 // ---- compaction of long lists: two launches that share a small table of per-span counts ----
-constexpr int kCompactSingleMax = 4096;   // up to here one workgroup walks the list (one launch, no table)
 constexpr int kMaxDevices = 64;
 std::mutex g_compact_mu;
 int32_t* g_compact_ws[kMaxDevices];       // gati_compact_misses: allocated on a device's first long list

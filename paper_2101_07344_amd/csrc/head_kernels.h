@@ -477,15 +477,19 @@ struct FinalizeArgs {
 
 // The finish: one workgroup of 1024 lanes, 1024 rows per step, turns each row's tile summaries
 // into class / confidence / hit; with ids_out it also compacts the misses in the same pass.
+// Batches beyond 1024 rows: launched without ids_out over several workgroups of 256 lanes (the rows
+// are independent), and compact_misses_kernel follows -- one launch more, but the summaries of
+// thousands of rows no longer pass through a single CU.
 // (Folding this into the output-layer kernel through last-arriver tickets was tried and lost:
 // device-scope fences between workgroups on different XCDs cost more than the extra launch.)
 __global__ __launch_bounds__(1024) void finalize_kernel(FinalizeArgs a) {
     __shared__ CompactState<16> st;
     const int n = active_rows(a.n_dev, a.n_max);   // read before n_miss is written (they may alias)
     const int tid = threadIdx.x;
-    const bool compact = a.ids_out != nullptr;
+    const bool compact = a.ids_out != nullptr;     // only ever launched as one workgroup of 1024 lanes
     if (tid == 0) st.carry = 0;
-    for (int base = 0; base < n; base += 1024) {
+    // without compaction the rows may be dealt out over several (smaller) workgroups
+    for (int base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
         const int i = base + tid;
         const bool live = i < n;
         bool is_hit = false;
