@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/gati.h"
+#include "train_conv_kernels.h"
 #include "train_kernels.h"
 #include "trainer_view.h"
 
@@ -34,7 +35,14 @@ struct gati_trainer {
     int device = 0, num_cu = 256;
     float *W1 = nullptr, *b1 = nullptr, *W2 = nullptr, *b2 = nullptr, *ws = nullptr, *bs = nullptr;
     float *h = nullptr, *z = nullptr, *q = nullptr, *dh = nullptr, *du = nullptr, *lp = nullptr, *ls = nullptr;
-    float* Xc = nullptr;       // Conv(k,s): gathered windows [max_rows*P][Cin]
+    float* W1t = nullptr;      // Conv(k,s) on the maps: the filters as [C][k*k][8], rewritten at the start of a step
+    float* Xc = nullptr;       // Conv(k,s) through the product over windows: gathered windows [max_rows*P][Cin]
+    // Conv(k,s) on the maps themselves (train_conv_kernels.h) where the shape allows; fixed at creation
+    struct ConvDirect {
+        bool on = false;
+        int f_wpc = 1, f_pp = 1, f_sg = 1, f_cpw = 1;    // forward: waves per channel, positions per lane, samples per workgroup, channels per wave and pass
+        int g_wpc = 1, g_ns = 1, g_splits = 1;           // filter gradient: waves per channel, samples per pass, sample splits wanted
+    } cd;
     float* part = nullptr;     // split-reduction slices of the largest product
     size_t part_floats = 0;
     // selector with a hidden layer: Hs units over input rows X = [features ; q] of stride Sx (Fsel + K rounded up
@@ -49,7 +57,7 @@ constexpr int kMaxSlices = 16;
 
 void free_all(gati_trainer* t) {
     void* ptrs[] = {t->W1, t->b1, t->W2, t->b2, t->ws, t->bs, t->h, t->z, t->q, t->dh, t->du, t->lp, t->ls, t->part,
-                    t->Ws, t->cs, t->vs, t->X, t->g, t->dg, t->G, t->Xc};
+                    t->Ws, t->cs, t->vs, t->X, t->g, t->dg, t->G, t->Xc, t->W1t};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -118,6 +126,38 @@ void permute_hidden_cols(const gati_trainer* t, const float* src, size_t lds, fl
     }
 }
 
+// Launch shapes of the direct Conv(k,s) kernels for maps of S values, P output positions, k x k taps, H filters.
+gati_trainer::ConvDirect plan_conv_direct(int C, int S, int P, int k, int H, int num_cu) {
+    gati_trainer::ConvDirect p;
+    if ((k != 3 && k != 5) || H > kConvTrainFilters || S > kConvTrainXFloats || P > kConvTrainMaxP || P < 1) return p;
+    const int kk2 = k * k;
+    // forward: the fewest lane slots that hold a map's positions; ties go to more channels per workgroup
+    long best = -1;
+    for (int wpc = 1; wpc <= 4; wpc *= 2) {
+        if ((4 / wpc) * S > kConvTrainXFloats) continue;
+        for (int pp = 1; pp <= 3; ++pp) {
+            const long slots = 64L * wpc * pp;
+            if (slots < P) continue;
+            const long cost = slots * 8 + wpc;
+            if (best < 0 || cost < best) { best = cost; p.f_wpc = wpc; p.f_pp = pp; }
+            break;
+        }
+    }
+    if (best < 0) return p;
+    const int fcw = 4 / p.f_wpc, slots = 64 * p.f_wpc * p.f_pp;
+    p.f_sg = std::max(1, std::min({slots / P, kConvTrainXFloats / (fcw * S), 64}));
+    p.f_cpw = std::max(1, std::min({kConvTrainXFloats / (p.f_sg * fcw * S), 16,
+                                    (C + fcw - 1) / fcw}));
+    // filter gradient: as many channels per workgroup as the staged maps allow, then samples per pass
+    const int gcw = 4 * S <= kConvTrainGXFloats ? 4 : 2 * S <= kConvTrainGXFloats ? 2 : 1;
+    p.g_wpc = 4 / gcw;
+    p.g_ns = std::max(1, std::min({kConvTrainGXFloats / (gcw * S), kConvTrainDFloats / (P * 8), 32}));
+    const int groups = (C + gcw - 1) / gcw;
+    p.g_splits = std::max(1, std::min((4 * num_cu + groups - 1) / groups, kMaxSlices));
+    p.on = true;
+    return p;
+}
+
 bool on_trainer_device(const gati_trainer* t) {
     int dev = -1;
     return hipGetDevice(&dev) == hipSuccess && dev == t->device;
@@ -127,7 +167,7 @@ bool on_trainer_device(const gati_trainer* t) {
 
 void gati::trainer_view(const gati_trainer* t, gati::TrainerView* v) {
     v->device = t->device; v->C = t->C; v->H = t->H; v->K = t->K; v->Cin = t->Cin; v->P = t->P; v->Hin = t->Hin;
-    v->Fsel = t->Fsel; v->conv = t->Xc != nullptr; v->sel_hidden_feat = t->sel_hidden_feat; v->no_selector = t->no_selector;
+    v->Fsel = t->Fsel; v->conv = t->conv_k > 0; v->sel_hidden_feat = t->sel_hidden_feat; v->no_selector = t->no_selector;
     v->Hs = t->Hs; v->Sx = t->Sx;
     v->W1 = t->W1; v->b1 = t->b1; v->W2 = t->W2; v->b2 = t->b2; v->ws = t->ws; v->bs = t->bs;
     v->Ws = t->Ws; v->cs = t->cs; v->vs = t->vs;
@@ -193,10 +233,26 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
     t->Hs = hidden ? desc->selector_hidden : 0;
     t->Sx = hidden ? (int)((F + K + 3) / 4 * 4) : 0;
     const size_t Hs = t->Hs, Sx = t->Sx;
-    const size_t mn[7] = {n * P * H, n * K, n * Hin, K * Hin, H * Cin, n * Hs, Hs * Sx};
+    if (conv_fc) {
+        t->cd = plan_conv_direct(desc->C, desc->S, oh * ow, desc->conv_k, desc->H, t->num_cu);
+        if (t->cd.on) {
+            const bool ok =
+                hipFuncSetAttribute(reinterpret_cast<const void*>(&train_conv_wgrad_kernel<3, 1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kConvTrainGradLds) == hipSuccess &&
+                hipFuncSetAttribute(reinterpret_cast<const void*>(&train_conv_wgrad_kernel<5, 2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kConvTrainGradLds) == hipSuccess;
+            if (!ok) { (void)hipGetLastError(); delete t; return GATI_ERR_DEVICE; }
+        }
+    }
+    // the direct Conv(k,s) kernels replace the two products over windows (and their slices)
+    const size_t conv_part = t->cd.on ? (size_t)t->cd.g_splits * desc->C * kConvTrainFilters * desc->conv_k * desc->conv_k : 0;
+    const size_t conv_bpart = t->cd.on ? (size_t)kMaxSlices * kConvTrainFilters : 0;   // bias gradient slices, behind the filters'
+
+    const size_t mn[7] = {t->cd.on ? n * P * kConvTrainFilters : n * P * H, n * K, n * Hin, K * Hin, t->cd.on ? 0 : H * Cin, n * Hs, Hs * Sx};
     t->part_floats = 0;
     for (size_t v : mn) t->part_floats = std::max(t->part_floats, v * kMaxSlices);
     t->part_floats = std::min<size_t>(t->part_floats, (size_t)64 << 20);   // 256 MB at most; fewer slices beyond
+    t->part_floats = std::max(t->part_floats, conv_part + conv_bpart);
     gati_status_t st = GATI_OK;
     auto take = [&](gati_status_t s) { if (st == GATI_OK) st = s; };
     take(dev_alloc(&t->W1, H * Cin, H ? w->W1 : nullptr));     // Conv(k,s): [Co][C][k][k] is [Co][C*k*k] as stored
@@ -211,7 +267,8 @@ gati_status_t gati_trainer_create(const gati_cache_desc_t* desc, const gati_cach
     take(dev_alloc(&t->lp, n, nullptr));
     take(dev_alloc(&t->ls, n, nullptr));
     take(dev_alloc(&t->part, t->part_floats, nullptr));
-    if (conv_fc) take(dev_alloc(&t->Xc, n * P * Cin, nullptr));
+    if (conv_fc && !t->cd.on) take(dev_alloc(&t->Xc, n * P * Cin, nullptr));
+    if (t->cd.on) take(dev_alloc(&t->W1t, (size_t)desc->C * desc->conv_k * desc->conv_k * kConvTrainFilters, nullptr));
     try {
         if (conv_fc) {
             std::vector<float> tmp(K * Hin);
@@ -280,7 +337,40 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
     // what the selector reads beside the class probabilities
     const float* sfeat = t->sel_hidden_feat ? t->h : pooled;
     const int ldsf = t->sel_hidden_feat ? Hin : ld_pooled, Fsel = t->Fsel;
-    if (t->Xc) {
+    ConvTrainArgs ca{};
+    if (t->cd.on) {
+        ca.x = pooled; ca.ldx = ld_pooled; ca.n = n; ca.C = t->conv_c; ca.ih = t->conv_ih; ca.iw = t->conv_iw;
+        ca.s = t->conv_s; ca.oh = t->conv_oh; ca.ow = t->conv_ow; ca.H = H; ca.W1 = t->W1; ca.W1t = t->W1t; ca.b1 = t->b1;
+        ca.h = t->h; ca.dh = t->dh; ca.part = t->part; ca.lr = lr;
+        ca.bpart = t->part + (size_t)t->cd.g_splits * t->conv_c * kConvTrainFilters * t->conv_k * t->conv_k;
+        ca.wpc = t->cd.f_wpc; ca.sg = t->cd.f_sg; ca.cpw = t->cd.f_cpw;
+        const int S = t->conv_ih * t->conv_iw;
+        ca.vec = aligned16(pooled, ld_pooled) && ((4 / ca.wpc) * ca.cpw * S) % 4 == 0 && (t->conv_c * S) % 4 == 0;
+        const int wt = t->conv_c * t->conv_k * t->conv_k * kConvTrainFilters;
+        train_conv_pack_kernel<<<(wt + 255) / 256, 256, 0, st>>>(ca, t->conv_k * t->conv_k);
+        if ((e = hipGetLastError()) != hipSuccess) goto fail;
+        const int nblk = (n + ca.sg - 1) / ca.sg;
+        // enough workgroups for about sixteen per compute unit, whole passes each, within the slices' room
+        const int passes = (t->conv_c + (4 / ca.wpc) * ca.cpw - 1) / ((4 / ca.wpc) * ca.cpw);
+        const long room = (long)(t->part_floats / ((size_t)n * P * kConvTrainFilters));
+        ca.csplit = (int)std::max<long>(1, std::min<long>({(16L * t->num_cu + nblk - 1) / nblk, 16, passes, room}));
+        const dim3 blocks(nblk, ca.csplit);
+        const int key = t->conv_k * 10 + t->cd.f_pp;
+        switch (key) {
+            case 31: train_conv_fwd_kernel<3, 1><<<blocks, 256, 0, st>>>(ca); break;
+            case 32: train_conv_fwd_kernel<3, 2><<<blocks, 256, 0, st>>>(ca); break;
+            case 33: train_conv_fwd_kernel<3, 3><<<blocks, 256, 0, st>>>(ca); break;
+            case 51: train_conv_fwd_kernel<5, 1><<<blocks, 256, 0, st>>>(ca); break;
+            case 52: train_conv_fwd_kernel<5, 2><<<blocks, 256, 0, st>>>(ca); break;
+            default: train_conv_fwd_kernel<5, 3><<<blocks, 256, 0, st>>>(ca); break;
+        }
+        if ((e = hipGetLastError()) != hipSuccess) goto fail;
+        if (ca.csplit > 1) {
+            const long hv = (long)n * P * H;
+            train_conv_finish_kernel<<<(int)((hv + 255) / 256), 256, 0, st>>>(ca);
+            if ((e = hipGetLastError()) != hipSuccess) goto fail;
+        }
+    } else if (t->Xc) {
         Im2colArgs ia;
         ia.x = pooled; ia.ldx = ld_pooled; ia.Xc = t->Xc; ia.n = n; ia.C = t->conv_c; ia.ih = t->conv_ih; ia.iw = t->conv_iw;
         ia.k = t->conv_k; ia.s = t->conv_s; ia.oh = t->conv_oh; ia.ow = t->conv_ow;
@@ -289,7 +379,7 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
         if ((e = hipGetLastError()) != hipSuccess) goto fail;
         a1 = t->Xc; lda1 = Cin;
     }
-    if (H) {
+    if (H && !t->cd.on) {
         g = GemmArgs{}; g.A = a1; g.lda = lda1; g.B = t->W1; g.ldb = Cin; g.M = n * P; g.N = H; g.Kd = Cin;
         g.out = t->h; g.ldo = H; g.bias = t->b1;
         if ((e = launch_gemm<false, true, EPI_BIAS_RELU>(t, g, st)) != hipSuccess) goto fail;
@@ -336,7 +426,23 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
     g = GemmArgs{}; g.A = t->z; g.lda = K; g.B = hin; g.ldb = ldh; g.M = K; g.N = Hin; g.Kd = n;
     g.out = t->W2; g.ldo = Hin; g.lr = lr;
     if ((e = launch_gemm<true, false, EPI_SGD>(t, g, st)) != hipSuccess) goto fail;
-    if (H) {
+    if (t->cd.on) {
+        // W1 -= lr * (filter gradient over all samples and positions), split over the samples
+        ca.wpc = t->cd.g_wpc; ca.ns = t->cd.g_ns;
+        const int cw = 4 / ca.wpc;
+        ca.vec = aligned16(pooled, ld_pooled) && (cw * t->conv_ih * t->conv_iw) % 4 == 0 &&
+                 (t->conv_c * t->conv_ih * t->conv_iw) % 4 == 0 && H == kConvTrainFilters;
+        int rps = (n + t->cd.g_splits - 1) / t->cd.g_splits;
+        rps = (rps + ca.ns - 1) / ca.ns * ca.ns;
+        ca.rows_per_split = rps; ca.splits = (n + rps - 1) / rps;
+        const dim3 grid((t->conv_c + cw - 1) / cw, ca.splits);
+        if (t->conv_k == 3) train_conv_wgrad_kernel<3, 1><<<grid, 256, kConvTrainGradLds, st>>>(ca);
+        else train_conv_wgrad_kernel<5, 2><<<grid, 256, kConvTrainGradLds, st>>>(ca);
+        if ((e = hipGetLastError()) != hipSuccess) goto fail;
+        const int kk2 = t->conv_k * t->conv_k;
+        train_conv_update_kernel<<<(H * t->conv_c * kk2 + 255) / 256, 256, 0, st>>>(ca, kk2);
+        if ((e = hipGetLastError()) != hipSuccess) goto fail;
+    } else if (H) {
         // W1 -= lr dh^T a1      (dh as [n*P][H])
         g = GemmArgs{}; g.A = t->dh; g.lda = H; g.B = a1; g.ldb = lda1; g.M = H; g.N = Cin; g.Kd = n * P;
         g.out = t->W1; g.ldo = Cin; g.lr = lr;
@@ -349,6 +455,7 @@ gati_status_t gati_trainer_step(gati_trainer_t* t, const float* pooled, int32_t 
         const ColsumJob none{t->z, K, 0, nullptr, t->b2, 0, 0};
         c.job[0] = ColsumJob{t->z, K, K, nullptr, t->b2, 0, n};
         c.job[1] = ColsumJob{t->dh, H, H, nullptr, t->b1, 0, n * P};     // dh as [n*P][H]
+        if (t->cd.on) c.job[1] = none;                                   // done with the filters, from the same staged values
         if (t->Hs) {
             c.job[2] = ColsumJob{t->dg, t->Hs, t->Hs, nullptr, t->cs, 0, n};
             c.job[3] = ColsumJob{t->g, t->Hs, t->Hs, t->du, t->vs, 0, n};
@@ -377,7 +484,7 @@ gati_status_t gati_trainer_get_weights(gati_trainer_t* t, float* W1, float* b1, 
     if (!on_trainer_device(t)) return GATI_ERR_DEVICE;
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
     const size_t H = t->H, K = t->K, Cin = t->Cin, Hin = t->Hin, F = t->Fsel;
-    const bool permute = t->Xc != nullptr;                  // Conv(k,s): hidden-value columns back to [filter][position]
+    const bool permute = t->conv_k > 0;                  // Conv(k,s): hidden-value columns back to [filter][position]
     try {
         std::vector<float> w2(permute ? K * Hin : 0), wsel(permute && has_ws ? F + K : 0);
         struct { float* dst; const float* src; size_t n; } cp[] = {
@@ -402,14 +509,14 @@ gati_status_t gati_trainer_get_hidden_selector(gati_trainer_t* t, float* Ws, flo
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return GATI_ERR_DEVICE; }
     const size_t cols = (size_t)t->Fsel + t->K, w = cols * sizeof(float);
     try {
-        std::vector<float> tmp(t->Xc ? (size_t)t->Hs * cols : 0);
-        float* dst = t->Xc ? tmp.data() : Ws;
+        std::vector<float> tmp(t->conv_k ? (size_t)t->Hs * cols : 0);
+        float* dst = t->conv_k ? tmp.data() : Ws;
         if (hipMemcpy2D(dst, w, t->Ws, (size_t)t->Sx * sizeof(float), w, t->Hs, hipMemcpyDeviceToHost) != hipSuccess ||
             hipMemcpy(cs, t->cs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess ||
             hipMemcpy(vs, t->vs, (size_t)t->Hs * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) {
             (void)hipGetLastError(); return GATI_ERR_DEVICE;
         }
-        if (t->Xc) permute_hidden_cols(t, tmp.data(), cols, Ws, cols, t->Hs, t->K, false);
+        if (t->conv_k) permute_hidden_cols(t, tmp.data(), cols, Ws, cols, t->Hs, t->K, false);
     } catch (const std::bad_alloc&) { return GATI_ERR_OOM; }
     return GATI_OK;
 }

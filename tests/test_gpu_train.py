@@ -430,10 +430,16 @@ def test_fc_predictor_step(C, S, H, K, n, selector):
 @pytest.mark.parametrize("C,ih,iw,Co,k,s,K,n,selector", [
     (4, 9, 8, 5, 3, 2, 6, 20, "linear"), (16, 14, 14, 8, 3, 1, 10, 24, "linear"), (8, 12, 12, 8, 5, 2, 33, 40, "hidden"),
     (3, 6, 6, 2, 6, 1, 4, 9, "softmax"),
+    # shapes that the kernels working on the maps themselves take (3 x 3 / 5 x 5 taps, up to 8 filters), one per
+    # way of dealing positions, channels and samples out: a partial channel group; four waves per map;
+    # two waves per map; a ResNet stage-1 map; several samples per wave, per pass and a ragged last sample split
+    (6, 30, 30, 8, 5, 2, 7, 10, "linear"), (5, 26, 24, 7, 3, 1, 5, 6, "linear"), (4, 40, 40, 8, 3, 2, 6, 7, "softmax"),
+    (3, 56, 56, 8, 5, 2, 10, 5, "linear"), (8, 7, 7, 8, 3, 1, 6, 70, "linear"), (9, 5, 5, 3, 3, 1, 4, 133, "hidden"),
+    (8, 9, 9, 12, 3, 1, 5, 12, "linear"),        # more than 8 filters: the product over gathered windows
 ])
 def test_conv_predictor_step(C, ih, iw, Co, k, s, K, n, selector):
-    """Conv(k,s): weight gradients of the filters through the product over gathered windows; the caller's
-    [filter][position] order of the hidden values survives the trainer's internal order."""
+    """Conv(k,s): weight gradients of the filters, on the maps themselves or through the product over gathered
+    windows; the caller's [filter][position] order of the hidden values survives the trainer's internal order."""
     rng = np.random.default_rng(C * ih + Co * k + s)
     oh, ow = (ih - k) // s + 1, (iw - k) // s + 1
     F = Co * oh * ow
