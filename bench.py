@@ -610,6 +610,11 @@ def time_training(spec, weights, caches, acts, torch, g, W, with_cpu, reps=10):
             wb = 2 * Hd * L.C * L.S * 4
             row["W1_update_bytes"] = wb
             row["hbm_floor_us"] = round(wb / (HBM_PEAK_GBS * 1e9) * 1e6, 1)
+        if conv_fc:
+            # the convolution's two kernels run on the vector units: fp32 FMA without packed instructions,
+            # 256 CUs x 64 lanes x 2 flop x 2.4 GHz
+            row["bound"] = "alu"
+            row["frac_of_fp32_vector_rate_unpacked"] = round(flops / (us * 1e-6) / 1e12 / 78.6, 4)
         if fc_mlp or conv_fc:
             out.append(row)
             tr.close()
