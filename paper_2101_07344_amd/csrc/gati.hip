@@ -1100,7 +1100,6 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
         plan_pool(c);
     }
 
-    const int K = desc->K;
     gati_status_t st = upload_weights(c, w);
     if (st == GATI_OK && c->variant == POOL_NCS_ADAPTIVE) {
         // window table of the tiled adaptive-pool kernel; window i of an axis covers

@@ -130,7 +130,6 @@ void permute_hidden_cols(const gati_trainer* t, const float* src, size_t lds, fl
 gati_trainer::ConvDirect plan_conv_direct(int C, int S, int P, int k, int H, int num_cu) {
     gati_trainer::ConvDirect p;
     if ((k != 3 && k != 5) || H > kConvTrainFilters || S > kConvTrainXFloats || P > kConvTrainMaxP || P < 1) return p;
-    const int kk2 = k * k;
     // forward: the fewest lane slots that hold a map's positions; ties go to more channels per workgroup
     long best = -1;
     for (int wpc = 1; wpc <= 4; wpc *= 2) {
