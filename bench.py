@@ -37,6 +37,7 @@ PROFILED_TRAFFIC = {
     ("resnet50", "ncs_wave[C=256,S=3136,bf16]"): (819_310_000, "profiles/pool_ncs_wave_bf16_resnet50_hbm_traffic.md"),
     ("bert_base", "nsc_unit[C=768,S=128,bf16]"): (142_730_000, "profiles/pool_nsc_unit_bf16_bert_base_hbm_traffic.md"),
     ("resnet50_conv", "conv_rows[C=256,S=3136,bf16]"): (833_320_000, "profiles/conv_rows_bf16_resnet50_conv_hbm_traffic.md"),
+    ("resnet50_pool", "ncs_adaptive[C=256,S=3136,bf16]"): (825_590_000, "profiles/pool_ncs_adaptive_bf16_resnet50_pool_hbm_traffic.md"),
 }
 
 
