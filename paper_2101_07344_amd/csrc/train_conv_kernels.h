@@ -9,10 +9,11 @@
 //
 // Work layout shared by both kernels: a workgroup is 4 waves; `wpc` (1, 2 or 4) waves share a
 // channel, so a workgroup step covers cw = 4 / wpc channels; the lanes of a channel's waves are
-// dealt the output positions.  Maps and the operands that are uniform over positions (filters,
-// hidden gradients) are staged through LDS in passes, with 16-byte loads that are all in flight
-// together where the caller's rows allow it (`vec`), element by element otherwise.  Every sum
-// has a fixed order.  gfx950, 64-wide waves.
+// dealt the output positions.  Maps (and, in the gradient kernel, the hidden gradients) are staged
+// through LDS in passes, with 16-byte loads that are issued one pass ahead where the caller's rows
+// allow it (`vec`), element by element otherwise; the filter values of a wave's channel are the
+// same for all its lanes and come through the scalar cache.  Every sum has a fixed order.
+// gfx950, 64-wide waves.
 #pragma once
 
 #include "common.h"
@@ -31,7 +32,7 @@ struct ConvTrainArgs {
     const float* x; int ldx;          // [n][ldx] maps, channel-major: x[i][c*ih*iw + y*iw + xx]
     int n, C, ih, iw, s, oh, ow, H;   // H filters (<= 8)
     float* W1;                        // [H][C*k*k]
-    float* W1t;                       // [C][k*k][8]: the filters as the forward pass stages them, zero past H
+    float* W1t;                       // [C][k*k][8]: the filters as the forward pass reads them, zero past H
     float* b1;                        // [H]
     float* h;                         // forward out: [n][oh*ow][H]
     const float* dh;                  // gradient in: [n][oh*ow][H], zero where h is zero
