@@ -110,6 +110,16 @@ def time_pool_launches(spec, caches, stack, acts, keys, reps, torch):
             groups.append([l, l])
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in groups]
           for _ in range(reps)]
+    # Launches of a few microseconds end before the host has enqueued the next one, and the idle time would
+    # land between the events: give the host a head start of a few milliseconds of plain reads, so that every
+    # timed launch and event is already queued when the GPU reaches it.
+    import paper_2101_07344_amd as g
+    blocker = torch.empty(64 << 20, dtype=torch.float32, device="cuda")
+    sink = torch.zeros(256 * 32 * 1024, dtype=torch.float32, device="cuda")
+    lead_ms = 0.012 * (reps + 1) * (L + 2 * len(groups))      # ~12 us of host time per call
+    torch.cuda.synchronize()
+    for _ in range(int(lead_ms / 0.04) + 1):                  # a 256 MB read takes ~40 us
+        g.gati_probe_stream_read(blocker, blocker.numel() * 4, sink, 1)
     for r in range(-1, reps):           # r = -1: warm-up
         for gi, (lo, hi) in enumerate(groups):
             if r >= 0:
@@ -317,9 +327,13 @@ def plain_read_same_sizes(spec, acts, counts, torch, g, reps=5):
     if total == 0:
         return None
     best = None
+    blocker = torch.empty(64 << 20, dtype=torch.float32, device="cuda")
     for bpc in (0, 1, 32):
         ts = []
         for r in range(-1, reps):
+            # host head start, as in time_pool_launches
+            for _ in range(int(0.012 * (len(acts) + 2) / 0.04) + 1):
+                g.gati_probe_stream_read(blocker, blocker.numel() * 4, sink, 1)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for a, nb in zip(acts, nbytes):
