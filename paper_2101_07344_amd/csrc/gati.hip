@@ -756,6 +756,14 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
     f2.n_max = n_max; f2.n_dev = n_dev;
     f2.K = c->desc.K; f2.ws_prob = c->ws_prob; f2.logits = logits; f2.stats = c->stats;
     const int n_tiles = c->Kp / (32 * c->fc2_nt);
+    // few classes (one column tile): the output layer finishes its rows itself, and what is left of the finish
+    // is the compaction of the flags
+    const bool fused_finish = n_tiles == 1 && !sel_hidden && !c->pool_fc && (!ids_out || n_max <= kCompactSingleMax);
+    if (fused_finish) {
+        f2.fin = 1; f2.fin_bs = weights_of(c)->bs; f2.fin_tau = weights_of(c)->tau;
+        f2.fin_softmax_only = c->desc.selector == GATI_SEL_SOFTMAX ? 1 : 0;
+        f2.fin_class = pred_class; f2.fin_conf = confidence; f2.fin_hit = hit;
+    }
     if (c->fc2_nt == 2) {
         // thousands of features (Pool(h), Conv(k,s)): the instance that fetches its activation rows by whole lines
         if constexpr (BF16) {
@@ -773,6 +781,13 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
 output_layer_launched:
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (fused_finish) {
+        if (!ids_out) return hipSuccess;
+        CompactArgs ca;
+        ca.hit = hit; ca.ids_in = ids_in; ca.n_dev = n_dev; ca.n_max = n_max; ca.ids_out = ids_out; ca.n_miss = n_miss;
+        compact_misses_kernel<<<1, 1024, 0, st>>>(ca);
+        return hipGetLastError();
+    }
 
     FinalizeArgs fa = {};
     if (sel_hidden) {

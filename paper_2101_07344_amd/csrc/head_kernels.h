@@ -79,6 +79,14 @@ struct FcArgs {
     const float* ws_prob;  // [N] selector weights of the class probabilities, zero padded
     float* logits;         // [n, K] or null
     TileStat* stats;       // [rows_pad, N/(32*NT)]
+    // heads whose classes fit one column tile: the tile's summary is the row's, and this kernel writes class,
+    // confidence and hit flag itself (u_pool must come from an earlier launch); stats is then unused
+    int fin;
+    float fin_bs, fin_tau;
+    int fin_softmax_only;
+    int32_t* fin_class;    // [n]
+    float* fin_conf;       // [n]
+    uint8_t* fin_hit;      // [n]
 };
 
 // One row's per-tile softmax summaries merged in tile order: the running (max, sum, wsum) is
@@ -411,7 +419,14 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
         if (sub == 0) {
             TileStat s;
             s.max = bm; s.sum = ps; s.wsum = pt; s.arg = bi;
-            a.stats[(long)(row0 + lr) * n_tiles_x + bx] = s;
+            if (a.fin) {
+                const int row = row0 + lr;
+                if (row < n)
+                    finish_row(&s, 1, a.u_pool[row], a.fin_bs, a.fin_tau, a.fin_softmax_only != 0, &a.fin_class[row],
+                               &a.fin_conf[row], &a.fin_hit[row]);
+            } else {
+                a.stats[(long)(row0 + lr) * n_tiles_x + bx] = s;
+            }
         }
         if (a.p32) selector_pool_part(a, row0, bx, a.n_dev, a.n_max, n_tiles_x);   // predictors without a hidden-layer kernel
     }
