@@ -152,6 +152,27 @@ def time_graph(stack, acts, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps
 
 
+def time_uncompacted(spec, caches, acts, steps, warmup, torch):
+    """The stack without layer-to-layer compaction: every layer looks up the whole batch, as a batch does
+    that runs until its slowest member is done (Section 7, the paper's batch mode).  What the miss lists save."""
+    n = spec.batch
+    pc = torch.empty(n, dtype=torch.int32, device="cuda")
+    conf = torch.empty(n, device="cuda")
+    hit = torch.empty(n, dtype=torch.uint8, device="cuda")
+    def one_pass():
+        for cache, a in zip(caches, acts):
+            cache.lookup(a, None, n, None, pc, conf, hit)
+    for _ in range(warmup):
+        one_pass()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        one_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
 def time_overlap(stack, acts, steps, warmup, torch, gemm_dim=4096):
     """Lookups beside a stand-in for the base DNN (the paper's serving arrangement, Section 6:
     base model on one stream, cache lookups on a second one).  The stand-in is one bf16
@@ -394,7 +415,7 @@ def time_compaction(cache, stack, batch, torch, reps=20):
 
 
 def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_probe=False,
-                 graph=False, overlap=False, yardstick=False, train=False, ceiling=False):
+                 graph=False, overlap=False, yardstick=False, train=False, ceiling=False, uncompacted=False):
     t_build = time.perf_counter()
     spec, labels, weights, caches, stack, acts = build_workload(name, torch, g, W)
     if copy_probe:
@@ -485,6 +506,11 @@ def run_workload(name, steps, warmup, with_cpu, cpu_requests, torch, g, W, copy_
         out["graph_ms_per_step"] = round(time_graph(stack, acts, steps, warmup, torch), 4)
     if overlap and spec.storage == "gather":
         out["overlap"] = time_overlap(stack, acts, steps, warmup, torch)
+    if uncompacted and spec.storage == "gather":
+        ms_all = time_uncompacted(spec, caches, acts, steps, warmup, torch)
+        out["uncompacted"] = {"ms_per_step": round(ms_all, 4), "lookups_per_step": spec.batch * n_layers,
+                              "requests_per_s": round(spec.batch / (ms_all * 1e-3), 1),
+                              "requests_per_s_compacted": round(spec.batch / (ms_step * 1e-3), 1)}
     if ceiling:
         sc = stream_read_ceiling(acts, torch, g)
         out["stream_read_ceiling"] = sc
@@ -664,6 +690,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="also time the pass replayed from a captured HIP graph")
     ap.add_argument("--overlap", action="store_true",
                     help="also time the lookups beside a synthetic base-DNN stand-in, same stream vs side stream")
+    ap.add_argument("--uncompacted", action="store_true",
+                    help="also time the stack with every layer looking up the whole batch (no miss lists)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain tensor copy of layer 0's activations (known size), the reference "
                          "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -696,7 +724,7 @@ def main():
         spec, main_res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
                                       args.cpu_requests, torch, g, W, copy_probe=args.copy_probe,
                                       graph=args.graph, overlap=args.overlap, yardstick=args.gemm_yardstick,
-                                      train=args.train, ceiling=True)
+                                      train=args.train, ceiling=True, uncompacted=args.uncompacted)
         others = {}
         for name in [n for n in args.also.split(",") if n and n != args.workload]:
             _, r = run_workload(name, args.steps, args.warmup, False, 0, torch, g, W)
@@ -725,7 +753,7 @@ def main():
         "pool_kernels": main_res["pool_kernels"],
         "others": others,
     }
-    for key in ("head_us_per_step", "dependent_launch_floor", "compact_alone_us", "graph_ms_per_step", "overlap", "library_pool", "train_step"):
+    for key in ("head_us_per_step", "dependent_launch_floor", "compact_alone_us", "graph_ms_per_step", "overlap", "uncompacted", "library_pool", "train_step"):
         if key in main_res:
             line[key] = main_res[key]
     if args.gemm_yardstick and L0.predictor == "fc_mlp":
