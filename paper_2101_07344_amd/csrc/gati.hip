@@ -765,9 +765,10 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
         f2.fin_class = pred_class; f2.fin_conf = confidence; f2.fin_hit = hit;
     }
     if (c->fc2_nt == 2) {
-        // thousands of features (Pool(h), Conv(k,s)): the instance that fetches its activation rows by whole lines
+        // a thousand features or more (Pool(h), Conv(k,s), the hidden layer of FC(h)): the instance that fetches its
+        // activation rows by whole lines
         if constexpr (BF16) {
-            if (f2.Kdim >= 2048 && f2.Kdim % 256 == 0) {
+            if (f2.Kdim >= 1024 && f2.Kdim % 256 == 0) {
                 fc_kernel<true, 2, false, 8, true><<<dim3(n_tiles, row_tiles), 256, 0, st>>>(f2);
                 goto output_layer_launched;
             }
@@ -1064,9 +1065,9 @@ gati_status_t gati_cache_create(const gati_cache_desc_t* desc, const gati_cache_
     c->conv_fc = conv_fc;
     c->conv_oh = conv_oh; c->conv_ow = conv_ow;
     c->F = (int)F_l;
-    // features are padded to whole k-step groups; thousands of them (an output layer straight over pooled or
-    // convolved features) to 256, so that each of the 4 waves of fc_kernel owns whole 128-byte lines of a row
-    c->Cp = round_up(c->F, (no_hidden_kernel && c->F >= 2048) ? 256 : 64);
+    // features are padded to whole k-step groups; a thousand or more of them (an output layer straight over pooled
+    // or convolved features) to 256, so that each of the 4 waves of fc_kernel owns whole 128-byte lines of a row
+    c->Cp = round_up(c->F, (no_hidden_kernel && c->F >= 1024) ? 256 : 64);
     c->Hp = no_hidden_kernel ? c->Cp : round_up(desc->H, 64);   // width of the layer that feeds the output FC
     c->fc2_nt = desc->K > 96 ? 2 : 1;
     c->Kp = round_up(desc->K, 32 * c->fc2_nt);

@@ -176,8 +176,8 @@ __device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, in
 // !HIDDEN: epilogue bias -> logits (optional store) and the tile's softmax/argmax summary.
 // U: k-steps per pipeline stage (two stages in registers): 4 when a wave's share of the reduction is
 // at most 8 k-steps (everything is in flight at once with half the registers), else 8.
-// ASTAGE (bf16, NT = 2, Kdim a multiple of 256): long reductions -- the output layer over thousands of
-// features.  A lane's A fragment is 16 bytes of ITS row, so a wave-wide fragment load touches 32
+// ASTAGE (bf16, NT = 2, Kdim a multiple of 256): long reductions -- the output layer over a thousand
+// features or more.  A lane's A fragment is 16 bytes of ITS row, so a wave-wide fragment load touches 32
 // different 128-byte lines and uses 32 bytes of each: the texture path, which takes a line per clock,
 // is then busy 4x longer on A than the bytes need and the kernel is bound by it (counters at
 // F = 4096: waves stalled on issue 70 % of the time, 7.5 M line accesses per launch).  Here every wave
