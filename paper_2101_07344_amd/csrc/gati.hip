@@ -740,8 +740,17 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
         f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
         f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
         if (!sel_hidden) { f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp; }
-        if (deep(f1)) fc_kernel<BF16, 1, true, 8><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
-        else fc_kernel<BF16, 1, true, 4><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
+        bool f1_done = false;
+        if constexpr (BF16) {
+            if (f1.Kdim >= 1024 && f1.Kdim % 256 == 0) {
+                fc_kernel<true, 1, true, 8, true><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
+                f1_done = true;
+            }
+        }
+        if (!f1_done) {
+            if (deep(f1)) fc_kernel<BF16, 1, true, 8><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
+            else fc_kernel<BF16, 1, true, 4><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
+        }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         f2.A = c->h; f2.Kdim = c->Hp;

@@ -176,8 +176,8 @@ __device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, in
 // !HIDDEN: epilogue bias -> logits (optional store) and the tile's softmax/argmax summary.
 // U: k-steps per pipeline stage (two stages in registers): 4 when a wave's share of the reduction is
 // at most 8 k-steps (everything is in flight at once with half the registers), else 8.
-// ASTAGE (bf16, NT = 2, Kdim a multiple of 256): long reductions -- the output layer over a thousand
-// features or more.  A lane's A fragment is 16 bytes of ITS row, so a wave-wide fragment load touches 32
+// ASTAGE (bf16, Kdim a multiple of 256): long reductions -- the output layer over a thousand features
+// or more, the hidden layer over a thousand channels or more.  A lane's A fragment is 16 bytes of ITS row, so a wave-wide fragment load touches 32
 // different 128-byte lines and uses 32 bytes of each: the texture path, which takes a line per clock,
 // is then busy 4x longer on A than the bytes need and the kernel is bound by it (counters at
 // F = 4096: waves stalled on issue 70 % of the time, 7.5 M line accesses per launch).  Here every wave
@@ -187,17 +187,18 @@ __device__ __forceinline__ void selector_pool_part(const FcArgs& a, int row0, in
 // slice of `red`, which it writes only after its last fragment read: no barrier is involved.
 template <bool BF16, int NT, bool HIDDEN, int U, bool ASTAGE = false>
 __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
-    static_assert(!ASTAGE || (BF16 && NT == 2 && !HIDDEN), "staged A: bf16 output layer with 64-column tiles");
+    static_assert(!ASTAGE || BF16, "staged A: bf16 operands");
     using M = Mma<BF16>;
     using frag_t = typename M::frag_t;
     constexpr int kStep = M::kStep, kLane = M::kLane;
-    __shared__ float red[4][NT * 16][64];      // split-K partial tiles, [wave][tile*16 + j][lane]
+    // split-K partial tiles, [wave][tile*16 + j][lane]; the staged-A instance parks two 4 KB blocks per wave there
+    __shared__ float red[4][ASTAGE ? 32 : NT * 16][64];
 
-    // tile of this workgroup.  The long-reduction instance deals the tiles out so that one XCD (consecutive
+    // tile of this workgroup.  The long-reduction output layer deals the tiles out so that one XCD (consecutive
     // workgroup ids go round the 8 XCDs) owns a block of 8 row tiles x (column tiles / 4): its L2 then holds
     // 8 activation tiles and a quarter of the weights instead of all activation tiles and an eighth of the weights
     int bx = blockIdx.x, by = blockIdx.y;
-    if constexpr (ASTAGE) {
+    if constexpr (ASTAGE && !HIDDEN) {
         if ((gridDim.x & 3) == 0 && (gridDim.y & 15) == 0) {
             const int lin = blockIdx.y * gridDim.x + blockIdx.x;
             const int xcd = lin & 7, j = lin >> 3;                       // j: 0 .. gx*gy/8 - 1 within the XCD
