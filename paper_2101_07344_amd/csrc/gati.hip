@@ -733,6 +733,18 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
     const bool sel_hidden = c->desc.selector == GATI_SEL_HIDDEN;
     // a wave's share of the reduction beyond 8 k-steps: the kernel instance with the deeper load pipeline
     auto deep = [](const FcArgs& f) { return f.Kdim / (BF16 ? 16 : 8) / 4 > 8; };
+    // a layer with ReLU (predictor FC1, selector first layer): over 1024 inputs and more, the instance that fetches its
+    // operand rows by whole lines
+    auto launch_hidden = [&](const FcArgs& f, int col_tiles) {
+        if constexpr (BF16) {
+            if (f.Kdim >= 1024 && f.Kdim % 256 == 0) {
+                fc_kernel<true, 1, true, 8, true><<<dim3(col_tiles, row_tiles), 256, 0, st>>>(f);
+                return;
+            }
+        }
+        if (deep(f)) fc_kernel<BF16, 1, true, 8><<<dim3(col_tiles, row_tiles), 256, 0, st>>>(f);
+        else fc_kernel<BF16, 1, true, 4><<<dim3(col_tiles, row_tiles), 256, 0, st>>>(f);
+    };
     if (sel_hidden && !logits) logits = c->zbuf;     // the selector's first layer reads the class probabilities
     FcArgs f2 = {};
     if (!c->pool_fc) {
@@ -740,17 +752,7 @@ hipError_t launch_head_t(const gati_cache* c, int n_max, const int32_t* n_dev, i
         f1.A = BF16 ? c->p16 : (const void*)c->p; f1.Wp = c->W1; f1.bias = c->b1; f1.Kdim = c->Cp; f1.N = c->Hp;
         f1.n_max = n_max; f1.n_dev = n_dev; f1.h = c->h;
         if (!sel_hidden) { f1.p32 = c->p; f1.ws_pool = c->ws_pool; f1.u_pool = c->u_pool; f1.ldp = c->Cp; }
-        bool f1_done = false;
-        if constexpr (BF16) {
-            if (f1.Kdim >= 1024 && f1.Kdim % 256 == 0) {
-                fc_kernel<true, 1, true, 8, true><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
-                f1_done = true;
-            }
-        }
-        if (!f1_done) {
-            if (deep(f1)) fc_kernel<BF16, 1, true, 8><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
-            else fc_kernel<BF16, 1, true, 4><<<dim3(c->Hp / 32, row_tiles), 256, 0, st>>>(f1);
-        }
+        launch_hidden(f1, c->Hp / 32);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         f2.A = c->h; f2.Kdim = c->Hp;
@@ -812,8 +814,7 @@ output_layer_launched:
         FcArgs fs = {};
         fs.A = c->sel_in; fs.Wp = c->Ws; fs.bias = c->cs; fs.Kdim = c->Sin; fs.N = c->Hsp;
         fs.n_max = n_max; fs.n_dev = n_dev; fs.h = c->sel_g;
-        if (deep(fs)) fc_kernel<BF16, 1, true, 8><<<dim3(c->Hsp / 32, row_tiles), 256, 0, st>>>(fs);
-        else fc_kernel<BF16, 1, true, 4><<<dim3(c->Hsp / 32, row_tiles), 256, 0, st>>>(fs);
+        launch_hidden(fs, c->Hsp / 32);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         fa.sel_g = c->sel_g; fa.sel_vs = c->vs; fa.sel_hs = c->Hs; fa.ldg = c->Hsp; fa.g_bf16 = BF16 ? 1 : 0;
