@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
     __shared__ float red[4][ASTAGE ? 32 : NT * 16][64];
 
     // tile of this workgroup.  The long-reduction output layer deals the tiles out so that one XCD (consecutive
-    // workgroup ids go round the 8 XCDs) owns a block of 8 row tiles x (column tiles / 4): its L2 then holds
+    // workgroup ids go round the 8 XCDs) owns 8 of every 16 row tiles x (column tiles / 4): its L2 then holds
     // 8 activation tiles and a quarter of the weights instead of all activation tiles and an eighth of the weights
     int bx = blockIdx.x, by = blockIdx.y;
     if constexpr (ASTAGE && !HIDDEN) {
@@ -205,7 +205,8 @@ __global__ __launch_bounds__(256) void fc_kernel(FcArgs a) {
             const int cpx = gridDim.x >> 2;                              // column tiles per XCD
             const int per = 8 * cpx;                                     // tiles of one XCD per block of 16 row tiles
             const int blk = j / per, jj = j - blk * per;
-            by = blk * 16 + (xcd & 1) * 8 + (jj & 7);
+            by = blk * 16 + (jj & 7) * 2 + (xcd & 1);                    // even / odd row tiles: a batch that fills only
+                                                                         // its first row tiles still keeps every XCD busy
             bx = (xcd >> 1) * cpx + (jj >> 3);
         }
     }
